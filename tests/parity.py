@@ -1,0 +1,46 @@
+"""Error metrics of the parity gate (shared by the GPU tests and the benchmark's self-check).
+
+Gate: per (batch, head) Frobenius-relative error <= tol, and per-row relative error
+||o_i - o*_i||_2 / ||o*_i||_2 <= tol for rows i >= 4d, <= 10*tol for rows i < 4d (the normal
+matrix of the earliest rows has rank <= i before the ridge, so their conditioning is worse by
+orders of magnitude).  tol = 1e-4 for fp32 inputs, 2e-2 for bf16 inputs.
+"""
+import numpy as np
+
+
+def row_errors(got, ref):
+    """got, ref: [..., rows, dv].  Per-row relative L2 error."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    num = np.linalg.norm(got - ref, axis=-1)
+    den = np.maximum(np.linalg.norm(ref, axis=-1), 1e-30)
+    return num / den
+
+
+def frobenius_error(got, ref):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    return np.linalg.norm((got - ref).reshape(-1)) / max(np.linalg.norm(ref.reshape(-1)), 1e-30)
+
+
+def check(got, ref, rows, d, tol, what=""):
+    """got, ref: [B, H, len(rows), dv]; rows: the query index of each row.  Asserts the gate and
+    returns a summary dict."""
+    rows = np.asarray(rows)
+    assert np.all(np.isfinite(np.asarray(got, dtype=np.float64))), what + ": non-finite output"
+    err = row_errors(got, ref)                                   # [B, H, R]
+    early = rows < 4 * d
+    bound = np.where(early, 10.0 * tol, tol)
+    worst = np.unravel_index(np.argmax(err / bound), err.shape)
+    summary = {
+        "median": float(np.median(err)), "p99": float(np.quantile(err, 0.99)),
+        "max": float(err.max()), "worst_row": int(rows[worst[-1]]),
+        "worst_ratio_to_bound": float((err / bound).max()),
+    }
+    B, H = err.shape[:2]
+    fro = max(frobenius_error(got[b][h], ref[b][h]) for b in range(B) for h in range(H))
+    summary["frobenius_max"] = float(fro)
+    assert fro <= tol, "%s: Frobenius error %.3e > %.1e (%s)" % (what, fro, tol, summary)
+    assert np.all(err <= bound), "%s: row %d error %.3e exceeds %.1e (%s)" % (
+        what, summary["worst_row"], err[worst], bound[worst[-1]], summary)
+    return summary
