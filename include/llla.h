@@ -1,0 +1,134 @@
+/*
+ * llla.h -- C ABI of the MI355X (gfx950) Local Linear Attention library.
+ *
+ * Local Linear Attention (arxiv 2510.01450, Section 2.3): for every query q_i, fit
+ * f(x) = b + W (x - q_i) to the visible key/value pairs (k_j, v_j) by weighted ridge least squares
+ * (objective Eq. (lla_obj)) and return the intercept b as the output o_i.  In the paper's symbols
+ * (Eq. (query_specific), Eq. (lla)):
+ *
+ *     w_ij   = exp(scale * <q_i, k_j> - m_i),   m_i = max over visible j of scale * <q_i, k_j>
+ *     z_ij   = k_j - q_i
+ *     omega_i = sum_j w_ij,  mu_i = sum_j w_ij z_ij,  Sigma_i = sum_j w_ij z_ij z_ij^T + lambda I
+ *     rho_i  = Sigma_i^{-1} mu_i,   delta_i = omega_i - mu_i . rho_i
+ *     o_i    = sum_j w_ij (1 - z_ij . rho_i) / delta_i * v_j
+ *
+ * Conventions of this library where the paper leaves a choice:
+ *   - the kernel is the dot-product exponential of the matrix form and Algorithm 1 (Section 3.2),
+ *     scale = 1/h;  the paper's default bandwidth corresponds to scale = 1/sqrt(d);
+ *   - lambda is added to moments of the row-max-normalised weights above (largest weight of a row
+ *     is exactly 1), which is what Algorithm 1 computes after its last key block; outputs are
+ *     therefore invariant to adding a constant to all logits of a row;
+ *   - "+ lambda I" exactly as in Eq. (query_specific); the intercept is not penalised;
+ *   - causal means j <= i, inclusive (the tril mask of Section 3.2);
+ *   - the per-query system is solved exactly (on-chip factorisation), not by a fixed number of
+ *     conjugate-gradient iterations (Appendix C is the paper's approximate alternative).
+ *
+ * Memory and execution contract (all entry points):
+ *   - every data pointer is a DEVICE pointer owned by the caller; the library never allocates or
+ *     frees device memory, never synchronises the device, and enqueues all work on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream);
+ *   - tensors are [batch, head, seq, d] with the innermost (d) stride equal to 1; the other strides
+ *     are given in elements in an llla_strides;
+ *   - inputs are never modified, outputs are fully overwritten, results are deterministic;
+ *   - arguments are validated on the host before anything is enqueued; on error nothing has been
+ *     launched and the outputs are untouched (LLLA_ERR_LAUNCH excepted);
+ *   - `workspace` is scratch of at least the size the matching *_workspace_bytes() call returns
+ *     (256-byte aligned); it holds Theta(B*H*n*d) data only -- no per-query d x d matrix and no
+ *     n x n matrix is ever written to device memory.  Calls that share a workspace must be
+ *     ordered on one stream.
+ */
+#ifndef LLLA_H
+#define LLLA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LLLA_OK = 0,
+    LLLA_ERR_NULL = 1,        /* a required pointer is NULL */
+    LLLA_ERR_SHAPE = 2,       /* B, H, n, L or d <= 0, or a stride too small for the shape */
+    LLLA_ERR_DTYPE = 3,       /* unknown llla_dtype */
+    LLLA_ERR_PARAM = 4,       /* lambda <= 0 or not finite, scale not finite */
+    LLLA_ERR_ALIGN = 5,       /* base pointer or stride not 16-byte compatible */
+    LLLA_ERR_WORKSPACE = 6,   /* workspace NULL/unaligned or smaller than *_workspace_bytes() */
+    LLLA_ERR_UNSUPPORTED = 7, /* d not in {16, 32, 64, 128}, or causal == 0 with a path lacking it */
+    LLLA_ERR_LAUNCH = 8       /* the HIP runtime refused a launch */
+} llla_status;
+
+typedef enum { LLLA_F32 = 0, LLLA_BF16 = 1 } llla_dtype;
+
+/* Element strides of a [batch, head, seq, d] tensor; the d stride is 1 by contract.
+ * Each must be a multiple of 4 (f32) or 8 (bf16) elements so that rows stay 16-byte aligned. */
+typedef struct {
+    int64_t batch;
+    int64_t head;
+    int64_t seq;
+} llla_strides;
+
+/* Which kernels a forward call uses.  AUTO picks the MFMA path when it exists for (dtype, d) and
+ * the portable vector-ALU path otherwise; the other two force one (for tests and measurement). */
+typedef enum { LLLA_PATH_AUTO = 0, LLLA_PATH_VALU = 1, LLLA_PATH_MFMA = 2 } llla_path;
+
+/*
+ * llla_forward -- Section 3.2 (matrix form and Algorithm 1): O = LLA(Q, K, V; lambda, h) for all
+ * n query rows of every (batch, head).
+ *   Q, K, V : device, [B, H, n, d] in dtype `in`, strides sq / sk / sv
+ *   O       : device, [B, H, n, d] in dtype `out`, strides so
+ *   causal  : 1 = row i sees keys 0..i (the paper's tril mask); 0 = every row sees all n keys
+ *   lambda  : ridge, > 0 (Sigma_i has rank <= i without it, Appendix C)
+ *   scale   : 1/h
+ *   Returns LLLA_OK or the first failed check.
+ */
+size_t llla_forward_workspace_bytes(int B, int H, int n, int d, llla_dtype in);
+
+llla_status llla_forward(const void *Q, const void *K, const void *V, void *O,
+                         llla_strides sq, llla_strides sk, llla_strides sv, llla_strides so,
+                         int B, int H, int n, int d, llla_dtype in, llla_dtype out,
+                         int causal, float lambda, float scale,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* Same as llla_forward with the kernel family chosen by the caller. */
+llla_status llla_forward_path(const void *Q, const void *K, const void *V, void *O,
+                              llla_strides sq, llla_strides sk, llla_strides sv, llla_strides so,
+                              int B, int H, int n, int d, llla_dtype in, llla_dtype out,
+                              int causal, float lambda, float scale, llla_path path,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * llla_decode -- the inference step the paper mentions (Sections 1 and 2.3: LLA keeps a Theta(n d)
+ * KV cache): one new query per (batch, head) against the cached keys and values, the new token's
+ * own (k, v) already appended, i.e. the last row of a causal forward over seqlens[b] positions.
+ *   q       : device, [B, H, d] contiguous, dtype `in`
+ *   Kc, Vc  : device, [B, H, L_max, d] caches in dtype `in`, strides sk / sv
+ *   o       : device, [B, H, d] contiguous, dtype `out`
+ *   seqlens : device int32 [B], valid length of each sequence (1..L_max), or NULL = all L_max
+ */
+size_t llla_decode_workspace_bytes(int B, int H, int L_max, int d, llla_dtype in);
+
+llla_status llla_decode(const void *q, const void *Kc, const void *Vc, void *o,
+                        llla_strides sk, llla_strides sv, const int32_t *seqlens,
+                        int B, int H, int L_max, int d, llla_dtype in, llla_dtype out,
+                        float lambda, float scale,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/* Same as llla_decode with the kernel family chosen by the caller. */
+llla_status llla_decode_path(const void *q, const void *Kc, const void *Vc, void *o,
+                             llla_strides sk, llla_strides sv, const int32_t *seqlens,
+                             int B, int H, int L_max, int d, llla_dtype in, llla_dtype out,
+                             float lambda, float scale, llla_path path,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char *llla_status_string(llla_status status);
+
+/* Library version, "major.minor.patch". */
+const char *llla_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LLLA_H */

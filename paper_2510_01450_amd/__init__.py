@@ -1,0 +1,8 @@
+"""MI355X-native Local Linear Attention (arxiv 2510.01450): thin Python binding of the C ABI.
+
+``llla_forward`` / ``llla_decode`` marshal torch device tensors into the ``extern "C"`` entry points
+of ``libllla.so`` (declared in ``include/llla.h``); every step of the method runs in the library's
+HIP kernels.  There is no CPU or PyTorch fallback: a missing library is an error.
+"""
+from .binding import (LlaError, PATHS, decode_workspace_bytes, forward_workspace_bytes, lib,  # noqa: F401
+                      lib_path, llla_decode, llla_forward, status_string, version)

@@ -1,0 +1,145 @@
+"""ctypes binding of libllla.so -- argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libllla.so")
+_lib = None
+
+PATHS = {"auto": 0, "valu": 1, "mfma": 2}
+_DTYPES = {torch.float32: 0, torch.bfloat16: 1}
+
+
+class LlaError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = int(code)
+        super().__init__("%s failed: status %d (%s)" % (where, code, status_string(code)))
+
+
+class _Strides(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int64), ("head", ctypes.c_int64), ("seq", ctypes.c_int64)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded C-ABI library.  Builds it with hipcc only if no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _build
+        _build.build()
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, sz, i32, f32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_float
+    L.llla_forward_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
+    L.llla_forward_workspace_bytes.restype = sz
+    L.llla_decode_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
+    L.llla_decode_workspace_bytes.restype = sz
+    fwd = [vp, vp, vp, vp, _Strides, _Strides, _Strides, _Strides, i32, i32, i32, i32, i32, i32, i32, f32, f32]
+    L.llla_forward.argtypes = fwd + [vp, sz, vp]
+    L.llla_forward.restype = i32
+    L.llla_forward_path.argtypes = fwd + [i32, vp, sz, vp]
+    L.llla_forward_path.restype = i32
+    dec = [vp, vp, vp, vp, _Strides, _Strides, vp, i32, i32, i32, i32, i32, i32, f32, f32]
+    L.llla_decode.argtypes = dec + [vp, sz, vp]
+    L.llla_decode.restype = i32
+    L.llla_decode_path.argtypes = dec + [i32, vp, sz, vp]
+    L.llla_decode_path.restype = i32
+    L.llla_status_string.argtypes = [i32]
+    L.llla_status_string.restype = ctypes.c_char_p
+    L.llla_version.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def status_string(code: int) -> str:
+    return lib().llla_status_string(int(code)).decode()
+
+
+def version() -> str:
+    return lib().llla_version().decode()
+
+
+def forward_workspace_bytes(B, H, n, d, dtype) -> int:
+    return int(lib().llla_forward_workspace_bytes(B, H, n, d, _DTYPES[dtype]))
+
+
+def decode_workspace_bytes(B, H, L_max, d, dtype) -> int:
+    return int(lib().llla_decode_workspace_bytes(B, H, L_max, d, _DTYPES[dtype]))
+
+
+def _strides4(t: torch.Tensor) -> _Strides:
+    if t.dim() != 4 or t.stride(3) != 1:
+        raise ValueError("expected a [B, H, n, d] tensor with unit stride along d")
+    return _Strides(t.stride(0), t.stride(1), t.stride(2))
+
+
+def _stream_ptr(stream) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def _workspace(nbytes: int, device, workspace):
+    if workspace is None:
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+    return workspace
+
+
+def llla_forward(Q, K, V, lam: float, scale: float, causal: bool = True, out_dtype=None, path: str = "auto",
+                 workspace=None, out=None, stream=None):
+    """O = LLA(Q, K, V) for [B, H, n, d] device tensors (f32 or bf16).  Returns O ([B, H, n, d])."""
+    if not (Q.is_cuda and K.is_cuda and V.is_cuda):
+        raise ValueError("llla_forward needs device tensors; this library has no CPU path")
+    if not (Q.dtype == K.dtype == V.dtype) or Q.dtype not in _DTYPES:
+        raise ValueError("Q, K, V must share dtype float32 or bfloat16")
+    B, H, n, d = Q.shape
+    if K.shape != Q.shape or V.shape != Q.shape:
+        raise ValueError("Q, K, V must have the same [B, H, n, d] shape")
+    out_dtype = torch.float32 if out_dtype is None else out_dtype
+    O = torch.empty((B, H, n, d), dtype=out_dtype, device=Q.device) if out is None else out
+    L = lib()
+    need = forward_workspace_bytes(B, H, n, d, Q.dtype)
+    ws = _workspace(need, Q.device, workspace)
+    st = L.llla_forward_path(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                             _strides4(Q), _strides4(K), _strides4(V), _strides4(O),
+                             B, H, n, d, _DTYPES[Q.dtype], _DTYPES[O.dtype], 1 if causal else 0,
+                             float(lam), float(scale), PATHS[path],
+                             ws.data_ptr(), ws.numel() * ws.element_size(), _stream_ptr(stream))
+    if st != 0:
+        raise LlaError(st, "llla_forward")
+    return O
+
+
+def llla_decode(q, Kc, Vc, lam: float, scale: float, seqlens=None, out_dtype=None, path: str = "auto",
+                workspace=None, out=None, stream=None):
+    """One query per (batch, head) against [B, H, L_max, d] caches.  q: [B, H, d].  Returns [B, H, d]."""
+    if not (q.is_cuda and Kc.is_cuda and Vc.is_cuda):
+        raise ValueError("llla_decode needs device tensors; this library has no CPU path")
+    if not (q.dtype == Kc.dtype == Vc.dtype) or q.dtype not in _DTYPES:
+        raise ValueError("q, Kc, Vc must share dtype float32 or bfloat16")
+    B, H, Lmax, d = Kc.shape
+    if tuple(q.shape) != (B, H, d) or Vc.shape != Kc.shape or not q.is_contiguous():
+        raise ValueError("q must be contiguous [B, H, d]; caches [B, H, L_max, d]")
+    if seqlens is not None and (seqlens.dtype != torch.int32 or not seqlens.is_cuda or seqlens.numel() != B):
+        raise ValueError("seqlens must be a device int32 tensor of B entries")
+    out_dtype = torch.float32 if out_dtype is None else out_dtype
+    o = torch.empty((B, H, d), dtype=out_dtype, device=q.device) if out is None else out
+    L = lib()
+    need = decode_workspace_bytes(B, H, Lmax, d, q.dtype)
+    ws = _workspace(need, q.device, workspace)
+    st = L.llla_decode_path(q.data_ptr(), Kc.data_ptr(), Vc.data_ptr(), o.data_ptr(),
+                            _strides4(Kc), _strides4(Vc),
+                            0 if seqlens is None else seqlens.data_ptr(),
+                            B, H, Lmax, d, _DTYPES[q.dtype], _DTYPES[o.dtype],
+                            float(lam), float(scale), PATHS[path],
+                            ws.data_ptr(), ws.numel() * ws.element_size(), _stream_ptr(stream))
+    if st != 0:
+        raise LlaError(st, "llla_decode")
+    return o

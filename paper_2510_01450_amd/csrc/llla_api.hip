@@ -1,0 +1,177 @@
+// C ABI of the library: host-side validation and dispatch.  Every check runs before anything is
+// enqueued, so each error path can be exercised without a GPU.
+#include <cmath>
+
+#include "llla_common.hpp"
+
+namespace {
+
+using llla::Problem;
+
+constexpr int kMaxGridY = 65535;
+
+bool dim_supported(int d) { return d == 16 || d == 32 || d == 64 || d == 128; }
+bool dtype_ok(llla_dtype t) { return t == LLLA_F32 || t == LLLA_BF16; }
+size_t elem_size(llla_dtype t) { return t == LLLA_F32 ? 4 : 2; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool strides_aligned(const llla_strides &s, llla_dtype t)
+{
+    const int64_t q = 16 / (int64_t)elem_size(t);
+    return s.batch % q == 0 && s.head % q == 0 && s.seq % q == 0;
+}
+
+// the d stride is 1, so a row needs seq >= d; batch/head strides may alias only in degenerate shapes
+bool strides_cover(const llla_strides &s, int B, int H, int n, int d)
+{
+    if (s.seq < d && n > 1) return false;
+    if (s.head < 0 || s.batch < 0 || s.seq < 0) return false;
+    if (H > 1 && s.head == 0) return false;
+    if (B > 1 && s.batch == 0) return false;
+    return true;
+}
+
+llla_status check_common(int B, int H, int n, int d, llla_dtype in, llla_dtype out, float lambda, float scale)
+{
+    if (B <= 0 || H <= 0 || n <= 0 || d <= 0) return LLLA_ERR_SHAPE;
+    if (!dtype_ok(in) || !dtype_ok(out)) return LLLA_ERR_DTYPE;
+    if (!dim_supported(d)) return LLLA_ERR_UNSUPPORTED;
+    if ((int64_t)B * H > kMaxGridY) return LLLA_ERR_SHAPE;
+    if (!(lambda > 0.f) || !std::isfinite(lambda) || !std::isfinite(scale)) return LLLA_ERR_PARAM;
+    return LLLA_OK;
+}
+
+llla_status check_workspace(size_t need, void *ws, size_t ws_bytes)
+{
+    if (need == 0) return LLLA_OK;
+    if (ws == nullptr || ws_bytes < need) return LLLA_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return LLLA_ERR_WORKSPACE;
+    return LLLA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t llla_forward_workspace_bytes(int B, int H, int n, int d, llla_dtype in)
+{
+    if (B <= 0 || H <= 0 || n <= 0 || !dim_supported(d) || !dtype_ok(in)) return 0;
+    return llla::mfma_forward_workspace_bytes(B, H, n, d, in);
+}
+
+llla_status llla_forward_path(const void *Q, const void *K, const void *V, void *O, llla_strides sq,
+                              llla_strides sk, llla_strides sv, llla_strides so, int B, int H, int n, int d,
+                              llla_dtype in, llla_dtype out, int causal, float lambda, float scale,
+                              llla_path path, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!Q || !K || !V || !O) return LLLA_ERR_NULL;
+    llla_status st = check_common(B, H, n, d, in, out, lambda, scale);
+    if (st != LLLA_OK) return st;
+    if (path != LLLA_PATH_AUTO && path != LLLA_PATH_VALU && path != LLLA_PATH_MFMA) return LLLA_ERR_PARAM;
+    if (!strides_cover(sq, B, H, n, d) || !strides_cover(sk, B, H, n, d) || !strides_cover(sv, B, H, n, d) ||
+        !strides_cover(so, B, H, n, d))
+        return LLLA_ERR_SHAPE;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !strides_aligned(sq, in) ||
+        !strides_aligned(sk, in) || !strides_aligned(sv, in) || !strides_aligned(so, out))
+        return LLLA_ERR_ALIGN;
+
+    const bool has_mfma = llla::mfma_forward_supported(d, in, causal != 0);
+    if (path == LLLA_PATH_MFMA && !has_mfma) return LLLA_ERR_UNSUPPORTED;
+    const bool use_mfma = has_mfma && path != LLLA_PATH_VALU;
+    if (use_mfma) {
+        st = check_workspace(llla::mfma_forward_workspace_bytes(B, H, n, d, in), workspace, workspace_bytes);
+        if (st != LLLA_OK) return st;
+    }
+
+    Problem p{};
+    p.Q = Q; p.K = K; p.V = V; p.O = O;
+    p.sq = sq; p.sk = sk; p.sv = sv; p.so = so;
+    p.seqlens = nullptr;
+    p.B = B; p.H = H; p.n = n; p.d = d;
+    p.in = in; p.out = out;
+    p.causal = causal ? 1 : 0;
+    p.lambda = lambda; p.scale = scale;
+    p.ws = workspace; p.ws_bytes = workspace_bytes;
+    p.stream = static_cast<hipStream_t>(stream);
+    const hipError_t e = use_mfma ? llla::mfma_forward(p) : llla::valu_forward(p);
+    return e == hipSuccess ? LLLA_OK : LLLA_ERR_LAUNCH;
+}
+
+llla_status llla_forward(const void *Q, const void *K, const void *V, void *O, llla_strides sq, llla_strides sk,
+                         llla_strides sv, llla_strides so, int B, int H, int n, int d, llla_dtype in,
+                         llla_dtype out, int causal, float lambda, float scale, void *workspace,
+                         size_t workspace_bytes, void *stream)
+{
+    return llla_forward_path(Q, K, V, O, sq, sk, sv, so, B, H, n, d, in, out, causal, lambda, scale,
+                             LLLA_PATH_AUTO, workspace, workspace_bytes, stream);
+}
+
+size_t llla_decode_workspace_bytes(int B, int H, int L_max, int d, llla_dtype in)
+{
+    if (B <= 0 || H <= 0 || L_max <= 0 || !dim_supported(d) || !dtype_ok(in)) return 0;
+    return llla::mfma_decode_workspace_bytes(B, H, L_max, d, in);
+}
+
+llla_status llla_decode_path(const void *q, const void *Kc, const void *Vc, void *o, llla_strides sk,
+                             llla_strides sv, const int32_t *seqlens, int B, int H, int L_max, int d,
+                             llla_dtype in, llla_dtype out, float lambda, float scale, llla_path path,
+                             void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!q || !Kc || !Vc || !o) return LLLA_ERR_NULL;
+    llla_status st = check_common(B, H, L_max, d, in, out, lambda, scale);
+    if (st != LLLA_OK) return st;
+    if (path != LLLA_PATH_AUTO && path != LLLA_PATH_VALU && path != LLLA_PATH_MFMA) return LLLA_ERR_PARAM;
+    if (!strides_cover(sk, B, H, L_max, d) || !strides_cover(sv, B, H, L_max, d)) return LLLA_ERR_SHAPE;
+    if (!aligned16(q) || !aligned16(Kc) || !aligned16(Vc) || !aligned16(o) || !strides_aligned(sk, in) ||
+        !strides_aligned(sv, in) || (seqlens && (reinterpret_cast<uintptr_t>(seqlens) & 3u)))
+        return LLLA_ERR_ALIGN;
+
+    const bool has_mfma = llla::mfma_decode_supported(d, in);
+    if (path == LLLA_PATH_MFMA && !has_mfma) return LLLA_ERR_UNSUPPORTED;
+    const bool use_mfma = has_mfma && path != LLLA_PATH_VALU;
+    if (use_mfma) {
+        st = check_workspace(llla::mfma_decode_workspace_bytes(B, H, L_max, d, in), workspace, workspace_bytes);
+        if (st != LLLA_OK) return st;
+    }
+
+    Problem p{};
+    p.Q = q; p.K = Kc; p.V = Vc; p.O = o;
+    p.sk = sk; p.sv = sv;
+    p.seqlens = seqlens;
+    p.B = B; p.H = H; p.n = L_max; p.d = d;
+    p.in = in; p.out = out;
+    p.causal = 1;
+    p.lambda = lambda; p.scale = scale;
+    p.ws = workspace; p.ws_bytes = workspace_bytes;
+    p.stream = static_cast<hipStream_t>(stream);
+    const hipError_t e = use_mfma ? llla::mfma_decode(p) : llla::valu_decode(p);
+    return e == hipSuccess ? LLLA_OK : LLLA_ERR_LAUNCH;
+}
+
+llla_status llla_decode(const void *q, const void *Kc, const void *Vc, void *o, llla_strides sk, llla_strides sv,
+                        const int32_t *seqlens, int B, int H, int L_max, int d, llla_dtype in, llla_dtype out,
+                        float lambda, float scale, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return llla_decode_path(q, Kc, Vc, o, sk, sv, seqlens, B, H, L_max, d, in, out, lambda, scale,
+                            LLLA_PATH_AUTO, workspace, workspace_bytes, stream);
+}
+
+const char *llla_status_string(llla_status s)
+{
+    switch (s) {
+        case LLLA_OK: return "ok";
+        case LLLA_ERR_NULL: return "a required pointer is NULL";
+        case LLLA_ERR_SHAPE: return "bad shape or stride";
+        case LLLA_ERR_DTYPE: return "unknown dtype";
+        case LLLA_ERR_PARAM: return "lambda must be finite and > 0, scale finite, path valid";
+        case LLLA_ERR_ALIGN: return "pointers and strides must keep rows 16-byte aligned";
+        case LLLA_ERR_WORKSPACE: return "workspace missing, unaligned or too small";
+        case LLLA_ERR_UNSUPPORTED: return "unsupported head dimension or path";
+        case LLLA_ERR_LAUNCH: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+const char *llla_version(void) { return "0.1.0"; }
+
+}  // extern "C"

@@ -1,0 +1,62 @@
+// Shared declarations of the gfx950 Local Linear Attention library (host + device).
+// Nothing here is used by, or shared with, the CPU oracle.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "llla.h"
+
+namespace llla {
+
+// One forward or decode problem, as validated by the C ABI layer.
+struct Problem {
+    const void *Q, *K, *V;     // forward: [B,H,n,d]; decode: Q = q [B,H,d], K/V = caches [B,H,n,d]
+    void *O;                   // forward: [B,H,n,d]; decode: [B,H,d]
+    llla_strides sq, sk, sv, so;
+    const int32_t *seqlens;    // decode only (device, [B]) or nullptr
+    int B, H, n, d;            // n = sequence length (forward) or L_max (decode)
+    llla_dtype in, out;
+    int causal;
+    float lambda, scale;
+    void *ws;
+    size_t ws_bytes;
+    hipStream_t stream;
+};
+
+// Launchers return hipSuccess or the launch error.  Each lives in its own translation unit.
+hipError_t valu_forward(const Problem &p);
+hipError_t valu_decode(const Problem &p);
+
+// MFMA (matrix-core) paths; *_supported() says whether one exists for the shape and dtype.
+bool mfma_forward_supported(int d, llla_dtype in, bool causal);
+size_t mfma_forward_workspace_bytes(int B, int H, int n, int d, llla_dtype in);
+hipError_t mfma_forward(const Problem &p);
+bool mfma_decode_supported(int d, llla_dtype in);
+size_t mfma_decode_workspace_bytes(int B, int H, int L_max, int d, llla_dtype in);
+hipError_t mfma_decode(const Problem &p);
+
+// ---- storage types -----------------------------------------------------------------------------
+// bf16 is handled as raw uint16_t bits; conversions are written out so that rounding is explicit.
+typedef uint16_t bf16_t;
+
+__host__ __device__ inline float bf16_to_f32(bf16_t x)
+{
+    union { uint32_t u; float f; } c;
+    c.u = (uint32_t)x << 16;
+    return c.f;
+}
+
+// round-to-nearest-even; NaN stays NaN (quiet)
+__host__ __device__ inline bf16_t f32_to_bf16(float f)
+{
+    union { uint32_t u; float f; } c;
+    c.f = f;
+    if ((c.u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((c.u >> 16) | 0x40);
+    c.u += 0x7fffu + ((c.u >> 16) & 1u);
+    return (bf16_t)(c.u >> 16);
+}
+
+__host__ __device__ inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace llla

@@ -1,0 +1,415 @@
+// Portable vector-ALU path of Local Linear Attention for gfx950: every d in {16,32,64,128},
+// fp32 or bf16 inputs (bf16 is widened exactly), all arithmetic in fp32.
+//
+// One 256-thread workgroup serves QB "slots".  In the forward kernel a slot is one query row and
+// all slots sweep the same key tiles; in the decode kernel all slots serve the single query of a
+// (batch, head) and split the cache between them, their partial moments being merged with a
+// max-rescale before the solve.  Per slot the kernel follows the three sweeps of Algorithm 1
+// (Section 3.2) with two changes of substance:
+//   (1) the per-query statistics are the un-centred moments of Eq. (tilded_form) extended by the
+//       intercept column, i.e. the (d+1)x(d+1) matrix At = sum_j w_j [1;k_j][1;k_j]^T
+//       + lambda diag(0, I); it lives in registers (one TSxTS tile per thread) and in LDS, never
+//       in device memory;
+//   (2) the system is solved exactly by elimination in LDS (y = At^{-1} [1; q]) instead of by
+//       conjugate gradients; the output weights of Eq. (lla) are then s_ij = w_ij (y0 + k_j . y1)
+//       (y1 = -rho/delta, y0 = (1 + q . rho)/delta in the paper's symbols), so the third sweep is
+//       the relmm-style product K y1 followed by S V.
+// The running row maximum and the rescaling of the moments across key tiles are those of
+// Algorithm 1 (lines computing m, alpha and the updates of omega and M).
+#include "llla_common.hpp"
+
+namespace llla {
+namespace {
+
+constexpr int NT = 256;   // threads per workgroup
+constexpr int KT = 32;    // keys per slot per tile
+
+template <int D>
+struct Cfg {
+    static constexpr int TS = (D >= 64) ? 8 : 4;        // register tile edge
+    static constexpr int TG = D / TS;                    // tiles per matrix edge
+    static constexpr int TPQ = TG * TG;                  // threads per slot
+    static constexpr int QB = NT / TPQ;                  // slots per workgroup
+    static constexpr int LDK = D + 4;                    // LDS row pitch of K/V tiles (16 B aligned)
+    static constexpr int P = D + 1;                      // unknowns of the augmented system
+    static constexpr int LDS_SYS = (D + 2) | 1;          // odd pitch of [At | rhs]
+};
+
+template <typename T>
+struct Io;
+template <>
+struct Io<float> {
+    static constexpr int VEC = 4;
+    __device__ static void load(const float *g, float *dst)
+    {
+        const float4 v = *reinterpret_cast<const float4 *>(g);
+        dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+    }
+    __device__ static void store1(float *g, float v) { *g = v; }
+};
+template <>
+struct Io<bf16_t> {
+    static constexpr int VEC = 8;
+    __device__ static void load(const bf16_t *g, float *dst)
+    {
+        const uint4 v = *reinterpret_cast<const uint4 *>(g);
+        const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            dst[2 * i] = __uint_as_float(u[i] << 16);
+            dst[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
+        }
+    }
+    __device__ static void store1(bf16_t *g, float v) { *g = f32_to_bf16(v); }
+};
+
+// rows [row0, row0+rows_tile) of a [*, D] global matrix -> LDS tile (pitch LDK), zero beyond nvalid
+template <int D, typename T>
+__device__ inline void load_tile(float *lds, const T *g, int64_t row_stride, int row0, int rows_tile,
+                                 int nvalid, int tid)
+{
+    constexpr int VEC = Io<T>::VEC;
+    constexpr int CH = D / VEC;                          // chunks per row
+    constexpr int LDK = Cfg<D>::LDK;
+    for (int idx = tid; idx < rows_tile * CH; idx += NT) {
+        const int r = idx / CH, c = (idx % CH) * VEC;
+        float v[VEC];
+        if (row0 + r < nvalid) {
+            Io<T>::load(g + (int64_t)(row0 + r) * row_stride + c, v);
+        } else {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) v[i] = 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < VEC; i += 4)
+            *reinterpret_cast<float4 *>(lds + r * LDK + c + i) = make_float4(v[i], v[i + 1], v[i + 2], v[i + 3]);
+    }
+}
+
+template <int D>
+__device__ inline float dot_lds(const float *a, const float *b)
+{
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+    for (int c = 0; c < D; c += 4) {
+        const float4 x = *reinterpret_cast<const float4 *>(a + c);
+        const float4 y = *reinterpret_cast<const float4 *>(b + c);
+        s0 = fmaf(x.x, y.x, s0); s1 = fmaf(x.y, y.y, s1);
+        s2 = fmaf(x.z, y.z, s2); s3 = fmaf(x.w, y.w, s3);
+    }
+    return (s0 + s1) + (s2 + s3);
+}
+
+// Kernel.  DECODE = false: grid.x = ceil(n/QB) query blocks (heaviest first), grid.y = B*H.
+//          DECODE = true : grid.x = 1, grid.y = B*H; all slots share the query and split the keys.
+template <int D, typename TI, typename TO, bool DECODE>
+__global__ __launch_bounds__(NT) void valu_kernel(const TI *__restrict__ Qg, const TI *__restrict__ Kg,
+                                                  const TI *__restrict__ Vg, TO *__restrict__ Og,
+                                                  llla_strides sq, llla_strides sk, llla_strides sv,
+                                                  llla_strides so, const int32_t *__restrict__ seqlens,
+                                                  int H, int n, int causal, float lambda, float scale)
+{
+    using C = Cfg<D>;
+    constexpr int TS = C::TS, TG = C::TG, TPQ = C::TPQ, QB = C::QB, LDK = C::LDK, P = C::P,
+                  LS = C::LDS_SYS;
+    constexpr int KROWS = DECODE ? QB * KT : KT;         // key rows staged per tile
+    constexpr int NSYS = DECODE ? 1 : QB;
+    constexpr int TILE_F = 2 * KROWS * LDK + 2 * QB * KT;   // ks, vs, logits, weights
+    constexpr int SYS_F = NSYS * P * LS;
+    constexpr int UNION_F = (TILE_F > SYS_F) ? TILE_F : SYS_F;
+
+    __shared__ __align__(16) float smem[UNION_F + QB * D + QB * (P + 3) + 4 * QB];
+    float *ks = smem;                                     // [KROWS][LDK]
+    float *vs = ks + KROWS * LDK;                         // [KROWS][LDK]
+    float *sl = vs + KROWS * LDK;                         // [QB][KT] logits, later coefficients
+    float *wl = sl + QB * KT;                             // [QB][KT] weights
+    float *sys = smem;                                    // [NSYS][P][LS], aliases the tiles
+    float *qs = smem + UNION_F;                           // [QB][D]
+    float *ys = qs + QB * D;                              // [QB][P+3]  solution y = At^{-1}[1;q]
+    float *ms = ys + QB * (P + 3);                        // [QB] running max
+    float *al = ms + QB;                                  // [QB] rescale factor of this tile
+    float *fs = al + QB;                                  // [QB] decode merge factors
+    float *red = fs + QB;                                 // [QB] spare
+
+    const int tid = threadIdx.x;
+    const int slot = tid / TPQ;
+    const int r = tid % TPQ;
+    const int ta = r / TG, tb = r % TG;
+    const int bh = blockIdx.y;
+    const int b = bh / H, h = bh % H;
+
+    const TI *Kh = Kg + b * sk.batch + h * sk.head;
+    const TI *Vh = Vg + b * sv.batch + h * sv.head;
+
+    int nkeys;          // keys that exist for this head
+    int i0 = 0;         // first query row of the block (forward)
+    if (DECODE) {
+        nkeys = seqlens ? seqlens[b] : n;
+        nkeys = nkeys < 1 ? 1 : (nkeys > n ? n : nkeys);
+    } else {
+        nkeys = n;
+        const int nqb = gridDim.x;
+        i0 = (nqb - 1 - (int)blockIdx.x) * QB;          // long rows are scheduled first
+    }
+    const int my_i = DECODE ? nkeys - 1 : i0 + slot;    // query row of this slot
+    const bool slot_live = DECODE ? true : (my_i < n);
+    // last key (exclusive) any slot of the block can see
+    const int kend = DECODE ? nkeys : (causal ? min(n, i0 + QB) : n);
+    const int my_last = (DECODE || !causal) ? nkeys - 1 : min(my_i, n - 1);   // last visible key
+
+    // ---- query rows -> LDS ----------------------------------------------------------------------
+    for (int idx = tid; idx < QB * D; idx += NT) {
+        const int s = idx / D, c = idx % D;
+        float v = 0.f;
+        if (DECODE) {
+            const TI *qp = Qg + (int64_t)bh * D;
+            v = sizeof(TI) == 2 ? bf16_to_f32(((const bf16_t *)qp)[c]) : ((const float *)qp)[c];
+        } else if (i0 + s < n) {
+            const TI *qp = Qg + b * sq.batch + h * sq.head + (int64_t)(i0 + s) * sq.seq;
+            v = sizeof(TI) == 2 ? bf16_to_f32(((const bf16_t *)qp)[c]) : ((const float *)qp)[c];
+        }
+        qs[idx] = v;
+    }
+    if (tid < QB) ms[tid] = -INFINITY;
+
+    // ---- sweep 1: un-centred moments with running max (Algorithm 1, first loop) -----------------
+    float acc[TS][TS];
+    float mu[TS];
+    float omega = 0.f;
+#pragma unroll
+    for (int x = 0; x < TS; ++x) {
+        mu[x] = 0.f;
+#pragma unroll
+        for (int y = 0; y < TS; ++y) acc[x][y] = 0.f;
+    }
+    const int koff = DECODE ? slot * KT : 0;             // this slot's rows inside the staged tile
+
+    for (int kt0 = 0; kt0 < kend; kt0 += KROWS) {
+        __syncthreads();                                 // previous tile fully consumed
+        load_tile<D, TI>(ks, Kh, sk.seq, kt0, KROWS, nkeys, tid);
+        __syncthreads();
+        for (int idx = tid; idx < QB * KT; idx += NT) {  // logits of (slot, key)
+            const int s = idx / KT, kj = idx % KT;
+            const int row = (DECODE ? s * KT : 0) + kj;
+            const int j = kt0 + row;
+            const int last = (DECODE || !causal) ? nkeys - 1 : min(i0 + s, n - 1);
+            float v = -INFINITY;
+            if (j <= last) v = scale * dot_lds<D>(qs + s * D, ks + row * LDK);
+            sl[idx] = v;
+        }
+        __syncthreads();
+        if (tid < QB) {                                  // running max and rescale factor per slot
+            float mx = ms[tid];
+            const float mold = mx;
+            for (int kj = 0; kj < KT; ++kj) mx = fmaxf(mx, sl[tid * KT + kj]);
+            ms[tid] = mx;
+            al[tid] = (mold == -INFINITY) ? 0.f : __expf(mold - mx);
+        }
+        __syncthreads();
+        for (int idx = tid; idx < QB * KT; idx += NT) {  // weights, 0 for masked keys
+            const float mx = ms[idx / KT];
+            const float s = sl[idx];
+            wl[idx] = (s == -INFINITY) ? 0.f : __expf(s - mx);
+        }
+        __syncthreads();
+        {
+            const float alpha = al[slot];
+            if (alpha != 1.f) {
+                omega *= alpha;
+#pragma unroll
+                for (int x = 0; x < TS; ++x) {
+                    mu[x] *= alpha;
+#pragma unroll
+                    for (int y = 0; y < TS; ++y) acc[x][y] *= alpha;
+                }
+            }
+            const int jn = min(KT, my_last - (kt0 + koff) + 1);   // visible keys of this slot here
+            for (int kj = 0; kj < jn; ++kj) {
+                const float w = wl[slot * KT + kj];
+                const float *krow = ks + (koff + kj) * LDK;
+                float a[TS], bb[TS];
+#pragma unroll
+                for (int x = 0; x < TS; x += 4) {
+                    const float4 va = *reinterpret_cast<const float4 *>(krow + ta * TS + x);
+                    const float4 vb = *reinterpret_cast<const float4 *>(krow + tb * TS + x);
+                    a[x] = va.x * w; a[x + 1] = va.y * w; a[x + 2] = va.z * w; a[x + 3] = va.w * w;
+                    bb[x] = vb.x; bb[x + 1] = vb.y; bb[x + 2] = vb.z; bb[x + 3] = vb.w;
+                }
+                omega += w;
+#pragma unroll
+                for (int x = 0; x < TS; ++x) {
+                    mu[x] += a[x];
+#pragma unroll
+                    for (int y = 0; y < TS; ++y) acc[x][y] = fmaf(a[x], bb[y], acc[x][y]);
+                }
+            }
+        }
+    }
+    __syncthreads();                                     // tiles are dead; sys may overwrite them
+
+    // ---- the (d+1)x(d+1) system [At | rhs] in LDS -----------------------------------------------
+    if (DECODE) {
+        // merge the slots' partial moments: common max, then an ordered (deterministic) sum
+        if (tid < QB) {
+            float mx = -INFINITY;
+            for (int s = 0; s < QB; ++s) mx = fmaxf(mx, ms[s]);
+            fs[tid] = (ms[tid] == -INFINITY) ? 0.f : __expf(ms[tid] - mx);
+            red[tid] = mx;
+        }
+        for (int idx = tid; idx < P * LS; idx += NT) sys[idx] = 0.f;
+        __syncthreads();
+        for (int s = 0; s < QB; ++s) {
+            if (slot == s) {
+                const float f = fs[s];
+#pragma unroll
+                for (int x = 0; x < TS; ++x)
+#pragma unroll
+                    for (int y = 0; y < TS; ++y)
+                        sys[(1 + ta * TS + x) * LS + 1 + tb * TS + y] += f * acc[x][y];
+                if (tb == 0) {
+#pragma unroll
+                    for (int x = 0; x < TS; ++x) sys[(1 + ta * TS + x) * LS] += f * mu[x];
+                }
+                if (r == 0) sys[0] += f * omega;
+            }
+            __syncthreads();
+        }
+        if (tid < QB) ms[tid] = red[tid];                // every slot now works relative to the max
+        for (int c = tid; c < D; c += NT) {
+            sys[c + 1] = sys[(c + 1) * LS];              // row 0 mirrors column 0
+            sys[(c + 1) * LS + c + 1] += lambda;
+            sys[(c + 1) * LS + P] = qs[c];
+        }
+        if (tid == 0) sys[P] = 1.f;
+    } else {
+        float *S = sys + slot * P * LS;
+#pragma unroll
+        for (int x = 0; x < TS; ++x)
+#pragma unroll
+            for (int y = 0; y < TS; ++y) {
+                const int rr = ta * TS + x, cc = tb * TS + y;
+                S[(1 + rr) * LS + 1 + cc] = acc[x][y] + (rr == cc ? lambda : 0.f);
+            }
+        if (tb == 0) {
+#pragma unroll
+            for (int x = 0; x < TS; ++x) {
+                S[(1 + ta * TS + x) * LS] = mu[x];
+                S[1 + ta * TS + x] = mu[x];
+            }
+        }
+        if (r == 0) {
+            // a dead slot (row >= n) gets a harmless identity-like pivot
+            S[0] = slot_live ? omega : 1.f;
+            S[P] = 1.f;
+        }
+        for (int c = r; c < D; c += TPQ) S[(c + 1) * LS + P] = qs[slot * D + c];
+    }
+
+    // ---- exact solve by elimination (the matrix is symmetric positive definite) -----------------
+    {
+        float *S = DECODE ? sys : sys + slot * P * LS;
+        const int gt = DECODE ? tid : r;
+        constexpr int GS = DECODE ? NT : TPQ;
+        for (int k = 0; k < P; ++k) {
+            __syncthreads();
+            const float pinv = 1.f / S[k * LS + k];
+            for (int row = k + 1 + gt; row < P; row += GS) {
+                const float f = S[row * LS + k] * pinv;
+                for (int c = k + 1; c <= P; ++c) S[row * LS + c] = fmaf(-f, S[k * LS + c], S[row * LS + c]);
+            }
+        }
+        float *yv = ys + (DECODE ? 0 : slot * (P + 3));
+        for (int k = P - 1; k >= 0; --k) {
+            __syncthreads();
+            const float yk = S[k * LS + P] / S[k * LS + k];
+            if (gt == 0) yv[k] = yk;
+            for (int row = gt; row < k; row += GS) S[row * LS + P] = fmaf(-S[row * LS + k], yk, S[row * LS + P]);
+        }
+    }
+    __syncthreads();
+
+    // ---- sweep 3: output weights s_ij = w_ij (y0 + k_j . y1) and O = S V ------------------------
+    const float *yv = ys + (DECODE ? 0 : slot * (P + 3));
+    float o = 0.f;
+    for (int kt0 = 0; kt0 < kend; kt0 += KROWS) {
+        __syncthreads();
+        load_tile<D, TI>(ks, Kh, sk.seq, kt0, KROWS, nkeys, tid);
+        load_tile<D, TI>(vs, Vh, sv.seq, kt0, KROWS, nkeys, tid);
+        __syncthreads();
+        for (int idx = tid; idx < QB * KT; idx += NT) {
+            const int s = idx / KT, kj = idx % KT;
+            const int row = (DECODE ? s * KT : 0) + kj;
+            const int j = kt0 + row;
+            const int last = (DECODE || !causal) ? nkeys - 1 : min(i0 + s, n - 1);
+            float cval = 0.f;
+            if (j <= last) {
+                const float *ysl = ys + (DECODE ? 0 : s * (P + 3));
+                const float lg = scale * dot_lds<D>(qs + s * D, ks + row * LDK);
+                // y1 starts at ysl[1]; copy-free unaligned dot
+                float u = 0.f;
+                for (int c = 0; c < D; ++c) u = fmaf(ysl[1 + c], ks[row * LDK + c], u);
+                cval = __expf(lg - ms[s]) * (ysl[0] + u);
+            }
+            sl[idx] = cval;
+        }
+        __syncthreads();
+        if (r < D) {
+            const int jn = min(KT, my_last - (kt0 + koff) + 1);
+            for (int kj = 0; kj < jn; ++kj) o = fmaf(sl[slot * KT + kj], vs[(koff + kj) * LDK + r], o);
+        }
+    }
+    (void)yv;
+
+    if (DECODE) {
+        __syncthreads();
+        float *osum = sys;                               // [D], tiles are dead again
+        for (int c = tid; c < D; c += NT) osum[c] = 0.f;
+        __syncthreads();
+        for (int s = 0; s < QB; ++s) {
+            if (slot == s && r < D) osum[r] += o;
+            __syncthreads();
+        }
+        for (int c = tid; c < D; c += NT) Io<TO>::store1(Og + (int64_t)bh * D + c, osum[c]);
+    } else if (slot_live && r < D) {
+        TO *op = Og + b * so.batch + h * so.head + (int64_t)my_i * so.seq;
+        Io<TO>::store1(op + r, o);
+    }
+}
+
+template <int D, typename TI, typename TO, bool DECODE>
+hipError_t launch(const Problem &p)
+{
+    using C = Cfg<D>;
+    dim3 grid(DECODE ? 1 : (p.n + C::QB - 1) / C::QB, p.B * p.H);
+    hipLaunchKernelGGL((valu_kernel<D, TI, TO, DECODE>), grid, dim3(NT), 0, p.stream,
+                       (const TI *)p.Q, (const TI *)p.K, (const TI *)p.V, (TO *)p.O, p.sq, p.sk, p.sv,
+                       p.so, p.seqlens, p.H, p.n, p.causal, p.lambda, p.scale);
+    return hipGetLastError();
+}
+
+template <int D, bool DECODE>
+hipError_t by_dtype(const Problem &p)
+{
+    if (p.in == LLLA_F32)
+        return p.out == LLLA_F32 ? launch<D, float, float, DECODE>(p) : launch<D, float, bf16_t, DECODE>(p);
+    return p.out == LLLA_F32 ? launch<D, bf16_t, float, DECODE>(p) : launch<D, bf16_t, bf16_t, DECODE>(p);
+}
+
+template <bool DECODE>
+hipError_t by_dim(const Problem &p)
+{
+    switch (p.d) {
+        case 16: return by_dtype<16, DECODE>(p);
+        case 32: return by_dtype<32, DECODE>(p);
+        case 64: return by_dtype<64, DECODE>(p);
+        case 128: return by_dtype<128, DECODE>(p);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+hipError_t valu_forward(const Problem &p) { return by_dim<false>(p); }
+hipError_t valu_decode(const Problem &p) { return by_dim<true>(p); }
+
+}  // namespace llla

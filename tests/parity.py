@@ -1,9 +1,12 @@
 """Error metrics of the parity gate (shared by the GPU tests and the benchmark's self-check).
 
-Gate: per (batch, head) Frobenius-relative error <= tol, and per-row relative error
-||o_i - o*_i||_2 / ||o*_i||_2 <= tol for rows i >= 4d, <= 10*tol for rows i < 4d (the normal
-matrix of the earliest rows has rank <= i before the ridge, so their conditioning is worse by
-orders of magnitude).  tol = 1e-4 for fp32 inputs, 2e-2 for bf16 inputs.
+Gate, with tol = 1e-4 for fp32 inputs and 2e-2 for bf16 inputs:
+  * per row, ||o_i - o*_i||_2 / ||o*_i||_2 <= tol for rows i >= 4d and <= 10*tol for rows i < 4d
+    (the normal matrix of the earliest rows has rank <= i before the ridge, so their conditioning
+    is worse by orders of magnitude);
+  * per (batch, head), the Frobenius-relative error over the checked rows i >= 4d is <= tol, over
+    the checked rows i < 4d it is <= 10*tol, and over all checked rows it is <= tol whenever at
+    least half of them are late rows (every named configuration is; tiny ragged cases are not).
 """
 import numpy as np
 
@@ -38,9 +41,21 @@ def check(got, ref, rows, d, tol, what=""):
         "worst_ratio_to_bound": float((err / bound).max()),
     }
     B, H = err.shape[:2]
-    fro = max(frobenius_error(got[b][h], ref[b][h]) for b in range(B) for h in range(H))
-    summary["frobenius_max"] = float(fro)
-    assert fro <= tol, "%s: Frobenius error %.3e > %.1e (%s)" % (what, fro, tol, summary)
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    late = ~early
+    fro_all = max(frobenius_error(got[b, h], ref[b, h]) for b in range(B) for h in range(H))
+    summary["frobenius_max"] = float(fro_all)
+    if late.any():
+        fro = max(frobenius_error(got[b, h][late], ref[b, h][late]) for b in range(B) for h in range(H))
+        summary["frobenius_late"] = float(fro)
+        assert fro <= tol, "%s: Frobenius error (rows >= 4d) %.3e > %.1e (%s)" % (what, fro, tol, summary)
+    if early.any():
+        fro = max(frobenius_error(got[b, h][early], ref[b, h][early]) for b in range(B) for h in range(H))
+        summary["frobenius_early"] = float(fro)
+        assert fro <= 10 * tol, "%s: Frobenius error (rows < 4d) %.3e > %.1e (%s)" % (what, fro, 10 * tol, summary)
+    if late.sum() >= early.sum():
+        assert fro_all <= tol, "%s: Frobenius error %.3e > %.1e (%s)" % (what, fro_all, tol, summary)
     assert np.all(err <= bound), "%s: row %d error %.3e exceeds %.1e (%s)" % (
         what, summary["worst_row"], err[worst], bound[worst[-1]], summary)
     return summary

@@ -1,0 +1,84 @@
+"""Host-side checks of the C ABI (no GPU needed): the library loads, exports every symbol that
+include/llla.h declares, and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2510_01450_amd as llla
+from paper_2510_01450_amd.binding import _Strides
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000          # never dereferenced: every call below fails validation first
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "llla.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(llla_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared_symbols()
+    assert {"llla_forward", "llla_decode", "llla_forward_workspace_bytes", "llla_decode_workspace_bytes",
+            "llla_status_string", "llla_version"} <= set(names)
+    L = ctypes.CDLL(llla.lib_path())
+    for name in names:
+        assert hasattr(L, name), name
+
+
+def _fwd(Q=FAKE, K=FAKE, V=FAKE, O=FAKE, sq=None, B=1, H=1, n=64, d=64, din=0, dout=0, causal=1, lam=1e-2,
+         scale=0.125, path=0, ws=0, wsb=0):
+    s = _Strides(H * n * d, n * d, d) if sq is None else sq
+    return llla.lib().llla_forward_path(Q, K, V, O, s, s, s, s, B, H, n, d, din, dout, causal, lam, scale, path,
+                                        ws, wsb, 0)
+
+
+def _dec(q=FAKE, K=FAKE, V=FAKE, o=FAKE, B=1, H=1, L=64, d=64, din=0, dout=0, lam=1e-2, scale=0.125, path=0,
+         sk=None):
+    s = _Strides(H * L * d, L * d, d) if sk is None else sk
+    return llla.lib().llla_decode_path(q, K, V, o, s, s, 0, B, H, L, d, din, dout, lam, scale, path, 0, 0, 0)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(Q=0), 1), (dict(O=0), 1),
+    (dict(n=0), 2), (dict(B=-1), 2), (dict(sq=_Strides(64 * 64, 64 * 64, 32)), 2), (dict(B=70000), 2),
+    (dict(din=7), 3), (dict(dout=-1), 3),
+    (dict(lam=0.0), 4), (dict(lam=-1.0), 4), (dict(lam=float("nan")), 4), (dict(lam=float("inf")), 4),
+    (dict(scale=float("inf")), 4), (dict(path=9), 4),
+    (dict(Q=FAKE + 4), 5), (dict(sq=_Strides(64 * 64, 64 * 64, 66)), 5),
+    (dict(d=48), 7), (dict(d=256), 7),
+])
+def test_forward_rejects_bad_arguments(kw, code):
+    assert _fwd(**kw) == code
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(q=0), 1), (dict(L=0), 2), (dict(din=5), 3), (dict(lam=0.0), 4), (dict(K=FAKE + 2), 5), (dict(d=20), 7),
+    (dict(sk=_Strides(64 * 64, 64 * 64, 8)), 2),
+])
+def test_decode_rejects_bad_arguments(kw, code):
+    assert _dec(**kw) == code
+
+
+def test_status_strings_and_version():
+    seen = {llla.status_string(c) for c in range(9)}
+    assert len(seen) == 9 and "ok" in seen
+    assert re.match(r"^\d+\.\d+\.\d+$", llla.version())
+
+
+def test_workspace_queries_are_pure():
+    import torch
+    assert llla.forward_workspace_bytes(0, 1, 1, 64, torch.float32) == 0
+    a = llla.forward_workspace_bytes(4, 16, 4096, 64, torch.bfloat16)
+    assert a == llla.forward_workspace_bytes(4, 16, 4096, 64, torch.bfloat16)
+    # Theta(B*H*n*d): far below one d x d matrix per query
+    assert a < 4 * 16 * 4096 * 64 * 64
+
+
+def test_product_has_no_cpu_fallback():
+    import torch
+    x = torch.zeros(1, 1, 8, 16)
+    with pytest.raises(ValueError):
+        llla.llla_forward(x, x, x, 1e-2, 0.25)
