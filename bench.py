@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the LLA hot path on one MI355X.
+
+One "step" = one pass of the whole hot path (llla_forward, or llla_decode for the decode workload)
+over one batch of seeded synthetic input that is already resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3|C3b|C4|C2|C1|C5] [--path auto|valu|mfma]
+
+metric  : tokens/s of the causal forward (B*n / t)  -- or generated tokens/s for decode (B / t)
+roofline: the dominant kernel's algorithmic flops (forward; d^2+11d per causal pair plus
+          d^3/3+4d^2 per row) or bytes (decode; K and V read once) over its measured duration
+cpu_baseline: the fp64 oracle as it stands, timed on the host cores on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_16BIT = 2.5e15      # dense bf16/f16 MFMA, flop/s
+PEAK_FP32_VALU = 157.3e12     # fp32 vector, flop/s
+PEAK_HBM = 8.0e12             # B/s
+
+
+def forward_flops(B, H, n, d):
+    """Algorithmic flops of a causal forward: symmetric half of the second moment and the solve."""
+    pairs = n * (n + 1) // 2
+    return B * H * (pairs * (d * d + 11 * d) + n * (d ** 3 / 3.0 + 4 * d * d))
+
+
+def executed_mfma_flops(B, H, n, d):
+    """What a full-square d x d second moment plus the small products issues per causal pair."""
+    pairs = n * (n + 1) // 2
+    return B * H * pairs * (2 * d * d + 12 * d)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="C3")
+    ap.add_argument("--path", default="auto", choices=["auto", "valu", "mfma"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures ONE GPU (one MI355X per box); --gpus %d is not run. "
+              "How the path would shard over several GPUs is described in DESIGN.md." % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2510_01450_amd as llla
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (no CPU fallback exists)", file=sys.stderr)
+        sys.exit(3)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = workloads.ALL[args.workload.upper() if args.workload.upper() in workloads.ALL else args.workload]
+    decode = w.kind == "decode"
+    steps = args.steps if args.steps is not None else (20 if not decode else 30)
+    warmup = args.warmup if args.warmup is not None else 3
+
+    t0 = time.time()
+    cpu_in = workloads.make_inputs(w)
+    n_rot = 3 if decode else 1          # decode: rotate distinct caches, each >> the 256 MB infinity cache
+    dev_in = [tuple(t.to(dev) for t in cpu_in)]
+    for r in range(1, n_rot):
+        g = torch.Generator(device=dev).manual_seed(workloads.SEED0 + 77 + r)
+        dev_in.append((dev_in[0][0],) + tuple(
+            torch.randn(t.shape, generator=g, device=dev, dtype=torch.float32).to(t.dtype) for t in cpu_in[1:]))
+    gen_s = time.time() - t0
+    dt = workloads.torch_dtype(w)
+    if decode:
+        need = llla.decode_workspace_bytes(w.B, w.H, w.n, w.d, dt)
+        out = torch.empty((w.B, w.H, w.d), dtype=torch.float32, device=dev)
+    else:
+        need = llla.forward_workspace_bytes(w.B, w.H, w.n, w.d, dt)
+        out = torch.empty((w.B, w.H, w.n, w.d), dtype=torch.float32, device=dev)
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+
+    def step(i):
+        a, b, c = dev_in[i % n_rot]
+        if decode:
+            llla.llla_decode(a, b, c, w.lam, w.scale, path=args.path, workspace=ws, out=out)
+        else:
+            llla.llla_forward(a, b, c, w.lam, w.scale, path=args.path, workspace=ws, out=out)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    t_start = time.perf_counter()
+    for i in range(steps):
+        evs[i][0].record()
+        step(i)
+        evs[i][1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+    per = np.array([a.elapsed_time(b) for a, b in evs])          # ms, device time of each step
+    ms = wall * 1e3 / steps
+
+    # stage timings from the library (HIP events on the same stream), when it offers them
+    stages = llla.last_stage_ms() if hasattr(llla, "last_stage_ms") else None
+
+    if decode:
+        tokens = w.B
+        algo_bytes = 2.0 * w.B * w.H * w.n * w.d * cpu_in[1].element_size()
+        dom_ms = float(np.mean(per))
+        roof = {"bound": "hbm", "achieved": algo_bytes / (dom_ms * 1e-3) / 1e9, "peak": PEAK_HBM / 1e9,
+                "unit": "GB/s", "traffic": None, "kernel": "llla_decode (whole call)",
+                "algorithmic_bytes_per_launch": algo_bytes, "kernel_ms": dom_ms}
+    else:
+        tokens = w.B * w.n
+        flops = forward_flops(w.B, w.H, w.n, w.d)
+        dom_ms = float(np.mean(per))
+        kernel = "llla_forward (whole call)"
+        peak = PEAK_MFMA_16BIT
+        if w.dtype == "f32":
+            peak = PEAK_FP32_VALU
+        roof = {"bound": "mfma", "achieved": flops / (dom_ms * 1e-3) / 1e12, "peak": peak / 1e12,
+                "unit": "TFLOP/s", "traffic": None, "kernel": kernel,
+                "algorithmic_flops_per_launch": flops, "kernel_ms": dom_ms,
+                "executed_mfma_class_flops": executed_mfma_flops(w.B, w.H, w.n, w.d)}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+
+    result = {
+        "metric": "LLA causal forward tokens/s" if not decode else "LLA decode generated tokens/s",
+        "value": tokens / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": ms, "ms_per_step_device_median": float(np.median(per)),
+        "ms_per_step_device_min": float(per.min()), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32" if w.dtype == "f32" else "bf16 in, f16/f32 MFMA, f32 accumulate",
+        "data": "synthetic (seeded, %s)" % w.values,
+        "config": {"workload": w.name, "B": w.B, "H": w.H, "n": w.n, "d": w.d, "lambda": w.lam,
+                   "scale": w.scale, "path": args.path, "input_setup_s": round(gen_s, 2)},
+        "roofline": roof,
+    }
+    if stages:
+        result["stages_ms"] = stages
+    if not decode:
+        result["tflops_algorithmic"] = roof["achieved"]
+
+    # ---- self-check of the timed configuration on a few rows + CPU baseline (same oracle call) ----
+    if not args.no_cpu_baseline or not args.no_check:
+        import oracle
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        from parity import check
+        torch.cuda.synchronize()
+        if decode:
+            step(0)
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+            nh = w.B * w.H if w.B * w.H <= 512 else 512
+            q, Kc, Vc = cpu_in
+            t1 = time.perf_counter()
+            qf, Kf, Vf = (t.reshape((1, w.B * w.H) + tuple(t.shape[2:]))[:, :nh] for t in (q, Kc, Vc))
+            ref = oracle.decode(qf, Kf, Vf, w.lam, w.scale)
+            cpu_s = time.perf_counter() - t1
+            summ = check(got.reshape(1, w.B * w.H, 1, w.d)[:, :nh], ref[:, :, None], np.array([w.n - 1]), w.d, w.tol,
+                         "bench decode")
+            full = cpu_s * (w.B * w.H) / nh
+            result["cpu_baseline"] = {"value": w.B / full, "unit": "tokens/s", "cores": oracle.threads(),
+                                      "kind": "oracle", "sample": "%d of %d (batch, head) pairs, %.1f s; scaled by count"
+                                      % (nh, w.B * w.H, cpu_s)}
+        else:
+            step(0)
+            torch.cuda.synchronize()
+            Q, K, V = cpu_in
+            rows = workloads.sample_rows(w, n_random=64) if w.n > 1024 else list(range(w.n))
+            got = out[0, 0].cpu().numpy()[rows]
+            t1 = time.perf_counter()
+            nrep = 0
+            while True:                         # bounded sample: a few heads' worth of sampled rows
+                ref = oracle.forward_head(Q[0, nrep % w.H], K[0, nrep % w.H], V[0, nrep % w.H], w.lam, w.scale,
+                                          rows=rows)
+                if nrep == 0:
+                    ref0 = ref
+                nrep += 1
+                if time.perf_counter() - t1 > 10.0:
+                    break
+            cpu_s = time.perf_counter() - t1
+            summ = check(got[None, None], ref0[None, None], np.array(rows), w.d, w.tol, "bench forward")
+            work_all = w.B * w.H * (w.n * (w.n + 1) / 2.0)
+            work_s = nrep * float(np.sum(np.asarray(rows) + 1.0))
+            full = cpu_s * work_all / work_s
+            result["cpu_baseline"] = {"value": w.B * w.n / full, "unit": "tokens/s", "cores": oracle.threads(),
+                                      "kind": "oracle",
+                                      "sample": "%d sampled rows x %d heads in %.1f s; scaled by causal pairs (x%.0f)"
+                                      % (len(rows), nrep, cpu_s, work_all / work_s)}
+        result["parity_check"] = summ
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
