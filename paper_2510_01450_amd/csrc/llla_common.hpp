@@ -26,6 +26,8 @@ struct Problem {
 
 // Launchers return hipSuccess or the launch error.  Each lives in its own translation unit.
 hipError_t valu_forward(const Problem &p);
+// causal forward restricted to query rows [0, nrows); nrows must be a multiple of 16
+hipError_t valu_forward_rows(const Problem &p, int nrows);
 hipError_t valu_decode(const Problem &p);
 
 // MFMA (matrix-core) paths; *_supported() says whether one exists for the shape and dtype.

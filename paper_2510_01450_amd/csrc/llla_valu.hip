@@ -376,11 +376,12 @@ __global__ __launch_bounds__(NT) void valu_kernel(const TI *__restrict__ Qg, con
     }
 }
 
+// nrows: the forward kernel serves query rows [0, nrows) only (nrows = n for a full forward)
 template <int D, typename TI, typename TO, bool DECODE>
-hipError_t launch(const Problem &p)
+hipError_t launch(const Problem &p, int nrows)
 {
     using C = Cfg<D>;
-    dim3 grid(DECODE ? 1 : (p.n + C::QB - 1) / C::QB, p.B * p.H);
+    dim3 grid(DECODE ? 1 : (nrows + C::QB - 1) / C::QB, p.B * p.H);
     hipLaunchKernelGGL((valu_kernel<D, TI, TO, DECODE>), grid, dim3(NT), 0, p.stream,
                        (const TI *)p.Q, (const TI *)p.K, (const TI *)p.V, (TO *)p.O, p.sq, p.sk, p.sv,
                        p.so, p.seqlens, p.H, p.n, p.causal, p.lambda, p.scale);
@@ -388,28 +389,29 @@ hipError_t launch(const Problem &p)
 }
 
 template <int D, bool DECODE>
-hipError_t by_dtype(const Problem &p)
+hipError_t by_dtype(const Problem &p, int nrows)
 {
     if (p.in == LLLA_F32)
-        return p.out == LLLA_F32 ? launch<D, float, float, DECODE>(p) : launch<D, float, bf16_t, DECODE>(p);
-    return p.out == LLLA_F32 ? launch<D, bf16_t, float, DECODE>(p) : launch<D, bf16_t, bf16_t, DECODE>(p);
+        return p.out == LLLA_F32 ? launch<D, float, float, DECODE>(p, nrows) : launch<D, float, bf16_t, DECODE>(p, nrows);
+    return p.out == LLLA_F32 ? launch<D, bf16_t, float, DECODE>(p, nrows) : launch<D, bf16_t, bf16_t, DECODE>(p, nrows);
 }
 
 template <bool DECODE>
-hipError_t by_dim(const Problem &p)
+hipError_t by_dim(const Problem &p, int nrows)
 {
     switch (p.d) {
-        case 16: return by_dtype<16, DECODE>(p);
-        case 32: return by_dtype<32, DECODE>(p);
-        case 64: return by_dtype<64, DECODE>(p);
-        case 128: return by_dtype<128, DECODE>(p);
+        case 16: return by_dtype<16, DECODE>(p, nrows);
+        case 32: return by_dtype<32, DECODE>(p, nrows);
+        case 64: return by_dtype<64, DECODE>(p, nrows);
+        case 128: return by_dtype<128, DECODE>(p, nrows);
         default: return hipErrorInvalidValue;
     }
 }
 
 }  // namespace
 
-hipError_t valu_forward(const Problem &p) { return by_dim<false>(p); }
-hipError_t valu_decode(const Problem &p) { return by_dim<true>(p); }
+hipError_t valu_forward(const Problem &p) { return by_dim<false>(p, p.n); }
+hipError_t valu_forward_rows(const Problem &p, int nrows) { return by_dim<false>(p, nrows < p.n ? nrows : p.n); }
+hipError_t valu_decode(const Problem &p) { return by_dim<true>(p, 1); }
 
 }  // namespace llla
