@@ -41,7 +41,7 @@ struct Layout {
 Layout make_layout(int B, int H, int n)
 {
     Layout L;
-    L.nkb = (n + KB - 1) / KB;
+    L.nkb = 2 * ((n + 2 * KB - 1) / (2 * KB));      // 32-key blocks, an even count
     L.npad = L.nkb * KB;
     const size_t bh = (size_t)B * H;
     size_t off = 0;
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(NT) void sweep_kernel(const bf16_t *__restrict__ Qg
 {
     __shared__ __align__(16) bf16_t kn[KB * KN_PITCH];
     __shared__ __align__(16) bf16_t vt[MAXONLY ? 8 : D * VT_PITCH];
-    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, g = lane / 16, nn = lane % 16;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64, g = lane / 16, nn = lane % 16;
     const int bh = blockIdx.y, b = bh / H, h = bh % H;
     const int nqb = gridDim.x;
     const int i0 = first_row + (nqb - 1 - (int)blockIdx.x) * 64;      // long rows first
@@ -278,8 +278,8 @@ __global__ __launch_bounds__(NT) void sweep_kernel(const bf16_t *__restrict__ Qg
 
 // ------------------------------------------------------------------------------------------------
 // moments + solve
-constexpr int KT_PITCH = KB + 8;     // halves per feature row of the transposed K tile in LDS
-constexpr int WT_PITCH = KB + 8;     // halves per query row of the weight tile
+constexpr int KB2 = 2 * KB;          // keys per pipeline step of the moments kernel
+constexpr int WT_PITCH = KB2 + 8;    // halves per query row of the weight tile
 constexpr int SC_PITCH = 20;         // floats per row of a 16x16 scratch tile
 
 // Upper Cholesky factor and its inverse for the diagonal tiles of the wave's four queries at once:
@@ -339,115 +339,270 @@ __device__ inline void chol_inv16(float (&a)[16], float (&li)[16], int r)
     for (int c = 0; c < 16; ++c) li[c] *= dinv_own;          // L^{-1} = D^{-1} L''^{-1}
 }
 
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+typedef const __attribute__((address_space(1))) void *glb_void_ptr;
+
+// 16 bytes per lane straight from global memory into LDS (no registers): lane l's data lands at
+// lds_base + 16 l, the global address is per lane.  Written as inline assembly on purpose: the
+// compiler makes every later LDS read wait for a DMA it knows about (it cannot tell the two
+// buffers apart), which would serialise the prefetch; here the waits are placed by hand with
+// dma_wait() before the data is read.  The s_nop is the wait state gfx9 needs between a scalar
+// write of M0 and an LDS-DMA instruction that reads it.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ inline void dma16(const void *gsrc, void *lds_base)
+{
+#ifdef LLLA_DBG_BUILTIN_DMA
+    __builtin_amdgcn_global_load_lds((glb_void_ptr)gsrc, (lds_void_ptr)lds_base, 16, 0, 0);
+    return;
+#endif
+    const unsigned lds = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void_ptr)lds_base);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(lds) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+__device__ inline void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// LDS tiles of one 64-key block are stored without padding (the DMA writes whole 1 KB wave rows);
+// 16-byte chunks are XOR-swizzled so that the MFMA operand reads stay free of bank conflicts:
+//   transposed tile (f16) : [sub-tile of 32 keys][feature row r][4 chunks of 8 keys], chunk c of row r at c ^ ((r>>2)&3)
+//   natural tile (bf16)   : [key][8 chunks of 8 features],                             chunk c of key k at c ^ ((k>>1)&7)
+constexpr int KT_SUB = D * KB;       // halves per transposed 32-key sub-tile (4 KB)
+constexpr int KN_TILE = KB2 * D;     // halves per natural 64-key tile (8 KB)
+constexpr int WT32_PITCH = KB2 + 4;  // floats per query row of the fp32 weight tile (PRECISE)
+
+// PRECISE: fp32 weights and a two-term f16 split of the scaled operand w k, i.e. an fp32-accurate
+// second moment; used for the first rows of a sequence, whose systems are the worst conditioned.
+template <bool PRECISE>
 __global__ __launch_bounds__(NT, 2) void moments_kernel(const bf16_t *__restrict__ Qg, const bf16_t *__restrict__ Kg,
                                                         llla_strides sq, llla_strides sk, int H, int n, int nkb,
                                                         int first_row, float cscale, float lambda,
                                                         const _Float16 *__restrict__ KT, const float *__restrict__ Mg,
                                                         float *__restrict__ Yg)
 {
-    __shared__ __align__(16) _Float16 kt[2][D * KT_PITCH];
-    __shared__ __align__(16) _Float16 wt[2][QB * WT_PITCH];
+    __shared__ __align__(16) _Float16 kt[2][2][KT_SUB];
+    __shared__ __align__(16) bf16_t kn[2][KN_TILE];
+    __shared__ __align__(16) _Float16 wt[2][PRECISE ? 8 : QB * WT_PITCH];
+    __shared__ __align__(16) float wt32[2][PRECISE ? QB * WT32_PITCH : 4];
+    __shared__ float omp[4][QB];
     __shared__ __align__(16) float mus[QB][D + 4];
     __shared__ float oms[QB];
     __shared__ __align__(16) float sc[4][QW][16 * SC_PITCH];
 
-    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, g = lane / 16, nn = lane % 16;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64, g = lane / 16, nn = lane % 16;
     const int bh = blockIdx.y, b = bh / H, h = bh % H;
     const int nqb = gridDim.x;
     const int i0 = first_row + (nqb - 1 - (int)blockIdx.x) * QB;       // long rows first
     const int ilast = min(i0 + QB - 1, n - 1);
-    const int nblk = ilast / KB + 1;
+    const int nblk = ilast / KB2 + 1;                                  // blocks of 64 keys
+    const int mpitch = nkb * KB;
     const bf16_t *Kh = Kg + b * sk.batch + h * sk.head;
     const bf16_t *Qh = Qg + b * sq.batch + h * sq.head;
     const _Float16 *KTh = KT + (size_t)bh * nkb * (D * KB);
 
-    // S^T role (waves 0 and 1): lane (g, nn) serves query i0 + nn and keys 16*wave + 4g + r of a block
+    // S^T role: lane (g, nn) of wave w serves query i0 + nn and keys 16w + 4g + r of a 64-key block
     const int iq = i0 + nn, iqc = min(iq, n - 1);
     bf16x8 qf[2];
-    float mrow = 0.f;
-    if (wave < 2) {
+    {
         const bf16_t *qrow = Qh + (int64_t)iqc * sq.seq;
         qf[0] = *reinterpret_cast<const bf16x8 *>(qrow + 8 * g);
         qf[1] = *reinterpret_cast<const bf16x8 *>(qrow + 32 + 8 * g);
-        mrow = Mg[(size_t)bh * (nkb * KB) + iqc];
     }
+    const float mrow = Mg[(size_t)bh * mpitch + iqc];
 
     f32x4 acc[QW][10];
 #pragma unroll
     for (int q = 0; q < QW; ++q)
 #pragma unroll
         for (int t = 0; t < 10; ++t) acc[q][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    f32x4 mu_acc = {0.f, 0.f, 0.f, 0.f}, om_acc = {0.f, 0.f, 0.f, 0.f};
-    half8 ones;
+    f32x4 mu_acc = {0.f, 0.f, 0.f, 0.f};
+    float om_part = 0.f;            // this lane's share of omega for query i0 + nn
+#ifdef LLLA_DBG_LDSWQ
+    float dbg_mismatch = 0.f;
+#endif
+
+    // ---- per-lane constants of the staging and of the operand reads ------------------------------
+    // DMA, transposed tile: this wave fills slots [64 wave, 64 wave + 64) of each 32-key sub-tile
+    const int kts = 64 * wave + lane;                       // slot = row*4 + stored chunk
+    const int kts_row = kts >> 2, kts_col = (kts & 3) ^ ((kts_row >> 2) & 3);
+    const int kt_goff = kts_row * KB + kts_col * 8;         // halves inside a [feature][32 key] sub-tile
+    // DMA, natural tile: this wave fills its own 16 keys (slots [128 wave, 128 wave + 128))
+    int kn_key[2], kn_gcol[2];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) ones[t] = (_Float16)1.0f;
-
-    // prefetch block 0
-    const int kt_feat = tid / 4, kt_k0 = (tid % 4) * 8;
-    uint4 ktr = *reinterpret_cast<const uint4 *>(KTh + kt_feat * KB + kt_k0);
-    bf16x8 knr[2];
-    {
-        const int j = 16 * wave + nn;       // only meaningful for waves 0, 1
-        const int jc = min(j, n - 1);
-        if (wave < 2) {
-            knr[0] = *reinterpret_cast<const bf16x8 *>(Kh + (int64_t)jc * sk.seq + 8 * g);
-            knr[1] = *reinterpret_cast<const bf16x8 *>(Kh + (int64_t)jc * sk.seq + 32 + 8 * g);
-        }
+    for (int t = 0; t < 2; ++t) {
+        const int sl = 128 * wave + 64 * t + lane;          // slot = key*8 + stored chunk
+        kn_key[t] = sl >> 3;
+        kn_gcol[t] = ((sl & 7) ^ ((kn_key[t] >> 1) & 7)) * 8;
     }
+    // S^T operand reads of the natural tile: key 16 wave + nn, feature chunks g and 4 + g
+    const int skey = 16 * wave + nn;
+    const int kn_r0 = (skey * 8 + (g ^ ((skey >> 1) & 7))) * 8;
+    const int kn_r1 = (skey * 8 + ((4 + g) ^ ((skey >> 1) & 7))) * 8;
+    // second-moment operand reads of a transposed sub-tile: feature row 16 I + nn, key chunk g
+    const int kt_r = (nn * 4 + (g ^ ((nn >> 2) & 3))) * 8;  // + I * 16 * 32 halves
 
-    for (int c = 0; c < nblk; ++c) {
-        const int buf = c & 1;
-        *reinterpret_cast<uint4 *>(&kt[buf][kt_feat * KT_PITCH + kt_k0]) = ktr;
-        if (wave < 2) {
-            f32x4 z = {0.f, 0.f, 0.f, 0.f};
-            z = mfma_bf16(knr[0], qf[0], z);
-            z = mfma_bf16(knr[1], qf[1], z);
+    auto issue_dma = [&](int blk) {     // block blk -> LDS buffer blk & 1
+        const int buf = blk & 1;
+        const _Float16 *src = KTh + (size_t)blk * (2 * KT_SUB) + kt_goff;
+        dma16(src, &kt[buf][0][512 * wave]);
+        dma16(src + KT_SUB, &kt[buf][1][512 * wave]);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int j = min(blk * KB2 + kn_key[t], n - 1);
+            dma16(Kh + (int64_t)j * sk.seq + kn_gcol[t], &kn[buf][1024 * wave + 512 * t]);
+        }
+    };
+    auto make_weights = [&](int blk) {  // w = 2^(c<q,k> - m) for this wave's 16 keys of block blk
+        const int buf = blk & 1;
+        const bf16x8 k0 = *reinterpret_cast<const bf16x8 *>(&kn[buf][kn_r0]);
+        const bf16x8 k1 = *reinterpret_cast<const bf16x8 *>(&kn[buf][kn_r1]);
+        f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        z = mfma_bf16(k0, qf[0], z);
+        z = mfma_bf16(k1, qf[1], z);
+        float wf[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int j = blk * KB2 + 16 * wave + 4 * g + r;
+            const float wgt = __builtin_amdgcn_exp2f(z[r] * cscale - mrow);
+            wf[r] = (j <= iq) ? wgt : 0.f;
+        }
+        if (PRECISE) {
+            *reinterpret_cast<f32x4 *>(&wt32[buf][nn * WT32_PITCH + 16 * wave + 4 * g]) = f32x4{wf[0], wf[1], wf[2], wf[3]};
+            om_part += (wf[0] + wf[1]) + (wf[2] + wf[3]);
+        } else {
             half4 wv;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int j = c * KB + 16 * wave + 4 * g + r;
-                const float wgt = __builtin_amdgcn_exp2f(z[r] * cscale - mrow);
-                wv[r] = (_Float16)((j <= iq) ? wgt : 0.f);
+                wv[r] = (_Float16)wf[r];
+                om_part += (float)wv[r];        // omega sums the weights exactly as the MFMAs see them
             }
             *reinterpret_cast<half4 *>(&wt[buf][nn * WT_PITCH + 16 * wave + 4 * g]) = wv;
         }
-        if (c + 1 < nblk) {                 // prefetch the next block while this one is consumed
-            ktr = *reinterpret_cast<const uint4 *>(KTh + (size_t)(c + 1) * (D * KB) + kt_feat * KB + kt_k0);
-            if (wave < 2) {
-                const int jc = min((c + 1) * KB + 16 * wave + nn, n - 1);
-                knr[0] = *reinterpret_cast<const bf16x8 *>(Kh + (int64_t)jc * sk.seq + 8 * g);
-                knr[1] = *reinterpret_cast<const bf16x8 *>(Kh + (int64_t)jc * sk.seq + 32 + 8 * g);
-            }
-        }
-        __syncthreads();
+    };
 
-        half8 bf[4];
+    // Software pipeline over blocks of 64 keys: iteration c consumes block c while the DMA of block
+    // c+1 lands; the weights of block c+1 are produced in the middle of the iteration (each wave
+    // reads only the keys it fetched itself, so its own vmcnt wait suffices).  One barrier per block.
+    issue_dma(0);
+    dma_wait();
+    __syncthreads();
+    make_weights(0);
+    __syncthreads();
+
+#ifdef LLLA_TIMING_NO_GRAM
+    for (int c = 0; c < 1; ++c) {
+#else
+    for (int c = 0; c < nblk; ++c) {
+#endif
+        const int buf = c & 1;
+#ifndef LLLA_TIMING_NO_GLOAD
+        if (c + 1 < nblk) issue_dma(c + 1);
+#endif
 #pragma unroll
-        for (int I = 0; I < 4; ++I) bf[I] = *reinterpret_cast<const half8 *>(&kt[buf][(16 * I + nn) * KT_PITCH + 8 * g]);
+        for (int hf = 0; hf < 2; ++hf) {        // two halves of 32 keys
+            half8 bf[4];
 #pragma unroll
-        for (int q = 0; q < QW; ++q) {
-            const half8 wq = *reinterpret_cast<const half8 *>(&wt[buf][(QW * wave + q) * WT_PITCH + 8 * g]);
+            for (int I = 0; I < 4; ++I) bf[I] = *reinterpret_cast<const half8 *>(&kt[buf][hf][kt_r + I * 512]);
+            if (!PRECISE) {
+                // One LDS read brings the weights of all 16 queries (lane (g, nn): query (nn + 4 wave) % 16,
+                // keys 8g..8g+7), rotated so that this wave's own queries sit in lanes 0..3 of every row; the
+                // per-query operand scale is then a row broadcast (DPP) instead of four more LDS reads.
+                const half8 wa = *reinterpret_cast<const half8 *>(&wt[buf][((nn + QW * wave) & 15) * WT_PITCH + 32 * hf + 8 * g]);
+                const f32x4 wau = __builtin_bit_cast(f32x4, wa);
 #pragma unroll
-            for (int I = 0; I < 4; ++I) {
-                const half8 af = bf[I] * wq;
+                for (int q = 0; q < QW; ++q) {
+                    f32x4 wqu;
 #pragma unroll
-                for (int J = I; J < 4; ++J) acc[q][tix(I, J)] = mfma_f16(af, bf[J], acc[q][tix(I, J)]);
+                    for (int t = 0; t < 4; ++t) wqu[t] = (q == 0) ? row_bcast<0>(wau[t]) : (q == 1) ? row_bcast<1>(wau[t])
+                                                        : (q == 2) ? row_bcast<2>(wau[t]) : row_bcast<3>(wau[t]);
+#ifdef LLLA_DBG_LDSWQ
+                    const half8 wq = *reinterpret_cast<const half8 *>(&wt[buf][(QW * wave + q) * WT_PITCH + 32 * hf + 8 * g]);
+                    {
+                        const f32x4 ref = __builtin_bit_cast(f32x4, wq);
+                        for (int t = 0; t < 4; ++t)
+                            if (__builtin_bit_cast(int, ref[t]) != __builtin_bit_cast(int, wqu[t])) dbg_mismatch += 1.f;
+                    }
+#else
+                    const half8 wq = __builtin_bit_cast(half8, wqu);
+#endif
+#pragma unroll
+                    for (int I = 0; I < 4; ++I) {
+                        const half8 af = bf[I] * wq;
+#pragma unroll
+                        for (int J = I; J < 4; ++J) acc[q][tix(I, J)] = mfma_f16(af, bf[J], acc[q][tix(I, J)]);
+                    }
+                }
+                // mu~[query (4g + r + 4 wave) % 16][feature 16 wave + nn].  `wave` is a scalar (readfirstlane),
+                // so these are real branches: MFMA ignores the EXEC mask and must never sit in a block that is
+                // merely predicated off.
+                if (wave == 0) mu_acc = mfma_f16(wa, bf[0], mu_acc);
+                else if (wave == 1) mu_acc = mfma_f16(wa, bf[1], mu_acc);
+                else if (wave == 2) mu_acc = mfma_f16(wa, bf[2], mu_acc);
+                else mu_acc = mfma_f16(wa, bf[3], mu_acc);
+            } else {
+#pragma unroll
+                for (int q = 0; q < QW; ++q) {
+                    float wq[8];
+                    {
+                        const float *wp = &wt32[buf][(QW * wave + q) * WT32_PITCH + 32 * hf + 8 * g];
+                        const f32x4 w0 = *reinterpret_cast<const f32x4 *>(wp), w1 = *reinterpret_cast<const f32x4 *>(wp + 4);
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) { wq[t] = w0[t]; wq[4 + t] = w1[t]; }
+                    }
+#pragma unroll
+                    for (int I = 0; I < 4; ++I) {
+                        half8 ahi, alo;
+#pragma unroll
+                        for (int t = 0; t < 8; ++t) {
+                            const float pr = (float)bf[I][t] * wq[t];
+                            ahi[t] = (_Float16)pr;
+                            alo[t] = (_Float16)(pr - (float)ahi[t]);
+                        }
+#pragma unroll
+                        for (int J = I; J < 4; ++J) {
+                            acc[q][tix(I, J)] = mfma_f16(alo, bf[J], acc[q][tix(I, J)]);
+                            acc[q][tix(I, J)] = mfma_f16(ahi, bf[J], acc[q][tix(I, J)]);
+                        }
+                    }
+                }
+                // this wave's feature block for mu~ is re-read from LDS (indexing bf[] by the wave id
+                // would become a per-element select chain)
+                const half8 bw = *reinterpret_cast<const half8 *>(&kt[buf][hf][kt_r + wave * 512]);
+                half8 whi, wlo;
+                {
+                    const float *wp = &wt32[buf][nn * WT32_PITCH + 32 * hf + 8 * g];
+                    const f32x4 w0 = *reinterpret_cast<const f32x4 *>(wp), w1 = *reinterpret_cast<const f32x4 *>(wp + 4);
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        const float wv = t < 4 ? w0[t] : w1[t - 4];
+                        whi[t] = (_Float16)wv;
+                        wlo[t] = (_Float16)(wv - (float)whi[t]);
+                    }
+                }
+                mu_acc = mfma_f16(wlo, bw, mu_acc);
+                mu_acc = mfma_f16(whi, bw, mu_acc);
+            }
+            if (hf == 0 && c + 1 < nblk) {
+#ifndef LLLA_TIMING_NO_STAGE
+                dma_wait();                     // this wave's DMA of block c+1 has landed
+                make_weights(c + 1);
+#endif
             }
         }
-        {
-            const half8 wa = *reinterpret_cast<const half8 *>(&wt[buf][nn * WT_PITCH + 8 * g]);
-            mu_acc = mfma_f16(wa, bf[wave], mu_acc);          // mu~[query 4g+r][feature 16 wave + nn]
-            if (wave == 0) om_acc = mfma_f16(wa, ones, om_acc);
-        }
+#ifndef LLLA_TIMING_NO_BARRIER
+        __syncthreads();
+#endif
     }
+
+    // omega: lanes (g, nn) of all four waves hold partial sums for query i0 + nn
+    om_part += __shfl_xor(om_part, 16);
+    om_part += __shfl_xor(om_part, 32);
+    if (g == 0) omp[wave][nn] = om_part;
 
     // ---- hand mu~ and omega to the waves that own the queries ---------------------------------------
 #pragma unroll
-    for (int r = 0; r < 4; ++r) mus[4 * g + r][16 * wave + nn] = mu_acc[r];
-    if (wave == 0 && nn == 0) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) oms[4 * g + r] = om_acc[r];
-    }
+    for (int r = 0; r < 4; ++r) mus[PRECISE ? 4 * g + r : ((4 * g + r + QW * wave) & 15)][16 * wave + nn] = mu_acc[r];
+    __syncthreads();
+    if (tid < QB) oms[tid] = (omp[0][tid] + omp[1][tid]) + (omp[2][tid] + omp[3][tid]);
     __syncthreads();
 
     // ---- per-query solve: 16-blocked upper Cholesky with the right-hand sides [mu~ q] as a fifth
@@ -471,9 +626,18 @@ __global__ __launch_bounds__(NT, 2) void moments_kernel(const bf16_t *__restrict
         }
     }
 
+#ifdef LLLA_DBG_LDSWQ
+    float dbg_g00[QW], dbg_g37[QW];
+    for (int q = 0; q < QW; ++q) { dbg_g00[q] = acc[q][tix(0, 0)][0]; dbg_g37[q] = acc[q][tix(1, 3)][2]; }
+#endif
     float *scw = &sc[wave][0][0];
+#ifdef LLLA_TIMING_NO_SOLVE
+#pragma unroll 1
+    for (int P = 0; P < 0; ++P) {
+#else
 #pragma unroll
     for (int P = 0; P < 4; ++P) {
+#endif
         // diagonal tiles -> (query, row) lanes, symmetrised
 #pragma unroll
         for (int q = 0; q < QW; ++q)
@@ -580,6 +744,9 @@ __global__ __launch_bounds__(NT, 2) void moments_kernel(const bf16_t *__restrict
         for (int q = 0; q < QW; ++q) rhs[q][P] = tile_atb(zero, acc[q][tix(P, P)], rhs[q][P]);
     }
 
+#ifdef LLLA_DBG_LDSWQ
+    for (int o = 1; o < 64; o <<= 1) dbg_mismatch += __shfl_xor(dbg_mismatch, o);
+#endif
 #pragma unroll
     for (int q = 0; q < QW; ++q) {
         const int i = i0 + QW * wave + q;
@@ -587,7 +754,14 @@ __global__ __launch_bounds__(NT, 2) void moments_kernel(const bf16_t *__restrict
             float *yr = Yg + ((size_t)bh * n + i) * YP;
 #pragma unroll
             for (int P = 0; P < 4; ++P) *reinterpret_cast<f32x4 *>(yr + 16 * P + 4 * g) = rhs[q][P];
+#ifdef LLLA_DBG_DUMPMU
+            for (int P = 0; P < 4; ++P) for (int t = 0; t < 4; ++t) yr[16 * P + 4 * g + t] = mus[QW * wave + q][16 * P + 4 * g + t];
+#endif
             if (g == 0) yr[D] = y0v[q];
+#ifdef LLLA_DBG_LDSWQ
+            if (g == 0) yr[D + 1] = dbg_mismatch;
+            if (g == 0) { yr[D + 2] = dbg_g00[q]; yr[D + 3] = dbg_g37[q]; }
+#endif
         }
     }
 }
@@ -625,8 +799,8 @@ hipError_t mfma_forward(const Problem &p)
     hipLaunchKernelGGL((sweep_kernel<true>), dim3(nq64, bh), dim3(NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
                        first, cscale, VT, M, Y, p.O, p.so, 0);
     const int nq16 = (p.n - first + QB - 1) / QB;
-    hipLaunchKernelGGL(moments_kernel, dim3(nq16, bh), dim3(NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb, first,
-                       cscale, p.lambda, KT, M, Y);
+    hipLaunchKernelGGL((moments_kernel<false>), dim3(nq16, bh), dim3(NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
+                       first, cscale, p.lambda, KT, M, Y);
     hipLaunchKernelGGL((sweep_kernel<false>), dim3(nq64, bh), dim3(NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
                        first, cscale, VT, M, Y, p.O, p.so, p.out == LLLA_BF16 ? 1 : 0);
     return hipGetLastError();
