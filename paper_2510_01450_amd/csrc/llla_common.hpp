@@ -28,6 +28,9 @@ struct Problem {
 hipError_t valu_forward(const Problem &p);
 // causal forward restricted to query rows [0, nrows); nrows must be a multiple of 16
 hipError_t valu_forward_rows(const Problem &p, int nrows);
+// sweep 3 only, for query rows [0, nrows): y (pitch ypitch floats: y1 then y0) and the row maxima (log2
+// units) come from device memory
+hipError_t valu_forward_given(const Problem &p, int nrows, const float *M, int mpitch, const float *Y, int ypitch);
 hipError_t valu_decode(const Problem &p);
 
 // MFMA (matrix-core) paths; *_supported() says whether one exists for the shape and dtype.

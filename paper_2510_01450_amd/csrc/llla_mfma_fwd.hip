@@ -372,21 +372,34 @@ constexpr int WT32_PITCH = KB2 + 4;  // floats per query row of the fp32 weight 
 
 // PRECISE: fp32 weights and a two-term f16 split of the scaled operand w k, i.e. an fp32-accurate
 // second moment; used for the first rows of a sequence, whose systems are the worst conditioned.
+struct MomentsShared {
+    _Float16 kt[2][2][KT_SUB];                 // transposed K, two buffers x two 32-key sub-tiles
+    bf16_t kn[2][KN_TILE];                     // natural K, two buffers
+    union {
+        _Float16 h[2][QB * WT_PITCH];          // f16 weights (fast variant)
+        float f[2][QB * WT32_PITCH];           // fp32 weights (precise variant)
+    } w;
+    float omp[4][QB];
+    float mus[QB][D + 4];
+    float oms[QB];
+    float sc[4][QW][16 * SC_PITCH];            // per-wave scratch tiles of the solve
+};
+
 template <bool PRECISE>
-__global__ __launch_bounds__(NT, 2) void moments_kernel(const bf16_t *__restrict__ Qg, const bf16_t *__restrict__ Kg,
-                                                        llla_strides sq, llla_strides sk, int H, int n, int nkb,
-                                                        int first_row, float cscale, float lambda,
-                                                        const _Float16 *__restrict__ KT, const float *__restrict__ Mg,
-                                                        float *__restrict__ Yg)
+__device__ __forceinline__ void moments_body(MomentsShared &sm, const bf16_t *__restrict__ Qg,
+                                             const bf16_t *__restrict__ Kg, llla_strides sq, llla_strides sk, int H,
+                                             int n, int nkb, int first_row, float cscale, float lambda,
+                                             const _Float16 *__restrict__ KT, const float *__restrict__ Mg,
+                                             float *__restrict__ Yg)
 {
-    __shared__ __align__(16) _Float16 kt[2][2][KT_SUB];
-    __shared__ __align__(16) bf16_t kn[2][KN_TILE];
-    __shared__ __align__(16) _Float16 wt[2][PRECISE ? 8 : QB * WT_PITCH];
-    __shared__ __align__(16) float wt32[2][PRECISE ? QB * WT32_PITCH : 4];
-    __shared__ float omp[4][QB];
-    __shared__ __align__(16) float mus[QB][D + 4];
-    __shared__ float oms[QB];
-    __shared__ __align__(16) float sc[4][QW][16 * SC_PITCH];
+    auto &kt = sm.kt;
+    auto &kn = sm.kn;
+    auto &wt = sm.w.h;
+    auto &wt32 = sm.w.f;
+    auto &omp = sm.omp;
+    auto &mus = sm.mus;
+    auto &oms = sm.oms;
+    auto &sc = sm.sc;
 
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64, g = lane / 16, nn = lane % 16;
     const int bh = blockIdx.y, b = bh / H, h = bh % H;
@@ -766,6 +779,20 @@ __global__ __launch_bounds__(NT, 2) void moments_kernel(const bf16_t *__restrict
     }
 }
 
+// One launch serves every query block: blocks whose rows lie below precise_rows take the precise
+// variant.  The choice depends on blockIdx only, so it is a scalar branch (MFMA ignores EXEC).
+__global__ __launch_bounds__(NT, 2) void moments_kernel(const bf16_t *__restrict__ Qg, const bf16_t *__restrict__ Kg,
+                                                        llla_strides sq, llla_strides sk, int H, int n, int nkb,
+                                                        int precise_rows, float cscale, float lambda,
+                                                        const _Float16 *__restrict__ KT, const float *__restrict__ Mg,
+                                                        float *__restrict__ Yg)
+{
+    __shared__ __align__(16) MomentsShared sm;
+    const int i0 = ((int)gridDim.x - 1 - (int)blockIdx.x) * QB;
+    if (i0 < precise_rows) moments_body<true>(sm, Qg, Kg, sq, sk, H, n, nkb, 0, cscale, lambda, KT, Mg, Yg);
+    else moments_body<false>(sm, Qg, Kg, sq, sk, H, n, nkb, 0, cscale, lambda, KT, Mg, Yg);
+}
+
 }  // namespace
 
 bool mfma_forward_supported(int d, llla_dtype in, bool causal) { return d == D && in == LLLA_BF16 && causal; }
@@ -788,21 +815,24 @@ hipError_t mfma_forward(const Problem &p)
     const float cscale = p.scale * LOG2E;
     const int first = EARLY_ROWS < p.n ? EARLY_ROWS : p.n;
 
-    // the worst-conditioned early rows go through the fp32 vector path
-    hipError_t e = valu_forward_rows(p, first);
-    if (e != hipSuccess || first >= p.n) return e;
-
     const bf16_t *Q = static_cast<const bf16_t *>(p.Q), *K = static_cast<const bf16_t *>(p.K),
                  *V = static_cast<const bf16_t *>(p.V);
     hipLaunchKernelGGL(prep_kernel, dim3(L.nkb, bh), dim3(NT), 0, p.stream, K, V, p.sk, p.sv, p.H, p.n, L.nkb, KT, VT);
-    const int nq64 = (p.n - first + 63) / 64;
+    const int nq64 = (p.n + 63) / 64;
     hipLaunchKernelGGL((sweep_kernel<true>), dim3(nq64, bh), dim3(NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
-                       first, cscale, VT, M, Y, p.O, p.so, 0);
-    const int nq16 = (p.n - first + QB - 1) / QB;
-    hipLaunchKernelGGL((moments_kernel<false>), dim3(nq16, bh), dim3(NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
-                       first, cscale, p.lambda, KT, M, Y);
-    hipLaunchKernelGGL((sweep_kernel<false>), dim3(nq64, bh), dim3(NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
-                       first, cscale, VT, M, Y, p.O, p.so, p.out == LLLA_BF16 ? 1 : 0);
+                       0, cscale, VT, M, Y, p.O, p.so, 0);
+    const int nq16 = (p.n + QB - 1) / QB;
+    hipLaunchKernelGGL(moments_kernel, dim3(nq16, bh), dim3(NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb, first,
+                       cscale, p.lambda, KT, M, Y);
+    // output: the first rows are evaluated in fp32 on the vector ALUs (their weights y0 + k.y1 cancel
+    // to a few digits), the rest by the MFMA sweep
+    hipError_t e = valu_forward_given(p, first, M, L.npad, Y, YP);
+    if (e != hipSuccess) return e;
+    if (first < p.n) {
+        const int nq64b = (p.n - first + 63) / 64;
+        hipLaunchKernelGGL((sweep_kernel<false>), dim3(nq64b, bh), dim3(NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n,
+                           L.nkb, first, cscale, VT, M, Y, p.O, p.so, p.out == LLLA_BF16 ? 1 : 0);
+    }
     return hipGetLastError();
 }
 

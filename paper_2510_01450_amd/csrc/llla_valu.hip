@@ -102,12 +102,16 @@ __device__ inline float dot_lds(const float *a, const float *b)
 
 // Kernel.  DECODE = false: grid.x = ceil(n/QB) query blocks (heaviest first), grid.y = B*H.
 //          DECODE = true : grid.x = 1, grid.y = B*H; all slots share the query and split the keys.
-template <int D, typename TI, typename TO, bool DECODE>
+//          GIVEN  = true : (forward only) the per-row solution y and row maximum are read from
+//                          device memory (written by the MFMA moments kernel); only sweep 3 runs.
+template <int D, typename TI, typename TO, bool DECODE, bool GIVEN = false>
 __global__ __launch_bounds__(NT) void valu_kernel(const TI *__restrict__ Qg, const TI *__restrict__ Kg,
                                                   const TI *__restrict__ Vg, TO *__restrict__ Og,
                                                   llla_strides sq, llla_strides sk, llla_strides sv,
                                                   llla_strides so, const int32_t *__restrict__ seqlens,
-                                                  int H, int n, int causal, float lambda, float scale)
+                                                  int H, int n, int causal, float lambda, float scale,
+                                                  const float *__restrict__ Mg = nullptr, int mpitch = 0,
+                                                  const float *__restrict__ Yg = nullptr, int ypitch = 0)
 {
     using C = Cfg<D>;
     constexpr int TS = C::TS, TG = C::TG, TPQ = C::TPQ, QB = C::QB, LDK = C::LDK, P = C::P,
@@ -172,161 +176,174 @@ __global__ __launch_bounds__(NT) void valu_kernel(const TI *__restrict__ Qg, con
     }
     if (tid < QB) ms[tid] = -INFINITY;
 
-    // ---- sweep 1: un-centred moments with running max (Algorithm 1, first loop) -----------------
-    float acc[TS][TS];
-    float mu[TS];
-    float omega = 0.f;
-#pragma unroll
-    for (int x = 0; x < TS; ++x) {
-        mu[x] = 0.f;
-#pragma unroll
-        for (int y = 0; y < TS; ++y) acc[x][y] = 0.f;
-    }
     const int koff = DECODE ? slot * KT : 0;             // this slot's rows inside the staged tile
-
-    for (int kt0 = 0; kt0 < kend; kt0 += KROWS) {
-        __syncthreads();                                 // previous tile fully consumed
-        load_tile<D, TI>(ks, Kh, sk.seq, kt0, KROWS, nkeys, tid);
+    if (GIVEN) {
+        // y1 at [0, D), y0 at [D] of a row of Yg; the row maximum is stored in log2 units
+        for (int idx = tid; idx < QB * P; idx += NT) {
+            const int s2 = idx / P, c = idx % P;
+            const int i = min(i0 + s2, n - 1);
+            const float *yr = Yg + ((size_t)bh * n + i) * ypitch;
+            ys[s2 * (P + 3) + c] = (c == 0) ? yr[D] : yr[c - 1];
+        }
+        if (tid < QB) ms[tid] = Mg[(size_t)bh * mpitch + min(i0 + tid, n - 1)] * 0.6931471805599453f;
         __syncthreads();
-        for (int idx = tid; idx < QB * KT; idx += NT) {  // logits of (slot, key)
-            const int s = idx / KT, kj = idx % KT;
-            const int row = (DECODE ? s * KT : 0) + kj;
-            const int j = kt0 + row;
-            const int last = (DECODE || !causal) ? nkeys - 1 : min(i0 + s, n - 1);
-            float v = -INFINITY;
-            if (j <= last) v = scale * dot_lds<D>(qs + s * D, ks + row * LDK);
-            sl[idx] = v;
-        }
-        __syncthreads();
-        if (tid < QB) {                                  // running max and rescale factor per slot
-            float mx = ms[tid];
-            const float mold = mx;
-            for (int kj = 0; kj < KT; ++kj) mx = fmaxf(mx, sl[tid * KT + kj]);
-            ms[tid] = mx;
-            al[tid] = (mold == -INFINITY) ? 0.f : __expf(mold - mx);
-        }
-        __syncthreads();
-        for (int idx = tid; idx < QB * KT; idx += NT) {  // weights, 0 for masked keys
-            const float mx = ms[idx / KT];
-            const float s = sl[idx];
-            wl[idx] = (s == -INFINITY) ? 0.f : __expf(s - mx);
-        }
-        __syncthreads();
-        {
-            const float alpha = al[slot];
-            if (alpha != 1.f) {
-                omega *= alpha;
-#pragma unroll
-                for (int x = 0; x < TS; ++x) {
-                    mu[x] *= alpha;
-#pragma unroll
-                    for (int y = 0; y < TS; ++y) acc[x][y] *= alpha;
-                }
-            }
-            const int jn = min(KT, my_last - (kt0 + koff) + 1);   // visible keys of this slot here
-            for (int kj = 0; kj < jn; ++kj) {
-                const float w = wl[slot * KT + kj];
-                const float *krow = ks + (koff + kj) * LDK;
-                float a[TS], bb[TS];
-#pragma unroll
-                for (int x = 0; x < TS; x += 4) {
-                    const float4 va = *reinterpret_cast<const float4 *>(krow + ta * TS + x);
-                    const float4 vb = *reinterpret_cast<const float4 *>(krow + tb * TS + x);
-                    a[x] = va.x * w; a[x + 1] = va.y * w; a[x + 2] = va.z * w; a[x + 3] = va.w * w;
-                    bb[x] = vb.x; bb[x + 1] = vb.y; bb[x + 2] = vb.z; bb[x + 3] = vb.w;
-                }
-                omega += w;
-#pragma unroll
-                for (int x = 0; x < TS; ++x) {
-                    mu[x] += a[x];
-#pragma unroll
-                    for (int y = 0; y < TS; ++y) acc[x][y] = fmaf(a[x], bb[y], acc[x][y]);
-                }
-            }
-        }
-    }
-    __syncthreads();                                     // tiles are dead; sys may overwrite them
-
-    // ---- the (d+1)x(d+1) system [At | rhs] in LDS -----------------------------------------------
-    if (DECODE) {
-        // merge the slots' partial moments: common max, then an ordered (deterministic) sum
-        if (tid < QB) {
-            float mx = -INFINITY;
-            for (int s = 0; s < QB; ++s) mx = fmaxf(mx, ms[s]);
-            fs[tid] = (ms[tid] == -INFINITY) ? 0.f : __expf(ms[tid] - mx);
-            red[tid] = mx;
-        }
-        for (int idx = tid; idx < P * LS; idx += NT) sys[idx] = 0.f;
-        __syncthreads();
-        for (int s = 0; s < QB; ++s) {
-            if (slot == s) {
-                const float f = fs[s];
-#pragma unroll
-                for (int x = 0; x < TS; ++x)
-#pragma unroll
-                    for (int y = 0; y < TS; ++y)
-                        sys[(1 + ta * TS + x) * LS + 1 + tb * TS + y] += f * acc[x][y];
-                if (tb == 0) {
-#pragma unroll
-                    for (int x = 0; x < TS; ++x) sys[(1 + ta * TS + x) * LS] += f * mu[x];
-                }
-                if (r == 0) sys[0] += f * omega;
-            }
-            __syncthreads();
-        }
-        if (tid < QB) ms[tid] = red[tid];                // every slot now works relative to the max
-        for (int c = tid; c < D; c += NT) {
-            sys[c + 1] = sys[(c + 1) * LS];              // row 0 mirrors column 0
-            sys[(c + 1) * LS + c + 1] += lambda;
-            sys[(c + 1) * LS + P] = qs[c];
-        }
-        if (tid == 0) sys[P] = 1.f;
     } else {
-        float *S = sys + slot * P * LS;
+        // ---- sweep 1: un-centred moments with running max (Algorithm 1, first loop) -----------------
+        float acc[TS][TS];
+        float mu[TS];
+        float omega = 0.f;
 #pragma unroll
-        for (int x = 0; x < TS; ++x)
+        for (int x = 0; x < TS; ++x) {
+            mu[x] = 0.f;
 #pragma unroll
-            for (int y = 0; y < TS; ++y) {
-                const int rr = ta * TS + x, cc = tb * TS + y;
-                S[(1 + rr) * LS + 1 + cc] = acc[x][y] + (rr == cc ? lambda : 0.f);
-            }
-        if (tb == 0) {
-#pragma unroll
-            for (int x = 0; x < TS; ++x) {
-                S[(1 + ta * TS + x) * LS] = mu[x];
-                S[1 + ta * TS + x] = mu[x];
-            }
+            for (int y = 0; y < TS; ++y) acc[x][y] = 0.f;
         }
-        if (r == 0) {
-            // a dead slot (row >= n) gets a harmless identity-like pivot
-            S[0] = slot_live ? omega : 1.f;
-            S[P] = 1.f;
-        }
-        for (int c = r; c < D; c += TPQ) S[(c + 1) * LS + P] = qs[slot * D + c];
-    }
 
-    // ---- exact solve by elimination (the matrix is symmetric positive definite) -----------------
-    {
-        float *S = DECODE ? sys : sys + slot * P * LS;
-        const int gt = DECODE ? tid : r;
-        constexpr int GS = DECODE ? NT : TPQ;
-        for (int k = 0; k < P; ++k) {
+        for (int kt0 = 0; kt0 < kend; kt0 += KROWS) {
+            __syncthreads();                                 // previous tile fully consumed
+            load_tile<D, TI>(ks, Kh, sk.seq, kt0, KROWS, nkeys, tid);
             __syncthreads();
-            const float pinv = 1.f / S[k * LS + k];
-            for (int row = k + 1 + gt; row < P; row += GS) {
-                const float f = S[row * LS + k] * pinv;
-                for (int c = k + 1; c <= P; ++c) S[row * LS + c] = fmaf(-f, S[k * LS + c], S[row * LS + c]);
+            for (int idx = tid; idx < QB * KT; idx += NT) {  // logits of (slot, key)
+                const int s = idx / KT, kj = idx % KT;
+                const int row = (DECODE ? s * KT : 0) + kj;
+                const int j = kt0 + row;
+                const int last = (DECODE || !causal) ? nkeys - 1 : min(i0 + s, n - 1);
+                float v = -INFINITY;
+                if (j <= last) v = scale * dot_lds<D>(qs + s * D, ks + row * LDK);
+                sl[idx] = v;
+            }
+            __syncthreads();
+            if (tid < QB) {                                  // running max and rescale factor per slot
+                float mx = ms[tid];
+                const float mold = mx;
+                for (int kj = 0; kj < KT; ++kj) mx = fmaxf(mx, sl[tid * KT + kj]);
+                ms[tid] = mx;
+                al[tid] = (mold == -INFINITY) ? 0.f : __expf(mold - mx);
+            }
+            __syncthreads();
+            for (int idx = tid; idx < QB * KT; idx += NT) {  // weights, 0 for masked keys
+                const float mx = ms[idx / KT];
+                const float s = sl[idx];
+                wl[idx] = (s == -INFINITY) ? 0.f : __expf(s - mx);
+            }
+            __syncthreads();
+            {
+                const float alpha = al[slot];
+                if (alpha != 1.f) {
+                    omega *= alpha;
+#pragma unroll
+                    for (int x = 0; x < TS; ++x) {
+                        mu[x] *= alpha;
+#pragma unroll
+                        for (int y = 0; y < TS; ++y) acc[x][y] *= alpha;
+                    }
+                }
+                const int jn = min(KT, my_last - (kt0 + koff) + 1);   // visible keys of this slot here
+                for (int kj = 0; kj < jn; ++kj) {
+                    const float w = wl[slot * KT + kj];
+                    const float *krow = ks + (koff + kj) * LDK;
+                    float a[TS], bb[TS];
+#pragma unroll
+                    for (int x = 0; x < TS; x += 4) {
+                        const float4 va = *reinterpret_cast<const float4 *>(krow + ta * TS + x);
+                        const float4 vb = *reinterpret_cast<const float4 *>(krow + tb * TS + x);
+                        a[x] = va.x * w; a[x + 1] = va.y * w; a[x + 2] = va.z * w; a[x + 3] = va.w * w;
+                        bb[x] = vb.x; bb[x + 1] = vb.y; bb[x + 2] = vb.z; bb[x + 3] = vb.w;
+                    }
+                    omega += w;
+#pragma unroll
+                    for (int x = 0; x < TS; ++x) {
+                        mu[x] += a[x];
+#pragma unroll
+                        for (int y = 0; y < TS; ++y) acc[x][y] = fmaf(a[x], bb[y], acc[x][y]);
+                    }
+                }
             }
         }
-        float *yv = ys + (DECODE ? 0 : slot * (P + 3));
-        for (int k = P - 1; k >= 0; --k) {
+        __syncthreads();                                     // tiles are dead; sys may overwrite them
+
+        // ---- the (d+1)x(d+1) system [At | rhs] in LDS -----------------------------------------------
+        if (DECODE) {
+            // merge the slots' partial moments: common max, then an ordered (deterministic) sum
+            if (tid < QB) {
+                float mx = -INFINITY;
+                for (int s = 0; s < QB; ++s) mx = fmaxf(mx, ms[s]);
+                fs[tid] = (ms[tid] == -INFINITY) ? 0.f : __expf(ms[tid] - mx);
+                red[tid] = mx;
+            }
+            for (int idx = tid; idx < P * LS; idx += NT) sys[idx] = 0.f;
             __syncthreads();
-            const float yk = S[k * LS + P] / S[k * LS + k];
-            if (gt == 0) yv[k] = yk;
-            for (int row = gt; row < k; row += GS) S[row * LS + P] = fmaf(-S[row * LS + k], yk, S[row * LS + P]);
+            for (int s = 0; s < QB; ++s) {
+                if (slot == s) {
+                    const float f = fs[s];
+#pragma unroll
+                    for (int x = 0; x < TS; ++x)
+#pragma unroll
+                        for (int y = 0; y < TS; ++y)
+                            sys[(1 + ta * TS + x) * LS + 1 + tb * TS + y] += f * acc[x][y];
+                    if (tb == 0) {
+#pragma unroll
+                        for (int x = 0; x < TS; ++x) sys[(1 + ta * TS + x) * LS] += f * mu[x];
+                    }
+                    if (r == 0) sys[0] += f * omega;
+                }
+                __syncthreads();
+            }
+            if (tid < QB) ms[tid] = red[tid];                // every slot now works relative to the max
+            for (int c = tid; c < D; c += NT) {
+                sys[c + 1] = sys[(c + 1) * LS];              // row 0 mirrors column 0
+                sys[(c + 1) * LS + c + 1] += lambda;
+                sys[(c + 1) * LS + P] = qs[c];
+            }
+            if (tid == 0) sys[P] = 1.f;
+        } else {
+            float *S = sys + slot * P * LS;
+#pragma unroll
+            for (int x = 0; x < TS; ++x)
+#pragma unroll
+                for (int y = 0; y < TS; ++y) {
+                    const int rr = ta * TS + x, cc = tb * TS + y;
+                    S[(1 + rr) * LS + 1 + cc] = acc[x][y] + (rr == cc ? lambda : 0.f);
+                }
+            if (tb == 0) {
+#pragma unroll
+                for (int x = 0; x < TS; ++x) {
+                    S[(1 + ta * TS + x) * LS] = mu[x];
+                    S[1 + ta * TS + x] = mu[x];
+                }
+            }
+            if (r == 0) {
+                // a dead slot (row >= n) gets a harmless identity-like pivot
+                S[0] = slot_live ? omega : 1.f;
+                S[P] = 1.f;
+            }
+            for (int c = r; c < D; c += TPQ) S[(c + 1) * LS + P] = qs[slot * D + c];
         }
-    }
-    __syncthreads();
+
+        // ---- exact solve by elimination (the matrix is symmetric positive definite) -----------------
+        {
+            float *S = DECODE ? sys : sys + slot * P * LS;
+            const int gt = DECODE ? tid : r;
+            constexpr int GS = DECODE ? NT : TPQ;
+            for (int k = 0; k < P; ++k) {
+                __syncthreads();
+                const float pinv = 1.f / S[k * LS + k];
+                for (int row = k + 1 + gt; row < P; row += GS) {
+                    const float f = S[row * LS + k] * pinv;
+                    for (int c = k + 1; c <= P; ++c) S[row * LS + c] = fmaf(-f, S[k * LS + c], S[row * LS + c]);
+                }
+            }
+            float *yv = ys + (DECODE ? 0 : slot * (P + 3));
+            for (int k = P - 1; k >= 0; --k) {
+                __syncthreads();
+                const float yk = S[k * LS + P] / S[k * LS + k];
+                if (gt == 0) yv[k] = yk;
+                for (int row = gt; row < k; row += GS) S[row * LS + P] = fmaf(-S[row * LS + k], yk, S[row * LS + P]);
+            }
+        }
+        __syncthreads();
+
+    }   // !GIVEN
 
     // ---- sweep 3: output weights s_ij = w_ij (y0 + k_j . y1) and O = S V ------------------------
     const float *yv = ys + (DECODE ? 0 : slot * (P + 3));
@@ -409,6 +426,23 @@ hipError_t by_dim(const Problem &p, int nrows)
 }
 
 }  // namespace
+
+hipError_t valu_forward_given(const Problem &p, int nrows, const float *M, int mpitch, const float *Y, int ypitch)
+{
+    if (p.d != 64 || p.in != LLLA_BF16) return hipErrorInvalidValue;
+    using C = Cfg<64>;
+    nrows = nrows < p.n ? nrows : p.n;
+    dim3 grid((nrows + C::QB - 1) / C::QB, p.B * p.H);
+    if (p.out == LLLA_F32)
+        hipLaunchKernelGGL((valu_kernel<64, bf16_t, float, false, true>), grid, dim3(NT), 0, p.stream,
+                           (const bf16_t *)p.Q, (const bf16_t *)p.K, (const bf16_t *)p.V, (float *)p.O, p.sq, p.sk,
+                           p.sv, p.so, nullptr, p.H, p.n, 1, p.lambda, p.scale, M, mpitch, Y, ypitch);
+    else
+        hipLaunchKernelGGL((valu_kernel<64, bf16_t, bf16_t, false, true>), grid, dim3(NT), 0, p.stream,
+                           (const bf16_t *)p.Q, (const bf16_t *)p.K, (const bf16_t *)p.V, (bf16_t *)p.O, p.sq, p.sk,
+                           p.sv, p.so, nullptr, p.H, p.n, 1, p.lambda, p.scale, M, mpitch, Y, ypitch);
+    return hipGetLastError();
+}
 
 hipError_t valu_forward(const Problem &p) { return by_dim<false>(p, p.n); }
 hipError_t valu_forward_rows(const Problem &p, int nrows) { return by_dim<false>(p, nrows < p.n ? nrows : p.n); }
