@@ -110,28 +110,49 @@ def main():
     per = np.array([a.elapsed_time(b) for a, b in evs])          # ms, device time of each step
     ms = wall * 1e3 / steps
 
-    # stage timings from the library (HIP events on the same stream), when it offers them
-    stages = llla.last_stage_ms() if hasattr(llla, "last_stage_ms") else None
+    # ---- per-kernel durations: the library records HIP events around each kernel it enqueues on the
+    #      same stream (measurement aid); a second loop over the same launches, so that `value` above
+    #      is not perturbed by the event records
+    llla.profile_enable(True)
+    acc = {}
+    for i in range(steps):
+        step(i)
+        for k, v in llla.profile_last().items():
+            acc.setdefault(k, []).append(v)
+    llla.profile_enable(False)
+    stages = {k: float(np.mean(v)) for k, v in acc.items()}
+    dom = max(stages, key=stages.get) if stages else None
 
     if decode:
         tokens = w.B
         algo_bytes = 2.0 * w.B * w.H * w.n * w.d * cpu_in[1].element_size()
-        dom_ms = float(np.mean(per))
+        dom_ms = stages[dom] if dom else float(np.mean(per))
         roof = {"bound": "hbm", "achieved": algo_bytes / (dom_ms * 1e-3) / 1e9, "peak": PEAK_HBM / 1e9,
-                "unit": "GB/s", "traffic": None, "kernel": "llla_decode (whole call)",
+                "unit": "GB/s", "traffic": None, "kernel": dom or "llla_decode (whole call)",
                 "algorithmic_bytes_per_launch": algo_bytes, "kernel_ms": dom_ms}
     else:
         tokens = w.B * w.n
-        flops = forward_flops(w.B, w.H, w.n, w.d)
-        dom_ms = float(np.mean(per))
-        kernel = "llla_forward (whole call)"
-        peak = PEAK_MFMA_16BIT
-        if w.dtype == "f32":
-            peak = PEAK_FP32_VALU
-        roof = {"bound": "mfma", "achieved": flops / (dom_ms * 1e-3) / 1e12, "peak": peak / 1e12,
-                "unit": "TFLOP/s", "traffic": None, "kernel": kernel,
+        pairs = w.n * (w.n + 1) // 2
+        d = w.d
+        if dom == "moments":
+            # logits, weights, omega, mu~, symmetric half of Sigma~, and the per-row solve
+            flops = w.B * w.H * (pairs * (d * d + 5 * d) + w.n * (d ** 3 / 3.0 + 4 * d * d))
+            bound, peak = "mfma", PEAK_MFMA_16BIT
+        else:
+            flops = forward_flops(w.B, w.H, w.n, d)
+            bound, peak = ("mfma", PEAK_MFMA_16BIT) if w.dtype != "f32" else ("alu", PEAK_FP32_VALU)
+        dom_ms = stages[dom] if dom else float(np.mean(per))
+        roof = {"bound": bound, "achieved": flops / (dom_ms * 1e-3) / 1e12, "peak": peak / 1e12,
+                "unit": "TFLOP/s", "traffic": None, "kernel": dom or "llla_forward (whole call)",
                 "algorithmic_flops_per_launch": flops, "kernel_ms": dom_ms,
-                "executed_mfma_class_flops": executed_mfma_flops(w.B, w.H, w.n, w.d)}
+                "whole_call_algorithmic_tflops": forward_flops(w.B, w.H, w.n, d) / (float(np.mean(per)) * 1e-3) / 1e12}
+        if dom == "moments":
+            # what the kernel really issues to the matrix cores: per 64-key block and wave 82 f16 + 2 bf16
+            # MFMAs of 16x16x32 (16384 flop), per query 144 fp32 MFMAs of 16x16x4 (2048 flop)
+            blocks = sum((min(i0 + 15, w.n - 1) // 64 + 1) for i0 in range(0, w.n, 16))
+            issued = w.B * w.H * (blocks * 4 * 84 * 16384 + w.n * 144 * 2048)
+            roof["mfma_issued_tflops"] = issued / (dom_ms * 1e-3) / 1e12
+            roof["mfma_issued_frac_of_16bit_peak"] = roof["mfma_issued_tflops"] / (PEAK_MFMA_16BIT / 1e12)
     roof["frac"] = roof["achieved"] / roof["peak"]
 
     result = {
@@ -146,7 +167,7 @@ def main():
         "roofline": roof,
     }
     if stages:
-        result["stages_ms"] = stages
+        result["stages_ms"] = {k: round(v, 4) for k, v in stages.items()}
     if not decode:
         result["tflops_algorithmic"] = roof["achieved"]
 

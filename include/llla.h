@@ -25,7 +25,8 @@
  *
  * Memory and execution contract (all entry points):
  *   - every data pointer is a DEVICE pointer owned by the caller; the library never allocates or
- *     frees device memory, never synchronises the device, and enqueues all work on `stream`
+ *     frees device memory, never synchronises the device (llla_profile_last excepted), and enqueues
+ *     all work on `stream`
  *     (a hipStream_t passed as void*; NULL = the default stream);
  *   - tensors are [batch, head, seq, d] with the innermost (d) stride equal to 1; the other strides
  *     are given in elements in an llla_strides;
@@ -121,6 +122,17 @@ llla_status llla_decode_path(const void *q, const void *Kc, const void *Vc, void
                              int B, int H, int L_max, int d, llla_dtype in, llla_dtype out,
                              float lambda, float scale, llla_path path,
                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Measurement aid (used by bench.py; not part of the method).  After llla_profile_enable(1) every
+ * forward / decode call records HIP events around each kernel it enqueues, on the caller's stream.
+ * llla_profile_last() waits for the events of the most recent call and writes up to `max` stage
+ * durations in milliseconds to ms[] and pointers to static stage names to names[]; it returns
+ * the number of stages (0 if profiling is off or nothing was recorded).  This is the library's only
+ * process-wide state: it is not thread-safe and must stay off (the default) in production use.
+ */
+void llla_profile_enable(int on);
+int llla_profile_last(float *ms, const char **names, int max);
 
 /* Static, NUL-terminated description of a status code. */
 const char *llla_status_string(llla_status status);

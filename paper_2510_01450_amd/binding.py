@@ -55,6 +55,10 @@ def lib():
     L.llla_status_string.argtypes = [i32]
     L.llla_status_string.restype = ctypes.c_char_p
     L.llla_version.restype = ctypes.c_char_p
+    L.llla_profile_enable.argtypes = [i32]
+    L.llla_profile_enable.restype = None
+    L.llla_profile_last.argtypes = [ctypes.POINTER(f32), ctypes.POINTER(ctypes.c_char_p), i32]
+    L.llla_profile_last.restype = i32
     _lib = L
     return L
 
@@ -65,6 +69,19 @@ def status_string(code: int) -> str:
 
 def version() -> str:
     return lib().llla_version().decode()
+
+
+def profile_enable(on: bool) -> None:
+    """Measurement aid: record HIP events around every kernel of the following calls."""
+    lib().llla_profile_enable(1 if on else 0)
+
+
+def profile_last() -> dict:
+    """Stage name -> milliseconds of the most recent profiled call (waits for it to finish)."""
+    ms = (ctypes.c_float * 16)()
+    names = (ctypes.c_char_p * 16)()
+    k = lib().llla_profile_last(ms, names, 16)
+    return {names[i].decode(): float(ms[i]) for i in range(k)}
 
 
 def forward_workspace_bytes(B, H, n, d, dtype) -> int:

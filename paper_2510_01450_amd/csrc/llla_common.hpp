@@ -41,6 +41,13 @@ bool mfma_decode_supported(int d, llla_dtype in);
 size_t mfma_decode_workspace_bytes(int B, int H, int L_max, int d, llla_dtype in);
 hipError_t mfma_decode(const Problem &p);
 
+// ---- stage profiling (measurement aid, off by default) ------------------------------------------
+// stage_mark(stream, name) records an event and labels the work enqueued AFTER it, up to the next
+// mark; stage_begin() starts a new call, stage_end() closes the last stage.
+void stage_begin(hipStream_t stream);
+void stage_mark(hipStream_t stream, const char *name);
+void stage_end(hipStream_t stream);
+
 // ---- storage types -----------------------------------------------------------------------------
 // bf16 is handled as raw uint16_t bits; conversions are written out so that rounding is explicit.
 typedef uint16_t bf16_t;

@@ -817,19 +817,24 @@ hipError_t mfma_forward(const Problem &p)
 
     const bf16_t *Q = static_cast<const bf16_t *>(p.Q), *K = static_cast<const bf16_t *>(p.K),
                  *V = static_cast<const bf16_t *>(p.V);
+    stage_mark(p.stream, "prep");
     hipLaunchKernelGGL(prep_kernel, dim3(L.nkb, bh), dim3(NT), 0, p.stream, K, V, p.sk, p.sv, p.H, p.n, L.nkb, KT, VT);
     const int nq64 = (p.n + 63) / 64;
+    stage_mark(p.stream, "rowmax");
     hipLaunchKernelGGL((sweep_kernel<true>), dim3(nq64, bh), dim3(NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
                        0, cscale, VT, M, Y, p.O, p.so, 0);
     const int nq16 = (p.n + QB - 1) / QB;
+    stage_mark(p.stream, "moments");
     hipLaunchKernelGGL(moments_kernel, dim3(nq16, bh), dim3(NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb, first,
                        cscale, p.lambda, KT, M, Y);
     // output: the first rows are evaluated in fp32 on the vector ALUs (their weights y0 + k.y1 cancel
     // to a few digits), the rest by the MFMA sweep
+    stage_mark(p.stream, "output_early_rows");
     hipError_t e = valu_forward_given(p, first, M, L.npad, Y, YP);
     if (e != hipSuccess) return e;
     if (first < p.n) {
         const int nq64b = (p.n - first + 63) / 64;
+        stage_mark(p.stream, "output");
         hipLaunchKernelGGL((sweep_kernel<false>), dim3(nq64b, bh), dim3(NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n,
                            L.nkb, first, cscale, VT, M, Y, p.O, p.so, p.out == LLLA_BF16 ? 1 : 0);
     }
