@@ -1,0 +1,261 @@
+// Device helpers shared by the matrix-core (MFMA) kernels of the gfx950 LLA library: vector types,
+// MFMA wrappers, DPP broadcasts, LDS DMA, and the on-chip exact solve of the per-query system.
+#pragma once
+
+#include "llla_common.hpp"
+
+namespace llla {
+namespace mfma {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int D = 64;          // head dimension of this path
+constexpr int KB = 32;         // keys per block
+constexpr int NT = 256;        // threads per workgroup (4 waves)
+constexpr int QW = 4;          // queries per wave in the moments kernel
+constexpr int QB = 16;         // queries per workgroup in the moments kernel
+constexpr int YP = D + 4;      // pitch of a y row in the workspace: y1[0..D), y0 at [D]
+constexpr int EARLY_ROWS = 4 * D;
+constexpr float LOG2E = 1.4426950408889634f;
+
+__device__ inline void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+template <int C>
+__device__ inline float row_bcast(float x)   // value of lane C of the caller's 16-lane row
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x150 + C, 0xf, 0xf, false));
+}
+__device__ inline float lane_xor1(float x)   // value of lane ^ 1
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xf, 0xf, false));
+}
+
+__device__ inline f32x4 mfma_f16(half8 a, half8 b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
+__device__ inline f32x4 mfma_bf16(bf16x8 a, bf16x8 b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0); }
+
+// C += A^T B for 16x16 fp32 tiles held in the MFMA accumulator layout (lane (g,n), reg t = X[4g+t][n]).
+// The contraction slot (chunk kc, lane group g) is mapped to index 4g+kc, which is exactly where
+// register kc of both tiles sits, so no data moves.
+__device__ inline f32x4 tile_atb(f32x4 c, f32x4 a, f32x4 b)
+{
+#pragma unroll
+    for (int kc = 0; kc < 4; ++kc) c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[kc], b[kc], c, 0, 0, 0);
+    return c;
+}
+
+__host__ __device__ constexpr int tix(int I, int J) { return I * 4 - I * (I - 1) / 2 + (J - I); }
+
+constexpr int SC_PITCH = 20;         // floats per row of a 16x16 scratch tile
+
+// Upper Cholesky factor and its inverse for the diagonal tiles of the wave's four queries at once:
+// lane 16q + r owns row r of query q's symmetric 16x16 tile (a[c] = T[r][c]).  On return
+// li[c] = (L^{-1})[r][c] with T = L L^T (zero above the diagonal).
+__device__ inline void chol_inv16(float (&a)[16], float (&li)[16], int r)
+{
+    float l2[16];       // L[r][k] / L[k][k]  (column-scaled factor, strictly lower part kept)
+    float dinv_own = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        float dk, ak = a[k];
+        switch (k) {    // diagonal entry of step k, broadcast from lane k of the row
+#define LLLA_BC(K) case K: dk = row_bcast<K>(ak); break;
+            LLLA_BC(0) LLLA_BC(1) LLLA_BC(2) LLLA_BC(3) LLLA_BC(4) LLLA_BC(5) LLLA_BC(6) LLLA_BC(7)
+            LLLA_BC(8) LLLA_BC(9) LLLA_BC(10) LLLA_BC(11) LLLA_BC(12) LLLA_BC(13) LLLA_BC(14) LLLA_BC(15)
+#undef LLLA_BC
+            default: dk = 1.f;
+        }
+        float rinv = __builtin_amdgcn_rsqf(dk);
+        rinv = rinv * (1.5f - 0.5f * dk * rinv * rinv);      // one Newton step
+        const float u = (r >= k) ? ak * rinv : 0.f;          // L[r][k]
+        l2[k] = (r > k) ? u * rinv : 0.f;
+        dinv_own = (r == k) ? rinv : dinv_own;
+#pragma unroll
+        for (int c = k + 1; c < 16; ++c) {
+            float uc;
+            switch (c) {
+#define LLLA_BC(K) case K: uc = row_bcast<K>(u); break;
+                LLLA_BC(1) LLLA_BC(2) LLLA_BC(3) LLLA_BC(4) LLLA_BC(5) LLLA_BC(6) LLLA_BC(7) LLLA_BC(8)
+                LLLA_BC(9) LLLA_BC(10) LLLA_BC(11) LLLA_BC(12) LLLA_BC(13) LLLA_BC(14) LLLA_BC(15)
+#undef LLLA_BC
+                default: uc = 0.f;
+            }
+            a[c] = fmaf(-u, uc, a[c]);
+        }
+    }
+    // M = (unit lower L'')^{-1}:  M[r][c] = [r==c] - sum_{c<=p<r} L''[r][p] M[p][c]
+#pragma unroll
+    for (int c = 0; c < 16; ++c) li[c] = (r == c) ? 1.f : 0.f;
+#pragma unroll
+    for (int p = 0; p < 15; ++p) {
+#pragma unroll
+        for (int c = 0; c <= p; ++c) {
+            float mp;
+            switch (p) {
+#define LLLA_BC(K) case K: mp = row_bcast<K>(li[c]); break;
+                LLLA_BC(0) LLLA_BC(1) LLLA_BC(2) LLLA_BC(3) LLLA_BC(4) LLLA_BC(5) LLLA_BC(6) LLLA_BC(7)
+                LLLA_BC(8) LLLA_BC(9) LLLA_BC(10) LLLA_BC(11) LLLA_BC(12) LLLA_BC(13) LLLA_BC(14)
+#undef LLLA_BC
+                default: mp = 0.f;
+            }
+            li[c] = fmaf(-l2[p], mp, li[c]);
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < 16; ++c) li[c] *= dinv_own;          // L^{-1} = D^{-1} L''^{-1}
+}
+
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+typedef const __attribute__((address_space(1))) void *glb_void_ptr;
+
+// 16 bytes per lane straight from global memory into LDS (no registers): lane l's data lands at
+// lds_base + 16 l, the global address is per lane.  Written as inline assembly on purpose: the
+// compiler makes every later LDS read wait for a DMA it knows about (it cannot tell the two
+// buffers apart), which would serialise the prefetch; here the waits are placed by hand with
+// dma_wait() before the data is read.  The s_nop is the wait state gfx9 needs between a scalar
+// write of M0 and an LDS-DMA instruction that reads it.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ inline void dma16(const void *gsrc, void *lds_base)
+{
+    const unsigned lds = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void_ptr)lds_base);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(lds) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+__device__ inline void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Exact solve of the wave's QW augmented systems, all in registers / wave-private LDS scratch:
+//   in : acc[q][tix(I,J)]  upper-triangular 16x16 tiles of Sigma~_q (MFMA accumulator layout, lambda not yet added)
+//        rhs[q][P]         tile column with mu~_q in column 0 and q_q in column 1 (other columns 0)
+//        om4[q]            omega_q;  scw: >= QW*16*SC_PITCH floats of LDS owned by this wave
+//   out: rhs[q][P] column 0 (lanes nn == 0) = y1_q,  y0v[q] = y0_q (valid in lanes nn == 0)
+// with [omega mu~^T; mu~ Sigma~ + lambda I] [y0; y1] = [1; q].  16-blocked upper Cholesky whose block
+// products are C += A^T B on fp32 MFMA; diagonal tiles of the QW queries are factorised together
+// in (query, row) lanes with DPP row broadcasts.
+__device__ __forceinline__ void solve_wave(f32x4 (&acc)[QW][10], f32x4 (&rhs)[QW][4], float (&y0v)[QW],
+                                           const float (&om4)[QW], float *scw, float lambda, int g, int nn)
+{
+#pragma unroll
+    for (int q = 0; q < QW; ++q)
+#pragma unroll
+        for (int P = 0; P < 4; ++P)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc[q][tix(P, P)][t] += (nn == 4 * g + t) ? lambda : 0.f;
+
+#pragma unroll
+    for (int P = 0; P < 4; ++P) {
+        // diagonal tiles -> (query, row) lanes, symmetrised
+#pragma unroll
+        for (int q = 0; q < QW; ++q)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) scw[q * 16 * SC_PITCH + (4 * g + t) * SC_PITCH + nn] = acc[q][tix(P, P)][t];
+        wave_sync();
+        float a[16], li[16];
+        {
+            const float *my = scw + g * 16 * SC_PITCH;
+#pragma unroll
+            for (int c4 = 0; c4 < 4; ++c4) {
+                const f32x4 v = *reinterpret_cast<const f32x4 *>(my + nn * SC_PITCH + 4 * c4);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) a[4 * c4 + t] = v[t];
+            }
+#pragma unroll
+            for (int c = 0; c < 16; ++c) a[c] = 0.5f * (a[c] + my[c * SC_PITCH + nn]);
+        }
+        wave_sync();
+        chol_inv16(a, li, nn);
+        {
+            float *my = scw + g * 16 * SC_PITCH;
+#pragma unroll
+            for (int c4 = 0; c4 < 4; ++c4)
+                *reinterpret_cast<f32x4 *>(my + nn * SC_PITCH + 4 * c4) = f32x4{li[4 * c4], li[4 * c4 + 1], li[4 * c4 + 2], li[4 * c4 + 3]};
+        }
+        wave_sync();
+#pragma unroll
+        for (int q = 0; q < QW; ++q) {
+            const float *tq = scw + q * 16 * SC_PITCH;
+            // U^{-1} in tile layout: reg t = Uinv[4g+t][nn] = Linv[nn][4g+t]
+            const f32x4 ui = *reinterpret_cast<const f32x4 *>(tq + nn * SC_PITCH + 4 * g);
+            // L^{-1} in tile layout (kept in the slot of the consumed diagonal tile for the back substitution)
+            f32x4 lt;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) lt[t] = tq[(4 * g + t) * SC_PITCH + nn];
+            acc[q][tix(P, P)] = lt;
+            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int J = P + 1; J < 4; ++J) acc[q][tix(P, J)] = tile_atb(zero, ui, acc[q][tix(P, J)]);
+            rhs[q][P] = tile_atb(zero, ui, rhs[q][P]);
+#pragma unroll
+            for (int I = P + 1; I < 4; ++I) {
+                const f32x4 neg = -acc[q][tix(P, I)];
+#pragma unroll
+                for (int J = I; J < 4; ++J) acc[q][tix(I, J)] = tile_atb(acc[q][tix(I, J)], neg, acc[q][tix(P, J)]);
+                rhs[q][I] = tile_atb(rhs[q][I], neg, rhs[q][P]);
+            }
+        }
+        wave_sync();
+    }
+
+    // rhs[q][P]: column 0 = a = U^{-T} mu~, column 1 = c = U^{-T} q.  Schur step on the intercept:
+    // y0 = (1 - a.c) / (omega - a.a);  y1 = U^{-1} (c - a y0)
+#pragma unroll
+    for (int q = 0; q < QW; ++q) {
+        float saa = 0.f, sac = 0.f;
+#pragma unroll
+        for (int P = 0; P < 4; ++P)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float v = rhs[q][P][t];
+                const float o = lane_xor1(v);
+                saa = fmaf(v, v, saa);
+                sac = fmaf(v, o, sac);
+            }
+        saa += __shfl_xor(saa, 16); saa += __shfl_xor(saa, 32);
+        sac += __shfl_xor(sac, 16); sac += __shfl_xor(sac, 32);
+        const float om = om4[q];
+        const float y0 = (1.f - sac) / (om - saa);           // valid in lanes nn == 0
+        y0v[q] = y0;
+#pragma unroll
+        for (int P = 0; P < 4; ++P)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float av = rhs[q][P][t];
+                const float cv = lane_xor1(av);
+                rhs[q][P][t] = (nn == 0) ? (cv - av * y0) : 0.f;
+            }
+    }
+
+    // back substitution, block rows 3..0:  x_P = Uinv_P (t_P - sum_{J>P} U(P,J) x_J)
+#pragma unroll
+    for (int P = 3; P >= 0; --P) {
+#pragma unroll
+        for (int J = P + 1; J < 4; ++J) {
+            // transpose U(P,J) through the scratch tile so that it can be the A^T operand
+#pragma unroll
+            for (int q = 0; q < QW; ++q)
+                *reinterpret_cast<f32x4 *>(scw + q * 16 * SC_PITCH + nn * SC_PITCH + 4 * g) = acc[q][tix(P, J)];
+            wave_sync();
+#pragma unroll
+            for (int q = 0; q < QW; ++q) {
+                f32x4 ut;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) ut[t] = -scw[q * 16 * SC_PITCH + (4 * g + t) * SC_PITCH + nn];
+                rhs[q][P] = tile_atb(rhs[q][P], ut, rhs[q][J]);
+            }
+            wave_sync();
+        }
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int q = 0; q < QW; ++q) rhs[q][P] = tile_atb(zero, acc[q][tix(P, P)], rhs[q][P]);
+    }
+
+}
+
+}  // namespace mfma
+}  // namespace llla

@@ -14,24 +14,12 @@
 //           y0 = (1 + q.rho)/delta), a flash-style sweep.
 // The first 4d rows of every sequence, whose systems are the worst conditioned, are served by the
 // fp32 vector-ALU kernel instead (same result, higher-precision second moment).
-#include "llla_common.hpp"
+#include "llla_mfma_common.hpp"
 
 namespace llla {
 namespace {
 
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int D = 64;          // head dimension of this path
-constexpr int KB = 32;         // keys per block
-constexpr int NT = 256;        // threads per workgroup (4 waves)
-constexpr int QW = 4;          // queries per wave in the moments kernel
-constexpr int QB = 16;         // queries per workgroup in the moments kernel
-constexpr int YP = D + 4;      // pitch of a y row in the workspace: y1[0..D), y0 at [D]
-constexpr int EARLY_ROWS = 4 * D;
-constexpr float LOG2E = 1.4426950408889634f;
+using namespace mfma;
 
 struct Layout {
     size_t kt, vt, m, y, total;
@@ -52,37 +40,6 @@ Layout make_layout(int B, int H, int n)
     L.total = off;
     return L;
 }
-
-__device__ inline void wave_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-}
-
-template <int C>
-__device__ inline float row_bcast(float x)   // value of lane C of the caller's 16-lane row
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x150 + C, 0xf, 0xf, false));
-}
-__device__ inline float lane_xor1(float x)   // value of lane ^ 1
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xf, 0xf, false));
-}
-
-__device__ inline f32x4 mfma_f16(half8 a, half8 b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
-__device__ inline f32x4 mfma_bf16(bf16x8 a, bf16x8 b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0); }
-
-// C += A^T B for 16x16 fp32 tiles held in the MFMA accumulator layout (lane (g,n), reg t = X[4g+t][n]).
-// The contraction slot (chunk kc, lane group g) is mapped to index 4g+kc, which is exactly where
-// register kc of both tiles sits, so no data moves.
-__device__ inline f32x4 tile_atb(f32x4 c, f32x4 a, f32x4 b)
-{
-#pragma unroll
-    for (int kc = 0; kc < 4; ++kc) c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[kc], b[kc], c, 0, 0, 0);
-    return c;
-}
-
-__host__ __device__ constexpr int tix(int I, int J) { return I * 4 - I * (I - 1) / 2 + (J - I); }
 
 // ------------------------------------------------------------------------------------------------
 // prep: re-tile K (-> f16) and V (bf16) as [bh][key block][feature][32 keys]
@@ -280,88 +237,6 @@ __global__ __launch_bounds__(NT) void sweep_kernel(const bf16_t *__restrict__ Qg
 // moments + solve
 constexpr int KB2 = 2 * KB;          // keys per pipeline step of the moments kernel
 constexpr int WT_PITCH = KB2 + 8;    // halves per query row of the weight tile
-constexpr int SC_PITCH = 20;         // floats per row of a 16x16 scratch tile
-
-// Upper Cholesky factor and its inverse for the diagonal tiles of the wave's four queries at once:
-// lane 16q + r owns row r of query q's symmetric 16x16 tile (a[c] = T[r][c]).  On return
-// li[c] = (L^{-1})[r][c] with T = L L^T (zero above the diagonal).
-__device__ inline void chol_inv16(float (&a)[16], float (&li)[16], int r)
-{
-    float l2[16];       // L[r][k] / L[k][k]  (column-scaled factor, strictly lower part kept)
-    float dinv_own = 0.f;
-#pragma unroll
-    for (int k = 0; k < 16; ++k) {
-        float dk, ak = a[k];
-        switch (k) {    // diagonal entry of step k, broadcast from lane k of the row
-#define LLLA_BC(K) case K: dk = row_bcast<K>(ak); break;
-            LLLA_BC(0) LLLA_BC(1) LLLA_BC(2) LLLA_BC(3) LLLA_BC(4) LLLA_BC(5) LLLA_BC(6) LLLA_BC(7)
-            LLLA_BC(8) LLLA_BC(9) LLLA_BC(10) LLLA_BC(11) LLLA_BC(12) LLLA_BC(13) LLLA_BC(14) LLLA_BC(15)
-#undef LLLA_BC
-            default: dk = 1.f;
-        }
-        float rinv = __builtin_amdgcn_rsqf(dk);
-        rinv = rinv * (1.5f - 0.5f * dk * rinv * rinv);      // one Newton step
-        const float u = (r >= k) ? ak * rinv : 0.f;          // L[r][k]
-        l2[k] = (r > k) ? u * rinv : 0.f;
-        dinv_own = (r == k) ? rinv : dinv_own;
-#pragma unroll
-        for (int c = k + 1; c < 16; ++c) {
-            float uc;
-            switch (c) {
-#define LLLA_BC(K) case K: uc = row_bcast<K>(u); break;
-                LLLA_BC(1) LLLA_BC(2) LLLA_BC(3) LLLA_BC(4) LLLA_BC(5) LLLA_BC(6) LLLA_BC(7) LLLA_BC(8)
-                LLLA_BC(9) LLLA_BC(10) LLLA_BC(11) LLLA_BC(12) LLLA_BC(13) LLLA_BC(14) LLLA_BC(15)
-#undef LLLA_BC
-                default: uc = 0.f;
-            }
-            a[c] = fmaf(-u, uc, a[c]);
-        }
-    }
-    // M = (unit lower L'')^{-1}:  M[r][c] = [r==c] - sum_{c<=p<r} L''[r][p] M[p][c]
-#pragma unroll
-    for (int c = 0; c < 16; ++c) li[c] = (r == c) ? 1.f : 0.f;
-#pragma unroll
-    for (int p = 0; p < 15; ++p) {
-#pragma unroll
-        for (int c = 0; c <= p; ++c) {
-            float mp;
-            switch (p) {
-#define LLLA_BC(K) case K: mp = row_bcast<K>(li[c]); break;
-                LLLA_BC(0) LLLA_BC(1) LLLA_BC(2) LLLA_BC(3) LLLA_BC(4) LLLA_BC(5) LLLA_BC(6) LLLA_BC(7)
-                LLLA_BC(8) LLLA_BC(9) LLLA_BC(10) LLLA_BC(11) LLLA_BC(12) LLLA_BC(13) LLLA_BC(14)
-#undef LLLA_BC
-                default: mp = 0.f;
-            }
-            li[c] = fmaf(-l2[p], mp, li[c]);
-        }
-    }
-#pragma unroll
-    for (int c = 0; c < 16; ++c) li[c] *= dinv_own;          // L^{-1} = D^{-1} L''^{-1}
-}
-
-typedef __attribute__((address_space(3))) void *lds_void_ptr;
-typedef const __attribute__((address_space(1))) void *glb_void_ptr;
-
-// 16 bytes per lane straight from global memory into LDS (no registers): lane l's data lands at
-// lds_base + 16 l, the global address is per lane.  Written as inline assembly on purpose: the
-// compiler makes every later LDS read wait for a DMA it knows about (it cannot tell the two
-// buffers apart), which would serialise the prefetch; here the waits are placed by hand with
-// dma_wait() before the data is read.  The s_nop is the wait state gfx9 needs between a scalar
-// write of M0 and an LDS-DMA instruction that reads it.
-#pragma clang diagnostic push
-#pragma clang diagnostic ignored "-Winline-asm"
-__device__ inline void dma16(const void *gsrc, void *lds_base)
-{
-#ifdef LLLA_DBG_BUILTIN_DMA
-    __builtin_amdgcn_global_load_lds((glb_void_ptr)gsrc, (lds_void_ptr)lds_base, 16, 0, 0);
-    return;
-#endif
-    const unsigned lds = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void_ptr)lds_base);
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(lds) : "memory", "m0");
-}
-#pragma clang diagnostic pop
-__device__ inline void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
 // LDS tiles of one 64-key block are stored without padding (the DMA writes whole 1 KB wave rows);
 // 16-byte chunks are XOR-swizzled so that the MFMA operand reads stay free of bank conflicts:
 //   transposed tile (f16) : [sub-tile of 32 keys][feature row r][4 chunks of 8 keys], chunk c of row r at c ^ ((r>>2)&3)
@@ -429,9 +304,6 @@ __device__ __forceinline__ void moments_body(MomentsShared &sm, const bf16_t *__
         for (int t = 0; t < 10; ++t) acc[q][t] = f32x4{0.f, 0.f, 0.f, 0.f};
     f32x4 mu_acc = {0.f, 0.f, 0.f, 0.f};
     float om_part = 0.f;            // this lane's share of omega for query i0 + nn
-#ifdef LLLA_DBG_LDSWQ
-    float dbg_mismatch = 0.f;
-#endif
 
     // ---- per-lane constants of the staging and of the operand reads ------------------------------
     // DMA, transposed tile: this wave fills slots [64 wave, 64 wave + 64) of each 32-key sub-tile
@@ -501,15 +373,9 @@ __device__ __forceinline__ void moments_body(MomentsShared &sm, const bf16_t *__
     make_weights(0);
     __syncthreads();
 
-#ifdef LLLA_TIMING_NO_GRAM
-    for (int c = 0; c < 1; ++c) {
-#else
     for (int c = 0; c < nblk; ++c) {
-#endif
         const int buf = c & 1;
-#ifndef LLLA_TIMING_NO_GLOAD
         if (c + 1 < nblk) issue_dma(c + 1);
-#endif
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf) {        // two halves of 32 keys
             half8 bf[4];
@@ -527,16 +393,7 @@ __device__ __forceinline__ void moments_body(MomentsShared &sm, const bf16_t *__
 #pragma unroll
                     for (int t = 0; t < 4; ++t) wqu[t] = (q == 0) ? row_bcast<0>(wau[t]) : (q == 1) ? row_bcast<1>(wau[t])
                                                         : (q == 2) ? row_bcast<2>(wau[t]) : row_bcast<3>(wau[t]);
-#ifdef LLLA_DBG_LDSWQ
-                    const half8 wq = *reinterpret_cast<const half8 *>(&wt[buf][(QW * wave + q) * WT_PITCH + 32 * hf + 8 * g]);
-                    {
-                        const f32x4 ref = __builtin_bit_cast(f32x4, wq);
-                        for (int t = 0; t < 4; ++t)
-                            if (__builtin_bit_cast(int, ref[t]) != __builtin_bit_cast(int, wqu[t])) dbg_mismatch += 1.f;
-                    }
-#else
                     const half8 wq = __builtin_bit_cast(half8, wqu);
-#endif
 #pragma unroll
                     for (int I = 0; I < 4; ++I) {
                         const half8 af = bf[I] * wq;
@@ -595,15 +452,11 @@ __device__ __forceinline__ void moments_body(MomentsShared &sm, const bf16_t *__
                 mu_acc = mfma_f16(whi, bw, mu_acc);
             }
             if (hf == 0 && c + 1 < nblk) {
-#ifndef LLLA_TIMING_NO_STAGE
                 dma_wait();                     // this wave's DMA of block c+1 has landed
                 make_weights(c + 1);
-#endif
             }
         }
-#ifndef LLLA_TIMING_NO_BARRIER
         __syncthreads();
-#endif
     }
 
     // omega: lanes (g, nn) of all four waves hold partial sums for query i0 + nn
@@ -634,132 +487,15 @@ __device__ __forceinline__ void moments_body(MomentsShared &sm, const bf16_t *__
                 if (nn == 0) v = mus[qi][row];
                 if (nn == 1) v = bf16_to_f32(qrow[row]);
                 rhs[q][P][t] = v;
-                acc[q][tix(P, P)][t] += (nn == 4 * g + t) ? lambda : 0.f;
             }
         }
     }
 
-#ifdef LLLA_DBG_LDSWQ
-    float dbg_g00[QW], dbg_g37[QW];
-    for (int q = 0; q < QW; ++q) { dbg_g00[q] = acc[q][tix(0, 0)][0]; dbg_g37[q] = acc[q][tix(1, 3)][2]; }
-#endif
-    float *scw = &sc[wave][0][0];
-#ifdef LLLA_TIMING_NO_SOLVE
-#pragma unroll 1
-    for (int P = 0; P < 0; ++P) {
-#else
+    float y0v[QW], om4[QW];
 #pragma unroll
-    for (int P = 0; P < 4; ++P) {
-#endif
-        // diagonal tiles -> (query, row) lanes, symmetrised
-#pragma unroll
-        for (int q = 0; q < QW; ++q)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) scw[q * 16 * SC_PITCH + (4 * g + t) * SC_PITCH + nn] = acc[q][tix(P, P)][t];
-        wave_sync();
-        float a[16], li[16];
-        {
-            const float *my = scw + g * 16 * SC_PITCH;
-#pragma unroll
-            for (int c4 = 0; c4 < 4; ++c4) {
-                const f32x4 v = *reinterpret_cast<const f32x4 *>(my + nn * SC_PITCH + 4 * c4);
-#pragma unroll
-                for (int t = 0; t < 4; ++t) a[4 * c4 + t] = v[t];
-            }
-#pragma unroll
-            for (int c = 0; c < 16; ++c) a[c] = 0.5f * (a[c] + my[c * SC_PITCH + nn]);
-        }
-        wave_sync();
-        chol_inv16(a, li, nn);
-        {
-            float *my = scw + g * 16 * SC_PITCH;
-#pragma unroll
-            for (int c4 = 0; c4 < 4; ++c4)
-                *reinterpret_cast<f32x4 *>(my + nn * SC_PITCH + 4 * c4) = f32x4{li[4 * c4], li[4 * c4 + 1], li[4 * c4 + 2], li[4 * c4 + 3]};
-        }
-        wave_sync();
-#pragma unroll
-        for (int q = 0; q < QW; ++q) {
-            const float *tq = scw + q * 16 * SC_PITCH;
-            // U^{-1} in tile layout: reg t = Uinv[4g+t][nn] = Linv[nn][4g+t]
-            const f32x4 ui = *reinterpret_cast<const f32x4 *>(tq + nn * SC_PITCH + 4 * g);
-            // L^{-1} in tile layout (kept in the slot of the consumed diagonal tile for the back substitution)
-            f32x4 lt;
-#pragma unroll
-            for (int t = 0; t < 4; ++t) lt[t] = tq[(4 * g + t) * SC_PITCH + nn];
-            acc[q][tix(P, P)] = lt;
-            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int J = P + 1; J < 4; ++J) acc[q][tix(P, J)] = tile_atb(zero, ui, acc[q][tix(P, J)]);
-            rhs[q][P] = tile_atb(zero, ui, rhs[q][P]);
-#pragma unroll
-            for (int I = P + 1; I < 4; ++I) {
-                const f32x4 neg = -acc[q][tix(P, I)];
-#pragma unroll
-                for (int J = I; J < 4; ++J) acc[q][tix(I, J)] = tile_atb(acc[q][tix(I, J)], neg, acc[q][tix(P, J)]);
-                rhs[q][I] = tile_atb(rhs[q][I], neg, rhs[q][P]);
-            }
-        }
-        wave_sync();
-    }
+    for (int q = 0; q < QW; ++q) om4[q] = oms[QW * wave + q];
+    solve_wave(acc, rhs, y0v, om4, &sc[wave][0][0], lambda, g, nn);
 
-    // rhs[q][P]: column 0 = a = U^{-T} mu~, column 1 = c = U^{-T} q.  Schur step on the intercept:
-    // y0 = (1 - a.c) / (omega - a.a);  y1 = U^{-1} (c - a y0)
-    float y0v[QW];
-#pragma unroll
-    for (int q = 0; q < QW; ++q) {
-        float saa = 0.f, sac = 0.f;
-#pragma unroll
-        for (int P = 0; P < 4; ++P)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const float v = rhs[q][P][t];
-                const float o = lane_xor1(v);
-                saa = fmaf(v, v, saa);
-                sac = fmaf(v, o, sac);
-            }
-        saa += __shfl_xor(saa, 16); saa += __shfl_xor(saa, 32);
-        sac += __shfl_xor(sac, 16); sac += __shfl_xor(sac, 32);
-        const float om = oms[QW * wave + q];
-        const float y0 = (1.f - sac) / (om - saa);           // valid in lanes nn == 0
-        y0v[q] = y0;
-#pragma unroll
-        for (int P = 0; P < 4; ++P)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const float av = rhs[q][P][t];
-                const float cv = lane_xor1(av);
-                rhs[q][P][t] = (nn == 0) ? (cv - av * y0) : 0.f;
-            }
-    }
-
-    // back substitution, block rows 3..0:  x_P = Uinv_P (t_P - sum_{J>P} U(P,J) x_J)
-#pragma unroll
-    for (int P = 3; P >= 0; --P) {
-#pragma unroll
-        for (int J = P + 1; J < 4; ++J) {
-            // transpose U(P,J) through the scratch tile so that it can be the A^T operand
-#pragma unroll
-            for (int q = 0; q < QW; ++q)
-                *reinterpret_cast<f32x4 *>(scw + q * 16 * SC_PITCH + nn * SC_PITCH + 4 * g) = acc[q][tix(P, J)];
-            wave_sync();
-#pragma unroll
-            for (int q = 0; q < QW; ++q) {
-                f32x4 ut;
-#pragma unroll
-                for (int t = 0; t < 4; ++t) ut[t] = -scw[q * 16 * SC_PITCH + (4 * g + t) * SC_PITCH + nn];
-                rhs[q][P] = tile_atb(rhs[q][P], ut, rhs[q][J]);
-            }
-            wave_sync();
-        }
-        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int q = 0; q < QW; ++q) rhs[q][P] = tile_atb(zero, acc[q][tix(P, P)], rhs[q][P]);
-    }
-
-#ifdef LLLA_DBG_LDSWQ
-    for (int o = 1; o < 64; o <<= 1) dbg_mismatch += __shfl_xor(dbg_mismatch, o);
-#endif
 #pragma unroll
     for (int q = 0; q < QW; ++q) {
         const int i = i0 + QW * wave + q;
@@ -767,14 +503,7 @@ __device__ __forceinline__ void moments_body(MomentsShared &sm, const bf16_t *__
             float *yr = Yg + ((size_t)bh * n + i) * YP;
 #pragma unroll
             for (int P = 0; P < 4; ++P) *reinterpret_cast<f32x4 *>(yr + 16 * P + 4 * g) = rhs[q][P];
-#ifdef LLLA_DBG_DUMPMU
-            for (int P = 0; P < 4; ++P) for (int t = 0; t < 4; ++t) yr[16 * P + 4 * g + t] = mus[QW * wave + q][16 * P + 4 * g + t];
-#endif
             if (g == 0) yr[D] = y0v[q];
-#ifdef LLLA_DBG_LDSWQ
-            if (g == 0) yr[D + 1] = dbg_mismatch;
-            if (g == 0) { yr[D + 2] = dbg_g00[q]; yr[D + 3] = dbg_g37[q]; }
-#endif
         }
     }
 }
