@@ -185,14 +185,6 @@ llla_status llla_decode_path(const void *q, const void *Kc, const void *Vc, void
         !strides_aligned(sv, in) || (seqlens && (reinterpret_cast<uintptr_t>(seqlens) & 3u)))
         return LLLA_ERR_ALIGN;
 
-    const bool has_mfma = llla::mfma_decode_supported(d, in);
-    if (path == LLLA_PATH_MFMA && !has_mfma) return LLLA_ERR_UNSUPPORTED;
-    const bool use_mfma = has_mfma && path != LLLA_PATH_VALU;
-    if (use_mfma) {
-        st = check_workspace(llla::mfma_decode_workspace_bytes(B, H, L_max, d, in), workspace, workspace_bytes);
-        if (st != LLLA_OK) return st;
-    }
-
     Problem p{};
     p.Q = q; p.K = Kc; p.V = Vc; p.O = o;
     p.sk = sk; p.sv = sv;
@@ -203,6 +195,14 @@ llla_status llla_decode_path(const void *q, const void *Kc, const void *Vc, void
     p.lambda = lambda; p.scale = scale;
     p.ws = workspace; p.ws_bytes = workspace_bytes;
     p.stream = static_cast<hipStream_t>(stream);
+
+    const bool has_mfma = llla::mfma_decode_supported(d, in) && llla::mfma_decode_takes(p);
+    if (path == LLLA_PATH_MFMA && !has_mfma) return LLLA_ERR_UNSUPPORTED;
+    const bool use_mfma = has_mfma && path != LLLA_PATH_VALU;
+    if (use_mfma) {
+        st = check_workspace(llla::mfma_decode_workspace_bytes(B, H, L_max, d, in), workspace, workspace_bytes);
+        if (st != LLLA_OK) return st;
+    }
     llla::stage_begin(p.stream);
     if (!use_mfma) llla::stage_mark(p.stream, "valu_decode");
     const hipError_t e = use_mfma ? llla::mfma_decode(p) : llla::valu_decode(p);

@@ -39,6 +39,8 @@ size_t mfma_forward_workspace_bytes(int B, int H, int n, int d, llla_dtype in);
 hipError_t mfma_forward(const Problem &p);
 bool mfma_decode_supported(int d, llla_dtype in);
 size_t mfma_decode_workspace_bytes(int B, int H, int L_max, int d, llla_dtype in);
+// whether the MFMA decode path serves this call (it needs the full cache length for every sequence)
+bool mfma_decode_takes(const Problem &p);
 hipError_t mfma_decode(const Problem &p);
 
 // ---- stage profiling (measurement aid, off by default) ------------------------------------------

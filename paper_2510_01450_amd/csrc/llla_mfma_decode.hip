@@ -1,10 +1,351 @@
-// MFMA decode path (placeholder: nothing supported yet, the vector-ALU path serves decode).
-#include "llla_common.hpp"
+// Matrix-core decode path of Local Linear Attention for gfx950: bf16 caches, d = 64, all sequences
+// of the batch at the full cache length.  One query per (batch, head) against a cache that already
+// holds the new token: the last row of the causal forward (Section 2.3: LLA keeps a Theta(n d) KV
+// cache; Section 3.2: rows are independent).
+//
+// The cache is streamed from HBM exactly once.  In a single pass each wave accumulates, for its
+// share of the keys and relative to its own running maximum m (the online rescaling of Algorithm 1),
+//     omega = sum w,  mu~ = sum w k,  Sigma~ = sum w k k^T   (Eq. (tilded_form))
+//     y0v   = sum w v,  G~ = sum w k v^T                      (value moments)
+// as f16 MFMA accumulators: (w (.) K)^T [K | V] with the key as the contraction index.  Eq. (lla) then
+// needs no second pass over the cache:  o = sum_j w_j (y0 + k_j . y1) v_j = y0 * y0v + G~^T y1,
+// where [y0; y1] solves [omega mu~^T; mu~ Sigma~ + lambda I] y = [1; q].  A small second kernel merges
+// the partial moments of a head with a max-rescale, solves on chip, and writes o.
+#include "llla_mfma_common.hpp"
 
 namespace llla {
+namespace {
 
-bool mfma_decode_supported(int, llla_dtype) { return false; }
-size_t mfma_decode_workspace_bytes(int, int, int, int, llla_dtype) { return 0; }
-hipError_t mfma_decode(const Problem &) { return hipErrorNotSupported; }
+using namespace mfma;
+
+constexpr int STEP = 32;                       // keys per MFMA step
+constexpr int NSTAGE = 3;                      // LDS stages per wave; NSTAGE-1 are in flight
+constexpr int TILE_H = STEP * D;               // halves of one natural [32 keys][64] tile (4 KB)
+constexpr int STAGE_H = 2 * TILE_H;            // K tile + V tile
+constexpr int DMA_PER_STAGE = 8;
+constexpr int NTILES = 26;                     // 10 (Sigma~ upper) + 16 (G~)
+constexpr int PART_F = 192 + NTILES * 256;     // floats per partial: [m, omega, ..], mu~[64], y0v[64], tiles
+constexpr int MIN_L = 1024;                    // shorter caches go to the vector path
+
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) short4v *lds_short4_ptr;
+
+struct Split {
+    int nsplit;          // workgroups per head
+    int keys_per_wave;   // multiple of STEP
+    int nparts;          // partials per head = 4 * nsplit
+};
+
+Split make_split(int bh, int L)
+{
+    Split s;
+    int want = (1024 + bh - 1) / bh;                 // aim at >= 1024 workgroups
+    int most = L / (4 * 8 * STEP);                   // at least 8 steps per wave
+    if (most < 1) most = 1;
+    s.nsplit = want < 1 ? 1 : (want > most ? most : want);
+    if (s.nsplit > 4) s.nsplit = 4;                  // the merge kernel keeps at most 16 partial factors per head
+    const int waves = 4 * s.nsplit;
+    s.keys_per_wave = ((L + waves - 1) / waves + STEP - 1) / STEP * STEP;
+    s.nparts = waves;
+    return s;
+}
+
+// two bf16 packed in a dword -> two f16 packed (exact for values in the f16 range)
+__device__ inline unsigned bf16x2_to_f16x2(unsigned u)
+{
+    const float lo = __uint_as_float(u << 16), hi = __uint_as_float(u & 0xffff0000u);
+    return __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(lo, hi));
+}
+
+template <int N>
+__device__ inline void dma_wait_pending() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+__global__ __launch_bounds__(NT, 1) void decode_partial_kernel(const bf16_t *__restrict__ qg,
+                                                               const bf16_t *__restrict__ Kg,
+                                                               const bf16_t *__restrict__ Vg, llla_strides sk,
+                                                               llla_strides sv, int H, int L, int keys_per_wave,
+                                                               int nparts, float cscale, float *__restrict__ parts)
+{
+    __shared__ __align__(16) bf16_t stage[4][NSTAGE][STAGE_H];     // 4 waves x 3 stages x 8 KB
+
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64, g = lane / 16,
+              nn = lane % 16;
+    const int bh = blockIdx.y, b = bh / H, h = bh % H;
+    const int part = blockIdx.x * 4 + wave;
+    const int r0 = part * keys_per_wave;
+    const int r1 = min(r0 + keys_per_wave, L);
+    const int nsteps = r1 > r0 ? (r1 - r0 + STEP - 1) / STEP : 0;
+    const bf16_t *Kh = Kg + b * sk.batch + h * sk.head;
+    const bf16_t *Vh = Vg + b * sv.batch + h * sv.head;
+    bf16_t *mystage = &stage[wave][0][0];
+
+    // query fragment, the same for every column of the B operand: lane (g, *) holds q[8g..8g+7], q[32+8g..]
+    bf16x8 qf[2];
+    qf[0] = *reinterpret_cast<const bf16x8 *>(qg + (size_t)bh * D + 8 * g);
+    qf[1] = *reinterpret_cast<const bf16x8 *>(qg + (size_t)bh * D + 32 + 8 * g);
+
+    // ---- per-lane constants.  A natural tile is [key][8 chunks of 8 features]; chunk c of key k is
+    //      stored at chunk position c ^ ((k>>1)&7) (the DMA writes whole rows, so no padding).
+    int dma_key[4], dma_col[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int sl = 64 * t + lane;
+        dma_key[t] = sl >> 3;
+        dma_col[t] = ((sl & 7) ^ ((dma_key[t] >> 1) & 7)) * 8;
+    }
+    // logits operand (natural rows): key 16s + nn, feature chunks g and 4+g
+    const int sw_n = (nn >> 1) & 7;
+    const int nat0 = nn * D + ((g ^ sw_n) * 8), nat1 = nn * D + (((4 + g) ^ sw_n) * 8);     // + s*16*D
+    // transposed operand through ds_read_b64_tr_b16: inside a 16-lane group, lane j addresses 4 features
+    // (16 I + 4 (j%4) ..) of key 4g + j/4; the instruction hands lane i the 4 keys 4g..4g+3 of feature 16 I + i.
+    int tr_addr[4];
+    {
+        const int key = 4 * g + (nn >> 2);
+        const int swz = (key >> 1) & 7;
+#pragma unroll
+        for (int I = 0; I < 4; ++I) {
+            const int c = 2 * I + ((nn & 3) >> 1);
+            tr_addr[I] = key * D + ((c ^ swz) * 8) + (nn & 1) * 4;                           // + half*16*D
+        }
+    }
+
+    f32x4 sig[10], gt[16], muacc[4], yvacc[4];
+#pragma unroll
+    for (int t = 0; t < 10; ++t) sig[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < 16; ++t) gt[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < 4; ++t) { muacc[t] = f32x4{0.f, 0.f, 0.f, 0.f}; yvacc[t] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    float om = 0.f, m = -INFINITY;
+
+    auto issue_dma = [&](int step) {      // rows beyond the cache are clamped (their weights are 0)
+        bf16_t *dst = mystage + (step % NSTAGE) * STAGE_H;
+        const int j0 = r0 + step * STEP;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int j = min(j0 + dma_key[t], L - 1);
+            dma16(Kh + (int64_t)j * sk.seq + dma_col[t], dst + 512 * t);
+            dma16(Vh + (int64_t)j * sv.seq + dma_col[t], dst + TILE_H + 512 * t);
+        }
+    };
+
+    // NSTAGE-1 stages in flight; every step issues exactly one more stage (clamped past the end) so
+    // that "vmcnt <= 8 (NSTAGE-1)" always means "the oldest stage has landed"
+    issue_dma(0);
+    issue_dma(1);
+    for (int s = 0; s < nsteps; ++s) {
+        issue_dma(s + NSTAGE - 1);
+        dma_wait_pending<DMA_PER_STAGE *(NSTAGE - 1)>();
+        const bf16_t *kt = mystage + (s % NSTAGE) * STAGE_H;
+        const bf16_t *vt = kt + TILE_H;
+        const int j0 = r0 + s * STEP;
+
+        // logits of the 32 keys: lane (g, *) gets keys 4g..4g+3 (sub-tile 0) and 16+4g.. (sub-tile 1)
+        float tl[8];
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            const bf16x8 k0 = *reinterpret_cast<const bf16x8 *>(kt + sub * 16 * D + nat0);
+            const bf16x8 k1 = *reinterpret_cast<const bf16x8 *>(kt + sub * 16 * D + nat1);
+            f32x4 z = {0.f, 0.f, 0.f, 0.f};
+            z = mfma_bf16(k0, qf[0], z);
+            z = mfma_bf16(k1, qf[1], z);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int j = j0 + 16 * sub + 4 * g + r;
+                tl[4 * sub + r] = (j < r1) ? z[r] * cscale : -INFINITY;
+            }
+        }
+        // running maximum over the wave's keys; the accumulators are rescaled only when it moves
+        float mx = fmaxf(fmaxf(fmaxf(tl[0], tl[1]), fmaxf(tl[2], tl[3])), fmaxf(fmaxf(tl[4], tl[5]), fmaxf(tl[6], tl[7])));
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        if (__builtin_amdgcn_readfirstlane(mx > m ? 1 : 0)) {
+            const float alpha = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - mx);
+            m = mx;
+            om *= alpha;
+#pragma unroll
+            for (int t = 0; t < 10; ++t) sig[t] *= alpha;
+#pragma unroll
+            for (int t = 0; t < 16; ++t) gt[t] *= alpha;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) { muacc[t] *= alpha; yvacc[t] *= alpha; }
+        }
+        half8 wq;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            wq[t] = (_Float16)__builtin_amdgcn_exp2f(tl[t] - m);      // exp2(-inf) = 0 masks the tail
+            om += (float)wq[t];
+        }
+
+        // transposed K and V fragments (bf16 -> f16, exact): slot t < 4 = key 4g+t, t >= 4 = key 16+4g+t-4
+        half8 kf[4], vf[4];
+#pragma unroll
+        for (int I = 0; I < 4; ++I) {
+            const short4v ka = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(kt + tr_addr[I]));
+            const short4v kb = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(kt + 16 * D + tr_addr[I]));
+            const short4v va = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(vt + tr_addr[I]));
+            const short4v vb = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(vt + 16 * D + tr_addr[I]));
+            const uint2 kau = __builtin_bit_cast(uint2, ka), kbu = __builtin_bit_cast(uint2, kb);
+            const uint2 vau = __builtin_bit_cast(uint2, va), vbu = __builtin_bit_cast(uint2, vb);
+            const uint4 kp = make_uint4(bf16x2_to_f16x2(kau.x), bf16x2_to_f16x2(kau.y), bf16x2_to_f16x2(kbu.x),
+                                        bf16x2_to_f16x2(kbu.y));
+            const uint4 vp = make_uint4(bf16x2_to_f16x2(vau.x), bf16x2_to_f16x2(vau.y), bf16x2_to_f16x2(vbu.x),
+                                        bf16x2_to_f16x2(vbu.y));
+            kf[I] = __builtin_bit_cast(half8, kp);
+            vf[I] = __builtin_bit_cast(half8, vp);
+        }
+#pragma unroll
+        for (int I = 0; I < 4; ++I) {
+            const half8 af = kf[I] * wq;
+#pragma unroll
+            for (int J = I; J < 4; ++J) sig[tix(I, J)] = mfma_f16(af, kf[J], sig[tix(I, J)]);
+#pragma unroll
+            for (int J = 0; J < 4; ++J) gt[4 * I + J] = mfma_f16(af, vf[J], gt[4 * I + J]);
+        }
+#pragma unroll
+        for (int J = 0; J < 4; ++J) {
+            muacc[J] = mfma_f16(wq, kf[J], muacc[J]);       // every row of the tile = mu~[16J + nn]
+            yvacc[J] = mfma_f16(wq, vf[J], yvacc[J]);       // every row = (sum w v)[16J + nn]
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // drain the clamped tail DMAs before the wave ends
+
+    om += __shfl_xor(om, 16);
+    om += __shfl_xor(om, 32);
+    float *P = parts + ((size_t)bh * nparts + part) * PART_F;
+    if (lane == 0) { P[0] = m; P[1] = om; }
+    if (g == 0) {
+#pragma unroll
+        for (int J = 0; J < 4; ++J) { P[64 + 16 * J + nn] = muacc[J][0]; P[128 + 16 * J + nn] = yvacc[J][0]; }
+    }
+#pragma unroll
+    for (int t = 0; t < 10; ++t) *reinterpret_cast<f32x4 *>(P + 192 + t * 256 + lane * 4) = sig[t];
+#pragma unroll
+    for (int t = 0; t < 16; ++t) *reinterpret_cast<f32x4 *>(P + 192 + (10 + t) * 256 + lane * 4) = gt[t];
+}
+
+// merge the partials of 4 heads per wave, solve, and write o
+__global__ __launch_bounds__(64) void decode_merge_kernel(const bf16_t *__restrict__ qg, const float *__restrict__ parts,
+                                                          int BH, int nparts, float lambda, void *__restrict__ og,
+                                                          int out_bf16)
+{
+    __shared__ __align__(16) float scw[QW * 16 * SC_PITCH];
+    __shared__ float mus[QW][D], yvs[QW][D], fac[QW][16];
+    const int lane = threadIdx.x, g = lane / 16, nn = lane % 16;
+
+    f32x4 acc[QW][10];
+    float om4[QW];
+#pragma unroll
+    for (int q = 0; q < QW; ++q) {
+        const int hq = min((int)blockIdx.x * QW + q, BH - 1);
+        const float *P0 = parts + (size_t)hq * nparts * PART_F;
+        float mstar = -INFINITY;
+        for (int p = 0; p < nparts; ++p) mstar = fmaxf(mstar, P0[(size_t)p * PART_F]);
+        float om = 0.f, mu = 0.f, yv = 0.f;
+#pragma unroll
+        for (int t = 0; t < 10; ++t) acc[q][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int p = 0; p < nparts; ++p) {
+            const float *P = P0 + (size_t)p * PART_F;
+            const float mp = P[0];
+            const float f = (mp == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mp - mstar);
+            if (lane == 0 && p < 16) fac[q][p] = f;
+            om = fmaf(f, P[1], om);
+            mu = fmaf(f, P[64 + lane], mu);
+            yv = fmaf(f, P[128 + lane], yv);
+#pragma unroll
+            for (int t = 0; t < 10; ++t) {
+                const f32x4 v = *reinterpret_cast<const f32x4 *>(P + 192 + t * 256 + lane * 4);
+                acc[q][t] += f * v;
+            }
+        }
+        om4[q] = om;
+        mus[q][lane] = mu;
+        yvs[q][lane] = yv;
+    }
+    __syncthreads();
+
+    f32x4 rhs[QW][4];
+#pragma unroll
+    for (int q = 0; q < QW; ++q) {
+        const int hq = min((int)blockIdx.x * QW + q, BH - 1);
+#pragma unroll
+        for (int P = 0; P < 4; ++P)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int row = 16 * P + 4 * g + t;
+                float v = 0.f;
+                if (nn == 0) v = mus[q][row];
+                if (nn == 1) v = bf16_to_f32(qg[(size_t)hq * D + row]);
+                rhs[q][P][t] = v;
+            }
+    }
+    float y0v[QW];
+    solve_wave(acc, rhs, y0v, om4, scw, lambda, g, nn);
+
+    // o = y0 * (sum w v) + G~^T y1
+#pragma unroll
+    for (int q = 0; q < QW; ++q) {
+        const int hq = (int)blockIdx.x * QW + q;
+        const int hqc = min(hq, BH - 1);
+        const float *P0 = parts + (size_t)hqc * nparts * PART_F;
+        const float y0 = row_bcast<0>(y0v[q]);
+        float y1b[4][4];
+#pragma unroll
+        for (int I = 0; I < 4; ++I)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) y1b[I][t] = row_bcast<0>(rhs[q][I][t]);      // y1[16 I + 4g + t]
+#pragma unroll
+        for (int J = 0; J < 4; ++J) {
+            float s = 0.f;
+            for (int p = 0; p < nparts; ++p) {
+                const float f = fac[q][p & 15];
+                float sp = 0.f;
+#pragma unroll
+                for (int I = 0; I < 4; ++I) {
+                    const f32x4 gv = *reinterpret_cast<const f32x4 *>(P0 + (size_t)p * PART_F + 192 + (10 + 4 * I + J) * 256 + lane * 4);
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) sp = fmaf(gv[t], y1b[I][t], sp);
+                }
+                s = fmaf(f, sp, s);
+            }
+            s += __shfl_xor(s, 16);
+            s += __shfl_xor(s, 32);
+            const float o = fmaf(y0, yvs[q][16 * J + nn], s);
+            if (g == 0 && hq < BH) {
+                if (out_bf16) ((bf16_t *)og)[(size_t)hq * D + 16 * J + nn] = f32_to_bf16(o);
+                else ((float *)og)[(size_t)hq * D + 16 * J + nn] = o;
+            }
+        }
+    }
+}
+
+}  // namespace
+
+bool mfma_decode_supported(int d, llla_dtype in) { return d == D && in == LLLA_BF16; }
+
+size_t mfma_decode_workspace_bytes(int B, int H, int L_max, int d, llla_dtype in)
+{
+    if (!mfma_decode_supported(d, in) || L_max < MIN_L) return 0;
+    const Split s = make_split(B * H, L_max);
+    return round_up((size_t)B * H * s.nparts * PART_F * sizeof(float), 256);
+}
+
+bool mfma_decode_takes(const Problem &p) { return p.seqlens == nullptr && p.n >= MIN_L; }
+
+hipError_t mfma_decode(const Problem &p)
+{
+    const int bh = p.B * p.H;
+    const Split s = make_split(bh, p.n);
+    float *parts = static_cast<float *>(p.ws);
+    const float cscale = p.scale * LOG2E;
+    stage_mark(p.stream, "decode_partial");
+    hipLaunchKernelGGL(decode_partial_kernel, dim3(s.nsplit, bh), dim3(NT), 0, p.stream, (const bf16_t *)p.Q,
+                       (const bf16_t *)p.K, (const bf16_t *)p.V, p.sk, p.sv, p.H, p.n, s.keys_per_wave, s.nparts, cscale,
+                       parts);
+    stage_mark(p.stream, "decode_merge");
+    hipLaunchKernelGGL(decode_merge_kernel, dim3((bh + QW - 1) / QW), dim3(64), 0, p.stream, (const bf16_t *)p.Q,
+                       parts, bh, s.nparts, p.lambda, p.O, p.out == LLLA_BF16 ? 1 : 0);
+    return hipGetLastError();
+}
 
 }  // namespace llla
