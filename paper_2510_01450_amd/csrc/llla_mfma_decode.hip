@@ -19,7 +19,7 @@ namespace {
 using namespace mfma;
 
 constexpr int STEP = 32;                       // keys per MFMA step
-constexpr int NSTAGE = 3;                      // LDS stages per wave; NSTAGE-1 are in flight
+constexpr int NSTAGE = 2;                      // LDS stages per wave; NSTAGE-1 are in flight
 constexpr int TILE_H = STEP * D;               // halves of one natural [32 keys][64] tile (4 KB)
 constexpr int STAGE_H = 2 * TILE_H;            // K tile + V tile
 constexpr int DMA_PER_STAGE = 8;
@@ -43,7 +43,7 @@ Split make_split(int bh, int L)
     int most = L / (4 * 8 * STEP);                   // at least 8 steps per wave
     if (most < 1) most = 1;
     s.nsplit = want < 1 ? 1 : (want > most ? most : want);
-    if (s.nsplit > 4) s.nsplit = 4;                  // the merge kernel keeps at most 16 partial factors per head
+    if (s.nsplit > 8) s.nsplit = 8;
     const int waves = 4 * s.nsplit;
     s.keys_per_wave = ((L + waves - 1) / waves + STEP - 1) / STEP * STEP;
     s.nparts = waves;
@@ -60,13 +60,13 @@ __device__ inline unsigned bf16x2_to_f16x2(unsigned u)
 template <int N>
 __device__ inline void dma_wait_pending() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-__global__ __launch_bounds__(NT, 1) void decode_partial_kernel(const bf16_t *__restrict__ qg,
+__global__ __launch_bounds__(NT, 2) void decode_partial_kernel(const bf16_t *__restrict__ qg,
                                                                const bf16_t *__restrict__ Kg,
                                                                const bf16_t *__restrict__ Vg, llla_strides sk,
                                                                llla_strides sv, int H, int L, int keys_per_wave,
                                                                int nparts, float cscale, float *__restrict__ parts)
 {
-    __shared__ __align__(16) bf16_t stage[4][NSTAGE][STAGE_H];     // 4 waves x 3 stages x 8 KB
+    __shared__ __align__(16) bf16_t stage[4][NSTAGE][STAGE_H];     // 4 waves x NSTAGE stages x 8 KB
 
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64, g = lane / 16,
               nn = lane % 16;
@@ -131,8 +131,8 @@ __global__ __launch_bounds__(NT, 1) void decode_partial_kernel(const bf16_t *__r
 
     // NSTAGE-1 stages in flight; every step issues exactly one more stage (clamped past the end) so
     // that "vmcnt <= 8 (NSTAGE-1)" always means "the oldest stage has landed"
-    issue_dma(0);
-    issue_dma(1);
+#pragma unroll
+    for (int st = 0; st < NSTAGE - 1; ++st) issue_dma(st);
     for (int s = 0; s < nsteps; ++s) {
         issue_dma(s + NSTAGE - 1);
         dma_wait_pending<DMA_PER_STAGE *(NSTAGE - 1)>();
@@ -224,93 +224,96 @@ __global__ __launch_bounds__(NT, 1) void decode_partial_kernel(const bf16_t *__r
     for (int t = 0; t < 16; ++t) *reinterpret_cast<f32x4 *>(P + 192 + (10 + t) * 256 + lane * 4) = gt[t];
 }
 
-// merge the partials of 4 heads per wave, solve, and write o
-__global__ __launch_bounds__(64) void decode_merge_kernel(const bf16_t *__restrict__ qg, const float *__restrict__ parts,
-                                                          int BH, int nparts, float lambda, void *__restrict__ og,
-                                                          int out_bf16)
+// Merge, solve, output for 4 heads per workgroup (4 waves):
+//   phase 1  wave w sums the partial moments of head 4*block + w with the max-rescale factors
+//            2^(m_p - m*) into LDS (the merge step of Algorithm 1's running maximum);
+//   phase 2  wave 0 solves the four systems together (solve_wave works on four queries per wave);
+//   phase 3  wave w forms o = y0 * (sum w v) + G~^T y1 for its head.
+__global__ __launch_bounds__(NT, 1) void decode_merge_kernel(const bf16_t *__restrict__ qg, const float *__restrict__ parts,
+                                                             int BH, int nparts, float lambda, void *__restrict__ og,
+                                                             int out_bf16)
 {
+    __shared__ __align__(16) float merged[QW][NTILES][256];
     __shared__ __align__(16) float scw[QW * 16 * SC_PITCH];
-    __shared__ float mus[QW][D], yvs[QW][D], fac[QW][16];
-    const int lane = threadIdx.x, g = lane / 16, nn = lane % 16;
+    __shared__ float mus[QW][D], yvs[QW][D], oms[QW], ys[QW][D + 4];
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64, g = lane / 16,
+              nn = lane % 16;
 
-    f32x4 acc[QW][10];
-    float om4[QW];
-#pragma unroll
-    for (int q = 0; q < QW; ++q) {
-        const int hq = min((int)blockIdx.x * QW + q, BH - 1);
+    {   // phase 1
+        const int hq = min((int)blockIdx.x * QW + wave, BH - 1);
         const float *P0 = parts + (size_t)hq * nparts * PART_F;
         float mstar = -INFINITY;
         for (int p = 0; p < nparts; ++p) mstar = fmaxf(mstar, P0[(size_t)p * PART_F]);
         float om = 0.f, mu = 0.f, yv = 0.f;
+        f32x4 acc[NTILES];
 #pragma unroll
-        for (int t = 0; t < 10; ++t) acc[q][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < NTILES; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
         for (int p = 0; p < nparts; ++p) {
             const float *P = P0 + (size_t)p * PART_F;
             const float mp = P[0];
             const float f = (mp == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mp - mstar);
-            if (lane == 0 && p < 16) fac[q][p] = f;
             om = fmaf(f, P[1], om);
             mu = fmaf(f, P[64 + lane], mu);
             yv = fmaf(f, P[128 + lane], yv);
 #pragma unroll
-            for (int t = 0; t < 10; ++t) {
-                const f32x4 v = *reinterpret_cast<const f32x4 *>(P + 192 + t * 256 + lane * 4);
-                acc[q][t] += f * v;
-            }
+            for (int t = 0; t < NTILES; ++t) acc[t] += f * *reinterpret_cast<const f32x4 *>(P + 192 + t * 256 + lane * 4);
         }
-        om4[q] = om;
-        mus[q][lane] = mu;
-        yvs[q][lane] = yv;
+#pragma unroll
+        for (int t = 0; t < NTILES; ++t) *reinterpret_cast<f32x4 *>(&merged[wave][t][lane * 4]) = acc[t];
+        mus[wave][lane] = mu;
+        yvs[wave][lane] = yv;
+        if (lane == 0) oms[wave] = om;
     }
     __syncthreads();
 
-    f32x4 rhs[QW][4];
+    if (wave == 0) {   // phase 2 (scalar branch: the block contains MFMAs)
+        f32x4 acc[QW][10], rhs[QW][4];
+        float om4[QW], y0v[QW];
 #pragma unroll
-    for (int q = 0; q < QW; ++q) {
-        const int hq = min((int)blockIdx.x * QW + q, BH - 1);
+        for (int q = 0; q < QW; ++q) {
+            const int hq = min((int)blockIdx.x * QW + q, BH - 1);
+            om4[q] = oms[q];
 #pragma unroll
-        for (int P = 0; P < 4; ++P)
+            for (int t = 0; t < 10; ++t) acc[q][t] = *reinterpret_cast<const f32x4 *>(&merged[q][t][lane * 4]);
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int row = 16 * P + 4 * g + t;
-                float v = 0.f;
-                if (nn == 0) v = mus[q][row];
-                if (nn == 1) v = bf16_to_f32(qg[(size_t)hq * D + row]);
-                rhs[q][P][t] = v;
+            for (int P = 0; P < 4; ++P)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int row = 16 * P + 4 * g + t;
+                    float v = 0.f;
+                    if (nn == 0) v = mus[q][row];
+                    if (nn == 1) v = bf16_to_f32(qg[(size_t)hq * D + row]);
+                    rhs[q][P][t] = v;
+                }
+        }
+        solve_wave(acc, rhs, y0v, om4, scw, lambda, g, nn);
+        if (nn == 0) {
+#pragma unroll
+            for (int q = 0; q < QW; ++q) {
+#pragma unroll
+                for (int P = 0; P < 4; ++P) *reinterpret_cast<f32x4 *>(&ys[q][16 * P + 4 * g]) = rhs[q][P];
+                if (g == 0) ys[q][D] = y0v[q];
             }
+        }
     }
-    float y0v[QW];
-    solve_wave(acc, rhs, y0v, om4, scw, lambda, g, nn);
+    __syncthreads();
 
-    // o = y0 * (sum w v) + G~^T y1
-#pragma unroll
-    for (int q = 0; q < QW; ++q) {
-        const int hq = (int)blockIdx.x * QW + q;
-        const int hqc = min(hq, BH - 1);
-        const float *P0 = parts + (size_t)hqc * nparts * PART_F;
-        const float y0 = row_bcast<0>(y0v[q]);
-        float y1b[4][4];
-#pragma unroll
-        for (int I = 0; I < 4; ++I)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) y1b[I][t] = row_bcast<0>(rhs[q][I][t]);      // y1[16 I + 4g + t]
+    {   // phase 3
+        const int hq = (int)blockIdx.x * QW + wave;
+        const float y0 = ys[wave][D];
 #pragma unroll
         for (int J = 0; J < 4; ++J) {
             float s = 0.f;
-            for (int p = 0; p < nparts; ++p) {
-                const float f = fac[q][p & 15];
-                float sp = 0.f;
 #pragma unroll
-                for (int I = 0; I < 4; ++I) {
-                    const f32x4 gv = *reinterpret_cast<const f32x4 *>(P0 + (size_t)p * PART_F + 192 + (10 + 4 * I + J) * 256 + lane * 4);
+            for (int I = 0; I < 4; ++I) {
+                const f32x4 gv = *reinterpret_cast<const f32x4 *>(&merged[wave][10 + 4 * I + J][lane * 4]);
+                const f32x4 y1 = *reinterpret_cast<const f32x4 *>(&ys[wave][16 * I + 4 * g]);
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) sp = fmaf(gv[t], y1b[I][t], sp);
-                }
-                s = fmaf(f, sp, s);
+                for (int t = 0; t < 4; ++t) s = fmaf(gv[t], y1[t], s);      // G~[16I+4g+t][16J+nn] y1[16I+4g+t]
             }
             s += __shfl_xor(s, 16);
             s += __shfl_xor(s, 32);
-            const float o = fmaf(y0, yvs[q][16 * J + nn], s);
+            const float o = fmaf(y0, yvs[wave][16 * J + nn], s);
             if (g == 0 && hq < BH) {
                 if (out_bf16) ((bf16_t *)og)[(size_t)hq * D + 16 * J + nn] = f32_to_bf16(o);
                 else ((float *)og)[(size_t)hq * D + 16 * J + nn] = o;
@@ -343,7 +346,7 @@ hipError_t mfma_decode(const Problem &p)
                        (const bf16_t *)p.K, (const bf16_t *)p.V, p.sk, p.sv, p.H, p.n, s.keys_per_wave, s.nparts, cscale,
                        parts);
     stage_mark(p.stream, "decode_merge");
-    hipLaunchKernelGGL(decode_merge_kernel, dim3((bh + QW - 1) / QW), dim3(64), 0, p.stream, (const bf16_t *)p.Q,
+    hipLaunchKernelGGL(decode_merge_kernel, dim3((bh + QW - 1) / QW), dim3(NT), 0, p.stream, (const bf16_t *)p.Q,
                        parts, bh, s.nparts, p.lambda, p.O, p.out == LLLA_BF16 ? 1 : 0);
     return hipGetLastError();
 }
