@@ -132,15 +132,21 @@ __device__ inline void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memor
 
 // Exact solve of the wave's QW augmented systems, all in registers / wave-private LDS scratch:
 //   in : acc[q][tix(I,J)]  upper-triangular 16x16 tiles of Sigma~_q (MFMA accumulator layout, lambda not yet added)
-//        rhs[q][P]         tile column with mu~_q in column 0 and q_q in column 1 (other columns 0)
+//        build_rhs(rhs)    fills rhs[q][P], a tile column with mu~_q in column 0 and q_q in column 1 (other
+//                          columns 0); it is called after the factorisation so that the 16 right-hand-side
+//                          registers per query are not live while the diagonal tiles are factorised
 //        om4[q]            omega_q;  scw: >= QW*16*SC_PITCH floats of LDS owned by this wave
 //   out: rhs[q][P] column 0 (lanes nn == 0) = y1_q,  y0v[q] = y0_q (valid in lanes nn == 0)
-// with [omega mu~^T; mu~ Sigma~ + lambda I] [y0; y1] = [1; q].  16-blocked upper Cholesky whose block
-// products are C += A^T B on fp32 MFMA; diagonal tiles of the QW queries are factorised together
-// in (query, row) lanes with DPP row broadcasts.
+// with [omega mu~^T; mu~ Sigma~ + lambda I] [y0; y1] = [1; q].  16-blocked upper Cholesky
+// Sigma~ + lambda I = U^T U whose block products are C += A^T B on fp32 MFMA; diagonal tiles of the QW
+// queries are factorised together in (query, row) lanes with DPP row broadcasts; then forward
+// substitution of both right-hand sides, the Schur step on the intercept, and back substitution.
+template <class BuildRhs>
 __device__ __forceinline__ void solve_wave(f32x4 (&acc)[QW][10], f32x4 (&rhs)[QW][4], float (&y0v)[QW],
-                                           const float (&om4)[QW], float *scw, float lambda, int g, int nn)
+                                           const float (&om4)[QW], float *scw, float lambda, int g, int nn,
+                                           BuildRhs build_rhs)
 {
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int q = 0; q < QW; ++q)
 #pragma unroll
@@ -148,6 +154,7 @@ __device__ __forceinline__ void solve_wave(f32x4 (&acc)[QW][10], f32x4 (&rhs)[QW
 #pragma unroll
             for (int t = 0; t < 4; ++t) acc[q][tix(P, P)][t] += (nn == 4 * g + t) ? lambda : 0.f;
 
+    // ---- factorisation: afterwards acc(P,J), P < J, holds U(P,J) and acc(P,P) holds U(P,P)^{-1} -----------
 #pragma unroll
     for (int P = 0; P < 4; ++P) {
         // diagonal tiles -> (query, row) lanes, symmetrised
@@ -179,27 +186,31 @@ __device__ __forceinline__ void solve_wave(f32x4 (&acc)[QW][10], f32x4 (&rhs)[QW
         wave_sync();
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
-            const float *tq = scw + q * 16 * SC_PITCH;
-            // U^{-1} in tile layout: reg t = Uinv[4g+t][nn] = Linv[nn][4g+t]
-            const f32x4 ui = *reinterpret_cast<const f32x4 *>(tq + nn * SC_PITCH + 4 * g);
-            // L^{-1} in tile layout (kept in the slot of the consumed diagonal tile for the back substitution)
-            f32x4 lt;
-#pragma unroll
-            for (int t = 0; t < 4; ++t) lt[t] = tq[(4 * g + t) * SC_PITCH + nn];
-            acc[q][tix(P, P)] = lt;
-            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+            // U^{-1} in tile layout: reg t = Uinv[4g+t][nn] = Linv[nn][4g+t]; it replaces the consumed diagonal tile
+            const f32x4 ui = *reinterpret_cast<const f32x4 *>(scw + q * 16 * SC_PITCH + nn * SC_PITCH + 4 * g);
+            acc[q][tix(P, P)] = ui;
 #pragma unroll
             for (int J = P + 1; J < 4; ++J) acc[q][tix(P, J)] = tile_atb(zero, ui, acc[q][tix(P, J)]);
-            rhs[q][P] = tile_atb(zero, ui, rhs[q][P]);
 #pragma unroll
             for (int I = P + 1; I < 4; ++I) {
                 const f32x4 neg = -acc[q][tix(P, I)];
 #pragma unroll
                 for (int J = I; J < 4; ++J) acc[q][tix(I, J)] = tile_atb(acc[q][tix(I, J)], neg, acc[q][tix(P, J)]);
-                rhs[q][I] = tile_atb(rhs[q][I], neg, rhs[q][P]);
             }
         }
         wave_sync();
+    }
+
+    // ---- forward substitution of [mu~ q]:  r_P <- Uinv_P^T (r_P - sum_{I<P} U(I,P)^T r_I) ----------------
+    build_rhs(rhs);
+#pragma unroll
+    for (int P = 0; P < 4; ++P) {
+#pragma unroll
+        for (int q = 0; q < QW; ++q) {
+            rhs[q][P] = tile_atb(zero, acc[q][tix(P, P)], rhs[q][P]);
+#pragma unroll
+            for (int I = P + 1; I < 4; ++I) rhs[q][I] = tile_atb(rhs[q][I], -acc[q][tix(P, I)], rhs[q][P]);
+        }
     }
 
     // rhs[q][P]: column 0 = a = U^{-T} mu~, column 1 = c = U^{-T} q.  Schur step on the intercept:
@@ -218,8 +229,7 @@ __device__ __forceinline__ void solve_wave(f32x4 (&acc)[QW][10], f32x4 (&rhs)[QW
             }
         saa += __shfl_xor(saa, 16); saa += __shfl_xor(saa, 32);
         sac += __shfl_xor(sac, 16); sac += __shfl_xor(sac, 32);
-        const float om = om4[q];
-        const float y0 = (1.f - sac) / (om - saa);           // valid in lanes nn == 0
+        const float y0 = (1.f - sac) / (om4[q] - saa);       // valid in lanes nn == 0
         y0v[q] = y0;
 #pragma unroll
         for (int P = 0; P < 4; ++P)
@@ -231,30 +241,28 @@ __device__ __forceinline__ void solve_wave(f32x4 (&acc)[QW][10], f32x4 (&rhs)[QW
             }
     }
 
-    // back substitution, block rows 3..0:  x_P = Uinv_P (t_P - sum_{J>P} U(P,J) x_J)
+    // ---- back substitution, block rows 3..0:  x_P = Uinv_P (t_P - sum_{J>P} U(P,J) x_J).  C += A^T B needs
+    //      the transposes of U(P,J) and of Uinv_P as A: one trip through the scratch tile each ------------
 #pragma unroll
     for (int P = 3; P >= 0; --P) {
 #pragma unroll
-        for (int J = P + 1; J < 4; ++J) {
-            // transpose U(P,J) through the scratch tile so that it can be the A^T operand
+        for (int J = P + 1; J <= 4; ++J) {
+            const bool diag = (J == 4);
 #pragma unroll
             for (int q = 0; q < QW; ++q)
-                *reinterpret_cast<f32x4 *>(scw + q * 16 * SC_PITCH + nn * SC_PITCH + 4 * g) = acc[q][tix(P, J)];
+                *reinterpret_cast<f32x4 *>(scw + q * 16 * SC_PITCH + nn * SC_PITCH + 4 * g) = acc[q][diag ? tix(P, P) : tix(P, J)];
             wave_sync();
 #pragma unroll
             for (int q = 0; q < QW; ++q) {
-                f32x4 ut;
+                f32x4 tr;
 #pragma unroll
-                for (int t = 0; t < 4; ++t) ut[t] = -scw[q * 16 * SC_PITCH + (4 * g + t) * SC_PITCH + nn];
-                rhs[q][P] = tile_atb(rhs[q][P], ut, rhs[q][J]);
+                for (int t = 0; t < 4; ++t) tr[t] = scw[q * 16 * SC_PITCH + (4 * g + t) * SC_PITCH + nn];
+                if (diag) rhs[q][P] = tile_atb(zero, tr, rhs[q][P]);             // Uinv_P r
+                else rhs[q][P] = tile_atb(rhs[q][P], -tr, rhs[q][J]);            // r -= U(P,J) x_J
             }
             wave_sync();
         }
-        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int q = 0; q < QW; ++q) rhs[q][P] = tile_atb(zero, acc[q][tix(P, P)], rhs[q][P]);
     }
-
 }
 
 }  // namespace mfma

@@ -271,22 +271,26 @@ __global__ __launch_bounds__(NT, 1) void decode_merge_kernel(const bf16_t *__res
         float om4[QW], y0v[QW];
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
-            const int hq = min((int)blockIdx.x * QW + q, BH - 1);
             om4[q] = oms[q];
 #pragma unroll
             for (int t = 0; t < 10; ++t) acc[q][t] = *reinterpret_cast<const f32x4 *>(&merged[q][t][lane * 4]);
-#pragma unroll
-            for (int P = 0; P < 4; ++P)
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const int row = 16 * P + 4 * g + t;
-                    float v = 0.f;
-                    if (nn == 0) v = mus[q][row];
-                    if (nn == 1) v = bf16_to_f32(qg[(size_t)hq * D + row]);
-                    rhs[q][P][t] = v;
-                }
         }
-        solve_wave(acc, rhs, y0v, om4, scw, lambda, g, nn);
+        solve_wave(acc, rhs, y0v, om4, scw, lambda, g, nn, [&](f32x4 (&r)[QW][4]) {
+#pragma unroll
+            for (int q = 0; q < QW; ++q) {
+                const int hq = min((int)blockIdx.x * QW + q, BH - 1);
+#pragma unroll
+                for (int P = 0; P < 4; ++P)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const int row = 16 * P + 4 * g + t;
+                        float v = 0.f;
+                        if (nn == 0) v = mus[q][row];
+                        if (nn == 1) v = bf16_to_f32(qg[(size_t)hq * D + row]);
+                        r[q][P][t] = v;
+                    }
+            }
+        });
         if (nn == 0) {
 #pragma unroll
             for (int q = 0; q < QW; ++q) {

@@ -471,30 +471,28 @@ __device__ __forceinline__ void moments_body(MomentsShared &sm, const bf16_t *__
     if (tid < QB) oms[tid] = (omp[0][tid] + omp[1][tid]) + (omp[2][tid] + omp[3][tid]);
     __syncthreads();
 
-    // ---- per-query solve: 16-blocked upper Cholesky with the right-hand sides [mu~ q] as a fifth
-    //      block column; all block products are C += A^T B on fp32 MFMA -----------------------------
+    // ---- per-query solve (see solve_wave); the right-hand sides [mu~ q] are built inside it ----------
     f32x4 rhs[QW][4];
-#pragma unroll
-    for (int q = 0; q < QW; ++q) {
-        const int qi = QW * wave + q;
-        const bf16_t *qrow = Qh + (int64_t)min(i0 + qi, n - 1) * sq.seq;
-#pragma unroll
-        for (int P = 0; P < 4; ++P) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int row = 16 * P + 4 * g + t;
-                float v = 0.f;
-                if (nn == 0) v = mus[qi][row];
-                if (nn == 1) v = bf16_to_f32(qrow[row]);
-                rhs[q][P][t] = v;
-            }
-        }
-    }
-
     float y0v[QW], om4[QW];
 #pragma unroll
     for (int q = 0; q < QW; ++q) om4[q] = oms[QW * wave + q];
-    solve_wave(acc, rhs, y0v, om4, &sc[wave][0][0], lambda, g, nn);
+    solve_wave(acc, rhs, y0v, om4, &sc[wave][0][0], lambda, g, nn, [&](f32x4 (&r)[QW][4]) {
+#pragma unroll
+        for (int q = 0; q < QW; ++q) {
+            const int qi = QW * wave + q;
+            const bf16_t *qrow = Qh + (int64_t)min(i0 + qi, n - 1) * sq.seq;
+#pragma unroll
+            for (int P = 0; P < 4; ++P)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int row = 16 * P + 4 * g + t;
+                    float v = 0.f;
+                    if (nn == 0) v = mus[qi][row];
+                    if (nn == 1) v = bf16_to_f32(qrow[row]);
+                    r[q][P][t] = v;
+                }
+        }
+    });
 
 #pragma unroll
     for (int q = 0; q < QW; ++q) {
