@@ -26,6 +26,13 @@ PEAK_MFMA_16BIT = 2.5e15      # dense bf16/f16 MFMA, flop/s
 PEAK_FP32_VALU = 157.3e12     # fp32 vector, flop/s
 PEAK_HBM = 8.0e12             # B/s
 
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# same command, scaled with a copy kernel of known size (profiles/*_hbm_traffic.md, *_mfma_counters.md).
+MEASURED_TRAFFIC = {
+    ("C5_decode_bf16_L32768_d64", "decode_partial"): 4.325e9 + 0.111e9,
+    ("C3_prefill_bf16_n4096_d64", "moments"): 2.26e9 + 1.92e9,
+}
+
 
 def forward_flops(B, H, n, d):
     """Algorithmic flops of a causal forward: symmetric half of the second moment and the solve."""
@@ -154,6 +161,7 @@ def main():
             roof["mfma_issued_tflops"] = issued / (dom_ms * 1e-3) / 1e12
             roof["mfma_issued_frac_of_16bit_peak"] = roof["mfma_issued_tflops"] / (PEAK_MFMA_16BIT / 1e12)
     roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = MEASURED_TRAFFIC.get((w.name, dom))
 
     result = {
         "metric": "LLA causal forward tokens/s" if not decode else "LLA decode generated tokens/s",
