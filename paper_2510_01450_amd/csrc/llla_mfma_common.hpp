@@ -12,14 +12,26 @@ typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int D = 64;          // head dimension of this path
-constexpr int KB = 32;         // keys per block
-constexpr int NT = 256;        // threads per workgroup (4 waves)
-constexpr int QW = 4;          // queries per wave in the moments kernel
-constexpr int QB = 16;         // queries per workgroup in the moments kernel
-constexpr int YP = D + 4;      // pitch of a y row in the workspace: y1[0..D), y0 at [D]
-constexpr int EARLY_ROWS = 4 * D;
+constexpr int KB = 32;         // keys per workspace tile / MFMA step
 constexpr float LOG2E = 1.4426950408889634f;
+
+// Shape of the matrix-core kernels for head dimension DD (64 or 128).  The second moment of one
+// query is NTILE upper-triangular 16x16 fp32 tiles = 4*NTILE accumulator registers per lane, which
+// fixes how many queries a wave can carry: 4 at d = 64 (160 registers), 1 at d = 128 (144).
+template <int DD>
+struct Shape {
+    static constexpr int D = DD;
+    static constexpr int NB = DD / 16;                 // 16-wide feature blocks
+    static constexpr int NTILE = NB * (NB + 1) / 2;    // upper-triangular tiles
+    static constexpr int NF = DD / 32;                 // 32-feature steps of a logits MFMA chain
+    static constexpr int QW = (DD == 64) ? 4 : 1;      // queries per wave (moments kernel)
+    static constexpr int NW = NB;                      // waves per workgroup (moments kernel): one mu~ block each
+    static constexpr int QB = QW * NW;                 // queries per workgroup (moments kernel)
+    static constexpr int NT = 64 * NW;                 // threads per workgroup (moments kernel)
+    static constexpr int YP = DD + 4;                  // pitch of a y row in the workspace: y1[0..D), y0 at [D]
+    static constexpr int EARLY_ROWS = 4 * DD;          // rows served by the precise variant
+    __host__ __device__ static constexpr int tix(int I, int J) { return I * NB - I * (I - 1) / 2 + (J - I); }
+};
 
 __device__ inline void wave_sync()
 {
@@ -49,8 +61,6 @@ __device__ inline f32x4 tile_atb(f32x4 c, f32x4 a, f32x4 b)
     for (int kc = 0; kc < 4; ++kc) c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[kc], b[kc], c, 0, 0, 0);
     return c;
 }
-
-__host__ __device__ constexpr int tix(int I, int J) { return I * 4 - I * (I - 1) / 2 + (J - I); }
 
 constexpr int SC_PITCH = 20;         // floats per row of a 16x16 scratch tile
 
@@ -141,31 +151,35 @@ __device__ inline void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memor
 // Sigma~ + lambda I = U^T U whose block products are C += A^T B on fp32 MFMA; diagonal tiles of the QW
 // queries are factorised together in (query, row) lanes with DPP row broadcasts; then forward
 // substitution of both right-hand sides, the Schur step on the intercept, and back substitution.
-template <class BuildRhs>
-__device__ __forceinline__ void solve_wave(f32x4 (&acc)[QW][10], f32x4 (&rhs)[QW][4], float (&y0v)[QW],
-                                           const float (&om4)[QW], float *scw, float lambda, int g, int nn,
+template <int DD, class BuildRhs>
+__device__ __forceinline__ void solve_wave(f32x4 (&acc)[Shape<DD>::QW][Shape<DD>::NTILE],
+                                           f32x4 (&rhs)[Shape<DD>::QW][Shape<DD>::NB], float (&y0v)[Shape<DD>::QW],
+                                           const float (&om4)[Shape<DD>::QW], float *scw, float lambda, int g, int nn,
                                            BuildRhs build_rhs)
 {
+    using S = Shape<DD>;
+    constexpr int QW = S::QW, NB = S::NB;
+    const int gq = (g < QW) ? g : QW - 1;       // lane groups beyond the wave's queries shadow the last one
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int q = 0; q < QW; ++q)
 #pragma unroll
-        for (int P = 0; P < 4; ++P)
+        for (int P = 0; P < NB; ++P)
 #pragma unroll
-            for (int t = 0; t < 4; ++t) acc[q][tix(P, P)][t] += (nn == 4 * g + t) ? lambda : 0.f;
+            for (int t = 0; t < 4; ++t) acc[q][S::tix(P, P)][t] += (nn == 4 * g + t) ? lambda : 0.f;
 
     // ---- factorisation: afterwards acc(P,J), P < J, holds U(P,J) and acc(P,P) holds U(P,P)^{-1} -----------
 #pragma unroll
-    for (int P = 0; P < 4; ++P) {
+    for (int P = 0; P < NB; ++P) {
         // diagonal tiles -> (query, row) lanes, symmetrised
 #pragma unroll
         for (int q = 0; q < QW; ++q)
 #pragma unroll
-            for (int t = 0; t < 4; ++t) scw[q * 16 * SC_PITCH + (4 * g + t) * SC_PITCH + nn] = acc[q][tix(P, P)][t];
+            for (int t = 0; t < 4; ++t) scw[q * 16 * SC_PITCH + (4 * g + t) * SC_PITCH + nn] = acc[q][S::tix(P, P)][t];
         wave_sync();
         float a[16], li[16];
         {
-            const float *my = scw + g * 16 * SC_PITCH;
+            const float *my = scw + gq * 16 * SC_PITCH;
 #pragma unroll
             for (int c4 = 0; c4 < 4; ++c4) {
                 const f32x4 v = *reinterpret_cast<const f32x4 *>(my + nn * SC_PITCH + 4 * c4);
@@ -177,7 +191,7 @@ __device__ __forceinline__ void solve_wave(f32x4 (&acc)[QW][10], f32x4 (&rhs)[QW
         }
         wave_sync();
         chol_inv16(a, li, nn);
-        {
+        if (g < QW) {
             float *my = scw + g * 16 * SC_PITCH;
 #pragma unroll
             for (int c4 = 0; c4 < 4; ++c4)
@@ -188,14 +202,14 @@ __device__ __forceinline__ void solve_wave(f32x4 (&acc)[QW][10], f32x4 (&rhs)[QW
         for (int q = 0; q < QW; ++q) {
             // U^{-1} in tile layout: reg t = Uinv[4g+t][nn] = Linv[nn][4g+t]; it replaces the consumed diagonal tile
             const f32x4 ui = *reinterpret_cast<const f32x4 *>(scw + q * 16 * SC_PITCH + nn * SC_PITCH + 4 * g);
-            acc[q][tix(P, P)] = ui;
+            acc[q][S::tix(P, P)] = ui;
 #pragma unroll
-            for (int J = P + 1; J < 4; ++J) acc[q][tix(P, J)] = tile_atb(zero, ui, acc[q][tix(P, J)]);
+            for (int J = P + 1; J < NB; ++J) acc[q][S::tix(P, J)] = tile_atb(zero, ui, acc[q][S::tix(P, J)]);
 #pragma unroll
-            for (int I = P + 1; I < 4; ++I) {
-                const f32x4 neg = -acc[q][tix(P, I)];
+            for (int I = P + 1; I < NB; ++I) {
+                const f32x4 neg = -acc[q][S::tix(P, I)];
 #pragma unroll
-                for (int J = I; J < 4; ++J) acc[q][tix(I, J)] = tile_atb(acc[q][tix(I, J)], neg, acc[q][tix(P, J)]);
+                for (int J = I; J < NB; ++J) acc[q][S::tix(I, J)] = tile_atb(acc[q][S::tix(I, J)], neg, acc[q][S::tix(P, J)]);
             }
         }
         wave_sync();
@@ -204,12 +218,12 @@ __device__ __forceinline__ void solve_wave(f32x4 (&acc)[QW][10], f32x4 (&rhs)[QW
     // ---- forward substitution of [mu~ q]:  r_P <- Uinv_P^T (r_P - sum_{I<P} U(I,P)^T r_I) ----------------
     build_rhs(rhs);
 #pragma unroll
-    for (int P = 0; P < 4; ++P) {
+    for (int P = 0; P < NB; ++P) {
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
-            rhs[q][P] = tile_atb(zero, acc[q][tix(P, P)], rhs[q][P]);
+            rhs[q][P] = tile_atb(zero, acc[q][S::tix(P, P)], rhs[q][P]);
 #pragma unroll
-            for (int I = P + 1; I < 4; ++I) rhs[q][I] = tile_atb(rhs[q][I], -acc[q][tix(P, I)], rhs[q][P]);
+            for (int I = P + 1; I < NB; ++I) rhs[q][I] = tile_atb(rhs[q][I], -acc[q][S::tix(P, I)], rhs[q][P]);
         }
     }
 
@@ -219,7 +233,7 @@ __device__ __forceinline__ void solve_wave(f32x4 (&acc)[QW][10], f32x4 (&rhs)[QW
     for (int q = 0; q < QW; ++q) {
         float saa = 0.f, sac = 0.f;
 #pragma unroll
-        for (int P = 0; P < 4; ++P)
+        for (int P = 0; P < NB; ++P)
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const float v = rhs[q][P][t];
@@ -232,7 +246,7 @@ __device__ __forceinline__ void solve_wave(f32x4 (&acc)[QW][10], f32x4 (&rhs)[QW
         const float y0 = (1.f - sac) / (om4[q] - saa);       // valid in lanes nn == 0
         y0v[q] = y0;
 #pragma unroll
-        for (int P = 0; P < 4; ++P)
+        for (int P = 0; P < NB; ++P)
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const float av = rhs[q][P][t];
@@ -244,13 +258,13 @@ __device__ __forceinline__ void solve_wave(f32x4 (&acc)[QW][10], f32x4 (&rhs)[QW
     // ---- back substitution, block rows 3..0:  x_P = Uinv_P (t_P - sum_{J>P} U(P,J) x_J).  C += A^T B needs
     //      the transposes of U(P,J) and of Uinv_P as A: one trip through the scratch tile each ------------
 #pragma unroll
-    for (int P = 3; P >= 0; --P) {
+    for (int P = NB - 1; P >= 0; --P) {
 #pragma unroll
-        for (int J = P + 1; J <= 4; ++J) {
-            const bool diag = (J == 4);
+        for (int J = P + 1; J <= NB; ++J) {
+            const bool diag = (J == NB);
 #pragma unroll
             for (int q = 0; q < QW; ++q)
-                *reinterpret_cast<f32x4 *>(scw + q * 16 * SC_PITCH + nn * SC_PITCH + 4 * g) = acc[q][diag ? tix(P, P) : tix(P, J)];
+                *reinterpret_cast<f32x4 *>(scw + q * 16 * SC_PITCH + nn * SC_PITCH + 4 * g) = acc[q][diag ? S::tix(P, P) : S::tix(P, J)];
             wave_sync();
 #pragma unroll
             for (int q = 0; q < QW; ++q) {

@@ -18,6 +18,10 @@ namespace {
 
 using namespace mfma;
 
+using S64 = Shape<64>;
+constexpr int D = S64::D, QW = S64::QW, NT = 256;
+__host__ __device__ constexpr int tix(int I, int J) { return S64::tix(I, J); }
+
 constexpr int STEP = 32;                       // keys per MFMA step
 constexpr int NSTAGE = 2;                      // LDS stages per wave; NSTAGE-1 are in flight
 constexpr int TILE_H = STEP * D;               // halves of one natural [32 keys][64] tile (4 KB)
@@ -275,7 +279,7 @@ __global__ __launch_bounds__(NT, 1) void decode_merge_kernel(const bf16_t *__res
 #pragma unroll
             for (int t = 0; t < 10; ++t) acc[q][t] = *reinterpret_cast<const f32x4 *>(&merged[q][t][lane * 4]);
         }
-        solve_wave(acc, rhs, y0v, om4, scw, lambda, g, nn, [&](f32x4 (&r)[QW][4]) {
+        solve_wave<64>(acc, rhs, y0v, om4, scw, lambda, g, nn, [&](f32x4 (&r)[QW][4]) {
 #pragma unroll
             for (int q = 0; q < QW; ++q) {
                 const int hq = min((int)blockIdx.x * QW + q, BH - 1);

@@ -1,4 +1,4 @@
-// Matrix-core (MFMA) forward path of Local Linear Attention for gfx950: bf16 inputs, d = 64.
+// Matrix-core (MFMA) forward path of Local Linear Attention for gfx950: bf16 inputs, d = 64 or 128.
 //
 // Stages (all on the caller's stream, workspace holds only Theta(B*H*n*d) data):
 //   prep    K -> f16, V -> bf16, both re-tiled as [key block of 32][feature][key] so that MFMA
@@ -26,6 +26,7 @@ struct Layout {
     int nkb, npad;
 };
 
+template <int DD>
 Layout make_layout(int B, int H, int n)
 {
     Layout L;
@@ -33,26 +34,27 @@ Layout make_layout(int B, int H, int n)
     L.npad = L.nkb * KB;
     const size_t bh = (size_t)B * H;
     size_t off = 0;
-    L.kt = off; off += round_up(bh * L.npad * D * 2, 256);
-    L.vt = off; off += round_up(bh * L.npad * D * 2, 256);
+    L.kt = off; off += round_up(bh * L.npad * DD * 2, 256);
+    L.vt = off; off += round_up(bh * L.npad * DD * 2, 256);
     L.m = off;  off += round_up(bh * L.npad * 4, 256);
-    L.y = off;  off += round_up(bh * (size_t)n * YP * 4, 256);
+    L.y = off;  off += round_up(bh * (size_t)n * Shape<DD>::YP * 4, 256);
     L.total = off;
     return L;
 }
 
 // ------------------------------------------------------------------------------------------------
 // prep: re-tile K (-> f16) and V (bf16) as [bh][key block][feature][32 keys]
-__global__ __launch_bounds__(NT) void prep_kernel(const bf16_t *__restrict__ Kg, const bf16_t *__restrict__ Vg,
-                                                  llla_strides sk, llla_strides sv, int H, int n, int nkb,
-                                                  _Float16 *__restrict__ KT, bf16_t *__restrict__ VT)
+template <int DD>
+__global__ __launch_bounds__(256) void prep_kernel(const bf16_t *__restrict__ Kg, const bf16_t *__restrict__ Vg,
+                                                   llla_strides sk, llla_strides sv, int H, int n, int nkb,
+                                                   _Float16 *__restrict__ KT, bf16_t *__restrict__ VT)
 {
-    __shared__ bf16_t tile[2][KB][D + 2];
+    __shared__ bf16_t tile[2][KB][DD + 2];
     const int blk = blockIdx.x, bh = blockIdx.y, b = bh / H, h = bh % H, tid = threadIdx.x;
     const bf16_t *Kh = Kg + b * sk.batch + h * sk.head;
     const bf16_t *Vh = Vg + b * sv.batch + h * sv.head;
-    {
-        const int key = tid / 8, ch = (tid % 8) * 8;
+    for (int idx = tid; idx < KB * (DD / 8); idx += 256) {
+        const int key = idx / (DD / 8), ch = (idx % (DD / 8)) * 8;
         const int j = blk * KB + key;
         uint4 kv = make_uint4(0, 0, 0, 0), vv = kv;
         if (j < n) {
@@ -69,8 +71,8 @@ __global__ __launch_bounds__(NT) void prep_kernel(const bf16_t *__restrict__ Kg,
         }
     }
     __syncthreads();
-    {
-        const int feat = tid / 4, k0 = (tid % 4) * 8;
+    for (int idx = tid; idx < DD * 4; idx += 256) {
+        const int feat = idx / 4, k0 = (idx % 4) * 8;
         half8 ko;
         uint16_t vo[8];
 #pragma unroll
@@ -78,7 +80,7 @@ __global__ __launch_bounds__(NT) void prep_kernel(const bf16_t *__restrict__ Kg,
             ko[i] = (_Float16)bf16_to_f32(tile[0][k0 + i][feat]);
             vo[i] = tile[1][k0 + i][feat];
         }
-        const size_t base = ((size_t)bh * nkb + blk) * (D * KB) + feat * KB + k0;
+        const size_t base = ((size_t)bh * nkb + blk) * (DD * KB) + feat * KB + k0;
         *reinterpret_cast<half8 *>(KT + base) = ko;
         *reinterpret_cast<uint4 *>(VT + base) = make_uint4(vo[0] | (vo[1] << 16), vo[2] | (vo[3] << 16),
                                                            vo[4] | (vo[5] << 16), vo[6] | (vo[7] << 16));
@@ -89,18 +91,20 @@ __global__ __launch_bounds__(NT) void prep_kernel(const bf16_t *__restrict__ Kg,
 // Sweep over S^T = K Q^T for 64 queries per workgroup (16 per wave).
 //   MAXONLY: write the row maxima m_i (in log2 units) -- Algorithm 1's m after its last block.
 //   else   : third loop of Algorithm 1: S = W (y0 + K y1), O = S V.
-constexpr int KN_PITCH = D + 8;      // halves; rows of the natural K tile stay 16-byte aligned
 constexpr int VT_PITCH = KB + 8;     // halves
 
-template <bool MAXONLY>
-__global__ __launch_bounds__(NT) void sweep_kernel(const bf16_t *__restrict__ Qg, const bf16_t *__restrict__ Kg,
-                                                   llla_strides sq, llla_strides sk, int H, int n, int nkb,
-                                                   int first_row, float cscale, const bf16_t *__restrict__ VT,
-                                                   float *__restrict__ Mg, const float *__restrict__ Yg,
-                                                   void *__restrict__ Og, llla_strides so, int out_bf16)
+template <bool MAXONLY, int DD>
+__global__ __launch_bounds__(256) void sweep_kernel(const bf16_t *__restrict__ Qg, const bf16_t *__restrict__ Kg,
+                                                    llla_strides sq, llla_strides sk, int H, int n, int nkb,
+                                                    int first_row, float cscale, const bf16_t *__restrict__ VT,
+                                                    float *__restrict__ Mg, const float *__restrict__ Yg,
+                                                    void *__restrict__ Og, llla_strides so, int out_bf16)
 {
+    using S = Shape<DD>;
+    constexpr int NF = S::NF, NB = S::NB, YP = S::YP;
+    constexpr int KN_PITCH = DD + 8;     // halves; rows of the natural K tile stay 16-byte aligned
     __shared__ __align__(16) bf16_t kn[KB * KN_PITCH];
-    __shared__ __align__(16) bf16_t vt[MAXONLY ? 8 : D * VT_PITCH];
+    __shared__ __align__(16) bf16_t vt[MAXONLY ? 8 : DD * VT_PITCH];
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64, g = lane / 16, nn = lane % 16;
     const int bh = blockIdx.y, b = bh / H, h = bh % H;
     const int nqb = gridDim.x;
@@ -109,19 +113,19 @@ __global__ __launch_bounds__(NT) void sweep_kernel(const bf16_t *__restrict__ Qg
     const int iqc = min(iq, n - 1);
     const bf16_t *Kh = Kg + b * sk.batch + h * sk.head;
     const bf16_t *qrow = Qg + b * sq.batch + h * sq.head + (int64_t)iqc * sq.seq;
-    bf16x8 qf[2];
-    qf[0] = *reinterpret_cast<const bf16x8 *>(qrow + 8 * g);
-    qf[1] = *reinterpret_cast<const bf16x8 *>(qrow + 32 + 8 * g);
+    bf16x8 qf[NF];
+#pragma unroll
+    for (int f = 0; f < NF; ++f) qf[f] = *reinterpret_cast<const bf16x8 *>(qrow + 32 * f + 8 * g);
 
     float mrow = -INFINITY, y0 = 0.f;
-    bf16x8 yh[2], yl[2];
-    f32x4 oacc[4];
+    bf16x8 yh[NF], yl[NF];
+    f32x4 oacc[NB];
     if (!MAXONLY) {
         mrow = Mg[(size_t)bh * (nkb * KB) + iqc];
         const float *yr = Yg + ((size_t)bh * n + iqc) * YP;
-        y0 = yr[D];
+        y0 = yr[DD];
 #pragma unroll
-        for (int f = 0; f < 2; ++f)
+        for (int f = 0; f < NF; ++f)
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
                 const float v = yr[32 * f + 8 * g + t];
@@ -130,7 +134,7 @@ __global__ __launch_bounds__(NT) void sweep_kernel(const bf16_t *__restrict__ Qg
                 yl[f][t] = (__bf16)(v - (float)hi);
             }
 #pragma unroll
-        for (int J = 0; J < 4; ++J) oacc[J] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int J = 0; J < NB; ++J) oacc[J] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
     float mx[2][4];
 #pragma unroll
@@ -142,15 +146,18 @@ __global__ __launch_bounds__(NT) void sweep_kernel(const bf16_t *__restrict__ Qg
     const int nblk = ilast / KB + 1;
     for (int c = 0; c < nblk; ++c) {
         __syncthreads();
-        {   // stage K (natural) and V^T tiles
-            const int key = tid / 8, ch = (tid % 8) * 8;
+        // stage K (natural) and V^T tiles
+        for (int idx = tid; idx < KB * (DD / 8); idx += 256) {
+            const int key = idx / (DD / 8), ch = (idx % (DD / 8)) * 8;
             const int j = c * KB + key;
             uint4 kv = make_uint4(0, 0, 0, 0);
             if (j < n) kv = *reinterpret_cast<const uint4 *>(Kh + (int64_t)j * sk.seq + ch);
             *reinterpret_cast<uint4 *>(&kn[key * KN_PITCH + ch]) = kv;
-            if (!MAXONLY) {
-                const int feat = tid / 4, k0 = (tid % 4) * 8;
-                const uint4 vv = *reinterpret_cast<const uint4 *>(VT + ((size_t)bh * nkb + c) * (D * KB) + feat * KB + k0);
+        }
+        if (!MAXONLY) {
+            for (int idx = tid; idx < DD * 4; idx += 256) {
+                const int feat = idx / 4, k0 = (idx % 4) * 8;
+                const uint4 vv = *reinterpret_cast<const uint4 *>(VT + ((size_t)bh * nkb + c) * (DD * KB) + feat * KB + k0);
                 *reinterpret_cast<uint4 *>(&vt[feat * VT_PITCH + k0]) = vv;
             }
         }
@@ -158,17 +165,20 @@ __global__ __launch_bounds__(NT) void sweep_kernel(const bf16_t *__restrict__ Qg
         f32x4 st[2], ut[2];
 #pragma unroll
         for (int s = 0; s < 2; ++s) {       // two sub-tiles of 16 keys
-            const bf16x8 k0f = *reinterpret_cast<const bf16x8 *>(&kn[(16 * s + nn) * KN_PITCH + 8 * g]);
-            const bf16x8 k1f = *reinterpret_cast<const bf16x8 *>(&kn[(16 * s + nn) * KN_PITCH + 32 + 8 * g]);
+            bf16x8 kf[NF];
+#pragma unroll
+            for (int f = 0; f < NF; ++f) kf[f] = *reinterpret_cast<const bf16x8 *>(&kn[(16 * s + nn) * KN_PITCH + 32 * f + 8 * g]);
             f32x4 z = {0.f, 0.f, 0.f, 0.f};
-            z = mfma_bf16(k0f, qf[0], z);
-            st[s] = mfma_bf16(k1f, qf[1], z);
+#pragma unroll
+            for (int f = 0; f < NF; ++f) z = mfma_bf16(kf[f], qf[f], z);
+            st[s] = z;
             if (!MAXONLY) {
                 f32x4 u = {0.f, 0.f, 0.f, 0.f};
-                u = mfma_bf16(k0f, yl[0], u);
-                u = mfma_bf16(k1f, yl[1], u);
-                u = mfma_bf16(k0f, yh[0], u);
-                ut[s] = mfma_bf16(k1f, yh[1], u);
+#pragma unroll
+                for (int f = 0; f < NF; ++f) u = mfma_bf16(kf[f], yl[f], u);
+#pragma unroll
+                for (int f = 0; f < NF; ++f) u = mfma_bf16(kf[f], yh[f], u);
+                ut[s] = u;
             }
         }
         // lane (g, nn): st[s][r] = <k_j, q_iq> for key j = 32c + 16s + 4g + r
@@ -195,7 +205,7 @@ __global__ __launch_bounds__(NT) void sweep_kernel(const bf16_t *__restrict__ Qg
                     cl[4 * s + r] = (__bf16)(cv - (float)hi);
                 }
 #pragma unroll
-            for (int J = 0; J < 4; ++J) {
+            for (int J = 0; J < NB; ++J) {
                 bf16x8 vf;
                 const uint2 lo = *reinterpret_cast<const uint2 *>(&vt[(16 * J + nn) * VT_PITCH + 4 * g]);
                 const uint2 hi = *reinterpret_cast<const uint2 *>(&vt[(16 * J + nn) * VT_PITCH + 16 + 4 * g]);
@@ -224,7 +234,7 @@ __global__ __launch_bounds__(NT) void sweep_kernel(const bf16_t *__restrict__ Qg
             if (i < n) {
                 const int64_t off = b * so.batch + h * so.head + (int64_t)i * so.seq;
 #pragma unroll
-                for (int J = 0; J < 4; ++J) {
+                for (int J = 0; J < NB; ++J) {
                     if (out_bf16) ((bf16_t *)Og)[off + 16 * J + nn] = f32_to_bf16(oacc[J][r]);
                     else ((float *)Og)[off + 16 * J + nn] = oacc[J][r];
                 }
@@ -237,36 +247,47 @@ __global__ __launch_bounds__(NT) void sweep_kernel(const bf16_t *__restrict__ Qg
 // moments + solve
 constexpr int KB2 = 2 * KB;          // keys per pipeline step of the moments kernel
 constexpr int WT_PITCH = KB2 + 8;    // halves per query row of the weight tile
+constexpr int WT32_PITCH = KB2 + 4;  // floats per query row of the fp32 weight tile (PRECISE)
 // LDS tiles of one 64-key block are stored without padding (the DMA writes whole 1 KB wave rows);
 // 16-byte chunks are XOR-swizzled so that the MFMA operand reads stay free of bank conflicts:
 //   transposed tile (f16) : [sub-tile of 32 keys][feature row r][4 chunks of 8 keys], chunk c of row r at c ^ ((r>>2)&3)
-//   natural tile (bf16)   : [key][8 chunks of 8 features],                             chunk c of key k at c ^ ((k>>1)&7)
-constexpr int KT_SUB = D * KB;       // halves per transposed 32-key sub-tile (4 KB)
-constexpr int KN_TILE = KB2 * D;     // halves per natural 64-key tile (8 KB)
-constexpr int WT32_PITCH = KB2 + 4;  // floats per query row of the fp32 weight tile (PRECISE)
+//   natural tile (bf16)   : [key][d/8 chunks of 8 features], chunk c of key k at c ^ ((k>>1)&7) (d = 64), c ^ (k&15) (d = 128)
+
+template <int DD>
+struct MomentsShared {
+    using S = Shape<DD>;
+    _Float16 kt[2][2][DD * KB];                // transposed K, two buffers x two 32-key sub-tiles
+    bf16_t kn[2][KB2 * DD];                    // natural K, two buffers
+    union {
+        _Float16 h[2][16 * WT_PITCH];          // f16 weights (fast variant), 16 query rows (MFMA width)
+        float f[2][16 * WT32_PITCH];           // fp32 weights (precise variant)
+    } w;
+    float omp[4][16];
+    float mus[16][DD + 4];
+    float oms[16];
+    float sc[S::NW][S::QW][16 * SC_PITCH];     // per-wave scratch tiles of the solve
+};
+
+template <int CH>
+__device__ inline int nat_swizzle(int key) { return CH == 8 ? ((key >> 1) & 7) : (key & 15); }
 
 // PRECISE: fp32 weights and a two-term f16 split of the scaled operand w k, i.e. an fp32-accurate
 // second moment; used for the first rows of a sequence, whose systems are the worst conditioned.
-struct MomentsShared {
-    _Float16 kt[2][2][KT_SUB];                 // transposed K, two buffers x two 32-key sub-tiles
-    bf16_t kn[2][KN_TILE];                     // natural K, two buffers
-    union {
-        _Float16 h[2][QB * WT_PITCH];          // f16 weights (fast variant)
-        float f[2][QB * WT32_PITCH];           // fp32 weights (precise variant)
-    } w;
-    float omp[4][QB];
-    float mus[QB][D + 4];
-    float oms[QB];
-    float sc[4][QW][16 * SC_PITCH];            // per-wave scratch tiles of the solve
-};
-
-template <bool PRECISE>
-__device__ __forceinline__ void moments_body(MomentsShared &sm, const bf16_t *__restrict__ Qg,
+template <bool PRECISE, int DD>
+__device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t *__restrict__ Qg,
                                              const bf16_t *__restrict__ Kg, llla_strides sq, llla_strides sk, int H,
-                                             int n, int nkb, int first_row, float cscale, float lambda,
+                                             int n, int nkb, float cscale, float lambda,
                                              const _Float16 *__restrict__ KT, const float *__restrict__ Mg,
                                              float *__restrict__ Yg)
 {
+    using S = Shape<DD>;
+    constexpr int NB = S::NB, NTILE = S::NTILE, NF = S::NF, QW = S::QW, NW = S::NW, QB = S::QB, YP = S::YP;
+    constexpr int CH = DD / 8;                          // 16-byte chunks of a natural row
+    constexpr int KT_SUB = DD * KB;                     // halves per transposed 32-key sub-tile
+    constexpr int NAT_INSTR = 16 * CH / 64;             // DMA instructions of a weight wave: its 16 keys
+    constexpr int TW = (NW == 4) ? 4 : NW - 4;          // waves that fetch the transposed tiles
+    constexpr int TR_SLOTS = DD * 4 / TW;               // 16-byte slots per sub-tile and such wave
+    constexpr int TR_INSTR = TR_SLOTS / 64;
     auto &kt = sm.kt;
     auto &kn = sm.kn;
     auto &wt = sm.w.h;
@@ -279,76 +300,88 @@ __device__ __forceinline__ void moments_body(MomentsShared &sm, const bf16_t *__
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64, g = lane / 16, nn = lane % 16;
     const int bh = blockIdx.y, b = bh / H, h = bh % H;
     const int nqb = gridDim.x;
-    const int i0 = first_row + (nqb - 1 - (int)blockIdx.x) * QB;       // long rows first
+    const int i0 = (nqb - 1 - (int)blockIdx.x) * QB;                   // long rows first
     const int ilast = min(i0 + QB - 1, n - 1);
     const int nblk = ilast / KB2 + 1;                                  // blocks of 64 keys
     const int mpitch = nkb * KB;
     const bf16_t *Kh = Kg + b * sk.batch + h * sk.head;
     const bf16_t *Qh = Qg + b * sq.batch + h * sq.head;
-    const _Float16 *KTh = KT + (size_t)bh * nkb * (D * KB);
+    const _Float16 *KTh = KT + (size_t)bh * nkb * KT_SUB;
+    const bool w_wave = wave < 4;                       // computes weights: 16 keys x 16 query columns per block
+    const bool t_wave = (NW == 4) || wave >= 4;         // fetches the transposed tiles
+    const int tw = (NW == 4) ? wave : wave - 4;
 
-    // S^T role: lane (g, nn) of wave w serves query i0 + nn and keys 16w + 4g + r of a 64-key block
+    // weight role: lane (g, nn) of wave w < 4 serves query i0 + nn (nn < QB) and keys 16w + 4g + r
     const int iq = i0 + nn, iqc = min(iq, n - 1);
-    bf16x8 qf[2];
+    const bool q_live = nn < QB;
+    bf16x8 qf[NF];
     {
         const bf16_t *qrow = Qh + (int64_t)iqc * sq.seq;
-        qf[0] = *reinterpret_cast<const bf16x8 *>(qrow + 8 * g);
-        qf[1] = *reinterpret_cast<const bf16x8 *>(qrow + 32 + 8 * g);
+#pragma unroll
+        for (int f = 0; f < NF; ++f) qf[f] = *reinterpret_cast<const bf16x8 *>(qrow + 32 * f + 8 * g);
     }
     const float mrow = Mg[(size_t)bh * mpitch + iqc];
 
-    f32x4 acc[QW][10];
+    f32x4 acc[QW][NTILE];
 #pragma unroll
     for (int q = 0; q < QW; ++q)
 #pragma unroll
-        for (int t = 0; t < 10; ++t) acc[q][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < NTILE; ++t) acc[q][t] = f32x4{0.f, 0.f, 0.f, 0.f};
     f32x4 mu_acc = {0.f, 0.f, 0.f, 0.f};
     float om_part = 0.f;            // this lane's share of omega for query i0 + nn
 
     // ---- per-lane constants of the staging and of the operand reads ------------------------------
-    // DMA, transposed tile: this wave fills slots [64 wave, 64 wave + 64) of each 32-key sub-tile
-    const int kts = 64 * wave + lane;                       // slot = row*4 + stored chunk
-    const int kts_row = kts >> 2, kts_col = (kts & 3) ^ ((kts_row >> 2) & 3);
-    const int kt_goff = kts_row * KB + kts_col * 8;         // halves inside a [feature][32 key] sub-tile
-    // DMA, natural tile: this wave fills its own 16 keys (slots [128 wave, 128 wave + 128))
-    int kn_key[2], kn_gcol[2];
+    int tr_goff[TR_INSTR];                                  // halves inside a [feature][32 key] sub-tile
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        const int sl = 128 * wave + 64 * t + lane;          // slot = key*8 + stored chunk
-        kn_key[t] = sl >> 3;
-        kn_gcol[t] = ((sl & 7) ^ ((kn_key[t] >> 1) & 7)) * 8;
+    for (int t = 0; t < TR_INSTR; ++t) {
+        const int sl = tw * TR_SLOTS + 64 * t + lane;       // slot = row*4 + stored chunk
+        const int row = sl >> 2, col = (sl & 3) ^ ((row >> 2) & 3);
+        tr_goff[t] = row * KB + col * 8;
     }
-    // S^T operand reads of the natural tile: key 16 wave + nn, feature chunks g and 4 + g
+    int kn_key[NAT_INSTR], kn_gcol[NAT_INSTR];
+#pragma unroll
+    for (int t = 0; t < NAT_INSTR; ++t) {
+        const int sl = 16 * CH * wave + 64 * t + lane;      // slot = key*CH + stored chunk
+        kn_key[t] = sl / CH;
+        kn_gcol[t] = ((sl % CH) ^ nat_swizzle<CH>(kn_key[t])) * 8;
+    }
+    // logits operand reads of the natural tile: key 16 wave + nn, feature chunks g + 4f
     const int skey = 16 * wave + nn;
-    const int kn_r0 = (skey * 8 + (g ^ ((skey >> 1) & 7))) * 8;
-    const int kn_r1 = (skey * 8 + ((4 + g) ^ ((skey >> 1) & 7))) * 8;
+    int kn_r[NF];
+#pragma unroll
+    for (int f = 0; f < NF; ++f) kn_r[f] = (skey * CH + ((g + 4 * f) ^ nat_swizzle<CH>(skey))) * 8;
     // second-moment operand reads of a transposed sub-tile: feature row 16 I + nn, key chunk g
     const int kt_r = (nn * 4 + (g ^ ((nn >> 2) & 3))) * 8;  // + I * 16 * 32 halves
 
     auto issue_dma = [&](int blk) {     // block blk -> LDS buffer blk & 1
         const int buf = blk & 1;
-        const _Float16 *src = KTh + (size_t)blk * (2 * KT_SUB) + kt_goff;
-        dma16(src, &kt[buf][0][512 * wave]);
-        dma16(src + KT_SUB, &kt[buf][1][512 * wave]);
+        if (t_wave) {
+            const _Float16 *src = KTh + (size_t)blk * (2 * KT_SUB);
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const int j = min(blk * KB2 + kn_key[t], n - 1);
-            dma16(Kh + (int64_t)j * sk.seq + kn_gcol[t], &kn[buf][1024 * wave + 512 * t]);
+            for (int t = 0; t < TR_INSTR; ++t) {
+                dma16(src + tr_goff[t], &kt[buf][0][(tw * TR_SLOTS + 64 * t) * 8]);
+                dma16(src + KT_SUB + tr_goff[t], &kt[buf][1][(tw * TR_SLOTS + 64 * t) * 8]);
+            }
+        }
+        if (w_wave) {
+#pragma unroll
+            for (int t = 0; t < NAT_INSTR; ++t) {
+                const int j = min(blk * KB2 + kn_key[t], n - 1);
+                dma16(Kh + (int64_t)j * sk.seq + kn_gcol[t], &kn[buf][(16 * CH * wave + 64 * t) * 8]);
+            }
         }
     };
     auto make_weights = [&](int blk) {  // w = 2^(c<q,k> - m) for this wave's 16 keys of block blk
         const int buf = blk & 1;
-        const bf16x8 k0 = *reinterpret_cast<const bf16x8 *>(&kn[buf][kn_r0]);
-        const bf16x8 k1 = *reinterpret_cast<const bf16x8 *>(&kn[buf][kn_r1]);
         f32x4 z = {0.f, 0.f, 0.f, 0.f};
-        z = mfma_bf16(k0, qf[0], z);
-        z = mfma_bf16(k1, qf[1], z);
+#pragma unroll
+        for (int f = 0; f < NF; ++f) z = mfma_bf16(*reinterpret_cast<const bf16x8 *>(&kn[buf][kn_r[f]]), qf[f], z);
         float wf[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int j = blk * KB2 + 16 * wave + 4 * g + r;
             const float wgt = __builtin_amdgcn_exp2f(z[r] * cscale - mrow);
-            wf[r] = (j <= iq) ? wgt : 0.f;
+            wf[r] = (q_live && j <= iq) ? wgt : 0.f;
         }
         if (PRECISE) {
             *reinterpret_cast<f32x4 *>(&wt32[buf][nn * WT32_PITCH + 16 * wave + 4 * g]) = f32x4{wf[0], wf[1], wf[2], wf[3]};
@@ -365,12 +398,13 @@ __device__ __forceinline__ void moments_body(MomentsShared &sm, const bf16_t *__
     };
 
     // Software pipeline over blocks of 64 keys: iteration c consumes block c while the DMA of block
-    // c+1 lands; the weights of block c+1 are produced in the middle of the iteration (each wave
+    // c+1 lands; the weights of block c+1 are produced in the middle of the iteration (a weight wave
     // reads only the keys it fetched itself, so its own vmcnt wait suffices).  One barrier per block.
+    // `wave` is a scalar, so every branch around an MFMA below is a real branch (MFMA ignores EXEC).
     issue_dma(0);
     dma_wait();
     __syncthreads();
-    make_weights(0);
+    if (w_wave) make_weights(0);
     __syncthreads();
 
     for (int c = 0; c < nblk; ++c) {
@@ -378,13 +412,16 @@ __device__ __forceinline__ void moments_body(MomentsShared &sm, const bf16_t *__
         if (c + 1 < nblk) issue_dma(c + 1);
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf) {        // two halves of 32 keys
-            half8 bf[4];
+            half8 bf[NB];
 #pragma unroll
-            for (int I = 0; I < 4; ++I) bf[I] = *reinterpret_cast<const half8 *>(&kt[buf][hf][kt_r + I * 512]);
+            for (int I = 0; I < NB; ++I) bf[I] = *reinterpret_cast<const half8 *>(&kt[buf][hf][kt_r + I * 512]);
+            // this wave's feature block for mu~ is re-read from LDS (indexing bf[] by the wave id would
+            // become a per-element select chain)
+            const half8 bw = *reinterpret_cast<const half8 *>(&kt[buf][hf][kt_r + wave * 512]);
             if (!PRECISE) {
-                // One LDS read brings the weights of all 16 queries (lane (g, nn): query (nn + 4 wave) % 16,
-                // keys 8g..8g+7), rotated so that this wave's own queries sit in lanes 0..3 of every row; the
-                // per-query operand scale is then a row broadcast (DPP) instead of four more LDS reads.
+                // One LDS read brings the weights of all 16 query rows (lane (g, nn): row (nn + QW wave) % 16,
+                // keys 8g..8g+7), rotated so that this wave's own queries sit in lanes 0..QW-1 of every lane row;
+                // the per-query operand scale is then a row broadcast (DPP) instead of more LDS reads.
                 const half8 wa = *reinterpret_cast<const half8 *>(&wt[buf][((nn + QW * wave) & 15) * WT_PITCH + 32 * hf + 8 * g]);
                 const f32x4 wau = __builtin_bit_cast(f32x4, wa);
 #pragma unroll
@@ -395,19 +432,13 @@ __device__ __forceinline__ void moments_body(MomentsShared &sm, const bf16_t *__
                                                         : (q == 2) ? row_bcast<2>(wau[t]) : row_bcast<3>(wau[t]);
                     const half8 wq = __builtin_bit_cast(half8, wqu);
 #pragma unroll
-                    for (int I = 0; I < 4; ++I) {
+                    for (int I = 0; I < NB; ++I) {
                         const half8 af = bf[I] * wq;
 #pragma unroll
-                        for (int J = I; J < 4; ++J) acc[q][tix(I, J)] = mfma_f16(af, bf[J], acc[q][tix(I, J)]);
+                        for (int J = I; J < NB; ++J) acc[q][S::tix(I, J)] = mfma_f16(af, bf[J], acc[q][S::tix(I, J)]);
                     }
                 }
-                // mu~[query (4g + r + 4 wave) % 16][feature 16 wave + nn].  `wave` is a scalar (readfirstlane),
-                // so these are real branches: MFMA ignores the EXEC mask and must never sit in a block that is
-                // merely predicated off.
-                if (wave == 0) mu_acc = mfma_f16(wa, bf[0], mu_acc);
-                else if (wave == 1) mu_acc = mfma_f16(wa, bf[1], mu_acc);
-                else if (wave == 2) mu_acc = mfma_f16(wa, bf[2], mu_acc);
-                else mu_acc = mfma_f16(wa, bf[3], mu_acc);
+                mu_acc = mfma_f16(wa, bw, mu_acc);      // mu~[row (4g + r + QW wave) % 16][feature 16 wave + nn]
             } else {
 #pragma unroll
                 for (int q = 0; q < QW; ++q) {
@@ -419,7 +450,7 @@ __device__ __forceinline__ void moments_body(MomentsShared &sm, const bf16_t *__
                         for (int t = 0; t < 4; ++t) { wq[t] = w0[t]; wq[4 + t] = w1[t]; }
                     }
 #pragma unroll
-                    for (int I = 0; I < 4; ++I) {
+                    for (int I = 0; I < NB; ++I) {
                         half8 ahi, alo;
 #pragma unroll
                         for (int t = 0; t < 8; ++t) {
@@ -428,15 +459,12 @@ __device__ __forceinline__ void moments_body(MomentsShared &sm, const bf16_t *__
                             alo[t] = (_Float16)(pr - (float)ahi[t]);
                         }
 #pragma unroll
-                        for (int J = I; J < 4; ++J) {
-                            acc[q][tix(I, J)] = mfma_f16(alo, bf[J], acc[q][tix(I, J)]);
-                            acc[q][tix(I, J)] = mfma_f16(ahi, bf[J], acc[q][tix(I, J)]);
+                        for (int J = I; J < NB; ++J) {
+                            acc[q][S::tix(I, J)] = mfma_f16(alo, bf[J], acc[q][S::tix(I, J)]);
+                            acc[q][S::tix(I, J)] = mfma_f16(ahi, bf[J], acc[q][S::tix(I, J)]);
                         }
                     }
                 }
-                // this wave's feature block for mu~ is re-read from LDS (indexing bf[] by the wave id
-                // would become a per-element select chain)
-                const half8 bw = *reinterpret_cast<const half8 *>(&kt[buf][hf][kt_r + wave * 512]);
                 half8 whi, wlo;
                 {
                     const float *wp = &wt32[buf][nn * WT32_PITCH + 32 * hf + 8 * g];
@@ -448,41 +476,41 @@ __device__ __forceinline__ void moments_body(MomentsShared &sm, const bf16_t *__
                         wlo[t] = (_Float16)(wv - (float)whi[t]);
                     }
                 }
-                mu_acc = mfma_f16(wlo, bw, mu_acc);
+                mu_acc = mfma_f16(wlo, bw, mu_acc);     // mu~[row 4g + r][feature 16 wave + nn]
                 mu_acc = mfma_f16(whi, bw, mu_acc);
             }
             if (hf == 0 && c + 1 < nblk) {
                 dma_wait();                     // this wave's DMA of block c+1 has landed
-                make_weights(c + 1);
+                if (w_wave) make_weights(c + 1);
             }
         }
         __syncthreads();
     }
 
-    // omega: lanes (g, nn) of all four waves hold partial sums for query i0 + nn
+    // omega: lanes (g, nn) of the four weight waves hold partial sums for query row nn
     om_part += __shfl_xor(om_part, 16);
     om_part += __shfl_xor(om_part, 32);
-    if (g == 0) omp[wave][nn] = om_part;
+    if (w_wave && g == 0) omp[wave][nn] = om_part;
 
     // ---- hand mu~ and omega to the waves that own the queries ---------------------------------------
 #pragma unroll
     for (int r = 0; r < 4; ++r) mus[PRECISE ? 4 * g + r : ((4 * g + r + QW * wave) & 15)][16 * wave + nn] = mu_acc[r];
     __syncthreads();
-    if (tid < QB) oms[tid] = (omp[0][tid] + omp[1][tid]) + (omp[2][tid] + omp[3][tid]);
+    if (tid < 16) oms[tid] = (omp[0][tid] + omp[1][tid]) + (omp[2][tid] + omp[3][tid]);
     __syncthreads();
 
     // ---- per-query solve (see solve_wave); the right-hand sides [mu~ q] are built inside it ----------
-    f32x4 rhs[QW][4];
+    f32x4 rhs[QW][NB];
     float y0v[QW], om4[QW];
 #pragma unroll
     for (int q = 0; q < QW; ++q) om4[q] = oms[QW * wave + q];
-    solve_wave(acc, rhs, y0v, om4, &sc[wave][0][0], lambda, g, nn, [&](f32x4 (&r)[QW][4]) {
+    solve_wave<DD>(acc, rhs, y0v, om4, &sc[wave][0][0], lambda, g, nn, [&](f32x4 (&r)[QW][NB]) {
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
             const int qi = QW * wave + q;
             const bf16_t *qrow = Qh + (int64_t)min(i0 + qi, n - 1) * sq.seq;
 #pragma unroll
-            for (int P = 0; P < 4; ++P)
+            for (int P = 0; P < NB; ++P)
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     const int row = 16 * P + 4 * g + t;
@@ -500,39 +528,31 @@ __device__ __forceinline__ void moments_body(MomentsShared &sm, const bf16_t *__
         if (i < n && nn == 0) {
             float *yr = Yg + ((size_t)bh * n + i) * YP;
 #pragma unroll
-            for (int P = 0; P < 4; ++P) *reinterpret_cast<f32x4 *>(yr + 16 * P + 4 * g) = rhs[q][P];
-            if (g == 0) yr[D] = y0v[q];
+            for (int P = 0; P < NB; ++P) *reinterpret_cast<f32x4 *>(yr + 16 * P + 4 * g) = rhs[q][P];
+            if (g == 0) yr[DD] = y0v[q];
         }
     }
 }
 
 // One launch serves every query block: blocks whose rows lie below precise_rows take the precise
 // variant.  The choice depends on blockIdx only, so it is a scalar branch (MFMA ignores EXEC).
-__global__ __launch_bounds__(NT, 2) void moments_kernel(const bf16_t *__restrict__ Qg, const bf16_t *__restrict__ Kg,
-                                                        llla_strides sq, llla_strides sk, int H, int n, int nkb,
-                                                        int precise_rows, float cscale, float lambda,
-                                                        const _Float16 *__restrict__ KT, const float *__restrict__ Mg,
-                                                        float *__restrict__ Yg)
+template <int DD>
+__global__ __launch_bounds__(Shape<DD>::NT, DD == 64 ? 2 : 1) void moments_kernel(
+    const bf16_t *__restrict__ Qg, const bf16_t *__restrict__ Kg, llla_strides sq, llla_strides sk, int H, int n, int nkb,
+    int precise_rows, float cscale, float lambda, const _Float16 *__restrict__ KT, const float *__restrict__ Mg,
+    float *__restrict__ Yg)
 {
-    __shared__ __align__(16) MomentsShared sm;
-    const int i0 = ((int)gridDim.x - 1 - (int)blockIdx.x) * QB;
-    if (i0 < precise_rows) moments_body<true>(sm, Qg, Kg, sq, sk, H, n, nkb, 0, cscale, lambda, KT, Mg, Yg);
-    else moments_body<false>(sm, Qg, Kg, sq, sk, H, n, nkb, 0, cscale, lambda, KT, Mg, Yg);
+    __shared__ __align__(16) MomentsShared<DD> sm;
+    const int i0 = ((int)gridDim.x - 1 - (int)blockIdx.x) * Shape<DD>::QB;
+    if (i0 < precise_rows) moments_body<true, DD>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, KT, Mg, Yg);
+    else moments_body<false, DD>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, KT, Mg, Yg);
 }
 
-}  // namespace
-
-bool mfma_forward_supported(int d, llla_dtype in, bool causal) { return d == D && in == LLLA_BF16 && causal; }
-
-size_t mfma_forward_workspace_bytes(int B, int H, int n, int d, llla_dtype in)
+template <int DD>
+hipError_t forward_impl(const Problem &p)
 {
-    if (!mfma_forward_supported(d, in, true)) return 0;
-    return make_layout(B, H, n).total;
-}
-
-hipError_t mfma_forward(const Problem &p)
-{
-    const Layout L = make_layout(p.B, p.H, p.n);
+    using S = Shape<DD>;
+    const Layout L = make_layout<DD>(p.B, p.H, p.n);
     char *ws = static_cast<char *>(p.ws);
     _Float16 *KT = reinterpret_cast<_Float16 *>(ws + L.kt);
     bf16_t *VT = reinterpret_cast<bf16_t *>(ws + L.vt);
@@ -540,32 +560,44 @@ hipError_t mfma_forward(const Problem &p)
     float *Y = reinterpret_cast<float *>(ws + L.y);
     const int bh = p.B * p.H;
     const float cscale = p.scale * LOG2E;
-    const int first = EARLY_ROWS < p.n ? EARLY_ROWS : p.n;
+    const int first = S::EARLY_ROWS < p.n ? S::EARLY_ROWS : p.n;
 
     const bf16_t *Q = static_cast<const bf16_t *>(p.Q), *K = static_cast<const bf16_t *>(p.K),
                  *V = static_cast<const bf16_t *>(p.V);
     stage_mark(p.stream, "prep");
-    hipLaunchKernelGGL(prep_kernel, dim3(L.nkb, bh), dim3(NT), 0, p.stream, K, V, p.sk, p.sv, p.H, p.n, L.nkb, KT, VT);
+    hipLaunchKernelGGL((prep_kernel<DD>), dim3(L.nkb, bh), dim3(256), 0, p.stream, K, V, p.sk, p.sv, p.H, p.n, L.nkb, KT, VT);
     const int nq64 = (p.n + 63) / 64;
     stage_mark(p.stream, "rowmax");
-    hipLaunchKernelGGL((sweep_kernel<true>), dim3(nq64, bh), dim3(NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
+    hipLaunchKernelGGL((sweep_kernel<true, DD>), dim3(nq64, bh), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
                        0, cscale, VT, M, Y, p.O, p.so, 0);
-    const int nq16 = (p.n + QB - 1) / QB;
+    const int nqb = (p.n + S::QB - 1) / S::QB;
     stage_mark(p.stream, "moments");
-    hipLaunchKernelGGL(moments_kernel, dim3(nq16, bh), dim3(NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb, first,
-                       cscale, p.lambda, KT, M, Y);
+    hipLaunchKernelGGL((moments_kernel<DD>), dim3(nqb, bh), dim3(S::NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
+                       first, cscale, p.lambda, KT, M, Y);
     // output: the first rows are evaluated in fp32 on the vector ALUs (their weights y0 + k.y1 cancel
     // to a few digits), the rest by the MFMA sweep
     stage_mark(p.stream, "output_early_rows");
-    hipError_t e = valu_forward_given(p, first, M, L.npad, Y, YP);
+    hipError_t e = valu_forward_given(p, first, M, L.npad, Y, S::YP);
     if (e != hipSuccess) return e;
     if (first < p.n) {
         const int nq64b = (p.n - first + 63) / 64;
         stage_mark(p.stream, "output");
-        hipLaunchKernelGGL((sweep_kernel<false>), dim3(nq64b, bh), dim3(NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n,
+        hipLaunchKernelGGL((sweep_kernel<false, DD>), dim3(nq64b, bh), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n,
                            L.nkb, first, cscale, VT, M, Y, p.O, p.so, p.out == LLLA_BF16 ? 1 : 0);
     }
     return hipGetLastError();
 }
+
+}  // namespace
+
+bool mfma_forward_supported(int d, llla_dtype in, bool causal) { return (d == 64 || d == 128) && in == LLLA_BF16 && causal; }
+
+size_t mfma_forward_workspace_bytes(int B, int H, int n, int d, llla_dtype in)
+{
+    if (!mfma_forward_supported(d, in, true)) return 0;
+    return d == 64 ? make_layout<64>(B, H, n).total : make_layout<128>(B, H, n).total;
+}
+
+hipError_t mfma_forward(const Problem &p) { return p.d == 64 ? forward_impl<64>(p) : forward_impl<128>(p); }
 
 }  // namespace llla

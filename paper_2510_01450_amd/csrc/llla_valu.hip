@@ -425,23 +425,31 @@ hipError_t by_dim(const Problem &p, int nrows)
     }
 }
 
+template <int D>
+hipError_t launch_given(const Problem &p, int nrows, const float *M, int mpitch, const float *Y, int ypitch)
+{
+    using C = Cfg<D>;
+    nrows = nrows < p.n ? nrows : p.n;
+    dim3 grid((nrows + C::QB - 1) / C::QB, p.B * p.H);
+    if (p.out == LLLA_F32)
+        hipLaunchKernelGGL((valu_kernel<D, bf16_t, float, false, true>), grid, dim3(NT), 0, p.stream,
+                           (const bf16_t *)p.Q, (const bf16_t *)p.K, (const bf16_t *)p.V, (float *)p.O, p.sq, p.sk,
+                           p.sv, p.so, nullptr, p.H, p.n, 1, p.lambda, p.scale, M, mpitch, Y, ypitch);
+    else
+        hipLaunchKernelGGL((valu_kernel<D, bf16_t, bf16_t, false, true>), grid, dim3(NT), 0, p.stream,
+                           (const bf16_t *)p.Q, (const bf16_t *)p.K, (const bf16_t *)p.V, (bf16_t *)p.O, p.sq, p.sk,
+                           p.sv, p.so, nullptr, p.H, p.n, 1, p.lambda, p.scale, M, mpitch, Y, ypitch);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t valu_forward_given(const Problem &p, int nrows, const float *M, int mpitch, const float *Y, int ypitch)
 {
-    if (p.d != 64 || p.in != LLLA_BF16) return hipErrorInvalidValue;
-    using C = Cfg<64>;
-    nrows = nrows < p.n ? nrows : p.n;
-    dim3 grid((nrows + C::QB - 1) / C::QB, p.B * p.H);
-    if (p.out == LLLA_F32)
-        hipLaunchKernelGGL((valu_kernel<64, bf16_t, float, false, true>), grid, dim3(NT), 0, p.stream,
-                           (const bf16_t *)p.Q, (const bf16_t *)p.K, (const bf16_t *)p.V, (float *)p.O, p.sq, p.sk,
-                           p.sv, p.so, nullptr, p.H, p.n, 1, p.lambda, p.scale, M, mpitch, Y, ypitch);
-    else
-        hipLaunchKernelGGL((valu_kernel<64, bf16_t, bf16_t, false, true>), grid, dim3(NT), 0, p.stream,
-                           (const bf16_t *)p.Q, (const bf16_t *)p.K, (const bf16_t *)p.V, (bf16_t *)p.O, p.sq, p.sk,
-                           p.sv, p.so, nullptr, p.H, p.n, 1, p.lambda, p.scale, M, mpitch, Y, ypitch);
-    return hipGetLastError();
+    if (p.in != LLLA_BF16) return hipErrorInvalidValue;
+    if (p.d == 64) return launch_given<64>(p, nrows, M, mpitch, Y, ypitch);
+    if (p.d == 128) return launch_given<128>(p, nrows, M, mpitch, Y, ypitch);
+    return hipErrorInvalidValue;
 }
 
 hipError_t valu_forward(const Problem &p) { return by_dim<false>(p, p.n); }
