@@ -154,10 +154,15 @@ def main():
                 "algorithmic_flops_per_launch": flops, "kernel_ms": dom_ms,
                 "whole_call_algorithmic_tflops": forward_flops(w.B, w.H, w.n, d) / (float(np.mean(per)) * 1e-3) / 1e12}
         if dom == "moments":
-            # what the kernel really issues to the matrix cores: per 64-key block and wave 82 f16 + 2 bf16
-            # MFMAs of 16x16x32 (16384 flop), per query 144 fp32 MFMAs of 16x16x4 (2048 flop)
-            blocks = sum((min(i0 + 15, w.n - 1) // 64 + 1) for i0 in range(0, w.n, 16))
-            issued = w.B * w.H * (blocks * 4 * 84 * 16384 + w.n * 144 * 2048)
+            # what the kernel really issues to the matrix cores (16x16x32 MFMA = 16384 flop, 16x16x4 fp32 = 2048):
+            # per 64-key block and workgroup NW waves x (2 halves x QW x NTILE + 2) f16 MFMAs + 4 x NF bf16 ones
+            # for the logits; per row the blocked Cholesky, forward and back substitution in fp32 tile products
+            nb = d // 16
+            ntile, qw, nw, nf = nb * (nb + 1) // 2, (4 if d == 64 else 1), nb, d // 32
+            qb = qw * nw
+            blocks = sum((min(i0 + qb - 1, w.n - 1) // 64 + 1) for i0 in range(0, w.n, qb))
+            tile_ops = nb * (nb - 1) // 2 + sum(r * (r + 1) // 2 for r in range(nb)) + 2 * (nb + nb * (nb - 1) // 2)
+            issued = w.B * w.H * (blocks * (nw * (2 * qw * ntile + 2) + 4 * nf) * 16384 + w.n * tile_ops * 4 * 2048)
             roof["mfma_issued_tflops"] = issued / (dom_ms * 1e-3) / 1e12
             roof["mfma_issued_frac_of_16bit_peak"] = roof["mfma_issued_tflops"] / (PEAK_MFMA_16BIT / 1e12)
     roof["frac"] = roof["achieved"] / roof["peak"]

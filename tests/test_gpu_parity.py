@@ -88,6 +88,38 @@ def test_strided_inputs_and_bf16_output():
     print(check(got, ref, np.arange(w.n), w.d, w.tol, "strided"))
 
 
+@pytest.mark.parametrize("n,d", [(700, 64), (1100, 64), (600, 128), (1030, 128)])
+def test_mfma_path_all_outputs_and_bf16_output(n, d):
+    """The matrix-core path end to end (precise rows, fast rows, both output sweeps), forced with
+    path='mfma', all outputs against the oracle; bf16 output rounding is inside the bf16 tolerance."""
+    w = _small("mfma", 1, 3, n, d, "bf16", index=300 + n + d)
+    Q, K, V = workloads.make_inputs(w)
+    ref = oracle.forward(Q, K, V, w.lam, w.scale)
+    got = _run_forward(w, Q, K, V, path="mfma")
+    print(check(got, ref, np.arange(n), d, w.tol, "mfma n=%d d=%d" % (n, d)))
+    got16 = _run_forward(w, Q, K, V, path="mfma", out_dtype=torch.bfloat16)
+    print(check(got16, ref, np.arange(n), d, w.tol, "mfma bf16 out n=%d d=%d" % (n, d)))
+    valu = _run_forward(w, Q, K, V, path="valu")
+    late = np.arange(n) >= 4 * d
+    err = np.linalg.norm(got[..., late, :] - valu[..., late, :]) / np.linalg.norm(valu[..., late, :])
+    assert err < 2e-3, err          # the two kernel families agree far inside the tolerance
+
+
+def test_mfma_path_refuses_what_it_does_not_serve():
+    x = torch.zeros(1, 1, 64, 32, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(llla.LlaError) as e:
+        llla.llla_forward(x, x, x, 1e-2, 0.2, path="mfma")          # d = 32 has no matrix-core path
+    assert e.value.code == 7
+    y = torch.zeros(1, 1, 64, 64, dtype=torch.float32, device=DEV)
+    with pytest.raises(llla.LlaError) as e:
+        llla.llla_forward(y, y, y, 1e-2, 0.2, path="mfma")          # fp32 inputs neither
+    assert e.value.code == 7
+    z = torch.zeros(1, 1, 512, 64, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(llla.LlaError) as e:
+        llla.llla_forward(z, z, z, 1e-2, 0.2, path="mfma", workspace=torch.zeros(256, dtype=torch.uint8, device=DEV))
+    assert e.value.code == 6                                        # workspace too small
+
+
 def test_lambda_and_scale_are_honoured():
     w = _small("lam", 1, 2, 200, 32, "f32", index=90)
     Q, K, V = workloads.make_inputs(w)
@@ -129,6 +161,20 @@ def test_decode_matches_oracle(L, d, dtype, path):
     got = llla.llla_decode(q.to(DEV), Kc.to(DEV), Vc.to(DEV), w.lam, w.scale, path=path).cpu().numpy()
     rows = np.array([L - 1])
     print(check(got[:, :, None, :], ref[:, :, None, :], rows, d, w.tol, "decode L=%d d=%d %s" % (L, d, dtype)))
+
+
+@pytest.mark.parametrize("B,H,L", [(1, 2, 4096), (2, 3, 5000), (4, 8, 1024)])
+def test_decode_mfma_splits_and_bf16_output(B, H, L):
+    """The single-pass matrix-core decode with several cache splits per head and a ragged last step."""
+    w = _small("decm", B, H, L, 64, "bf16", index=400 + L).with_shape(kind="decode")
+    q, Kc, Vc = workloads.make_inputs(w)
+    ref = oracle.decode(q, Kc, Vc, w.lam, w.scale)
+    for od in (torch.float32, torch.bfloat16):
+        got = llla.llla_decode(q.to(DEV), Kc.to(DEV), Vc.to(DEV), w.lam, w.scale, path="mfma", out_dtype=od)
+        got = got.float().cpu().numpy()
+        print(check(got[:, :, None, :], ref[:, :, None, :], np.array([L - 1]), 64, w.tol, "decode mfma L=%d" % L))
+    valu = llla.llla_decode(q.to(DEV), Kc.to(DEV), Vc.to(DEV), w.lam, w.scale, path="valu").cpu().numpy()
+    assert np.linalg.norm(got - valu) / np.linalg.norm(valu) < 1e-2
 
 
 def test_decode_seqlens_and_forward_last_row():
