@@ -42,11 +42,11 @@ __device__ inline void wave_sync()
 template <int C>
 __device__ inline float row_bcast(float x)   // value of lane C of the caller's 16-lane row
 {
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x150 + C, 0xf, 0xf, false));
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x150 + C, 0xf, 0xf, true));
 }
 __device__ inline float lane_xor1(float x)   // value of lane ^ 1
 {
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xf, 0xf, false));
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xf, 0xf, true));
 }
 
 __device__ inline f32x4 mfma_f16(half8 a, half8 b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
@@ -211,6 +211,9 @@ __device__ __forceinline__ void solve_wave(f32x4 (&acc)[Shape<DD>::QW][Shape<DD>
 #pragma unroll
                 for (int J = I; J < NB; ++J) acc[q][S::tix(I, J)] = tile_atb(acc[q][S::tix(I, J)], neg, acc[q][S::tix(P, J)]);
             }
+            // one query at a time: its own tile products give the matrix cores enough independent work, and
+            // interleaving the queries only inflates the number of live registers
+            __builtin_amdgcn_sched_barrier(0);
         }
         wave_sync();
     }

@@ -288,10 +288,8 @@ __global__ __launch_bounds__(NT, 1) void decode_merge_kernel(const bf16_t *__res
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
                         const int row = 16 * P + 4 * g + t;
-                        float v = 0.f;
-                        if (nn == 0) v = mus[q][row];
-                        if (nn == 1) v = bf16_to_f32(qg[(size_t)hq * D + row]);
-                        r[q][P][t] = v;
+                        const float mv = mus[q][row], qv = bf16_to_f32(qg[(size_t)hq * D + row]);
+                        r[q][P][t] = (nn == 0) ? mv : ((nn == 1) ? qv : 0.f);
                     }
             }
         });

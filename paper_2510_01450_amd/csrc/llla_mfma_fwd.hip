@@ -513,11 +513,11 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
             for (int P = 0; P < NB; ++P)
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
+                    // every lane loads both values and selects: a load under a lane-dependent condition
+                    // would become a branch with its own wait per tile register
                     const int row = 16 * P + 4 * g + t;
-                    float v = 0.f;
-                    if (nn == 0) v = mus[qi][row];
-                    if (nn == 1) v = bf16_to_f32(qrow[row]);
-                    r[q][P][t] = v;
+                    const float mv = mus[qi][row], qv = bf16_to_f32(qrow[row]);
+                    r[q][P][t] = (nn == 0) ? mv : ((nn == 1) ? qv : 0.f);
                 }
         }
     });
