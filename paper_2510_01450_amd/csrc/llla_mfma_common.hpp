@@ -64,62 +64,168 @@ __device__ inline f32x4 tile_atb(f32x4 c, f32x4 a, f32x4 b)
 
 constexpr int SC_PITCH = 20;         // floats per row of a 16x16 scratch tile
 
+// Row-broadcast multiply-adds as VOP2 DPP instructions, a_i += (src of lane C_i of the 16-lane row) * mul:
+// the compiler does not fuse a DPP move into an FMA by itself, and these pairs are most of the vector-ALU
+// work of the diagonal-tile factorisation.  A DPP read needs two wait states after a vector-ALU write of the
+// register it reads, and the compiler's hazard handling does not look inside inline assembly; every
+// statement below therefore starts with its own s_nop 1, and all registers it reads through DPP are operands
+// of the statement, so whatever wrote them lies before that s_nop.
+//   fmac_bcastN<C0..>(a0.., src, mul): a_i += bcast_{C_i}(src) * mul        (rank-1 update of a row)
+//   fmac_selfN<C>(a0.., mul):          a_i += bcast_C(a_i) * mul            (triangular-inverse recursion)
+template <int C0>
+__device__ inline void fmac_bcast1(float &a0, float src, float mul)
+{
+    asm volatile("s_nop 1\n\t"
+                 "v_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+                 : "+v"(a0) : "v"(src), "v"(mul), "n"(C0));
+}
+template <int C0, int C1>
+__device__ inline void fmac_bcast2(float &a0, float &a1, float src, float mul)
+{
+    asm volatile("s_nop 1\n\t"
+                 "v_fmac_f32_dpp %0, %2, %3 row_newbcast:%4 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %1, %2, %3 row_newbcast:%5 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+                 : "+v"(a0), "+v"(a1) : "v"(src), "v"(mul), "n"(C0), "n"(C1));
+}
+template <int C0, int C1, int C2, int C3>
+__device__ inline void fmac_bcast4(float &a0, float &a1, float &a2, float &a3, float src, float mul)
+{
+    asm volatile("s_nop 1\n\t"
+                 "v_fmac_f32_dpp %0, %4, %5 row_newbcast:%6 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %1, %4, %5 row_newbcast:%7 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %2, %4, %5 row_newbcast:%8 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %3, %4, %5 row_newbcast:%9 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+                 : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3) : "v"(src), "v"(mul), "n"(C0), "n"(C1), "n"(C2), "n"(C3));
+}
+template <int C0, int C1, int C2, int C3, int C4, int C5, int C6, int C7>
+__device__ inline void fmac_bcast8(float &a0, float &a1, float &a2, float &a3, float &a4, float &a5, float &a6, float &a7, float src, float mul)
+{
+    asm volatile("s_nop 1\n\t"
+                 "v_fmac_f32_dpp %0, %8, %9 row_newbcast:%10 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %1, %8, %9 row_newbcast:%11 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %2, %8, %9 row_newbcast:%12 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %3, %8, %9 row_newbcast:%13 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %4, %8, %9 row_newbcast:%14 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %5, %8, %9 row_newbcast:%15 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %6, %8, %9 row_newbcast:%16 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %7, %8, %9 row_newbcast:%17 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+                 : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(a4), "+v"(a5), "+v"(a6), "+v"(a7) : "v"(src), "v"(mul), "n"(C0), "n"(C1), "n"(C2), "n"(C3), "n"(C4), "n"(C5), "n"(C6), "n"(C7));
+}
+template <int C>
+__device__ inline void fmac_self1(float &a0, float mul)
+{
+    asm volatile("s_nop 1\n\t"
+                 "v_fmac_f32_dpp %0, %0, %1 row_newbcast:%2 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+                 : "+v"(a0) : "v"(mul), "n"(C));
+}
+template <int C>
+__device__ inline void fmac_self2(float &a0, float &a1, float mul)
+{
+    asm volatile("s_nop 1\n\t"
+                 "v_fmac_f32_dpp %0, %0, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %1, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+                 : "+v"(a0), "+v"(a1) : "v"(mul), "n"(C));
+}
+template <int C>
+__device__ inline void fmac_self4(float &a0, float &a1, float &a2, float &a3, float mul)
+{
+    asm volatile("s_nop 1\n\t"
+                 "v_fmac_f32_dpp %0, %0, %4 row_newbcast:%5 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %1, %1, %4 row_newbcast:%5 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %2, %2, %4 row_newbcast:%5 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %3, %3, %4 row_newbcast:%5 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+                 : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3) : "v"(mul), "n"(C));
+}
+template <int C>
+__device__ inline void fmac_self8(float &a0, float &a1, float &a2, float &a3, float &a4, float &a5, float &a6, float &a7, float mul)
+{
+    asm volatile("s_nop 1\n\t"
+                 "v_fmac_f32_dpp %0, %0, %8 row_newbcast:%9 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %1, %1, %8 row_newbcast:%9 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %2, %2, %8 row_newbcast:%9 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %3, %3, %8 row_newbcast:%9 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %4, %4, %8 row_newbcast:%9 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %5, %5, %8 row_newbcast:%9 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %6, %6, %8 row_newbcast:%9 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %7, %7, %8 row_newbcast:%9 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+                 : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(a4), "+v"(a5), "+v"(a6), "+v"(a7) : "v"(mul), "n"(C));
+}
+template <int C>
+__device__ inline float bcast_settled(float src)     // row broadcast of a value that inline assembly may have written
+{
+    float d;
+    asm volatile("s_nop 1\n\tv_mov_b32_dpp %0, %1 row_newbcast:%2 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+                 : "=v"(d) : "v"(src), "n"(C));
+    return d;
+}
+
+// a[K+1..15] += bcast_c(src) * mul for c = K+1..15, in statements of 8, 4, 2 and 1 instructions
+template <int K>
+__device__ inline void rank1_row(float (&a)[16], float src, float mul)
+{
+    constexpr int N = 15 - K;
+    constexpr int c8 = K + 1, c4 = c8 + (N & 8), c2 = c4 + (N & 4), c1 = c2 + (N & 2);
+    if constexpr ((N & 8) != 0)
+        fmac_bcast8<c8, c8 + 1, c8 + 2, c8 + 3, c8 + 4, c8 + 5, c8 + 6, c8 + 7>(a[c8], a[c8 + 1], a[c8 + 2], a[c8 + 3], a[c8 + 4], a[c8 + 5],
+                                                                                a[c8 + 6], a[c8 + 7], src, mul);
+    if constexpr ((N & 4) != 0) fmac_bcast4<c4, c4 + 1, c4 + 2, c4 + 3>(a[c4], a[c4 + 1], a[c4 + 2], a[c4 + 3], src, mul);
+    if constexpr ((N & 2) != 0) fmac_bcast2<c2, c2 + 1>(a[c2], a[c2 + 1], src, mul);
+    if constexpr ((N & 1) != 0) fmac_bcast1<c1>(a[c1], src, mul);
+}
+// li[0..P] += bcast_P(li[c]) * mul
+template <int P>
+__device__ inline void trinv_row(float (&li)[16], float mul)
+{
+    constexpr int N = P + 1;
+    constexpr int c8 = 0, c4 = c8 + (N & 8), c2 = c4 + (N & 4), c1 = c2 + (N & 2);
+    if constexpr ((N & 8) != 0) fmac_self8<P>(li[c8], li[c8 + 1], li[c8 + 2], li[c8 + 3], li[c8 + 4], li[c8 + 5], li[c8 + 6], li[c8 + 7], mul);
+    if constexpr ((N & 4) != 0) fmac_self4<P>(li[c4], li[c4 + 1], li[c4 + 2], li[c4 + 3], mul);
+    if constexpr ((N & 2) != 0) fmac_self2<P>(li[c2], li[c2 + 1], mul);
+    if constexpr ((N & 1) != 0) fmac_self1<P>(li[c1], mul);
+}
+
+#define LLLA_SWITCH16(K, STMT)                                                                          \
+    switch (K) {                                                                                        \
+        case 0: { constexpr int KK = 0; STMT; } break;   case 1: { constexpr int KK = 1; STMT; } break;    \
+        case 2: { constexpr int KK = 2; STMT; } break;   case 3: { constexpr int KK = 3; STMT; } break;    \
+        case 4: { constexpr int KK = 4; STMT; } break;   case 5: { constexpr int KK = 5; STMT; } break;    \
+        case 6: { constexpr int KK = 6; STMT; } break;   case 7: { constexpr int KK = 7; STMT; } break;    \
+        case 8: { constexpr int KK = 8; STMT; } break;   case 9: { constexpr int KK = 9; STMT; } break;    \
+        case 10: { constexpr int KK = 10; STMT; } break; case 11: { constexpr int KK = 11; STMT; } break;  \
+        case 12: { constexpr int KK = 12; STMT; } break; case 13: { constexpr int KK = 13; STMT; } break;  \
+        case 14: { constexpr int KK = 14; STMT; } break; default: { constexpr int KK = 15; STMT; } break;  \
+    }
+
 // Upper Cholesky factor and its inverse for the diagonal tiles of the wave's four queries at once:
 // lane 16q + r owns row r of query q's symmetric 16x16 tile (a[c] = T[r][c]).  On return
-// li[c] = (L^{-1})[r][c] with T = L L^T (zero above the diagonal).
+// li[c] = -(L^{-1})[r][c] with T = L L^T (zero above the diagonal); the sign is the one solve_wave wants.
 __device__ inline void chol_inv16(float (&a)[16], float (&li)[16], int r)
 {
-    float l2[16];       // L[r][k] / L[k][k]  (column-scaled factor, strictly lower part kept)
+    float nl2[16];      // -L[r][k] / L[k][k]  (column-scaled factor, strictly lower part kept, negated)
     float dinv_own = 0.f;
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
-        float dk, ak = a[k];
-        switch (k) {    // diagonal entry of step k, broadcast from lane k of the row
-#define LLLA_BC(K) case K: dk = row_bcast<K>(ak); break;
-            LLLA_BC(0) LLLA_BC(1) LLLA_BC(2) LLLA_BC(3) LLLA_BC(4) LLLA_BC(5) LLLA_BC(6) LLLA_BC(7)
-            LLLA_BC(8) LLLA_BC(9) LLLA_BC(10) LLLA_BC(11) LLLA_BC(12) LLLA_BC(13) LLLA_BC(14) LLLA_BC(15)
-#undef LLLA_BC
-            default: dk = 1.f;
-        }
+        float dk;
+        const float ak = a[k];
+        LLLA_SWITCH16(k, dk = bcast_settled<KK>(ak));        // diagonal entry of step k, from lane k of the row
         float rinv = __builtin_amdgcn_rsqf(dk);
         rinv = rinv * (1.5f - 0.5f * dk * rinv * rinv);      // one Newton step
-        const float u = (r >= k) ? ak * rinv : 0.f;          // L[r][k]
-        l2[k] = (r > k) ? u * rinv : 0.f;
+        const float u = ak * rinv;                           // L[r][k] in rows r >= k; rows above are finished and never read again
+        const float nu = -u;
+        nl2[k] = (r > k) ? nu * rinv : 0.f;
         dinv_own = (r == k) ? rinv : dinv_own;
-#pragma unroll
-        for (int c = k + 1; c < 16; ++c) {
-            float uc;
-            switch (c) {
-#define LLLA_BC(K) case K: uc = row_bcast<K>(u); break;
-                LLLA_BC(1) LLLA_BC(2) LLLA_BC(3) LLLA_BC(4) LLLA_BC(5) LLLA_BC(6) LLLA_BC(7) LLLA_BC(8)
-                LLLA_BC(9) LLLA_BC(10) LLLA_BC(11) LLLA_BC(12) LLLA_BC(13) LLLA_BC(14) LLLA_BC(15)
-#undef LLLA_BC
-                default: uc = 0.f;
-            }
-            a[c] = fmaf(-u, uc, a[c]);
-        }
+        if (k < 15) { LLLA_SWITCH16(k, rank1_row<(KK < 15 ? KK : 14)>(a, u, nu)); }      // a[c] -= L[r][k] L[c][k], c > k
     }
     // M = (unit lower L'')^{-1}:  M[r][c] = [r==c] - sum_{c<=p<r} L''[r][p] M[p][c]
 #pragma unroll
     for (int c = 0; c < 16; ++c) li[c] = (r == c) ? 1.f : 0.f;
 #pragma unroll
-    for (int p = 0; p < 15; ++p) {
+    for (int p = 0; p < 15; ++p) { LLLA_SWITCH16(p, trinv_row<(KK < 15 ? KK : 14)>(li, nl2[p])); }
+    const float ndinv = -dinv_own;
 #pragma unroll
-        for (int c = 0; c <= p; ++c) {
-            float mp;
-            switch (p) {
-#define LLLA_BC(K) case K: mp = row_bcast<K>(li[c]); break;
-                LLLA_BC(0) LLLA_BC(1) LLLA_BC(2) LLLA_BC(3) LLLA_BC(4) LLLA_BC(5) LLLA_BC(6) LLLA_BC(7)
-                LLLA_BC(8) LLLA_BC(9) LLLA_BC(10) LLLA_BC(11) LLLA_BC(12) LLLA_BC(13) LLLA_BC(14)
-#undef LLLA_BC
-                default: mp = 0.f;
-            }
-            li[c] = fmaf(-l2[p], mp, li[c]);
-        }
-    }
-#pragma unroll
-    for (int c = 0; c < 16; ++c) li[c] *= dinv_own;          // L^{-1} = D^{-1} L''^{-1}
+    for (int c = 0; c < 16; ++c) li[c] *= ndinv;             // -L^{-1} = -D^{-1} L''^{-1}
 }
+#undef LLLA_SWITCH16
 
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 typedef const __attribute__((address_space(1))) void *glb_void_ptr;
@@ -141,8 +247,8 @@ __device__ inline void dma16(const void *gsrc, void *lds_base)
 __device__ inline void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // Exact solve of the wave's QW augmented systems, all in registers / wave-private LDS scratch:
-//   in : acc[q][tix(I,J)]  upper-triangular 16x16 tiles of Sigma~_q (MFMA accumulator layout, lambda not yet added)
-//        build_rhs(rhs)    fills rhs[q][P], a tile column with mu~_q in column 0 and q_q in column 1 (other
+//   in : acc[q][tix(I,J)]  upper-triangular 16x16 tiles of T_q = -(Sigma~_q + lambda I) (MFMA accumulator layout)
+//        build_rhs(rhs)    fills rhs[q][P], a tile column with -mu~_q in column 0 and -q_q in column 1 (other
 //                          columns 0); it is called after the factorisation so that the 16 right-hand-side
 //                          registers per query are not live while the diagonal tiles are factorised
 //        om4[q]            omega_q;  scw: >= QW*16*SC_PITCH floats of LDS owned by this wave
@@ -151,24 +257,21 @@ __device__ inline void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memor
 // Sigma~ + lambda I = U^T U whose block products are C += A^T B on fp32 MFMA; diagonal tiles of the QW
 // queries are factorised together in (query, row) lanes with DPP row broadcasts; then forward
 // substitution of both right-hand sides, the Schur step on the intercept, and back substitution.
+// The matrix cores only add products, so everything that the textbook recursion subtracts is carried
+// negated instead: the trailing matrix (T), the inverse diagonal factors (N_P = -U_PP^{-1}), and the
+// partial right-hand sides; no tile is ever negated on the vector ALU.
 template <int DD, class BuildRhs>
 __device__ __forceinline__ void solve_wave(f32x4 (&acc)[Shape<DD>::QW][Shape<DD>::NTILE],
                                            f32x4 (&rhs)[Shape<DD>::QW][Shape<DD>::NB], float (&y0v)[Shape<DD>::QW],
-                                           const float (&om4)[Shape<DD>::QW], float *scw, float lambda, int g, int nn,
+                                           const float (&om4)[Shape<DD>::QW], float *scw, int g, int nn,
                                            BuildRhs build_rhs)
 {
     using S = Shape<DD>;
     constexpr int QW = S::QW, NB = S::NB;
     const int gq = (g < QW) ? g : QW - 1;       // lane groups beyond the wave's queries shadow the last one
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int q = 0; q < QW; ++q)
-#pragma unroll
-        for (int P = 0; P < NB; ++P)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) acc[q][S::tix(P, P)][t] += (nn == 4 * g + t) ? lambda : 0.f;
 
-    // ---- factorisation: afterwards acc(P,J), P < J, holds U(P,J) and acc(P,P) holds U(P,P)^{-1} -----------
+    // ---- factorisation: afterwards acc(P,J), P < J, holds U(P,J) and acc(P,P) holds N_P = -U(P,P)^{-1} -----
 #pragma unroll
     for (int P = 0; P < NB; ++P) {
         // diagonal tiles -> (query, row) lanes, symmetrised
@@ -187,7 +290,7 @@ __device__ __forceinline__ void solve_wave(f32x4 (&acc)[Shape<DD>::QW][Shape<DD>
                 for (int t = 0; t < 4; ++t) a[4 * c4 + t] = v[t];
             }
 #pragma unroll
-            for (int c = 0; c < 16; ++c) a[c] = 0.5f * (a[c] + my[c * SC_PITCH + nn]);
+            for (int c = 0; c < 16; ++c) a[c] = -0.5f * (a[c] + my[c * SC_PITCH + nn]);    // -T, symmetrised
         }
         wave_sync();
         chol_inv16(a, li, nn);
@@ -200,17 +303,16 @@ __device__ __forceinline__ void solve_wave(f32x4 (&acc)[Shape<DD>::QW][Shape<DD>
         wave_sync();
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
-            // U^{-1} in tile layout: reg t = Uinv[4g+t][nn] = Linv[nn][4g+t]; it replaces the consumed diagonal tile
+            // N_P in tile layout: reg t = N[4g+t][nn] = -Linv[nn][4g+t]; it replaces the consumed diagonal tile;
+            // U(P,J) = N_P^T T(P,J), and the trailing tiles take T(I,J) += U(P,I)^T U(P,J)
             const f32x4 ui = *reinterpret_cast<const f32x4 *>(scw + q * 16 * SC_PITCH + nn * SC_PITCH + 4 * g);
             acc[q][S::tix(P, P)] = ui;
 #pragma unroll
             for (int J = P + 1; J < NB; ++J) acc[q][S::tix(P, J)] = tile_atb(zero, ui, acc[q][S::tix(P, J)]);
 #pragma unroll
-            for (int I = P + 1; I < NB; ++I) {
-                const f32x4 neg = -acc[q][S::tix(P, I)];
+            for (int I = P + 1; I < NB; ++I)
 #pragma unroll
-                for (int J = I; J < NB; ++J) acc[q][S::tix(I, J)] = tile_atb(acc[q][S::tix(I, J)], neg, acc[q][S::tix(P, J)]);
-            }
+                for (int J = I; J < NB; ++J) acc[q][S::tix(I, J)] = tile_atb(acc[q][S::tix(I, J)], acc[q][S::tix(P, I)], acc[q][S::tix(P, J)]);
             // one query at a time: its own tile products give the matrix cores enough independent work, and
             // interleaving the queries only inflates the number of live registers
             __builtin_amdgcn_sched_barrier(0);
@@ -218,7 +320,7 @@ __device__ __forceinline__ void solve_wave(f32x4 (&acc)[Shape<DD>::QW][Shape<DD>
         wave_sync();
     }
 
-    // ---- forward substitution of [mu~ q]:  r_P <- Uinv_P^T (r_P - sum_{I<P} U(I,P)^T r_I) ----------------
+    // ---- forward substitution of [mu~ q]:  t_P = -r_P + sum_{I<P} U(I,P)^T r_I,  r_P <- N_P^T t_P -------------
     build_rhs(rhs);
 #pragma unroll
     for (int P = 0; P < NB; ++P) {
@@ -226,12 +328,12 @@ __device__ __forceinline__ void solve_wave(f32x4 (&acc)[Shape<DD>::QW][Shape<DD>
         for (int q = 0; q < QW; ++q) {
             rhs[q][P] = tile_atb(zero, acc[q][S::tix(P, P)], rhs[q][P]);
 #pragma unroll
-            for (int I = P + 1; I < NB; ++I) rhs[q][I] = tile_atb(rhs[q][I], -acc[q][S::tix(P, I)], rhs[q][P]);
+            for (int I = P + 1; I < NB; ++I) rhs[q][I] = tile_atb(rhs[q][I], acc[q][S::tix(P, I)], rhs[q][P]);
         }
     }
 
     // rhs[q][P]: column 0 = a = U^{-T} mu~, column 1 = c = U^{-T} q.  Schur step on the intercept:
-    // y0 = (1 - a.c) / (omega - a.a);  y1 = U^{-1} (c - a y0)
+    // y0 = (1 - a.c) / (omega - a.a);  y1 = U^{-1} (c - a y0), started below as z = a y0 - c
 #pragma unroll
     for (int q = 0; q < QW; ++q) {
         float saa = 0.f, sac = 0.f;
@@ -254,12 +356,12 @@ __device__ __forceinline__ void solve_wave(f32x4 (&acc)[Shape<DD>::QW][Shape<DD>
             for (int t = 0; t < 4; ++t) {
                 const float av = rhs[q][P][t];
                 const float cv = lane_xor1(av);
-                rhs[q][P][t] = (nn == 0) ? (cv - av * y0) : 0.f;
+                rhs[q][P][t] = (nn == 0) ? (av * y0 - cv) : 0.f;
             }
     }
 
-    // ---- back substitution, block rows 3..0:  x_P = Uinv_P (t_P - sum_{J>P} U(P,J) x_J).  C += A^T B needs
-    //      the transposes of U(P,J) and of Uinv_P as A: one trip through the scratch tile each ------------
+    // ---- back substitution, block rows 3..0:  z_P += sum_{J>P} U(P,J) x_J,  x_P = N_P z_P.  C += A^T B needs
+    //      the transposes of U(P,J) and of N_P as A: one trip through the scratch tile each ---------------
 #pragma unroll
     for (int P = NB - 1; P >= 0; --P) {
 #pragma unroll
@@ -274,8 +376,8 @@ __device__ __forceinline__ void solve_wave(f32x4 (&acc)[Shape<DD>::QW][Shape<DD>
                 f32x4 tr;
 #pragma unroll
                 for (int t = 0; t < 4; ++t) tr[t] = scw[q * 16 * SC_PITCH + (4 * g + t) * SC_PITCH + nn];
-                if (diag) rhs[q][P] = tile_atb(zero, tr, rhs[q][P]);             // Uinv_P r
-                else rhs[q][P] = tile_atb(rhs[q][P], -tr, rhs[q][J]);            // r -= U(P,J) x_J
+                if (diag) rhs[q][P] = tile_atb(zero, tr, rhs[q][P]);             // N_P z
+                else rhs[q][P] = tile_atb(rhs[q][P], tr, rhs[q][J]);             // z += U(P,J) x_J
             }
             wave_sync();
         }

@@ -277,9 +277,13 @@ __global__ __launch_bounds__(NT, 1) void decode_merge_kernel(const bf16_t *__res
         for (int q = 0; q < QW; ++q) {
             om4[q] = oms[q];
 #pragma unroll
-            for (int t = 0; t < 10; ++t) acc[q][t] = *reinterpret_cast<const f32x4 *>(&merged[q][t][lane * 4]);
+            for (int t = 0; t < 10; ++t) acc[q][t] = -*reinterpret_cast<const f32x4 *>(&merged[q][t][lane * 4]);
+#pragma unroll
+            for (int P = 0; P < 4; ++P)     // solve_wave takes -(Sigma~ + lambda I)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) acc[q][Shape<64>::tix(P, P)][t] -= (nn == 4 * g + t) ? lambda : 0.f;
         }
-        solve_wave<64>(acc, rhs, y0v, om4, scw, lambda, g, nn, [&](f32x4 (&r)[QW][4]) {
+        solve_wave<64>(acc, rhs, y0v, om4, scw, g, nn, [&](f32x4 (&r)[QW][4]) {
 #pragma unroll
             for (int q = 0; q < QW; ++q) {
                 const int hq = min((int)blockIdx.x * QW + q, BH - 1);
@@ -289,7 +293,7 @@ __global__ __launch_bounds__(NT, 1) void decode_merge_kernel(const bf16_t *__res
                     for (int t = 0; t < 4; ++t) {
                         const int row = 16 * P + 4 * g + t;
                         const float mv = mus[q][row], qv = bf16_to_f32(qg[(size_t)hq * D + row]);
-                        r[q][P][t] = (nn == 0) ? mv : ((nn == 1) ? qv : 0.f);
+                        r[q][P][t] = (nn == 0) ? -mv : ((nn == 1) ? -qv : 0.f);
                     }
             }
         });

@@ -14,6 +14,8 @@
 //           y0 = (1 + q.rho)/delta), a flash-style sweep.
 // The first 4d rows of every sequence, whose systems are the worst conditioned, are served by the
 // fp32 vector-ALU kernel instead (same result, higher-precision second moment).
+#include <type_traits>
+
 #include "llla_mfma_common.hpp"
 
 namespace llla {
@@ -327,6 +329,14 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     for (int q = 0; q < QW; ++q)
 #pragma unroll
         for (int t = 0; t < NTILE; ++t) acc[q][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // The tiles accumulate T = -(Sigma~ + lambda I), the sign the solve works in (see solve_wave): the ridge is
+    // the starting value of the diagonal, and the scaled MFMA operand carries a minus sign that costs nothing.
+#pragma unroll
+    for (int q = 0; q < QW; ++q)
+#pragma unroll
+        for (int P = 0; P < NB; ++P)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc[q][S::tix(P, P)][t] = (nn == 4 * g + t) ? -lambda : 0.f;
     f32x4 mu_acc = {0.f, 0.f, 0.f, 0.f};
     float om_part = 0.f;            // this lane's share of omega for query i0 + nn
 
@@ -371,11 +381,20 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
             }
         }
     };
-    auto make_weights = [&](int blk) {  // w = 2^(c<q,k> - m) for this wave's 16 keys of block blk
-        const int buf = blk & 1;
+    // Weights of block blk, w = 2^(c<q,k> - m) for this wave's 16 keys, in three steps that the loop below
+    // spreads over an iteration so that no step waits on the one before it: operand reads, logits (MFMA), exp + store.
+    bf16x8 knf[NF];
+    auto weights_load = [&](int buf) {
+#pragma unroll
+        for (int f = 0; f < NF; ++f) knf[f] = *reinterpret_cast<const bf16x8 *>(&kn[buf][kn_r[f]]);
+    };
+    auto weights_logits = [&]() {
         f32x4 z = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int f = 0; f < NF; ++f) z = mfma_bf16(*reinterpret_cast<const bf16x8 *>(&kn[buf][kn_r[f]]), qf[f], z);
+        for (int f = 0; f < NF; ++f) z = mfma_bf16(knf[f], qf[f], z);
+        return z;
+    };
+    auto weights_store = [&](int blk, int buf, f32x4 z) {
         float wf[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -397,93 +416,105 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
         }
     };
 
-    // Software pipeline over blocks of 64 keys: iteration c consumes block c while the DMA of block
-    // c+1 lands; the weights of block c+1 are produced in the middle of the iteration (a weight wave
-    // reads only the keys it fetched itself, so its own vmcnt wait suffices).  One barrier per block.
-    // `wave` is a scalar, so every branch around an MFMA below is a real branch (MFMA ignores EXEC).
+    // Operand fragments of one half (32 keys) of a block and the MFMAs that consume them.
+    half8 bf[NB], bw, wa;
+    auto load_frags = [&](int buf, int hf) {
+#pragma unroll
+        for (int I = 0; I < NB; ++I) bf[I] = *reinterpret_cast<const half8 *>(&kt[buf][hf][kt_r + I * 512]);
+        // this wave's feature block for mu~ is re-read from LDS (indexing bf[] by the wave id would
+        // become a per-element select chain)
+        bw = *reinterpret_cast<const half8 *>(&kt[buf][hf][kt_r + wave * 512]);
+        // the f16 weights of all 16 query rows as the A operand of the mu~ product (lane (g, nn): row nn, keys 8g..8g+7)
+        if (!PRECISE) wa = *reinterpret_cast<const half8 *>(&wt[buf][nn * WT_PITCH + 32 * hf + 8 * g]);
+    };
+    auto compute_half = [&](int buf, int hf) {
+        if (!PRECISE) {
+            mu_acc = mfma_f16(wa, bw, mu_acc);      // mu~[row 4g + r][feature 16 wave + nn]
+            // the query's 8 weights of this lane's key chunk: one address per lane group (an LDS broadcast
+            // read), fetched one query ahead of its use
+            const _Float16 *wrow = &wt[buf][QW * wave * WT_PITCH + 32 * hf + 8 * g];
+            half8 wq_next = *reinterpret_cast<const half8 *>(wrow);
+#pragma unroll
+            for (int q = 0; q < QW; ++q) {
+                const half8 wq = wq_next;
+                if (q + 1 < QW) wq_next = *reinterpret_cast<const half8 *>(wrow + (q + 1) * WT_PITCH);
+#pragma unroll
+                for (int I = 0; I < NB; ++I) {
+                    const half8 af = -(bf[I] * wq);
+#pragma unroll
+                    for (int J = I; J < NB; ++J) acc[q][S::tix(I, J)] = mfma_f16(af, bf[J], acc[q][S::tix(I, J)]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < QW; ++q) {
+                float wq[8];
+                {
+                    const float *wp = &wt32[buf][(QW * wave + q) * WT32_PITCH + 32 * hf + 8 * g];
+                    const f32x4 w0 = *reinterpret_cast<const f32x4 *>(wp), w1 = *reinterpret_cast<const f32x4 *>(wp + 4);
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) { wq[t] = w0[t]; wq[4 + t] = w1[t]; }
+                }
+#pragma unroll
+                for (int I = 0; I < NB; ++I) {
+                    half8 ahi, alo;
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        const float pr = -((float)bf[I][t] * wq[t]);
+                        ahi[t] = (_Float16)pr;
+                        alo[t] = (_Float16)(pr - (float)ahi[t]);
+                    }
+#pragma unroll
+                    for (int J = I; J < NB; ++J) {
+                        acc[q][S::tix(I, J)] = mfma_f16(alo, bf[J], acc[q][S::tix(I, J)]);
+                        acc[q][S::tix(I, J)] = mfma_f16(ahi, bf[J], acc[q][S::tix(I, J)]);
+                    }
+                }
+            }
+            half8 whi, wlo;
+            {
+                const float *wp = &wt32[buf][nn * WT32_PITCH + 32 * hf + 8 * g];
+                const f32x4 w0 = *reinterpret_cast<const f32x4 *>(wp), w1 = *reinterpret_cast<const f32x4 *>(wp + 4);
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    const float wv = t < 4 ? w0[t] : w1[t - 4];
+                    whi[t] = (_Float16)wv;
+                    wlo[t] = (_Float16)(wv - (float)whi[t]);
+                }
+            }
+            mu_acc = mfma_f16(wlo, bw, mu_acc);     // mu~[row 4g + r][feature 16 wave + nn]
+            mu_acc = mfma_f16(whi, bw, mu_acc);
+        }
+    };
+
+    // Software pipeline over blocks of 64 keys: iteration c consumes block c while the DMA of block c+1
+    // lands, and produces the weights of block c+1 on the side: their operand reads go out together with
+    // the fragment reads of the second half, their logits ahead of its MFMAs, exp and store after them (a
+    // weight wave reads only the keys it fetched itself, so its own vmcnt wait suffices).  One barrier per
+    // block.  Past the last block every key is masked (j > iq): that extra round writes zeros to the idle
+    // weight buffer.  `wave` is a scalar, so every branch around an MFMA is a real branch (MFMA ignores EXEC).
     issue_dma(0);
     dma_wait();
     __syncthreads();
-    if (w_wave) make_weights(0);
+    if (w_wave) { weights_load(0); weights_store(0, 0, weights_logits()); }
     __syncthreads();
 
     for (int c = 0; c < nblk; ++c) {
         const int buf = c & 1;
         if (c + 1 < nblk) issue_dma(c + 1);
-#pragma unroll
-        for (int hf = 0; hf < 2; ++hf) {        // two halves of 32 keys
-            half8 bf[NB];
-#pragma unroll
-            for (int I = 0; I < NB; ++I) bf[I] = *reinterpret_cast<const half8 *>(&kt[buf][hf][kt_r + I * 512]);
-            // this wave's feature block for mu~ is re-read from LDS (indexing bf[] by the wave id would
-            // become a per-element select chain)
-            const half8 bw = *reinterpret_cast<const half8 *>(&kt[buf][hf][kt_r + wave * 512]);
-            if (!PRECISE) {
-                // One LDS read brings the weights of all 16 query rows (lane (g, nn): row (nn + QW wave) % 16,
-                // keys 8g..8g+7), rotated so that this wave's own queries sit in lanes 0..QW-1 of every lane row;
-                // the per-query operand scale is then a row broadcast (DPP) instead of more LDS reads.
-                const half8 wa = *reinterpret_cast<const half8 *>(&wt[buf][((nn + QW * wave) & 15) * WT_PITCH + 32 * hf + 8 * g]);
-                const f32x4 wau = __builtin_bit_cast(f32x4, wa);
-#pragma unroll
-                for (int q = 0; q < QW; ++q) {
-                    f32x4 wqu;
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) wqu[t] = (q == 0) ? row_bcast<0>(wau[t]) : (q == 1) ? row_bcast<1>(wau[t])
-                                                        : (q == 2) ? row_bcast<2>(wau[t]) : row_bcast<3>(wau[t]);
-                    const half8 wq = __builtin_bit_cast(half8, wqu);
-#pragma unroll
-                    for (int I = 0; I < NB; ++I) {
-                        const half8 af = bf[I] * wq;
-#pragma unroll
-                        for (int J = I; J < NB; ++J) acc[q][S::tix(I, J)] = mfma_f16(af, bf[J], acc[q][S::tix(I, J)]);
-                    }
-                }
-                mu_acc = mfma_f16(wa, bw, mu_acc);      // mu~[row (4g + r + QW wave) % 16][feature 16 wave + nn]
-            } else {
-#pragma unroll
-                for (int q = 0; q < QW; ++q) {
-                    float wq[8];
-                    {
-                        const float *wp = &wt32[buf][(QW * wave + q) * WT32_PITCH + 32 * hf + 8 * g];
-                        const f32x4 w0 = *reinterpret_cast<const f32x4 *>(wp), w1 = *reinterpret_cast<const f32x4 *>(wp + 4);
-#pragma unroll
-                        for (int t = 0; t < 4; ++t) { wq[t] = w0[t]; wq[4 + t] = w1[t]; }
-                    }
-#pragma unroll
-                    for (int I = 0; I < NB; ++I) {
-                        half8 ahi, alo;
-#pragma unroll
-                        for (int t = 0; t < 8; ++t) {
-                            const float pr = (float)bf[I][t] * wq[t];
-                            ahi[t] = (_Float16)pr;
-                            alo[t] = (_Float16)(pr - (float)ahi[t]);
-                        }
-#pragma unroll
-                        for (int J = I; J < NB; ++J) {
-                            acc[q][S::tix(I, J)] = mfma_f16(alo, bf[J], acc[q][S::tix(I, J)]);
-                            acc[q][S::tix(I, J)] = mfma_f16(ahi, bf[J], acc[q][S::tix(I, J)]);
-                        }
-                    }
-                }
-                half8 whi, wlo;
-                {
-                    const float *wp = &wt32[buf][nn * WT32_PITCH + 32 * hf + 8 * g];
-                    const f32x4 w0 = *reinterpret_cast<const f32x4 *>(wp), w1 = *reinterpret_cast<const f32x4 *>(wp + 4);
-#pragma unroll
-                    for (int t = 0; t < 8; ++t) {
-                        const float wv = t < 4 ? w0[t] : w1[t - 4];
-                        whi[t] = (_Float16)wv;
-                        wlo[t] = (_Float16)(wv - (float)whi[t]);
-                    }
-                }
-                mu_acc = mfma_f16(wlo, bw, mu_acc);     // mu~[row 4g + r][feature 16 wave + nn]
-                mu_acc = mfma_f16(whi, bw, mu_acc);
-            }
-            if (hf == 0 && c + 1 < nblk) {
-                dma_wait();                     // this wave's DMA of block c+1 has landed
-                if (w_wave) make_weights(c + 1);
-            }
-        }
+        load_frags(buf, 0);
+        compute_half(buf, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        dma_wait();                             // this wave's DMA of block c+1 has landed
+        if (NW == 4 || w_wave) weights_load(buf ^ 1);
+        load_frags(buf, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        if (NW == 4 || w_wave) z = weights_logits();
+        compute_half(buf, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (NW == 4 || w_wave) weights_store(c + 1, buf ^ 1, z);
         __syncthreads();
     }
 
@@ -494,7 +525,7 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
 
     // ---- hand mu~ and omega to the waves that own the queries ---------------------------------------
 #pragma unroll
-    for (int r = 0; r < 4; ++r) mus[PRECISE ? 4 * g + r : ((4 * g + r + QW * wave) & 15)][16 * wave + nn] = mu_acc[r];
+    for (int r = 0; r < 4; ++r) mus[4 * g + r][16 * wave + nn] = mu_acc[r];
     __syncthreads();
     if (tid < 16) oms[tid] = (omp[0][tid] + omp[1][tid]) + (omp[2][tid] + omp[3][tid]);
     __syncthreads();
@@ -504,7 +535,7 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     float y0v[QW], om4[QW];
 #pragma unroll
     for (int q = 0; q < QW; ++q) om4[q] = oms[QW * wave + q];
-    solve_wave<DD>(acc, rhs, y0v, om4, &sc[wave][0][0], lambda, g, nn, [&](f32x4 (&r)[QW][NB]) {
+    solve_wave<DD>(acc, rhs, y0v, om4, &sc[wave][0][0], g, nn, [&](f32x4 (&r)[QW][NB]) {
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
             const int qi = QW * wave + q;
@@ -517,7 +548,7 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
                     // would become a branch with its own wait per tile register
                     const int row = 16 * P + 4 * g + t;
                     const float mv = mus[qi][row], qv = bf16_to_f32(qrow[row]);
-                    r[q][P][t] = (nn == 0) ? mv : ((nn == 1) ? qv : 0.f);
+                    r[q][P][t] = (nn == 0) ? -mv : ((nn == 1) ? -qv : 0.f);
                 }
         }
     });
