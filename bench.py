@@ -30,7 +30,7 @@ PEAK_HBM = 8.0e12             # B/s
 # same command, scaled with a copy kernel of known size (profiles/*_hbm_traffic.md, *_mfma_counters.md).
 MEASURED_TRAFFIC = {
     ("C5_decode_bf16_L32768_d64", "decode_partial"): 4.325e9 + 0.111e9,
-    ("C3_prefill_bf16_n4096_d64", "moments"): 2.26e9 + 1.92e9,
+    ("C3_prefill_bf16_n4096_d64", "moments"): 0.762e9 + 0.521e9,
 }
 
 
