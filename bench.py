@@ -167,6 +167,19 @@ def main():
             roof["mfma_issued_frac_of_16bit_peak"] = roof["mfma_issued_tflops"] / (PEAK_MFMA_16BIT / 1e12)
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = MEASURED_TRAFFIC.get((w.name, dom))
+    if roof["bound"] == "mfma":
+        # context for `peak`: the 16-bit MFMA rate this GPU sustains under a chip-wide matrix-core load (the
+        # library's probe: independent 16x16x32 f16 MFMAs and nothing else), measured here with HIP events
+        sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+        llla.probe_mfma_f16(64, sink)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        probe_flops = sum(llla.probe_mfma_f16(512, sink) for _ in range(3))
+        e1.record()
+        torch.cuda.synchronize()
+        roof["sustained_mfma_probe_tflops"] = probe_flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        roof["frac_of_sustained_probe"] = roof["achieved"] / roof["sustained_mfma_probe_tflops"]
 
     result = {
         "metric": "LLA causal forward tokens/s" if not decode else "LLA decode generated tokens/s",

@@ -134,6 +134,16 @@ llla_status llla_decode_path(const void *q, const void *Kc, const void *Vc, void
 void llla_profile_enable(int on);
 int llla_profile_last(float *ms, const char **names, int max);
 
+/*
+ * Measurement aid (used by bench.py; not part of the method).  Enqueues one launch of nothing but
+ * independent v_mfma_f32_16x16x32_f16 instructions on every compute unit, `iters` x 8 per wavefront, and
+ * writes the number of floating-point operations of that launch to *flops (host).  Timing the launch
+ * on `stream` gives the 16-bit matrix-core rate the GPU sustains at the clock it settles to under such a
+ * load, the practical ceiling beside the published peak.  `scratch` is a device buffer of >= 4 bytes that
+ * is never written in practice (it only keeps the arithmetic alive).  1 <= iters <= 2^20.
+ */
+llla_status llla_probe_mfma_f16(int iters, void *scratch, double *flops, void *stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char *llla_status_string(llla_status status);
 

@@ -59,6 +59,8 @@ def lib():
     L.llla_profile_enable.restype = None
     L.llla_profile_last.argtypes = [ctypes.POINTER(f32), ctypes.POINTER(ctypes.c_char_p), i32]
     L.llla_profile_last.restype = i32
+    L.llla_probe_mfma_f16.argtypes = [i32, vp, ctypes.POINTER(ctypes.c_double), vp]
+    L.llla_probe_mfma_f16.restype = i32
     _lib = L
     return L
 
@@ -82,6 +84,16 @@ def profile_last() -> dict:
     names = (ctypes.c_char_p * 16)()
     k = lib().llla_profile_last(ms, names, 16)
     return {names[i].decode(): float(ms[i]) for i in range(k)}
+
+
+def probe_mfma_f16(iters: int, scratch) -> float:
+    """Measurement aid: enqueue the pure-MFMA probe on the current stream; returns its flop count."""
+    flops = ctypes.c_double(0.0)
+    st = lib().llla_probe_mfma_f16(int(iters), ctypes.c_void_p(scratch.data_ptr()), ctypes.byref(flops),
+                                   ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    if st != 0:
+        raise LlaError(st, status_string(st))
+    return float(flops.value)
 
 
 def forward_workspace_bytes(B, H, n, d, dtype) -> int:

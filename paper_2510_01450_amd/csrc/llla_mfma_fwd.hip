@@ -261,12 +261,13 @@ struct MomentsShared {
     _Float16 kt[2][2][DD * KB];                // transposed K, two buffers x two 32-key sub-tiles
     bf16_t kn[2][KB2 * DD];                    // natural K, two buffers
     union {
-        _Float16 h[2][16 * WT_PITCH];          // f16 weights (fast variant), 16 query rows (MFMA width)
-        float f[2][16 * WT32_PITCH];           // fp32 weights (precise variant)
+        _Float16 h[3][16 * WT_PITCH];          // f16 weights (fast variant), 16 query rows (MFMA width), 3 blocks in flight
+        float f[3][16 * WT32_PITCH];           // fp32 weights (precise variant)
     } w;
     float omp[4][16];
     float mus[16][DD + 4];
     float oms[16];
+    bf16_t qt[16][DD + 8];                     // the workgroup's query rows (operand of the logits)
     float sc[S::NW][S::QW][16 * SC_PITCH];     // per-wave scratch tiles of the solve
 };
 
@@ -316,11 +317,13 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     // weight role: lane (g, nn) of wave w < 4 serves query i0 + nn (nn < QB) and keys 16w + 4g + r
     const int iq = i0 + nn, iqc = min(iq, n - 1);
     const bool q_live = nn < QB;
-    bf16x8 qf[NF];
-    {
+    if (w_wave) {   // each (g, nn) lane of the four weight waves would store the same chunks: wave 0 does
         const bf16_t *qrow = Qh + (int64_t)iqc * sq.seq;
+        if (wave == 0) {
 #pragma unroll
-        for (int f = 0; f < NF; ++f) qf[f] = *reinterpret_cast<const bf16x8 *>(qrow + 32 * f + 8 * g);
+            for (int f = 0; f < NF; ++f)
+                *reinterpret_cast<bf16x8 *>(&sm.qt[nn][32 * f + 8 * g]) = *reinterpret_cast<const bf16x8 *>(qrow + 32 * f + 8 * g);
+        }
     }
     const float mrow = Mg[(size_t)bh * mpitch + iqc];
 
@@ -383,10 +386,13 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     };
     // Weights of block blk, w = 2^(c<q,k> - m) for this wave's 16 keys, in three steps that the loop below
     // spreads over an iteration so that no step waits on the one before it: operand reads, logits (MFMA), exp + store.
-    bf16x8 knf[NF];
+    bf16x8 knf[NF], qf[NF];
     auto weights_load = [&](int buf) {
 #pragma unroll
-        for (int f = 0; f < NF; ++f) knf[f] = *reinterpret_cast<const bf16x8 *>(&kn[buf][kn_r[f]]);
+        for (int f = 0; f < NF; ++f) {
+            knf[f] = *reinterpret_cast<const bf16x8 *>(&kn[buf][kn_r[f]]);
+            qf[f] = *reinterpret_cast<const bf16x8 *>(&sm.qt[nn][32 * f + 8 * g]);
+        }
     };
     auto weights_logits = [&]() {
         f32x4 z = {0.f, 0.f, 0.f, 0.f};
@@ -400,122 +406,146 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
         for (int r = 0; r < 4; ++r) {
             const int j = blk * KB2 + 16 * wave + 4 * g + r;
             const float wgt = __builtin_amdgcn_exp2f(z[r] * cscale - mrow);
-            wf[r] = (q_live && j <= iq) ? wgt : 0.f;
+            wf[r] = (q_live && j <= iq) ? -wgt : 0.f;     // stored negated: the tiles accumulate -(w k) k^T
         }
         if (PRECISE) {
             *reinterpret_cast<f32x4 *>(&wt32[buf][nn * WT32_PITCH + 16 * wave + 4 * g]) = f32x4{wf[0], wf[1], wf[2], wf[3]};
-            om_part += (wf[0] + wf[1]) + (wf[2] + wf[3]);
+            om_part -= (wf[0] + wf[1]) + (wf[2] + wf[3]);
         } else {
             half4 wv;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 wv[r] = (_Float16)wf[r];
-                om_part += (float)wv[r];        // omega sums the weights exactly as the MFMAs see them
+                om_part -= (float)wv[r];        // omega sums the weights exactly as the MFMAs see them
             }
             *reinterpret_cast<half4 *>(&wt[buf][nn * WT_PITCH + 16 * wave + 4 * g]) = wv;
         }
     };
 
-    // Operand fragments of one half (32 keys) of a block and the MFMAs that consume them.
-    half8 bf[NB], bw, wa;
-    auto load_frags = [&](int buf, int hf) {
+    // Operand fragments of one half (32 keys) of a block: the NB feature blocks of the transposed tile, and
+    // this wave's feature block for mu~ (re-read from LDS: indexing f[] by the wave id would become a
+    // per-element select chain).  Two sets, so that the next half is in flight while this one is consumed.
+    struct Frags { half8 f[NB]; };
+    Frags fa, fb;
+    auto load_frags = [&](Frags &fr, int buf, int hf) {
 #pragma unroll
-        for (int I = 0; I < NB; ++I) bf[I] = *reinterpret_cast<const half8 *>(&kt[buf][hf][kt_r + I * 512]);
-        // this wave's feature block for mu~ is re-read from LDS (indexing bf[] by the wave id would
-        // become a per-element select chain)
-        bw = *reinterpret_cast<const half8 *>(&kt[buf][hf][kt_r + wave * 512]);
-        // the f16 weights of all 16 query rows as the A operand of the mu~ product (lane (g, nn): row nn, keys 8g..8g+7)
-        if (!PRECISE) wa = *reinterpret_cast<const half8 *>(&wt[buf][nn * WT_PITCH + 32 * hf + 8 * g]);
+        for (int I = 0; I < NB; ++I) fr.f[I] = *reinterpret_cast<const half8 *>(&kt[buf][hf][kt_r + I * 512]);
     };
-    auto compute_half = [&](int buf, int hf) {
+    // The MFMAs of work items [lo, hi) of one half; item = (query q, feature block I), q-major.  wb = weight buffer.
+    auto compute_items = [&](const Frags &fr, int wb, int hf, int lo, int hi) {
         if (!PRECISE) {
-            mu_acc = mfma_f16(wa, bw, mu_acc);      // mu~[row 4g + r][feature 16 wave + nn]
-            // the query's 8 weights of this lane's key chunk: one address per lane group (an LDS broadcast
-            // read), fetched one query ahead of its use
-            const _Float16 *wrow = &wt[buf][QW * wave * WT_PITCH + 32 * hf + 8 * g];
-            half8 wq_next = *reinterpret_cast<const half8 *>(wrow);
+            // the query's 8 weights of this lane's key chunk: one address per lane group (an LDS broadcast read)
+            const _Float16 *wrow = &wt[wb][QW * wave * WT_PITCH + 32 * hf + 8 * g];
+            half8 wq = *reinterpret_cast<const half8 *>(wrow + (lo / NB) * WT_PITCH);
 #pragma unroll
-            for (int q = 0; q < QW; ++q) {
-                const half8 wq = wq_next;
-                if (q + 1 < QW) wq_next = *reinterpret_cast<const half8 *>(wrow + (q + 1) * WT_PITCH);
+            for (int it = lo; it < hi; ++it) {
+                const int q = it / NB, I = it % NB;
+                if (I == 0 && it != lo) wq = *reinterpret_cast<const half8 *>(wrow + q * WT_PITCH);
+                const half8 af = fr.f[I] * wq;
 #pragma unroll
-                for (int I = 0; I < NB; ++I) {
-                    const half8 af = -(bf[I] * wq);
-#pragma unroll
-                    for (int J = I; J < NB; ++J) acc[q][S::tix(I, J)] = mfma_f16(af, bf[J], acc[q][S::tix(I, J)]);
-                }
-                __builtin_amdgcn_sched_barrier(0);
+                for (int J = I; J < NB; ++J) acc[q][S::tix(I, J)] = mfma_f16(af, fr.f[J], acc[q][S::tix(I, J)]);
             }
         } else {
+            float wq[8];
 #pragma unroll
-            for (int q = 0; q < QW; ++q) {
-                float wq[8];
-                {
-                    const float *wp = &wt32[buf][(QW * wave + q) * WT32_PITCH + 32 * hf + 8 * g];
+            for (int it = lo; it < hi; ++it) {
+                const int q = it / NB, I = it % NB;
+                if (I == 0 || it == lo) {
+                    const float *wp = &wt32[wb][(QW * wave + q) * WT32_PITCH + 32 * hf + 8 * g];
                     const f32x4 w0 = *reinterpret_cast<const f32x4 *>(wp), w1 = *reinterpret_cast<const f32x4 *>(wp + 4);
 #pragma unroll
                     for (int t = 0; t < 4; ++t) { wq[t] = w0[t]; wq[4 + t] = w1[t]; }
                 }
-#pragma unroll
-                for (int I = 0; I < NB; ++I) {
-                    half8 ahi, alo;
-#pragma unroll
-                    for (int t = 0; t < 8; ++t) {
-                        const float pr = -((float)bf[I][t] * wq[t]);
-                        ahi[t] = (_Float16)pr;
-                        alo[t] = (_Float16)(pr - (float)ahi[t]);
-                    }
-#pragma unroll
-                    for (int J = I; J < NB; ++J) {
-                        acc[q][S::tix(I, J)] = mfma_f16(alo, bf[J], acc[q][S::tix(I, J)]);
-                        acc[q][S::tix(I, J)] = mfma_f16(ahi, bf[J], acc[q][S::tix(I, J)]);
-                    }
-                }
-            }
-            half8 whi, wlo;
-            {
-                const float *wp = &wt32[buf][nn * WT32_PITCH + 32 * hf + 8 * g];
-                const f32x4 w0 = *reinterpret_cast<const f32x4 *>(wp), w1 = *reinterpret_cast<const f32x4 *>(wp + 4);
+                half8 ahi, alo;
 #pragma unroll
                 for (int t = 0; t < 8; ++t) {
-                    const float wv = t < 4 ? w0[t] : w1[t - 4];
-                    whi[t] = (_Float16)wv;
-                    wlo[t] = (_Float16)(wv - (float)whi[t]);
+                    const float pr = (float)fr.f[I][t] * wq[t];
+                    ahi[t] = (_Float16)pr;
+                    alo[t] = (_Float16)(pr - (float)ahi[t]);
+                }
+#pragma unroll
+                for (int J = I; J < NB; ++J) {
+                    acc[q][S::tix(I, J)] = mfma_f16(alo, fr.f[J], acc[q][S::tix(I, J)]);
+                    acc[q][S::tix(I, J)] = mfma_f16(ahi, fr.f[J], acc[q][S::tix(I, J)]);
                 }
             }
-            mu_acc = mfma_f16(wlo, bw, mu_acc);     // mu~[row 4g + r][feature 16 wave + nn]
-            mu_acc = mfma_f16(whi, bw, mu_acc);
         }
     };
+    // -mu~ of one half: the (negated) weights of all 16 query rows are the A operand (lane (g, nn): row nn, keys
+    // 8g..8g+7), this wave's feature block of the tile the B operand (re-read from LDS: indexing f[] by the wave
+    // id would become a per-element select chain).  Operands are fetched by mu_load_a / mu_load_b, consumed by mu_mfma.
+    half8 mu_a, mu_a2, mu_b;
+    auto mu_load_b = [&](int buf, int hf) { mu_b = *reinterpret_cast<const half8 *>(&kt[buf][hf][kt_r + wave * 512]); };
+    auto mu_load_a = [&](int wb, int hf) {
+        if (!PRECISE) {
+            mu_a = *reinterpret_cast<const half8 *>(&wt[wb][nn * WT_PITCH + 32 * hf + 8 * g]);
+        } else {
+            const float *wp = &wt32[wb][nn * WT32_PITCH + 32 * hf + 8 * g];
+            const f32x4 w0 = *reinterpret_cast<const f32x4 *>(wp), w1 = *reinterpret_cast<const f32x4 *>(wp + 4);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const float wv = t < 4 ? w0[t] : w1[t - 4];
+                mu_a[t] = (_Float16)wv;
+                mu_a2[t] = (_Float16)(wv - (float)mu_a[t]);
+            }
+        }
+    };
+    auto mu_mfma = [&]() {
+        if (PRECISE) mu_acc = mfma_f16(mu_a2, mu_b, mu_acc);
+        mu_acc = mfma_f16(mu_a, mu_b, mu_acc);          // -mu~[row 4g + r][feature 16 wave + nn]
+    };
 
-    // Software pipeline over blocks of 64 keys: iteration c consumes block c while the DMA of block c+1
-    // lands, and produces the weights of block c+1 on the side: their operand reads go out together with
-    // the fragment reads of the second half, their logits ahead of its MFMAs, exp and store after them (a
-    // weight wave reads only the keys it fetched itself, so its own vmcnt wait suffices).  One barrier per
-    // block.  Past the last block every key is masked (j > iq): that extra round writes zeros to the idle
-    // weight buffer.  `wave` is a scalar, so every branch around an MFMA is a real branch (MFMA ignores EXEC).
+    // Software pipeline over blocks of 64 keys, one barrier per block, placed between its two halves:
+    //   first half of block c : fragments of its second half are fetched from LDS meanwhile; the weights of
+    //                           block c+1 are produced on the side (their key rows were fetched by this very
+    //                           wave, so its own vmcnt wait suffices) and stored before the barrier;
+    //   barrier               : block c+1 (tiles of all waves, weights) is now visible, and nobody reads the
+    //                           tiles of block c any more, so the DMA of block c+2 may overwrite them;
+    //   second half of block c: fragments of the first half of block c+1 are fetched meanwhile.
+    // The weights live in three buffers: a wave that is ahead writes the weights of block c+1 while one that
+    // is behind still reads those of block c-1.  Past the last block every key is masked (j > iq): that extra
+    // round stores zeros.  `wave` is a scalar, so every branch around an MFMA is a real branch (MFMA ignores EXEC).
+    constexpr int ITEMS = QW * NB, Q2 = ITEMS / 2, Q3 = 3 * ITEMS / 4;
     issue_dma(0);
+    if (nblk > 1) issue_dma(1);
     dma_wait();
     __syncthreads();
     if (w_wave) { weights_load(0); weights_store(0, 0, weights_logits()); }
     __syncthreads();
+    load_frags(fa, 0, 0);
 
+    int wb = 0;                                 // weight buffer of block c
     for (int c = 0; c < nblk; ++c) {
-        const int buf = c & 1;
-        if (c + 1 < nblk) issue_dma(c + 1);
-        load_frags(buf, 0);
-        compute_half(buf, 0);
+        const int buf = c & 1, wbn = (wb == 2) ? 0 : wb + 1;
+        // ---- first half -------------------------------------------------------------------------------
+        load_frags(fb, buf, 1);
         __builtin_amdgcn_sched_barrier(0);
-        dma_wait();                             // this wave's DMA of block c+1 has landed
+        compute_items(fa, wb, 0, 0, Q2);
+        __builtin_amdgcn_sched_barrier(0);
+        dma_wait();                             // this wave's part of block c+1 has landed
         if (NW == 4 || w_wave) weights_load(buf ^ 1);
-        load_frags(buf, 1);
+        mu_load_b(buf, 0);
+        mu_load_a(wb, 0);
         __builtin_amdgcn_sched_barrier(0);
+        compute_items(fa, wb, 0, Q2, Q3);
         f32x4 z = {0.f, 0.f, 0.f, 0.f};
         if (NW == 4 || w_wave) z = weights_logits();
-        compute_half(buf, 1);
+        mu_mfma();
+        compute_items(fa, wb, 0, Q3, ITEMS);
         __builtin_amdgcn_sched_barrier(0);
-        if (NW == 4 || w_wave) weights_store(c + 1, buf ^ 1, z);
+        if (NW == 4 || w_wave) weights_store(c + 1, wbn, z);
+        mu_load_b(buf, 1);                      // the last read of block c's tiles: they are overwritten after the barrier
         __syncthreads();
+        if (c + 2 < nblk) issue_dma(c + 2);
+        // ---- second half ------------------------------------------------------------------------------
+        load_frags(fa, buf ^ 1, 0);             // first half of block c+1 (unused after the last block)
+        mu_load_a(wb, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        compute_items(fb, wb, 1, 0, Q3);
+        mu_mfma();
+        compute_items(fb, wb, 1, Q3, ITEMS);
+        __builtin_amdgcn_sched_barrier(0);
+        wb = wbn;
     }
 
     // omega: lanes (g, nn) of the four weight waves hold partial sums for query row nn
@@ -525,7 +555,7 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
 
     // ---- hand mu~ and omega to the waves that own the queries ---------------------------------------
 #pragma unroll
-    for (int r = 0; r < 4; ++r) mus[4 * g + r][16 * wave + nn] = mu_acc[r];
+    for (int r = 0; r < 4; ++r) mus[4 * g + r][16 * wave + nn] = mu_acc[r];   // -mu~ (negated weights)
     __syncthreads();
     if (tid < 16) oms[tid] = (omp[0][tid] + omp[1][tid]) + (omp[2][tid] + omp[3][tid]);
     __syncthreads();
@@ -548,7 +578,7 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
                     // would become a branch with its own wait per tile register
                     const int row = 16 * P + 4 * g + t;
                     const float mv = mus[qi][row], qv = bf16_to_f32(qrow[row]);
-                    r[q][P][t] = (nn == 0) ? -mv : ((nn == 1) ? -qv : 0.f);
+                    r[q][P][t] = (nn == 0) ? mv : ((nn == 1) ? -qv : 0.f);      // mus holds -mu~
                 }
         }
     });
