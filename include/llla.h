@@ -106,7 +106,8 @@ llla_status llla_forward_path(const void *Q, const void *K, const void *V, void 
  *   q       : device, [B, H, d] contiguous, dtype `in`
  *   Kc, Vc  : device, [B, H, L_max, d] caches in dtype `in`, strides sk / sv
  *   o       : device, [B, H, d] contiguous, dtype `out`
- *   seqlens : device int32 [B], valid length of each sequence (1..L_max), or NULL = all L_max
+ *   seqlens : device int32 [B], valid length of each sequence (1..L_max), or NULL = all L_max;
+ *             cache rows at and beyond a sequence's length are never read
  */
 size_t llla_decode_workspace_bytes(int B, int H, int L_max, int d, llla_dtype in);
 

@@ -1,5 +1,5 @@
-// Matrix-core decode path of Local Linear Attention for gfx950: bf16 caches, d = 64, all sequences
-// of the batch at the full cache length.  One query per (batch, head) against a cache that already
+// Matrix-core decode path of Local Linear Attention for gfx950: bf16 caches, d = 64, cache capacity
+// L_max >= 1024, optional per-sequence lengths.  One query per (batch, head) against a cache that already
 // holds the new token: the last row of the causal forward (Section 2.3: LLA keeps a Theta(n d) KV
 // cache; Section 3.2: rows are independent).
 //
@@ -67,8 +67,9 @@ __device__ inline void dma_wait_pending() { asm volatile("s_waitcnt vmcnt(%0)" :
 __global__ __launch_bounds__(NT, 2) void decode_partial_kernel(const bf16_t *__restrict__ qg,
                                                                const bf16_t *__restrict__ Kg,
                                                                const bf16_t *__restrict__ Vg, llla_strides sk,
-                                                               llla_strides sv, int H, int L, int keys_per_wave,
-                                                               int nparts, float cscale, float *__restrict__ parts)
+                                                               llla_strides sv, const int32_t *__restrict__ seqlens,
+                                                               int H, int L_max, int nparts, float cscale,
+                                                               float *__restrict__ parts)
 {
     __shared__ __align__(16) bf16_t stage[4][NSTAGE][STAGE_H];     // 4 waves x NSTAGE stages x 8 KB
 
@@ -76,6 +77,10 @@ __global__ __launch_bounds__(NT, 2) void decode_partial_kernel(const bf16_t *__r
               nn = lane % 16;
     const int bh = blockIdx.y, b = bh / H, h = bh % H;
     const int part = blockIdx.x * 4 + wave;
+    // the sequence's own length decides the share of each wave, so short sequences stay balanced too; rows at
+    // and beyond L are never read (a cache tail may hold anything, and 0 * NaN would poison the moments)
+    const int L = seqlens ? min(max(seqlens[b], 1), L_max) : L_max;
+    const int keys_per_wave = ((L + nparts - 1) / nparts + STEP - 1) / STEP * STEP;
     const int r0 = part * keys_per_wave;
     const int r1 = min(r0 + keys_per_wave, L);
     const int nsteps = r1 > r0 ? (r1 - r0 + STEP - 1) / STEP : 0;
@@ -343,7 +348,7 @@ size_t mfma_decode_workspace_bytes(int B, int H, int L_max, int d, llla_dtype in
     return round_up((size_t)B * H * s.nparts * PART_F * sizeof(float), 256);
 }
 
-bool mfma_decode_takes(const Problem &p) { return p.seqlens == nullptr && p.n >= MIN_L; }
+bool mfma_decode_takes(const Problem &p) { return p.n >= MIN_L; }
 
 hipError_t mfma_decode(const Problem &p)
 {
@@ -353,8 +358,7 @@ hipError_t mfma_decode(const Problem &p)
     const float cscale = p.scale * LOG2E;
     stage_mark(p.stream, "decode_partial");
     hipLaunchKernelGGL(decode_partial_kernel, dim3(s.nsplit, bh), dim3(NT), 0, p.stream, (const bf16_t *)p.Q,
-                       (const bf16_t *)p.K, (const bf16_t *)p.V, p.sk, p.sv, p.H, p.n, s.keys_per_wave, s.nparts, cscale,
-                       parts);
+                       (const bf16_t *)p.K, (const bf16_t *)p.V, p.sk, p.sv, p.seqlens, p.H, p.n, s.nparts, cscale, parts);
     stage_mark(p.stream, "decode_merge");
     hipLaunchKernelGGL(decode_merge_kernel, dim3((bh + QW - 1) / QW), dim3(NT), 0, p.stream, (const bf16_t *)p.Q,
                        parts, bh, s.nparts, p.lambda, p.O, p.out == LLLA_BF16 ? 1 : 0);

@@ -195,6 +195,25 @@ def test_decode_seqlens_and_forward_last_row():
     assert err < 1e-3, err
 
 
+@pytest.mark.parametrize("path", ["mfma", "valu"])
+def test_decode_seqlens_long_cache_ignores_the_tail(path):
+    """Per-sequence lengths on a cache long enough for the matrix-core path; everything at and beyond a
+    sequence's length is poisoned with NaN and must not reach the output."""
+    w = _small("decsl2", 5, 2, 3000, 64, "bf16", index=121).with_shape(kind="decode")
+    q, Kc, Vc = workloads.make_inputs(w)
+    lens = [3000, 1, 33, 1024, 2999]
+    ref = oracle.decode(q, Kc, Vc, w.lam, w.scale, seqlens=lens)
+    Kp, Vp = Kc.clone(), Vc.clone()
+    for b, L in enumerate(lens):
+        Kp[b, :, L:] = float("nan")
+        Vp[b, :, L:] = float("nan")
+    sl = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    got = llla.llla_decode(q.to(DEV), Kp.to(DEV), Vp.to(DEV), w.lam, w.scale, seqlens=sl, path=path).cpu().numpy()
+    for b, L in enumerate(lens):
+        print(check(got[b:b + 1, :, None, :], ref[b:b + 1, :, None, :], np.array([L - 1]), w.d, w.tol,
+                    "decode %s seqlen %d of 3000" % (path, L)))
+
+
 # ---- the large configurations: sampled rows --------------------------------------------------------
 def _sampled(w, heads):
     Q, K, V = workloads.make_inputs(w)
