@@ -243,6 +243,13 @@ __device__ inline void dma16(const void *gsrc, void *lds_base)
     const unsigned lds = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void_ptr)lds_base);
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(lds) : "memory", "m0");
 }
+// The same with a wave-uniform base address in scalar registers plus a 32-bit per-lane byte offset: no vector-ALU
+// address arithmetic per transfer.
+__device__ inline void dma16_base(const void *sbase, unsigned voff, void *lds_base)
+{
+    const unsigned lds = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void_ptr)lds_base);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds) : "memory", "m0");
+}
 #pragma clang diagnostic pop
 __device__ inline void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 

@@ -83,7 +83,7 @@ __global__ __launch_bounds__(NT, 2) void decode_partial_kernel(const bf16_t *__r
     const int keys_per_wave = ((L + nparts - 1) / nparts + STEP - 1) / STEP * STEP;
     const int r0 = part * keys_per_wave;
     const int r1 = min(r0 + keys_per_wave, L);
-    const int nsteps = r1 > r0 ? (r1 - r0 + STEP - 1) / STEP : 0;
+    const int nsteps = __builtin_amdgcn_readfirstlane(r1 > r0 ? (r1 - r0 + STEP - 1) / STEP : 0);
     const bf16_t *Kh = Kg + b * sk.batch + h * sk.head;
     const bf16_t *Vh = Vg + b * sv.batch + h * sv.head;
     bf16_t *mystage = &stage[wave][0][0];
@@ -127,14 +127,37 @@ __global__ __launch_bounds__(NT, 2) void decode_partial_kernel(const bf16_t *__r
     for (int t = 0; t < 4; ++t) { muacc[t] = f32x4{0.f, 0.f, 0.f, 0.f}; yvacc[t] = f32x4{0.f, 0.f, 0.f, 0.f}; }
     float om = 0.f, m = -INFINITY;
 
-    auto issue_dma = [&](int step) {      // rows beyond the cache are clamped (their weights are 0)
-        bf16_t *dst = mystage + (step % NSTAGE) * STAGE_H;
-        const int j0 = r0 + step * STEP;
+    // Waves that start together on equally spaced addresses would keep hitting the same memory channels in
+    // step; each wave therefore sweeps its share of the keys from a different starting step and wraps around
+    // (the moments do not depend on the order of the keys).
+    const int rot = nsteps > 0 ? (int)((part * 7u + bh * 13u) % (unsigned)nsteps) : 0;
+    auto step_pos = [&](int step) { const int t = step + rot; return t >= nsteps ? t - nsteps : t; };
+    // addresses: a scalar base per step (row j0 of the head) plus per-lane byte offsets that never change, so a
+    // transfer costs no vector-ALU work; only a step that reaches past the sequence clamps its rows per lane
+    // (to the last valid row: their weights are 0)
+    unsigned koff[4], voff[4];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int j = min(j0 + dma_key[t], L - 1);
-            dma16(Kh + (int64_t)j * sk.seq + dma_col[t], dst + 512 * t);
-            dma16(Vh + (int64_t)j * sv.seq + dma_col[t], dst + TILE_H + 512 * t);
+    for (int t = 0; t < 4; ++t) {
+        koff[t] = 2u * (unsigned)(dma_key[t] * (int)sk.seq + dma_col[t]);
+        voff[t] = 2u * (unsigned)(dma_key[t] * (int)sv.seq + dma_col[t]);
+    }
+    auto issue_dma = [&](int step) {
+        bf16_t *dst = mystage + (step % NSTAGE) * STAGE_H;
+        const int j0 = r0 + step_pos(step < nsteps ? step : 0) * STEP;
+        if (j0 + STEP <= L) {
+            const bf16_t *kb = Kh + (int64_t)j0 * sk.seq, *vb = Vh + (int64_t)j0 * sv.seq;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                dma16_base(kb, koff[t], dst + 512 * t);
+                dma16_base(vb, voff[t], dst + TILE_H + 512 * t);
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int j = min(j0 + dma_key[t], L - 1);
+                dma16(Kh + (int64_t)j * sk.seq + dma_col[t], dst + 512 * t);
+                dma16(Vh + (int64_t)j * sv.seq + dma_col[t], dst + TILE_H + 512 * t);
+            }
         }
     };
 
@@ -147,7 +170,7 @@ __global__ __launch_bounds__(NT, 2) void decode_partial_kernel(const bf16_t *__r
         dma_wait_pending<DMA_PER_STAGE *(NSTAGE - 1)>();
         const bf16_t *kt = mystage + (s % NSTAGE) * STAGE_H;
         const bf16_t *vt = kt + TILE_H;
-        const int j0 = r0 + s * STEP;
+        const int j0 = r0 + step_pos(s) * STEP;
 
         // logits of the 32 keys: lane (g, *) gets keys 4g..4g+3 (sub-tile 0) and 16+4g.. (sub-tile 1)
         float tl[8];
@@ -348,7 +371,12 @@ size_t mfma_decode_workspace_bytes(int B, int H, int L_max, int d, llla_dtype in
     return round_up((size_t)B * H * s.nparts * PART_F * sizeof(float), 256);
 }
 
-bool mfma_decode_takes(const Problem &p) { return p.n >= MIN_L; }
+bool mfma_decode_takes(const Problem &p)
+{
+    // per-lane byte offsets inside one 32-key step are kept in 32 bits
+    const int64_t reach = 2 * 32 * (p.sk.seq > p.sv.seq ? p.sk.seq : p.sv.seq);
+    return p.n >= MIN_L && reach < (int64_t(1) << 31);
+}
 
 hipError_t mfma_decode(const Problem &p)
 {
