@@ -41,6 +41,10 @@ def _load():
                                          ctypes.c_double, ctypes.c_double, ctypes.c_int,
                                          ip, ctypes.c_int, dp]
         lib.llla_oracle_rows.restype = ctypes.c_int
+        lib.llla_oracle_rows_ex.argtypes = [dp, dp, dp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                            ctypes.c_double, dp, ctypes.c_double, ctypes.c_int,
+                                            ip, ctypes.c_int, dp, dp, dp]
+        lib.llla_oracle_rows_ex.restype = ctypes.c_int
         lib.llla_oracle_decode.argtypes = [dp, dp, dp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                            ctypes.c_double, ctypes.c_double, dp]
         lib.llla_oracle_decode.restype = ctypes.c_int
@@ -83,6 +87,40 @@ def forward_head(Q, K, V, lam: float, scale: float, causal: bool = True, rows=No
     if bad:
         raise FloatingPointError("oracle: %d rows had a non positive-definite normal matrix" % bad)
     return out
+
+
+def forward_head_ex(Q, K, V, lam, scale: float, causal: bool = True, rows=None):
+    """One head with the extras: ``lam`` a float or an [n] array of per-row ridges.  Returns
+    (O [len(rows), dv], rho [len(rows), d], delta [len(rows)]) in fp64."""
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    n, d = Q.shape
+    dv = V.shape[1]
+    rows = np.arange(n, dtype=np.int32) if rows is None else np.ascontiguousarray(rows, dtype=np.int32)
+    lam_rows = None if np.ndim(lam) == 0 else _f64(lam)
+    assert lam_rows is None or lam_rows.shape == (n,)
+    out = np.empty((len(rows), dv), dtype=np.float64)
+    rho = np.empty((len(rows), d), dtype=np.float64)
+    delta = np.empty((len(rows),), dtype=np.float64)
+    bad = _load().llla_oracle_rows_ex(_dp(Q), _dp(K), _dp(V), n, d, dv, float(lam) if lam_rows is None else 0.0,
+                                      _dp(lam_rows) if lam_rows is not None else None, float(scale),
+                                      1 if causal else 0, rows.ctypes.data_as(ctypes.POINTER(ctypes.c_int)),
+                                      len(rows), _dp(out), _dp(rho), _dp(delta))
+    if bad:
+        raise FloatingPointError("oracle: %d rows had a non positive-definite normal matrix" % bad)
+    return out, rho, delta
+
+
+def forward_ex(Q, K, V, lam, scale: float, causal: bool = True, rows=None):
+    """Q, K, V: [B, H, n, d]; ``lam`` a float or a [B, H, n] array.  Returns (O, rho, delta) stacked over B, H."""
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    B, H = Q.shape[:2]
+    lam_a = None if np.ndim(lam) == 0 else _f64(lam)
+    res = [[forward_head_ex(Q[b, h], K[b, h], V[b, h], lam if lam_a is None else lam_a[b, h], scale, causal, rows)
+            for h in range(H)] for b in range(B)]
+    O = np.asarray([[r[0] for r in row] for row in res])
+    R = np.asarray([[r[1] for r in row] for row in res])
+    Dl = np.asarray([[r[2] for r in row] for row in res])
+    return O, R, Dl
 
 
 def forward(Q, K, V, lam: float, scale: float, causal: bool = True, rows=None) -> np.ndarray:

@@ -27,6 +27,12 @@
  * have been seen (its running maximum equals the true row maximum), and lambda is added to
  * moments of exactly these max-shifted weights, as in Algorithms 1 and 2.
  *
+ * Optional extras of the *_ex entry point: a ridge per query row (Appendix C makes lambda a learnable,
+ * position-dependent quantity; row i then uses lambda_i in its own normal equations and nothing else
+ * changes), and the two per-row statistics of Eq. (lla) that FlashLLA keeps for its backward pass
+ * (end of Section 3.2): rho_i = Sigma_i^{-1} mu_i and delta_i = omega_i - mu_i^T rho_i, computed here
+ * from the blocks omega_i, mu_i, Sigma_i of A by a second, separate Cholesky of the d x d block.
+ *
  * Nothing here is blocked, fused, recentred or iterated: no tilde moments, no relmm, no CG.
  * Build: gcc -O2 -fopenmp -shared -fPIC -o libllla_oracle.so llla_oracle.c -lm
  */
@@ -74,7 +80,8 @@ static void chol_solve(const double *L, int p, double *B, int m)
 /* One query against nk keys.  q: [d]; K: [nk, d]; V: [nk, dv]; out: [dv].
  * scratch: (d+1)*(d+1) + (d+1)*dv + nk doubles.  Returns 0, or 1 if A is not positive definite. */
 static int lla_one_query(const double *q, const double *K, const double *V, int nk, int d, int dv,
-                         double lambda, double scale, double *out, double *scratch)
+                         double lambda, double scale, double *out, double *scratch, double *rho,
+                         double *delta)
 {
     const int p = d + 1;
     double *A = scratch;
@@ -107,6 +114,29 @@ static int lla_one_query(const double *q, const double *K, const double *V, int 
     }
     for (int r = 1; r < p; ++r) A[r * p + r] += lambda;   /* ridge on W only, not on b */
 
+    if (rho || delta) {
+        /* Eq. (lla): rho = Sigma^{-1} mu, delta = omega - mu^T rho, with omega = A[0][0], mu = A[1:,0] and
+         * Sigma (ridge included) = A[1:,1:]; the lower triangle of A is what was accumulated above */
+        double *Sg = (double *)malloc(sizeof(double) * (size_t)d * d);
+        double *rh = (double *)malloc(sizeof(double) * (size_t)d);
+        if (!Sg || !rh) { free(Sg); free(rh); free(x); return 2; }
+        for (int r = 0; r < d; ++r) {
+            for (int c = 0; c <= r; ++c) Sg[r * d + c] = A[(r + 1) * p + (c + 1)];
+            rh[r] = A[(r + 1) * p];
+        }
+        int sbad = chol_factor(Sg, d);
+        if (!sbad) {
+            chol_solve(Sg, d, rh, 1);
+            double dl = A[0];
+            for (int r = 0; r < d; ++r) dl -= A[(r + 1) * p] * rh[r];
+            if (rho) for (int r = 0; r < d; ++r) rho[r] = rh[r];
+            if (delta) *delta = dl;
+        }
+        free(Sg);
+        free(rh);
+        if (sbad) { free(x); return 1; }
+    }
+
     int bad = chol_factor(A, p);
     if (!bad) {
         chol_solve(A, p, Bv, dv);
@@ -121,10 +151,13 @@ static int lla_one_query(const double *q, const double *K, const double *V, int 
  *   Q [n, d], K [n, d], V [n, dv] row-major fp64; rows[nrows] are 0-based query indices;
  *   causal != 0: row i sees keys 0..i inclusive; causal == 0: every row sees all n keys.
  *   O [nrows, dv] receives the outputs in the order of rows[].
+ *   lambda_rows: NULL, or [n] ridges, row i using lambda_rows[i] instead of lambda.
+ *   R [nrows, d] and Delta [nrows]: NULL, or receive rho_i and delta_i of Eq. (lla).
  * Returns the number of rows whose normal matrix was not positive definite (0 when lambda > 0).
  */
-int llla_oracle_rows(const double *Q, const double *K, const double *V, int n, int d, int dv,
-                     double lambda, double scale, int causal, const int *rows, int nrows, double *O)
+int llla_oracle_rows_ex(const double *Q, const double *K, const double *V, int n, int d, int dv,
+                        double lambda, const double *lambda_rows, double scale, int causal, const int *rows,
+                        int nrows, double *O, double *R, double *Delta)
 {
     int failures = 0;
     const size_t per = (size_t)(d + 1) * (d + 1) + (size_t)(d + 1) * dv + (size_t)n;
@@ -136,12 +169,20 @@ int llla_oracle_rows(const double *Q, const double *K, const double *V, int n, i
             const int i = rows[t];
             const int nk = causal ? i + 1 : n;
             if (!scratch || i < 0 || i >= n) { failures += 1; continue; }
-            failures += lla_one_query(Q + (size_t)i * d, K, V, nk, d, dv, lambda, scale,
-                                      O + (size_t)t * dv, scratch) ? 1 : 0;
+            failures += lla_one_query(Q + (size_t)i * d, K, V, nk, d, dv, lambda_rows ? lambda_rows[i] : lambda,
+                                      scale, O + (size_t)t * dv, scratch, R ? R + (size_t)t * d : NULL,
+                                      Delta ? Delta + t : NULL) ? 1 : 0;
         }
         free(scratch);
     }
     return failures;
+}
+
+/* The same with one ridge for all rows and no statistics. */
+int llla_oracle_rows(const double *Q, const double *K, const double *V, int n, int d, int dv,
+                     double lambda, double scale, int causal, const int *rows, int nrows, double *O)
+{
+    return llla_oracle_rows_ex(Q, K, V, n, d, dv, lambda, NULL, scale, causal, rows, nrows, O, NULL, NULL);
 }
 
 /*
@@ -155,7 +196,7 @@ int llla_oracle_decode(const double *q, const double *K, const double *V, int L,
     const size_t per = (size_t)(d + 1) * (d + 1) + (size_t)(d + 1) * dv + (size_t)L;
     double *scratch = (double *)malloc(sizeof(double) * per);
     if (!scratch) return 2;
-    int bad = lla_one_query(q, K, V, L, d, dv, lambda, scale, o, scratch);
+    int bad = lla_one_query(q, K, V, L, d, dv, lambda, scale, o, scratch, NULL, NULL);
     free(scratch);
     return bad;
 }
