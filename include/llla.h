@@ -100,6 +100,25 @@ llla_status llla_forward_path(const void *Q, const void *K, const void *V, void 
                               void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * llla_forward_ex -- llla_forward_path with the two quantities the paper attaches to the forward pass:
+ *   lambda_rows : device float [B, H, n] contiguous, or NULL.  Appendix C makes the ridge a learnable,
+ *                 position-dependent quantity: row i then uses lambda_rows[b, h, i] in Eq. (query_specific)
+ *                 and `lambda` is ignored.  Every entry must be finite and > 0;
+ *                 being device memory they are not checked.
+ *   rho, delta  : device float [B, H, n, d] and [B, H, n] contiguous, or NULL each.  rho_i = Sigma_i^{-1} mu_i
+ *                 and delta_i = omega_i - mu_i . rho_i of Eq. (lla), the per-row statistics FlashLLA keeps
+ *                 for its backward pass (end of Section 3.2), relative to the same max-normalised weights
+ *                 as everything else here; written in fp32.
+ * Everything else as llla_forward_path.
+ */
+llla_status llla_forward_ex(const void *Q, const void *K, const void *V, void *O,
+                            llla_strides sq, llla_strides sk, llla_strides sv, llla_strides so,
+                            int B, int H, int n, int d, llla_dtype in, llla_dtype out,
+                            int causal, float lambda, const float *lambda_rows, float scale,
+                            float *rho, float *delta, llla_path path,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * llla_decode -- the inference step the paper mentions (Sections 1 and 2.3: LLA keeps a Theta(n d)
  * KV cache): one new query per (batch, head) against the cached keys and values, the new token's
  * own (k, v) already appended, i.e. the last row of a causal forward over seqlens[b] positions.

@@ -47,6 +47,8 @@ def lib():
     L.llla_forward.restype = i32
     L.llla_forward_path.argtypes = fwd + [i32, vp, sz, vp]
     L.llla_forward_path.restype = i32
+    L.llla_forward_ex.argtypes = fwd[:-1] + [vp, f32, vp, vp, i32, vp, sz, vp]
+    L.llla_forward_ex.restype = i32
     dec = [vp, vp, vp, vp, _Strides, _Strides, vp, i32, i32, i32, i32, i32, i32, f32, f32]
     L.llla_decode.argtypes = dec + [vp, sz, vp]
     L.llla_decode.restype = i32
@@ -121,9 +123,11 @@ def _workspace(nbytes: int, device, workspace):
     return workspace
 
 
-def llla_forward(Q, K, V, lam: float, scale: float, causal: bool = True, out_dtype=None, path: str = "auto",
-                 workspace=None, out=None, stream=None):
-    """O = LLA(Q, K, V) for [B, H, n, d] device tensors (f32 or bf16).  Returns O ([B, H, n, d])."""
+def llla_forward(Q, K, V, lam, scale: float, causal: bool = True, out_dtype=None, path: str = "auto",
+                 workspace=None, out=None, stream=None, return_stats: bool = False):
+    """O = LLA(Q, K, V) for [B, H, n, d] device tensors (f32 or bf16).  ``lam`` is a float or a device float32
+    tensor [B, H, n] (one ridge per query row).  Returns O ([B, H, n, d]), or (O, rho, delta) with the per-row
+    statistics of Eq. (lla) when ``return_stats`` is set."""
     if not (Q.is_cuda and K.is_cuda and V.is_cuda):
         raise ValueError("llla_forward needs device tensors; this library has no CPU path")
     if not (Q.dtype == K.dtype == V.dtype) or Q.dtype not in _DTYPES:
@@ -131,19 +135,29 @@ def llla_forward(Q, K, V, lam: float, scale: float, causal: bool = True, out_dty
     B, H, n, d = Q.shape
     if K.shape != Q.shape or V.shape != Q.shape:
         raise ValueError("Q, K, V must have the same [B, H, n, d] shape")
+    lam_rows = None
+    if torch.is_tensor(lam):
+        lam_rows = lam
+        if not (lam_rows.is_cuda and lam_rows.dtype == torch.float32 and tuple(lam_rows.shape) == (B, H, n)
+                and lam_rows.is_contiguous()):
+            raise ValueError("a per-row ridge must be a contiguous device float32 tensor [B, H, n]")
     out_dtype = torch.float32 if out_dtype is None else out_dtype
     O = torch.empty((B, H, n, d), dtype=out_dtype, device=Q.device) if out is None else out
+    rho = torch.empty((B, H, n, d), dtype=torch.float32, device=Q.device) if return_stats else None
+    delta = torch.empty((B, H, n), dtype=torch.float32, device=Q.device) if return_stats else None
     L = lib()
     need = forward_workspace_bytes(B, H, n, d, Q.dtype)
     ws = _workspace(need, Q.device, workspace)
-    st = L.llla_forward_path(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
-                             _strides4(Q), _strides4(K), _strides4(V), _strides4(O),
-                             B, H, n, d, _DTYPES[Q.dtype], _DTYPES[O.dtype], 1 if causal else 0,
-                             float(lam), float(scale), PATHS[path],
-                             ws.data_ptr(), ws.numel() * ws.element_size(), _stream_ptr(stream))
+    st = L.llla_forward_ex(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                           _strides4(Q), _strides4(K), _strides4(V), _strides4(O),
+                           B, H, n, d, _DTYPES[Q.dtype], _DTYPES[O.dtype], 1 if causal else 0,
+                           0.0 if lam_rows is not None else float(lam),
+                           None if lam_rows is None else lam_rows.data_ptr(), float(scale),
+                           None if rho is None else rho.data_ptr(), None if delta is None else delta.data_ptr(),
+                           PATHS[path], ws.data_ptr(), ws.numel() * ws.element_size(), _stream_ptr(stream))
     if st != 0:
         raise LlaError(st, "llla_forward")
-    return O
+    return (O, rho, delta) if return_stats else O
 
 
 def llla_decode(q, Kc, Vc, lam: float, scale: float, seqlens=None, out_dtype=None, path: str = "auto",

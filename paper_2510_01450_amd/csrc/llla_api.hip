@@ -115,14 +115,19 @@ size_t llla_forward_workspace_bytes(int B, int H, int n, int d, llla_dtype in)
     return llla::mfma_forward_workspace_bytes(B, H, n, d, in);
 }
 
-llla_status llla_forward_path(const void *Q, const void *K, const void *V, void *O, llla_strides sq,
-                              llla_strides sk, llla_strides sv, llla_strides so, int B, int H, int n, int d,
-                              llla_dtype in, llla_dtype out, int causal, float lambda, float scale,
-                              llla_path path, void *workspace, size_t workspace_bytes, void *stream)
+llla_status llla_forward_ex(const void *Q, const void *K, const void *V, void *O, llla_strides sq, llla_strides sk,
+                            llla_strides sv, llla_strides so, int B, int H, int n, int d, llla_dtype in,
+                            llla_dtype out, int causal, float lambda, const float *lambda_rows, float scale,
+                            float *rho, float *delta, llla_path path, void *workspace, size_t workspace_bytes,
+                            void *stream)
 {
     if (!Q || !K || !V || !O) return LLLA_ERR_NULL;
-    llla_status st = check_common(B, H, n, d, in, out, lambda, scale);
+    // with a ridge per row the scalar is ignored, whatever it holds
+    llla_status st = check_common(B, H, n, d, in, out, lambda_rows ? 1.f : lambda, scale);
     if (st != LLLA_OK) return st;
+    if ((reinterpret_cast<uintptr_t>(lambda_rows) & 3u) || (reinterpret_cast<uintptr_t>(rho) & 3u) ||
+        (reinterpret_cast<uintptr_t>(delta) & 3u))
+        return LLLA_ERR_ALIGN;
     if (path != LLLA_PATH_AUTO && path != LLLA_PATH_VALU && path != LLLA_PATH_MFMA) return LLLA_ERR_PARAM;
     if (!strides_cover(sq, B, H, n, d) || !strides_cover(sk, B, H, n, d) || !strides_cover(sv, B, H, n, d) ||
         !strides_cover(so, B, H, n, d))
@@ -147,6 +152,7 @@ llla_status llla_forward_path(const void *Q, const void *K, const void *V, void 
     p.in = in; p.out = out;
     p.causal = causal ? 1 : 0;
     p.lambda = lambda; p.scale = scale;
+    p.lambda_rows = lambda_rows; p.rho = rho; p.delta = delta;
     p.ws = workspace; p.ws_bytes = workspace_bytes;
     p.stream = static_cast<hipStream_t>(stream);
     llla::stage_begin(p.stream);
@@ -154,6 +160,15 @@ llla_status llla_forward_path(const void *Q, const void *K, const void *V, void 
     const hipError_t e = use_mfma ? llla::mfma_forward(p) : llla::valu_forward(p);
     llla::stage_end(p.stream);
     return e == hipSuccess ? LLLA_OK : LLLA_ERR_LAUNCH;
+}
+
+llla_status llla_forward_path(const void *Q, const void *K, const void *V, void *O, llla_strides sq,
+                              llla_strides sk, llla_strides sv, llla_strides so, int B, int H, int n, int d,
+                              llla_dtype in, llla_dtype out, int causal, float lambda, float scale,
+                              llla_path path, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return llla_forward_ex(Q, K, V, O, sq, sk, sv, so, B, H, n, d, in, out, causal, lambda, nullptr, scale, nullptr,
+                           nullptr, path, workspace, workspace_bytes, stream);
 }
 
 llla_status llla_forward(const void *Q, const void *K, const void *V, void *O, llla_strides sq, llla_strides sk,

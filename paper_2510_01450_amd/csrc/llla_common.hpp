@@ -19,6 +19,8 @@ struct Problem {
     llla_dtype in, out;
     int causal;
     float lambda, scale;
+    const float *lambda_rows;  // forward only: [B,H,n] ridge per query row, or nullptr (then `lambda` for all rows)
+    float *rho, *delta;        // forward only: optional outputs [B,H,n,d] and [B,H,n] (Eq. (lla)), or nullptr
     void *ws;
     size_t ws_bytes;
     hipStream_t stream;

@@ -49,6 +49,24 @@ __device__ inline float lane_xor1(float x)   // value of lane ^ 1
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xf, 0xf, true));
 }
 
+// x = hi + lo with both halves f16 (about 20 significant bits).  hi is x rounded toward zero by a conversion
+// builtin on purpose: a plain (_Float16) cast of a product may be fused with the multiply at one use (one
+// rounding of the exact product) and not at another (product rounded to fp32 first), the two results can differ
+// by one f16 ulp, and a lo computed against the one would then be added to the other.
+__device__ inline void split_f16(const float (&x)[8], half8 &hi, half8 &lo)
+{
+    typedef __fp16 fp16x2 __attribute__((ext_vector_type(2)));
+    typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const half2v h = __builtin_bit_cast(half2v, (fp16x2)__builtin_amdgcn_cvt_pkrtz(x[2 * p], x[2 * p + 1]));
+        const half2v l = __builtin_bit_cast(
+            half2v, (fp16x2)__builtin_amdgcn_cvt_pkrtz(x[2 * p] - (float)h[0], x[2 * p + 1] - (float)h[1]));
+        hi[2 * p] = h[0]; hi[2 * p + 1] = h[1];
+        lo[2 * p] = l[0]; lo[2 * p + 1] = l[1];
+    }
+}
+
 __device__ inline f32x4 mfma_f16(half8 a, half8 b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
 __device__ inline f32x4 mfma_bf16(bf16x8 a, bf16x8 b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0); }
 
@@ -199,7 +217,10 @@ __device__ inline void trinv_row(float (&li)[16], float mul)
 // Upper Cholesky factor and its inverse for the diagonal tiles of the wave's four queries at once:
 // lane 16q + r owns row r of query q's symmetric 16x16 tile (a[c] = T[r][c]).  On return
 // li[c] = -(L^{-1})[r][c] with T = L L^T (zero above the diagonal); the sign is the one solve_wave wants.
-__device__ inline void chol_inv16(float (&a)[16], float (&li)[16], int r)
+// pivot_floor: every pivot of the Cholesky factorisation of (a positive semi-definite matrix + lambda I) is
+// at least lambda in exact arithmetic; a computed pivot below the floor (half of lambda) is a rounding
+// artefact of an ill-conditioned early row and is raised to it, which keeps the factorisation finite.
+__device__ inline void chol_inv16(float (&a)[16], float (&li)[16], int r, float pivot_floor)
 {
     float nl2[16];      // -L[r][k] / L[k][k]  (column-scaled factor, strictly lower part kept, negated)
     float dinv_own = 0.f;
@@ -208,6 +229,7 @@ __device__ inline void chol_inv16(float (&a)[16], float (&li)[16], int r)
         float dk;
         const float ak = a[k];
         LLLA_SWITCH16(k, dk = bcast_settled<KK>(ak));        // diagonal entry of step k, from lane k of the row
+        dk = fmaxf(dk, pivot_floor);
         float rinv = __builtin_amdgcn_rsqf(dk);
         rinv = rinv * (1.5f - 0.5f * dk * rinv * rinv);      // one Newton step
         const float u = ak * rinv;                           // L[r][k] in rows r >= k; rows above are finished and never read again
@@ -259,6 +281,7 @@ __device__ inline void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memor
 //                          columns 0); it is called after the factorisation so that the 16 right-hand-side
 //                          registers per query are not live while the diagonal tiles are factorised
 //        om4[q]            omega_q;  scw: >= QW*16*SC_PITCH floats of LDS owned by this wave
+//        pivot_floor       per lane: half the ridge of the query of the lane's group (see chol_inv16)
 //   out: rhs[q][P] column 0 (lanes nn == 0) = y1_q,  y0v[q] = y0_q (valid in lanes nn == 0)
 // with [omega mu~^T; mu~ Sigma~ + lambda I] [y0; y1] = [1; q].  16-blocked upper Cholesky
 // Sigma~ + lambda I = U^T U whose block products are C += A^T B on fp32 MFMA; diagonal tiles of the QW
@@ -271,7 +294,7 @@ template <int DD, class BuildRhs>
 __device__ __forceinline__ void solve_wave(f32x4 (&acc)[Shape<DD>::QW][Shape<DD>::NTILE],
                                            f32x4 (&rhs)[Shape<DD>::QW][Shape<DD>::NB], float (&y0v)[Shape<DD>::QW],
                                            const float (&om4)[Shape<DD>::QW], float *scw, int g, int nn,
-                                           BuildRhs build_rhs)
+                                           float pivot_floor, BuildRhs build_rhs)
 {
     using S = Shape<DD>;
     constexpr int QW = S::QW, NB = S::NB;
@@ -300,7 +323,7 @@ __device__ __forceinline__ void solve_wave(f32x4 (&acc)[Shape<DD>::QW][Shape<DD>
             for (int c = 0; c < 16; ++c) a[c] = -0.5f * (a[c] + my[c * SC_PITCH + nn]);    // -T, symmetrised
         }
         wave_sync();
-        chol_inv16(a, li, nn);
+        chol_inv16(a, li, nn, pivot_floor);
         if (g < QW) {
             float *my = scw + g * 16 * SC_PITCH;
 #pragma unroll

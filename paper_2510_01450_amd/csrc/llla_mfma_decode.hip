@@ -311,7 +311,7 @@ __global__ __launch_bounds__(NT, 1) void decode_merge_kernel(const bf16_t *__res
 #pragma unroll
                 for (int t = 0; t < 4; ++t) acc[q][Shape<64>::tix(P, P)][t] -= (nn == 4 * g + t) ? lambda : 0.f;
         }
-        solve_wave<64>(acc, rhs, y0v, om4, scw, g, nn, [&](f32x4 (&r)[QW][4]) {
+        solve_wave<64>(acc, rhs, y0v, om4, scw, g, nn, 0.5f * lambda, [&](f32x4 (&r)[QW][4]) {
 #pragma unroll
             for (int q = 0; q < QW; ++q) {
                 const int hq = min((int)blockIdx.x * QW + q, BH - 1);

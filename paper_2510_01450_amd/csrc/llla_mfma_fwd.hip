@@ -280,8 +280,8 @@ template <bool PRECISE, int DD>
 __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t *__restrict__ Qg,
                                              const bf16_t *__restrict__ Kg, llla_strides sq, llla_strides sk, int H,
                                              int n, int nkb, float cscale, float lambda,
-                                             const _Float16 *__restrict__ KT, const float *__restrict__ Mg,
-                                             float *__restrict__ Yg)
+                                             const float *__restrict__ lam_rows, const _Float16 *__restrict__ KT,
+                                             const float *__restrict__ Mg, float *__restrict__ Yg)
 {
     using S = Shape<DD>;
     constexpr int NB = S::NB, NTILE = S::NTILE, NF = S::NF, QW = S::QW, NW = S::NW, QB = S::QB, YP = S::YP;
@@ -335,11 +335,14 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     // The tiles accumulate T = -(Sigma~ + lambda I), the sign the solve works in (see solve_wave): the ridge is
     // the starting value of the diagonal, and the scaled MFMA operand carries a minus sign that costs nothing.
 #pragma unroll
-    for (int q = 0; q < QW; ++q)
+    for (int q = 0; q < QW; ++q) {
+        // the ridge of the query's own row when one is given per row (Appendix C)
+        const float lq = lam_rows ? lam_rows[(size_t)bh * n + min(i0 + QW * wave + q, n - 1)] : lambda;
 #pragma unroll
         for (int P = 0; P < NB; ++P)
 #pragma unroll
-            for (int t = 0; t < 4; ++t) acc[q][S::tix(P, P)][t] = (nn == 4 * g + t) ? -lambda : 0.f;
+            for (int t = 0; t < 4; ++t) acc[q][S::tix(P, P)][t] = (nn == 4 * g + t) ? -lq : 0.f;
+    }
     f32x4 mu_acc = {0.f, 0.f, 0.f, 0.f};
     float om_part = 0.f;            // this lane's share of omega for query i0 + nn
 
@@ -457,12 +460,10 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
                     for (int t = 0; t < 4; ++t) { wq[t] = w0[t]; wq[4 + t] = w1[t]; }
                 }
                 half8 ahi, alo;
+                float pr[8];
 #pragma unroll
-                for (int t = 0; t < 8; ++t) {
-                    const float pr = (float)fr.f[I][t] * wq[t];
-                    ahi[t] = (_Float16)pr;
-                    alo[t] = (_Float16)(pr - (float)ahi[t]);
-                }
+                for (int t = 0; t < 8; ++t) pr[t] = (float)fr.f[I][t] * wq[t];
+                split_f16(pr, ahi, alo);
 #pragma unroll
                 for (int J = I; J < NB; ++J) {
                     acc[q][S::tix(I, J)] = mfma_f16(alo, fr.f[J], acc[q][S::tix(I, J)]);
@@ -482,12 +483,10 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
         } else {
             const float *wp = &wt32[wb][nn * WT32_PITCH + 32 * hf + 8 * g];
             const f32x4 w0 = *reinterpret_cast<const f32x4 *>(wp), w1 = *reinterpret_cast<const f32x4 *>(wp + 4);
+            float wv[8];
 #pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                const float wv = t < 4 ? w0[t] : w1[t - 4];
-                mu_a[t] = (_Float16)wv;
-                mu_a2[t] = (_Float16)(wv - (float)mu_a[t]);
-            }
+            for (int t = 0; t < 8; ++t) wv[t] = t < 4 ? w0[t] : w1[t - 4];
+            split_f16(wv, mu_a, mu_a2);
         }
     };
     auto mu_mfma = [&]() {
@@ -565,7 +564,9 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     float y0v[QW], om4[QW];
 #pragma unroll
     for (int q = 0; q < QW; ++q) om4[q] = oms[QW * wave + q];
-    solve_wave<DD>(acc, rhs, y0v, om4, &sc[wave][0][0], g, nn, [&](f32x4 (&r)[QW][NB]) {
+    const int gq_row = min(i0 + QW * wave + (g < QW ? g : QW - 1), n - 1);
+    const float pivot_floor = 0.5f * (lam_rows ? lam_rows[(size_t)bh * n + gq_row] : lambda);
+    solve_wave<DD>(acc, rhs, y0v, om4, &sc[wave][0][0], g, nn, pivot_floor, [&](f32x4 (&r)[QW][NB]) {
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
             const int qi = QW * wave + q;
@@ -600,13 +601,42 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
 template <int DD>
 __global__ __launch_bounds__(Shape<DD>::NT, DD == 64 ? 2 : 1) void moments_kernel(
     const bf16_t *__restrict__ Qg, const bf16_t *__restrict__ Kg, llla_strides sq, llla_strides sk, int H, int n, int nkb,
-    int precise_rows, float cscale, float lambda, const _Float16 *__restrict__ KT, const float *__restrict__ Mg,
-    float *__restrict__ Yg)
+    int precise_rows, float cscale, float lambda, const float *__restrict__ lam_rows, const _Float16 *__restrict__ KT,
+    const float *__restrict__ Mg, float *__restrict__ Yg)
 {
     __shared__ __align__(16) MomentsShared<DD> sm;
     const int i0 = ((int)gridDim.x - 1 - (int)blockIdx.x) * Shape<DD>::QB;
-    if (i0 < precise_rows) moments_body<true, DD>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, KT, Mg, Yg);
-    else moments_body<false, DD>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, KT, Mg, Yg);
+    if (i0 < precise_rows) moments_body<true, DD>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg);
+    else moments_body<false, DD>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg);
+}
+
+// Optional statistics of Eq. (lla) from the solved y of every row: with y1 = -rho/delta and
+// y0 = (1 + q.rho)/delta, 1/delta = y0 + q.y1 and rho = -delta y1.  One wave per row.
+template <int DD>
+__global__ __launch_bounds__(256) void stats_kernel(const bf16_t *__restrict__ Qg, llla_strides sq, int H, int n,
+                                                    const float *__restrict__ Yg, float *__restrict__ rho,
+                                                    float *__restrict__ delta)
+{
+    constexpr int YP = Shape<DD>::YP, PER = DD / 64;
+    const int lane = threadIdx.x % 64, i = blockIdx.x * 4 + threadIdx.x / 64, bh = blockIdx.y;
+    if (i >= n) return;
+    const bf16_t *qrow = Qg + (bh / H) * sq.batch + (bh % H) * sq.head + (int64_t)i * sq.seq;
+    const float *yr = Yg + ((size_t)bh * n + i) * YP;
+    float y1[PER], qy = 0.f;
+#pragma unroll
+    for (int t = 0; t < PER; ++t) {
+        y1[t] = yr[lane + 64 * t];
+        qy = fmaf(bf16_to_f32(qrow[lane + 64 * t]), y1[t], qy);
+    }
+#pragma unroll
+    for (int sft = 32; sft >= 1; sft >>= 1) qy += __shfl_xor(qy, sft);
+    const float dl = 1.f / (yr[DD] + qy);
+    const size_t row = (size_t)bh * n + i;
+    if (delta != nullptr && lane == 0) delta[row] = dl;
+    if (rho != nullptr) {
+#pragma unroll
+        for (int t = 0; t < PER; ++t) rho[row * DD + lane + 64 * t] = -dl * y1[t];
+    }
 }
 
 template <int DD>
@@ -634,7 +664,12 @@ hipError_t forward_impl(const Problem &p)
     const int nqb = (p.n + S::QB - 1) / S::QB;
     stage_mark(p.stream, "moments");
     hipLaunchKernelGGL((moments_kernel<DD>), dim3(nqb, bh), dim3(S::NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
-                       first, cscale, p.lambda, KT, M, Y);
+                       first, cscale, p.lambda, p.lambda_rows, KT, M, Y);
+    if (p.rho != nullptr || p.delta != nullptr) {
+        stage_mark(p.stream, "statistics");
+        hipLaunchKernelGGL((stats_kernel<DD>), dim3((p.n + 3) / 4, bh), dim3(256), 0, p.stream, Q, p.sq, p.H, p.n, Y, p.rho,
+                           p.delta);
+    }
     // output: the first rows are evaluated in fp32 on the vector ALUs (their weights y0 + k.y1 cancel
     // to a few digits), the rest by the MFMA sweep
     stage_mark(p.stream, "output_early_rows");

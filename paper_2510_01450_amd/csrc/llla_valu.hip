@@ -111,7 +111,9 @@ __global__ __launch_bounds__(NT) void valu_kernel(const TI *__restrict__ Qg, con
                                                   llla_strides so, const int32_t *__restrict__ seqlens,
                                                   int H, int n, int causal, float lambda, float scale,
                                                   const float *__restrict__ Mg = nullptr, int mpitch = 0,
-                                                  const float *__restrict__ Yg = nullptr, int ypitch = 0)
+                                                  const float *__restrict__ Yg = nullptr, int ypitch = 0,
+                                                  const float *__restrict__ LamRows = nullptr,
+                                                  float *__restrict__ Rho = nullptr, float *__restrict__ Delta = nullptr)
 {
     using C = Cfg<D>;
     constexpr int TS = C::TS, TG = C::TG, TPQ = C::TPQ, QB = C::QB, LDK = C::LDK, P = C::P,
@@ -160,6 +162,8 @@ __global__ __launch_bounds__(NT) void valu_kernel(const TI *__restrict__ Qg, con
     // last key (exclusive) any slot of the block can see
     const int kend = DECODE ? nkeys : (causal ? min(n, i0 + QB) : n);
     const int my_last = (DECODE || !causal) ? nkeys - 1 : min(my_i, n - 1);   // last visible key
+    // ridge of this slot's row (Appendix C: lambda may differ from position to position)
+    const float lam_slot = (!DECODE && LamRows) ? LamRows[(size_t)bh * n + min(my_i, n - 1)] : lambda;
 
     // ---- query rows -> LDS ----------------------------------------------------------------------
     for (int idx = tid; idx < QB * D; idx += NT) {
@@ -303,7 +307,7 @@ __global__ __launch_bounds__(NT) void valu_kernel(const TI *__restrict__ Qg, con
 #pragma unroll
                 for (int y = 0; y < TS; ++y) {
                     const int rr = ta * TS + x, cc = tb * TS + y;
-                    S[(1 + rr) * LS + 1 + cc] = acc[x][y] + (rr == cc ? lambda : 0.f);
+                    S[(1 + rr) * LS + 1 + cc] = acc[x][y] + (rr == cc ? lam_slot : 0.f);
                 }
             if (tb == 0) {
 #pragma unroll
@@ -343,6 +347,18 @@ __global__ __launch_bounds__(NT) void valu_kernel(const TI *__restrict__ Qg, con
         }
         __syncthreads();
 
+        // ---- optional statistics of Eq. (lla): with y1 = -rho/delta and y0 = (1 + q.rho)/delta,
+        //      1/delta = y0 + q.y1 and rho = -delta y1 ---------------------------------------------------
+        if (!DECODE && (Rho != nullptr || Delta != nullptr) && slot_live) {
+            const float *ysl = ys + slot * (P + 3);
+            float qy = 0.f;
+            for (int c = 0; c < D; ++c) qy = fmaf(qs[slot * D + c], ysl[1 + c], qy);
+            const float dl = 1.f / (ysl[0] + qy);
+            const size_t row = (size_t)bh * n + my_i;
+            if (Delta != nullptr && r == 0) Delta[row] = dl;
+            if (Rho != nullptr)
+                for (int c = r; c < D; c += TPQ) Rho[row * D + c] = -dl * ysl[1 + c];
+        }
     }   // !GIVEN
 
     // ---- sweep 3: output weights s_ij = w_ij (y0 + k_j . y1) and O = S V ------------------------
@@ -401,7 +417,9 @@ hipError_t launch(const Problem &p, int nrows)
     dim3 grid(DECODE ? 1 : (nrows + C::QB - 1) / C::QB, p.B * p.H);
     hipLaunchKernelGGL((valu_kernel<D, TI, TO, DECODE>), grid, dim3(NT), 0, p.stream,
                        (const TI *)p.Q, (const TI *)p.K, (const TI *)p.V, (TO *)p.O, p.sq, p.sk, p.sv,
-                       p.so, p.seqlens, p.H, p.n, p.causal, p.lambda, p.scale);
+                       p.so, p.seqlens, p.H, p.n, p.causal, p.lambda, p.scale, (const float *)nullptr, 0,
+                       (const float *)nullptr, 0, DECODE ? nullptr : p.lambda_rows, DECODE ? nullptr : p.rho,
+                       DECODE ? nullptr : p.delta);
     return hipGetLastError();
 }
 
@@ -434,11 +452,13 @@ hipError_t launch_given(const Problem &p, int nrows, const float *M, int mpitch,
     if (p.out == LLLA_F32)
         hipLaunchKernelGGL((valu_kernel<D, bf16_t, float, false, true>), grid, dim3(NT), 0, p.stream,
                            (const bf16_t *)p.Q, (const bf16_t *)p.K, (const bf16_t *)p.V, (float *)p.O, p.sq, p.sk,
-                           p.sv, p.so, nullptr, p.H, p.n, 1, p.lambda, p.scale, M, mpitch, Y, ypitch);
+                           p.sv, p.so, nullptr, p.H, p.n, 1, p.lambda, p.scale, M, mpitch, Y, ypitch, (const float *)nullptr,
+                           (float *)nullptr, (float *)nullptr);
     else
         hipLaunchKernelGGL((valu_kernel<D, bf16_t, bf16_t, false, true>), grid, dim3(NT), 0, p.stream,
                            (const bf16_t *)p.Q, (const bf16_t *)p.K, (const bf16_t *)p.V, (bf16_t *)p.O, p.sq, p.sk,
-                           p.sv, p.so, nullptr, p.H, p.n, 1, p.lambda, p.scale, M, mpitch, Y, ypitch);
+                           p.sv, p.so, nullptr, p.H, p.n, 1, p.lambda, p.scale, M, mpitch, Y, ypitch, (const float *)nullptr,
+                           (float *)nullptr, (float *)nullptr);
     return hipGetLastError();
 }
 

@@ -54,6 +54,23 @@ def test_forward_rejects_bad_arguments(kw, code):
     assert _fwd(**kw) == code
 
 
+def test_forward_ex_validation():
+    """The scalar ridge is ignored (not validated) when a per-row ridge is given; misaligned extras are refused.
+    FAKE pointers are never dereferenced: each call fails a later check (no workspace on the MFMA path is not
+    reached with fp32 inputs, so the calls below stop at the checks named)."""
+    s = _Strides(64 * 64, 64 * 64, 64)
+    ex = llla.lib().llla_forward_ex
+    # bad scalar lambda, no per-row ridge -> PARAM
+    assert ex(FAKE, FAKE, FAKE, FAKE, s, s, s, s, 1, 1, 64, 64, 0, 0, 1, 0.0, None, 0.125, None, None, 0, 0, 0, 0) == 4
+    # same scalar with a per-row ridge: passes that check and trips on the misaligned rho pointer instead
+    assert ex(FAKE, FAKE, FAKE, FAKE, s, s, s, s, 1, 1, 64, 64, 0, 0, 1, 0.0, FAKE, 0.125, FAKE + 2, None, 0, 0, 0,
+              0) == 5
+    assert ex(FAKE, FAKE, FAKE, FAKE, s, s, s, s, 1, 1, 64, 64, 0, 0, 1, 0.0, FAKE + 1, 0.125, None, None, 0, 0, 0,
+              0) == 5
+    # bf16 + MFMA path without workspace -> WORKSPACE (reached only after the ridge checks passed)
+    assert ex(FAKE, FAKE, FAKE, FAKE, s, s, s, s, 1, 1, 64, 64, 1, 0, 1, 0.0, FAKE, 0.125, None, None, 2, 0, 0, 0) == 6
+
+
 @pytest.mark.parametrize("kw,code", [
     (dict(q=0), 1), (dict(L=0), 2), (dict(din=5), 3), (dict(lam=0.0), 4), (dict(K=FAKE + 2), 5), (dict(d=20), 7),
     (dict(sk=_Strides(64 * 64, 64 * 64, 8)), 2),

@@ -249,3 +249,41 @@ def test_c5_decode_sampled_heads():
         ref = oracle.decode(q[b:b + 1, h:h + 1], Kc[b:b + 1, h:h + 1], Vc[b:b + 1, h:h + 1], w.lam, w.scale)
         print((b, h), check(got[b:b + 1, h:h + 1, None, :], ref[:, :, None, :], np.array([w.n - 1]), w.d, w.tol,
                             "C5 head %s" % ((b, h),)))
+
+
+# ---- extended forward: a ridge per row (Appendix C) and the statistics rho, delta of Eq. (lla) -----------
+def _stat_check(got_r, ref_r, got_d, ref_d, rows, d, tol, what):
+    """rho and delta against the oracle with the same gate as the outputs (delta as a 1-vector per row)."""
+    print(check(got_r, ref_r, rows, d, tol, what + " rho"))
+    print(check(got_d[..., None], ref_d[..., None], rows, d, tol, what + " delta"))
+
+
+@pytest.mark.parametrize("n,d,dtype,path", [
+    (130, 32, "f32", "valu"), (203, 64, "f32", "auto"), (150, 128, "f32", "auto"),
+    (131, 32, "bf16", "auto"), (333, 64, "bf16", "valu"), (333, 64, "bf16", "mfma"), (600, 64, "bf16", "mfma"),
+    (290, 128, "bf16", "mfma"),
+])
+def test_forward_ex_per_row_ridge_and_statistics(n, d, dtype, path):
+    w = _small("ex", 2, 2, n, d, dtype, index=700 + d + n)
+    Q, K, V = workloads.make_inputs(w)
+    g = torch.Generator().manual_seed(900 + n)
+    lam = (10.0 ** (torch.rand(2, 2, n, generator=g) * 2.0 - 3.0)).float()        # 1e-3 .. 1e-1, per row
+    refO, refR, refD = oracle.forward_ex(Q, K, V, lam.numpy(), w.scale)
+    O, R, Dl = llla.llla_forward(Q.to(DEV), K.to(DEV), V.to(DEV), lam.to(DEV), w.scale, path=path, return_stats=True)
+    torch.cuda.synchronize()
+    rows = np.arange(n)
+    print(check(O.cpu().numpy(), refO, rows, d, w.tol, "ex %s n=%d d=%d %s" % (path, n, d, dtype)))
+    _stat_check(R.cpu().numpy(), refR, Dl.cpu().numpy(), refD, rows, d, w.tol, "ex %s n=%d d=%d %s" % (path, n, d, dtype))
+    # a constant per-row ridge and the scalar give the same output; statistics do not disturb it
+    lam_c = torch.full((2, 2, n), w.lam, dtype=torch.float32, device=DEV)
+    a = llla.llla_forward(Q.to(DEV), K.to(DEV), V.to(DEV), lam_c, w.scale, path=path)
+    b, _, _ = llla.llla_forward(Q.to(DEV), K.to(DEV), V.to(DEV), w.lam, w.scale, path=path, return_stats=True)
+    c = llla.llla_forward(Q.to(DEV), K.to(DEV), V.to(DEV), w.lam, w.scale, path=path)
+    assert torch.equal(a, c) and torch.equal(b, c)
+
+
+def test_forward_ex_rejects_a_host_ridge_tensor():
+    w = _small("exbad", 1, 1, 64, 16, "f32")
+    Q, K, V = [t.to(DEV) for t in workloads.make_inputs(w)]
+    with pytest.raises(ValueError):
+        llla.llla_forward(Q, K, V, torch.full((1, 1, 64), 0.01), w.scale)
