@@ -317,12 +317,17 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     // weight role: lane (g, nn) of wave w < 4 serves query i0 + nn (nn < QB) and keys 16w + 4g + r
     const int iq = i0 + nn, iqc = min(iq, n - 1);
     const bool q_live = nn < QB;
-    if (w_wave) {   // each (g, nn) lane of the four weight waves would store the same chunks: wave 0 does
+    // The query operand of the logits: d = 64 re-reads it from LDS for every block (its registers go to the second
+    // fragment set), d = 128 keeps it in registers.
+    constexpr bool Q_IN_LDS = (DD == 64);
+    bf16x8 qf[NF];
+    {
         const bf16_t *qrow = Qh + (int64_t)iqc * sq.seq;
-        if (wave == 0) {
 #pragma unroll
-            for (int f = 0; f < NF; ++f)
-                *reinterpret_cast<bf16x8 *>(&sm.qt[nn][32 * f + 8 * g]) = *reinterpret_cast<const bf16x8 *>(qrow + 32 * f + 8 * g);
+        for (int f = 0; f < NF; ++f) {
+            qf[f] = *reinterpret_cast<const bf16x8 *>(qrow + 32 * f + 8 * g);
+            // each (g, nn) lane of the four weight waves would store the same chunks: wave 0 does
+            if (Q_IN_LDS && wave == 0) *reinterpret_cast<bf16x8 *>(&sm.qt[nn][32 * f + 8 * g]) = qf[f];
         }
     }
     const float mrow = Mg[(size_t)bh * mpitch + iqc];
@@ -389,12 +394,12 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     };
     // Weights of block blk, w = 2^(c<q,k> - m) for this wave's 16 keys, in three steps that the loop below
     // spreads over an iteration so that no step waits on the one before it: operand reads, logits (MFMA), exp + store.
-    bf16x8 knf[NF], qf[NF];
+    bf16x8 knf[NF];
     auto weights_load = [&](int buf) {
 #pragma unroll
         for (int f = 0; f < NF; ++f) {
             knf[f] = *reinterpret_cast<const bf16x8 *>(&kn[buf][kn_r[f]]);
-            qf[f] = *reinterpret_cast<const bf16x8 *>(&sm.qt[nn][32 * f + 8 * g]);
+            if (Q_IN_LDS) qf[f] = *reinterpret_cast<const bf16x8 *>(&sm.qt[nn][32 * f + 8 * g]);
         }
     };
     auto weights_logits = [&]() {
@@ -505,46 +510,77 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     // is behind still reads those of block c-1.  Past the last block every key is masked (j > iq): that extra
     // round stores zeros.  `wave` is a scalar, so every branch around an MFMA is a real branch (MFMA ignores EXEC).
     constexpr int ITEMS = QW * NB, Q2 = ITEMS / 2, Q3 = 3 * ITEMS / 4;
+    constexpr bool PREFETCH = (DD == 64);       // d = 128 has no registers for a second fragment set (see below)
     issue_dma(0);
-    if (nblk > 1) issue_dma(1);
+    if (PREFETCH && nblk > 1) issue_dma(1);
     dma_wait();
     __syncthreads();
     if (w_wave) { weights_load(0); weights_store(0, 0, weights_logits()); }
     __syncthreads();
-    load_frags(fa, 0, 0);
 
     int wb = 0;                                 // weight buffer of block c
-    for (int c = 0; c < nblk; ++c) {
-        const int buf = c & 1, wbn = (wb == 2) ? 0 : wb + 1;
-        // ---- first half -------------------------------------------------------------------------------
-        load_frags(fb, buf, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        compute_items(fa, wb, 0, 0, Q2);
-        __builtin_amdgcn_sched_barrier(0);
-        dma_wait();                             // this wave's part of block c+1 has landed
-        if (NW == 4 || w_wave) weights_load(buf ^ 1);
-        mu_load_b(buf, 0);
-        mu_load_a(wb, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        compute_items(fa, wb, 0, Q2, Q3);
-        f32x4 z = {0.f, 0.f, 0.f, 0.f};
-        if (NW == 4 || w_wave) z = weights_logits();
-        mu_mfma();
-        compute_items(fa, wb, 0, Q3, ITEMS);
-        __builtin_amdgcn_sched_barrier(0);
-        if (NW == 4 || w_wave) weights_store(c + 1, wbn, z);
-        mu_load_b(buf, 1);                      // the last read of block c's tiles: they are overwritten after the barrier
-        __syncthreads();
-        if (c + 2 < nblk) issue_dma(c + 2);
-        // ---- second half ------------------------------------------------------------------------------
-        load_frags(fa, buf ^ 1, 0);             // first half of block c+1 (unused after the last block)
-        mu_load_a(wb, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        compute_items(fb, wb, 1, 0, Q3);
-        mu_mfma();
-        compute_items(fb, wb, 1, Q3, ITEMS);
-        __builtin_amdgcn_sched_barrier(0);
-        wb = wbn;
+    if (PREFETCH) {
+        load_frags(fa, 0, 0);
+        for (int c = 0; c < nblk; ++c) {
+            const int buf = c & 1, wbn = (wb == 2) ? 0 : wb + 1;
+            // ---- first half ---------------------------------------------------------------------------
+            load_frags(fb, buf, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_items(fa, wb, 0, 0, Q2);
+            __builtin_amdgcn_sched_barrier(0);
+            dma_wait();                         // this wave's part of block c+1 has landed
+            if (NW == 4 || w_wave) weights_load(buf ^ 1);
+            mu_load_b(buf, 0);
+            mu_load_a(wb, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_items(fa, wb, 0, Q2, Q3);
+            f32x4 z = {0.f, 0.f, 0.f, 0.f};
+            if (NW == 4 || w_wave) z = weights_logits();
+            mu_mfma();
+            compute_items(fa, wb, 0, Q3, ITEMS);
+            __builtin_amdgcn_sched_barrier(0);
+            if (NW == 4 || w_wave) weights_store(c + 1, wbn, z);
+            mu_load_b(buf, 1);                  // the last read of block c's tiles: they are overwritten after the barrier
+            __syncthreads();
+            if (c + 2 < nblk) issue_dma(c + 2);
+            // ---- second half --------------------------------------------------------------------------
+            load_frags(fa, buf ^ 1, 0);         // first half of block c+1 (unused after the last block)
+            mu_load_a(wb, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_items(fb, wb, 1, 0, Q3);
+            mu_mfma();
+            compute_items(fb, wb, 1, Q3, ITEMS);
+            __builtin_amdgcn_sched_barrier(0);
+            wb = wbn;
+        }
+    } else {
+        // One fragment set: the barrier sits at the end of the block, the DMA of block c+1 is issued at its
+        // start, and each half fetches its own fragments; the weights of block c+1 are produced around the
+        // second half.
+        for (int c = 0; c < nblk; ++c) {
+            const int buf = c & 1, wbn = (wb == 2) ? 0 : wb + 1;
+            if (c + 1 < nblk) issue_dma(c + 1);
+            load_frags(fa, buf, 0);
+            mu_load_b(buf, 0);
+            mu_load_a(wb, 0);
+            compute_items(fa, wb, 0, 0, ITEMS);
+            mu_mfma();
+            __builtin_amdgcn_sched_barrier(0);
+            dma_wait();                         // this wave's part of block c+1 has landed
+            if (w_wave) weights_load(buf ^ 1);
+            load_frags(fa, buf, 1);
+            mu_load_b(buf, 1);
+            mu_load_a(wb, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            f32x4 z = {0.f, 0.f, 0.f, 0.f};
+            if (w_wave) z = weights_logits();
+            compute_items(fa, wb, 1, 0, ITEMS);
+            mu_mfma();
+            __builtin_amdgcn_sched_barrier(0);
+            if (w_wave) weights_store(c + 1, wbn, z);
+            __syncthreads();
+            wb = wbn;
+        }
     }
 
     // omega: lanes (g, nn) of the four weight waves hold partial sums for query row nn
