@@ -55,6 +55,8 @@ def main():
     ap.add_argument("--path", default="auto", choices=["auto", "valu", "mfma"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--ex", action="store_true",
+                    help="forward workloads: time llla_forward_ex with a ridge per row and the statistics rho, delta")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures ONE GPU (one MI355X per box); --gpus %d is not run. "
@@ -96,10 +98,18 @@ def main():
         out = torch.empty((w.B, w.H, w.n, w.d), dtype=torch.float32, device=dev)
     ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
 
+    ex = args.ex and not decode
+    # the per-row ridge is the workload's lambda in every row, so that the outputs stay those of the plain call
+    lam_rows = torch.full((w.B, w.H, w.n), w.lam, dtype=torch.float32, device=dev) if ex else None
+    stats = {}
+
     def step(i):
         a, b, c = dev_in[i % n_rot]
         if decode:
             llla.llla_decode(a, b, c, w.lam, w.scale, path=args.path, workspace=ws, out=out)
+        elif ex:
+            _, stats["rho"], stats["delta"] = llla.llla_forward(a, b, c, lam_rows, w.scale, path=args.path, workspace=ws,
+                                                               out=out, return_stats=True)
         else:
             llla.llla_forward(a, b, c, w.lam, w.scale, path=args.path, workspace=ws, out=out)
 
@@ -189,7 +199,9 @@ def main():
         "vs_baseline": None, "dtype": "f32" if w.dtype == "f32" else "bf16 in, f16/f32 MFMA, f32 accumulate",
         "data": "synthetic (seeded, %s)" % w.values,
         "config": {"workload": w.name, "B": w.B, "H": w.H, "n": w.n, "d": w.d, "lambda": w.lam,
-                   "scale": w.scale, "path": args.path, "input_setup_s": round(gen_s, 2)},
+                   "scale": w.scale, "path": args.path, "input_setup_s": round(gen_s, 2),
+                   "entry": "llla_forward_ex (ridge per row, rho and delta written)" if ex else
+                   ("llla_decode" if decode else "llla_forward")},
         "roofline": roof,
     }
     if stages:
@@ -237,6 +249,12 @@ def main():
                     break
             cpu_s = time.perf_counter() - t1
             summ = check(got[None, None], ref0[None, None], np.array(rows), w.d, w.tol, "bench forward")
+            if ex:
+                _, rref, dref = oracle.forward_head_ex(Q[0, 0], K[0, 0], V[0, 0], w.lam, w.scale, rows=rows)
+                summ["rho"] = check(stats["rho"][0, 0].cpu().numpy()[rows][None, None], rref[None, None], np.array(rows),
+                                    w.d, w.tol, "bench rho")
+                summ["delta"] = check(stats["delta"][0, 0].cpu().numpy()[rows][None, None, :, None],
+                                      dref[None, None, :, None], np.array(rows), w.d, w.tol, "bench delta")
             work_all = w.B * w.H * (w.n * (w.n + 1) / 2.0)
             work_s = nrep * float(np.sum(np.asarray(rows) + 1.0))
             full = cpu_s * work_all / work_s
