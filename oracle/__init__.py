@@ -45,6 +45,10 @@ def _load():
                                             ctypes.c_double, dp, ctypes.c_double, ctypes.c_int,
                                             ip, ctypes.c_int, dp, dp, dp]
         lib.llla_oracle_rows_ex.restype = ctypes.c_int
+        lib.llla_oracle_rows_cg.argtypes = [dp, dp, dp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                            ctypes.c_double, ctypes.c_double, ctypes.c_int, ctypes.c_int,
+                                            ctypes.c_double, ip, ctypes.c_int, dp, dp, dp, ip]
+        lib.llla_oracle_rows_cg.restype = ctypes.c_int
         lib.llla_oracle_decode.argtypes = [dp, dp, dp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                            ctypes.c_double, ctypes.c_double, dp]
         lib.llla_oracle_decode.restype = ctypes.c_int
@@ -121,6 +125,26 @@ def forward_ex(Q, K, V, lam, scale: float, causal: bool = True, rows=None):
     R = np.asarray([[r[1] for r in row] for row in res])
     Dl = np.asarray([[r[2] for r in row] for row in res])
     return O, R, Dl
+
+
+def forward_head_cg(Q, K, V, lam: float, scale: float, T: int, eps: float = 0.0, causal: bool = True, rows=None):
+    """One head in the paper's approximate mode (T conjugate-gradient steps for rho, Appendix C).  Returns
+    (O [len(rows), dv], rho [len(rows), d], delta [len(rows)], iterations used [len(rows)])."""
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    n, d = Q.shape
+    dv = V.shape[1]
+    rows = np.arange(n, dtype=np.int32) if rows is None else np.ascontiguousarray(rows, dtype=np.int32)
+    out = np.empty((len(rows), dv), dtype=np.float64)
+    rho = np.empty((len(rows), d), dtype=np.float64)
+    delta = np.empty((len(rows),), dtype=np.float64)
+    used = np.zeros((len(rows),), dtype=np.int32)
+    ipp = ctypes.POINTER(ctypes.c_int)
+    bad = _load().llla_oracle_rows_cg(_dp(Q), _dp(K), _dp(V), n, d, dv, float(lam), float(scale), 1 if causal else 0,
+                                      int(T), float(eps), rows.ctypes.data_as(ipp), len(rows), _dp(out), _dp(rho),
+                                      _dp(delta), used.ctypes.data_as(ipp))
+    if bad:
+        raise ValueError("oracle cg: %d bad row indices" % bad)
+    return out, rho, delta, used
 
 
 def forward(Q, K, V, lam: float, scale: float, causal: bool = True, rows=None) -> np.ndarray:

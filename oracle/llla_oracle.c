@@ -221,6 +221,94 @@ int llla_oracle_decode_batch(const double *q, const double *K, const double *V, 
     return failures;
 }
 
+/*
+ * Approximate mode: the paper's own way of getting rho_i (Section 3.1, "Matrix-free inversion via conjugate
+ * gradients", and the CG solver of Appendix C).  Sigma_i rho = mu_i is solved by T steps of the textbook
+ * conjugate-gradient recursion started at X = 0 (so the first residual and search direction are mu_i), with the
+ * matrix only ever applied to a vector, in the matrix-free form of Section 3.1:
+ *     Sigma p = sum_j w_j (k_j . p) k_j - (q . p) mu~ - (mu~ . p) q + omega (q . p) q + lambda p,
+ * mu~ = sum_j w_j k_j the un-centred first moment.  (The printed solver's correction line reads Y where the search
+ * direction P is meant; the matvec equation of Section 3.1 is followed.)  A system whose residual norm is below eps
+ * when an iteration starts is frozen (the paper's active mask).  Then delta = omega - mu . rho and the output is
+ * Eq. (lla) with those rho, delta.  Everything in fp64, no blocking.
+ * used[t] receives the number of iterations row rows[t] actually performed (may be NULL).
+ */
+static void cg_one_query(const double *q, const double *K, const double *V, int nk, int d, int dv, double lambda,
+                         double scale, int T, double eps, double *out, double *rho_out, double *delta_out, int *used)
+{
+    double *w = (double *)malloc(sizeof(double) * nk);
+    double *mut = (double *)calloc(d, sizeof(double));      /* mu~ */
+    double *mu = (double *)malloc(sizeof(double) * d);
+    double *x = (double *)calloc(d, sizeof(double));
+    double *r = (double *)malloc(sizeof(double) * d);
+    double *p = (double *)malloc(sizeof(double) * d);
+    double *sp = (double *)malloc(sizeof(double) * d);
+    double m = -INFINITY, omega = 0.0;
+    for (int j = 0; j < nk; ++j) {
+        double s = 0.0;
+        for (int a = 0; a < d; ++a) s += q[a] * K[(size_t)j * d + a];
+        w[j] = scale * s;
+        if (w[j] > m) m = w[j];
+    }
+    for (int j = 0; j < nk; ++j) {
+        w[j] = exp(w[j] - m);
+        omega += w[j];
+        for (int a = 0; a < d; ++a) mut[a] += w[j] * K[(size_t)j * d + a];
+    }
+    for (int a = 0; a < d; ++a) { mu[a] = mut[a] - omega * q[a]; r[a] = mu[a]; p[a] = mu[a]; }
+    int it = 0;
+    for (; it < T; ++it) {
+        double rr = 0.0;
+        for (int a = 0; a < d; ++a) rr += r[a] * r[a];
+        if (sqrt(rr) < eps) break;                           /* active mask: this system is done */
+        double qp = 0.0, mp = 0.0;
+        for (int a = 0; a < d; ++a) { qp += q[a] * p[a]; mp += mut[a] * p[a]; sp[a] = 0.0; }
+        for (int j = 0; j < nk; ++j) {
+            double kp = 0.0;
+            for (int a = 0; a < d; ++a) kp += K[(size_t)j * d + a] * p[a];
+            for (int a = 0; a < d; ++a) sp[a] += w[j] * kp * K[(size_t)j * d + a];
+        }
+        double psp = 0.0;
+        for (int a = 0; a < d; ++a) {
+            sp[a] += -qp * mut[a] - mp * q[a] + omega * qp * q[a] + lambda * p[a];
+            psp += p[a] * sp[a];
+        }
+        const double alpha = rr / psp;
+        double rr2 = 0.0;
+        for (int a = 0; a < d; ++a) { x[a] += alpha * p[a]; r[a] -= alpha * sp[a]; rr2 += r[a] * r[a]; }
+        const double beta = rr2 / rr;
+        for (int a = 0; a < d; ++a) p[a] = r[a] + beta * p[a];
+    }
+    double delta = omega;
+    for (int a = 0; a < d; ++a) delta -= mu[a] * x[a];
+    for (int c = 0; c < dv; ++c) out[c] = 0.0;
+    for (int j = 0; j < nk; ++j) {                           /* Eq. (lla) with the approximate rho */
+        double zr = 0.0;
+        for (int a = 0; a < d; ++a) zr += (K[(size_t)j * d + a] - q[a]) * x[a];
+        const double sj = w[j] * (1.0 - zr) / delta;
+        for (int c = 0; c < dv; ++c) out[c] += sj * V[(size_t)j * dv + c];
+    }
+    if (rho_out) for (int a = 0; a < d; ++a) rho_out[a] = x[a];
+    if (delta_out) *delta_out = delta;
+    if (used) *used = it;
+    free(w); free(mut); free(mu); free(x); free(r); free(p); free(sp);
+}
+
+int llla_oracle_rows_cg(const double *Q, const double *K, const double *V, int n, int d, int dv, double lambda,
+                        double scale, int causal, int T, double eps, const int *rows, int nrows, double *O,
+                        double *R, double *Delta, int *used)
+{
+    int failures = 0;
+#pragma omp parallel for schedule(dynamic, 1) reduction(+ : failures)
+    for (int t = 0; t < nrows; ++t) {
+        const int i = rows[t];
+        if (i < 0 || i >= n) { failures += 1; continue; }
+        cg_one_query(Q + (size_t)i * d, K, V, causal ? i + 1 : n, d, dv, lambda, scale, T, eps, O + (size_t)t * dv,
+                     R ? R + (size_t)t * d : NULL, Delta ? Delta + t : NULL, used ? used + t : NULL);
+    }
+    return failures;
+}
+
 int llla_oracle_threads(void)
 {
 #ifdef _OPENMP

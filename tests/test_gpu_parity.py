@@ -232,6 +232,12 @@ def test_c3_prefill_sampled_rows():
     _sampled(w, [(0, h) for h in range(0, w.H, 4)] + [(3, 7), (2, 15)])
 
 
+def test_c3b_prefill_n8192_sampled_rows():
+    """The shape the matrix-core utilisation target is quoted for (d = 64, n = 8192)."""
+    w = workloads.C3B
+    _sampled(w, [(0, 0), (0, 9), (1, 15)])
+
+
 def test_c4_long_context_sampled_rows():
     w = workloads.C4
     _sampled(w, [(0, 0), (0, 5), (0, 15)])
