@@ -228,8 +228,9 @@ int llla_oracle_decode_batch(const double *q, const double *K, const double *V, 
  * matrix only ever applied to a vector, in the matrix-free form of Section 3.1:
  *     Sigma p = sum_j w_j (k_j . p) k_j - (q . p) mu~ - (mu~ . p) q + omega (q . p) q + lambda p,
  * mu~ = sum_j w_j k_j the un-centred first moment.  (The printed solver's correction line reads Y where the search
- * direction P is meant; the matvec equation of Section 3.1 is followed.)  A system whose residual norm is below eps
- * when an iteration starts is frozen (the paper's active mask).  Then delta = omega - mu . rho and the output is
+ * direction P is meant; the matvec equation of Section 3.1 is followed.)  A system whose residual norm is at or below
+ * eps when an iteration starts is frozen (the paper's active mask; "at or" so that eps = 0 still stops a system whose
+ * residual has become exactly zero instead of dividing 0 by 0).  Then delta = omega - mu . rho and the output is
  * Eq. (lla) with those rho, delta.  Everything in fp64, no blocking.
  * used[t] receives the number of iterations row rows[t] actually performed (may be NULL).
  */
@@ -260,7 +261,7 @@ static void cg_one_query(const double *q, const double *K, const double *V, int 
     for (; it < T; ++it) {
         double rr = 0.0;
         for (int a = 0; a < d; ++a) rr += r[a] * r[a];
-        if (sqrt(rr) < eps) break;                           /* active mask: this system is done */
+        if (sqrt(rr) <= eps) break;                          /* active mask: this system is done (also at rr == 0) */
         double qp = 0.0, mp = 0.0;
         for (int a = 0; a < d; ++a) { qp += q[a] * p[a]; mp += mut[a] * p[a]; sp[a] = 0.0; }
         for (int j = 0; j < nk; ++j) {
