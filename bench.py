@@ -55,6 +55,8 @@ def main():
     ap.add_argument("--path", default="auto", choices=["auto", "valu", "mfma"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--cg", type=int, default=None, metavar="T",
+                    help="forward workloads: time llla_forward_cg, the paper's approximate mode with T conjugate-gradient steps")
     ap.add_argument("--ex", action="store_true",
                     help="forward workloads: time llla_forward_ex with a ridge per row and the statistics rho, delta")
     args = ap.parse_args()
@@ -95,6 +97,8 @@ def main():
         out = torch.empty((w.B, w.H, w.d), dtype=torch.float32, device=dev)
     else:
         need = llla.forward_workspace_bytes(w.B, w.H, w.n, w.d, dt)
+        if args.cg is not None:
+            need = llla.forward_cg_workspace_bytes(w.B, w.H, w.n, w.d, dt)
         out = torch.empty((w.B, w.H, w.n, w.d), dtype=torch.float32, device=dev)
     ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
 
@@ -107,6 +111,8 @@ def main():
         a, b, c = dev_in[i % n_rot]
         if decode:
             llla.llla_decode(a, b, c, w.lam, w.scale, path=args.path, workspace=ws, out=out)
+        elif args.cg is not None:
+            llla.llla_forward_cg(a, b, c, w.lam, w.scale, args.cg, 0.0, workspace=ws, out=out)
         elif ex:
             _, stats["rho"], stats["delta"] = llla.llla_forward(a, b, c, lam_rows, w.scale, path=args.path, workspace=ws,
                                                                out=out, return_stats=True)
@@ -151,7 +157,11 @@ def main():
         tokens = w.B * w.n
         pairs = w.n * (w.n + 1) // 2
         d = w.d
-        if dom == "moments":
+        if dom == "cg_steps":
+            # per step and causal pair: logits (2d), k.p (2d), accumulate (2d); per row the vector updates (~12d)
+            flops = args.cg * w.B * w.H * (pairs * 6.0 * d + w.n * 12.0 * d)
+            bound, peak = "mfma", PEAK_MFMA_16BIT
+        elif dom == "moments":
             # logits, weights, omega, mu~, symmetric half of Sigma~, and the per-row solve
             flops = w.B * w.H * (pairs * (d * d + 5 * d) + w.n * (d ** 3 / 3.0 + 4 * d * d))
             bound, peak = "mfma", PEAK_MFMA_16BIT
@@ -200,7 +210,8 @@ def main():
         "data": "synthetic (seeded, %s)" % w.values,
         "config": {"workload": w.name, "B": w.B, "H": w.H, "n": w.n, "d": w.d, "lambda": w.lam,
                    "scale": w.scale, "path": args.path, "input_setup_s": round(gen_s, 2),
-                   "entry": "llla_forward_ex (ridge per row, rho and delta written)" if ex else
+                   "entry": ("llla_forward_cg (approximate: %d conjugate-gradient steps)" % args.cg) if args.cg is not None
+                   and not decode else "llla_forward_ex (ridge per row, rho and delta written)" if ex else
                    ("llla_decode" if decode else "llla_forward")},
         "roofline": roof,
     }
@@ -240,15 +251,32 @@ def main():
             t1 = time.perf_counter()
             nrep = 0
             while True:                         # bounded sample: a few heads' worth of sampled rows
-                ref = oracle.forward_head(Q[0, nrep % w.H], K[0, nrep % w.H], V[0, nrep % w.H], w.lam, w.scale,
-                                          rows=rows)
+                if args.cg is not None:
+                    ref = oracle.forward_head_cg(Q[0, nrep % w.H], K[0, nrep % w.H], V[0, nrep % w.H], w.lam, w.scale,
+                                                 args.cg, 0.0, rows=rows)[0]
+                else:
+                    ref = oracle.forward_head(Q[0, nrep % w.H], K[0, nrep % w.H], V[0, nrep % w.H], w.lam, w.scale,
+                                              rows=rows)
                 if nrep == 0:
                     ref0 = ref
                 nrep += 1
                 if time.perf_counter() - t1 > 10.0:
                     break
             cpu_s = time.perf_counter() - t1
-            summ = check(got[None, None], ref0[None, None], np.array(rows), w.d, w.tol, "bench forward")
+            if args.cg is not None:
+                # later CG iterates are not comparable element-wise (they are unstable under rounding); report how far
+                # the approximate outputs are from the exact forward of this library and from the fp64 CG oracle
+                exact = llla.llla_forward(*dev_in[0], w.lam, w.scale)[0, 0].cpu().numpy()[rows]
+                dist = np.linalg.norm(got - exact, axis=-1) / np.linalg.norm(exact, axis=-1)
+                dor = np.linalg.norm(got - ref0, axis=-1) / np.linalg.norm(ref0, axis=-1)
+                late = np.asarray(rows) >= 4 * w.d
+                summ = {"steps": args.cg,
+                        "distance_to_exact_forward": {"median": float(np.median(dist)), "p90": float(np.quantile(dist, 0.9)),
+                                                      "median_rows_ge_4d": float(np.median(dist[late])),
+                                                      "max_rows_ge_4d": float(dist[late].max())},
+                        "distance_to_fp64_cg_oracle": {"median": float(np.median(dor)), "p90": float(np.quantile(dor, 0.9))}}
+            else:
+                summ = check(got[None, None], ref0[None, None], np.array(rows), w.d, w.tol, "bench forward")
             if ex:
                 _, rref, dref = oracle.forward_head_ex(Q[0, 0], K[0, 0], V[0, 0], w.lam, w.scale, rows=rows)
                 summ["rho"] = check(stats["rho"][0, 0].cpu().numpy()[rows][None, None], rref[None, None], np.array(rows),

@@ -119,6 +119,26 @@ llla_status llla_forward_ex(const void *Q, const void *K, const void *V, void *O
                             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * llla_forward_cg -- the paper's approximate forward (Section 3.1 "matrix-free inversion via conjugate gradients",
+ * solver of Appendix C): rho_i is the iterate after at most `max_steps` conjugate-gradient steps on
+ * Sigma_i rho = mu_i, started at 0, with Sigma_i applied matrix-free; delta_i and the output follow from Eq. (lla)
+ * with that rho_i.  A row whose residual norm ||mu_i - Sigma_i rho|| is at or below `eps` when a step starts takes
+ * no further steps (the paper's active mask); eps = 0 runs max_steps steps unless the residual becomes exactly 0.
+ * max_steps = 0 gives softmax attention (rho = 0).  Causal; bf16 inputs with d = 64 or 128 only
+ * (LLLA_ERR_UNSUPPORTED otherwise).  0 <= max_steps <= 4096, eps >= 0.
+ *   rho, delta : optional outputs as in llla_forward_ex;  steps: optional device int32 [B, H, n], steps taken per row.
+ * Workspace: llla_forward_cg_workspace_bytes (larger than the exact forward's: the CG vectors of every row).
+ */
+size_t llla_forward_cg_workspace_bytes(int B, int H, int n, int d, llla_dtype in);
+
+llla_status llla_forward_cg(const void *Q, const void *K, const void *V, void *O,
+                            llla_strides sq, llla_strides sk, llla_strides sv, llla_strides so,
+                            int B, int H, int n, int d, llla_dtype in, llla_dtype out,
+                            float lambda, float scale, int max_steps, float eps,
+                            float *rho, float *delta, int32_t *steps,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * llla_decode -- the inference step the paper mentions (Sections 1 and 2.3: LLA keeps a Theta(n d)
  * KV cache): one new query per (batch, head) against the cached keys and values, the new token's
  * own (k, v) already appended, i.e. the last row of a causal forward over seqlens[b] positions.

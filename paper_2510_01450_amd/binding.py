@@ -49,6 +49,11 @@ def lib():
     L.llla_forward_path.restype = i32
     L.llla_forward_ex.argtypes = fwd[:-1] + [vp, f32, vp, vp, i32, vp, sz, vp]
     L.llla_forward_ex.restype = i32
+    L.llla_forward_cg_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
+    L.llla_forward_cg_workspace_bytes.restype = sz
+    L.llla_forward_cg.argtypes = [vp, vp, vp, vp, _Strides, _Strides, _Strides, _Strides, i32, i32, i32, i32, i32, i32,
+                                  f32, f32, i32, f32, vp, vp, vp, vp, sz, vp]
+    L.llla_forward_cg.restype = i32
     dec = [vp, vp, vp, vp, _Strides, _Strides, vp, i32, i32, i32, i32, i32, i32, f32, f32]
     L.llla_decode.argtypes = dec + [vp, sz, vp]
     L.llla_decode.restype = i32
@@ -158,6 +163,40 @@ def llla_forward(Q, K, V, lam, scale: float, causal: bool = True, out_dtype=None
     if st != 0:
         raise LlaError(st, "llla_forward")
     return (O, rho, delta) if return_stats else O
+
+
+def forward_cg_workspace_bytes(B, H, n, d, dtype) -> int:
+    return int(lib().llla_forward_cg_workspace_bytes(B, H, n, d, _DTYPES[dtype]))
+
+
+def llla_forward_cg(Q, K, V, lam: float, scale: float, max_steps: int, eps: float = 0.0, out_dtype=None,
+                    workspace=None, out=None, stream=None, return_stats: bool = False):
+    """The paper's approximate forward: rho from at most ``max_steps`` conjugate-gradient steps (bf16, d = 64 / 128,
+    causal).  Returns O, or (O, rho, delta, steps) with ``return_stats``."""
+    if not (Q.is_cuda and K.is_cuda and V.is_cuda):
+        raise ValueError("llla_forward_cg needs device tensors; this library has no CPU path")
+    if not (Q.dtype == K.dtype == V.dtype) or Q.dtype not in _DTYPES:
+        raise ValueError("Q, K, V must share dtype float32 or bfloat16")
+    B, H, n, d = Q.shape
+    if K.shape != Q.shape or V.shape != Q.shape:
+        raise ValueError("Q, K, V must have the same [B, H, n, d] shape")
+    out_dtype = torch.float32 if out_dtype is None else out_dtype
+    O = torch.empty((B, H, n, d), dtype=out_dtype, device=Q.device) if out is None else out
+    rho = torch.empty((B, H, n, d), dtype=torch.float32, device=Q.device) if return_stats else None
+    delta = torch.empty((B, H, n), dtype=torch.float32, device=Q.device) if return_stats else None
+    steps = torch.empty((B, H, n), dtype=torch.int32, device=Q.device) if return_stats else None
+    need = forward_cg_workspace_bytes(B, H, n, d, Q.dtype)
+    ws = _workspace(need, Q.device, workspace)
+    st = lib().llla_forward_cg(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                               _strides4(Q), _strides4(K), _strides4(V), _strides4(O),
+                               B, H, n, d, _DTYPES[Q.dtype], _DTYPES[O.dtype], float(lam), float(scale),
+                               int(max_steps), float(eps),
+                               None if rho is None else rho.data_ptr(), None if delta is None else delta.data_ptr(),
+                               None if steps is None else steps.data_ptr(),
+                               ws.data_ptr(), ws.numel() * ws.element_size(), _stream_ptr(stream))
+    if st != 0:
+        raise LlaError(st, "llla_forward_cg")
+    return (O, rho, delta, steps) if return_stats else O
 
 
 def llla_decode(q, Kc, Vc, lam: float, scale: float, seqlens=None, out_dtype=None, path: str = "auto",

@@ -180,6 +180,49 @@ llla_status llla_forward(const void *Q, const void *K, const void *V, void *O, l
                              LLLA_PATH_AUTO, workspace, workspace_bytes, stream);
 }
 
+size_t llla_forward_cg_workspace_bytes(int B, int H, int n, int d, llla_dtype in)
+{
+    if (B <= 0 || H <= 0 || n <= 0 || !dim_supported(d) || !dtype_ok(in)) return 0;
+    return llla::mfma_forward_cg_workspace_bytes(B, H, n, d, in);
+}
+
+llla_status llla_forward_cg(const void *Q, const void *K, const void *V, void *O, llla_strides sq, llla_strides sk,
+                            llla_strides sv, llla_strides so, int B, int H, int n, int d, llla_dtype in,
+                            llla_dtype out, float lambda, float scale, int max_steps, float eps, float *rho,
+                            float *delta, int32_t *steps, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!Q || !K || !V || !O) return LLLA_ERR_NULL;
+    llla_status st = check_common(B, H, n, d, in, out, lambda, scale);
+    if (st != LLLA_OK) return st;
+    if (max_steps < 0 || max_steps > 4096 || !(eps >= 0.f) || !std::isfinite(eps)) return LLLA_ERR_PARAM;
+    if (!strides_cover(sq, B, H, n, d) || !strides_cover(sk, B, H, n, d) || !strides_cover(sv, B, H, n, d) ||
+        !strides_cover(so, B, H, n, d))
+        return LLLA_ERR_SHAPE;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !strides_aligned(sq, in) ||
+        !strides_aligned(sk, in) || !strides_aligned(sv, in) || !strides_aligned(so, out) ||
+        (reinterpret_cast<uintptr_t>(rho) & 3u) || (reinterpret_cast<uintptr_t>(delta) & 3u) ||
+        (reinterpret_cast<uintptr_t>(steps) & 3u))
+        return LLLA_ERR_ALIGN;
+    if (!llla::mfma_forward_supported(d, in, true)) return LLLA_ERR_UNSUPPORTED;
+    st = check_workspace(llla::mfma_forward_cg_workspace_bytes(B, H, n, d, in), workspace, workspace_bytes);
+    if (st != LLLA_OK) return st;
+
+    Problem p{};
+    p.Q = Q; p.K = K; p.V = V; p.O = O;
+    p.sq = sq; p.sk = sk; p.sv = sv; p.so = so;
+    p.B = B; p.H = H; p.n = n; p.d = d;
+    p.in = in; p.out = out;
+    p.causal = 1;
+    p.lambda = lambda; p.scale = scale;
+    p.rho = rho; p.delta = delta;
+    p.ws = workspace; p.ws_bytes = workspace_bytes;
+    p.stream = static_cast<hipStream_t>(stream);
+    llla::stage_begin(p.stream);
+    const hipError_t e = llla::mfma_forward_cg(p, max_steps, eps, steps);
+    llla::stage_end(p.stream);
+    return e == hipSuccess ? LLLA_OK : LLLA_ERR_LAUNCH;
+}
+
 size_t llla_decode_workspace_bytes(int B, int H, int L_max, int d, llla_dtype in)
 {
     if (B <= 0 || H <= 0 || L_max <= 0 || !dim_supported(d) || !dtype_ok(in)) return 0;

@@ -39,6 +39,9 @@ hipError_t valu_decode(const Problem &p);
 bool mfma_forward_supported(int d, llla_dtype in, bool causal);
 size_t mfma_forward_workspace_bytes(int B, int H, int n, int d, llla_dtype in);
 hipError_t mfma_forward(const Problem &p);
+// approximate mode: T conjugate-gradient steps per row (bf16, d = 64 / 128, causal); iters: [B,H,n] steps done, or nullptr
+size_t mfma_forward_cg_workspace_bytes(int B, int H, int n, int d, llla_dtype in);
+hipError_t mfma_forward_cg(const Problem &p, int T, float eps, int32_t *iters);
 bool mfma_decode_supported(int d, llla_dtype in);
 size_t mfma_decode_workspace_bytes(int B, int H, int L_max, int d, llla_dtype in);
 // whether the MFMA decode path serves this call (it needs the full cache length for every sequence)

@@ -100,8 +100,13 @@ __global__ __launch_bounds__(256) void sweep_kernel(const bf16_t *__restrict__ Q
                                                     llla_strides sq, llla_strides sk, int H, int n, int nkb,
                                                     int first_row, float cscale, const bf16_t *__restrict__ VT,
                                                     float *__restrict__ Mg, const float *__restrict__ Yg,
-                                                    void *__restrict__ Og, llla_strides so, int out_bf16)
+                                                    void *__restrict__ Og, llla_strides so, int out_bf16,
+                                                    float *__restrict__ Csum = nullptr)
 {
+    // !MAXONLY is a general "coefficients times a tile" sweep: O_i = sum_j w_ij (y0_i + k_j . y1_i) t_j with the rows t_j
+    // of whatever VT holds (V for the output; K for the first moment and for the matrix-free product of the
+    // approximate mode).  Yg == nullptr means y0 = 1, y1 = 0 (plain weights); Csum, if given, receives sum_j of the
+    // coefficients of every row.
     using S = Shape<DD>;
     constexpr int NF = S::NF, NB = S::NB, YP = S::YP;
     constexpr int KN_PITCH = DD + 8;     // halves; rows of the natural K tile stay 16-byte aligned
@@ -124,13 +129,13 @@ __global__ __launch_bounds__(256) void sweep_kernel(const bf16_t *__restrict__ Q
     f32x4 oacc[NB];
     if (!MAXONLY) {
         mrow = Mg[(size_t)bh * (nkb * KB) + iqc];
-        const float *yr = Yg + ((size_t)bh * n + iqc) * YP;
-        y0 = yr[DD];
+        const float *yr = Yg ? Yg + ((size_t)bh * n + iqc) * YP : nullptr;
+        y0 = yr ? yr[DD] : 1.f;
 #pragma unroll
         for (int f = 0; f < NF; ++f)
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
-                const float v = yr[32 * f + 8 * g + t];
+                const float v = yr ? yr[32 * f + 8 * g + t] : 0.f;
                 const __bf16 hi = (__bf16)v;
                 yh[f][t] = hi;
                 yl[f][t] = (__bf16)(v - (float)hi);
@@ -143,6 +148,7 @@ __global__ __launch_bounds__(256) void sweep_kernel(const bf16_t *__restrict__ Q
     for (int s = 0; s < 2; ++s)
 #pragma unroll
         for (int r = 0; r < 4; ++r) mx[s][r] = -INFINITY;
+    float csum = 0.f;
 
     const int ilast = min(i0 + 63, n - 1);
     const int nblk = ilast / KB + 1;
@@ -202,6 +208,7 @@ __global__ __launch_bounds__(256) void sweep_kernel(const bf16_t *__restrict__ Q
                     const int j = c * KB + 16 * s + 4 * g + r;
                     const float wgt = __builtin_amdgcn_exp2f(st[s][r] * cscale - mrow);
                     const float cv = (j <= iq) ? wgt * (y0 + ut[s][r]) : 0.f;
+                    csum += cv;
                     const __bf16 hi = (__bf16)cv;
                     ch[4 * s + r] = hi;
                     cl[4 * s + r] = (__bf16)(cv - (float)hi);
@@ -229,6 +236,11 @@ __global__ __launch_bounds__(256) void sweep_kernel(const bf16_t *__restrict__ Q
         m = fmaxf(m, __shfl_xor(m, 32));
         if (g == 0 && iq < n) Mg[(size_t)bh * (nkb * KB) + iq] = m;
     } else {
+        if (Csum != nullptr) {      // lanes (g, nn), g = 0..3, hold the coefficients of query nn for disjoint keys
+            csum += __shfl_xor(csum, 16);
+            csum += __shfl_xor(csum, 32);
+            if (g == 0 && iq < n) Csum[(size_t)bh * n + iq] = csum;
+        }
         // oacc[J]: lane (g, nn) reg r = O[query i0 + 16 wave + 4g + r][feature 16J + nn]
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -720,6 +732,198 @@ hipError_t forward_impl(const Problem &p)
     return hipGetLastError();
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// Approximate mode of the paper (Section 3.1 "matrix-free inversion", solver of Appendix C): rho_i from T steps of
+// conjugate gradients on Sigma_i rho = mu_i, Sigma_i applied matrix-free,
+//     Sigma p = sum_j w_j (k_j . p) k_j - (q . p) mu~ - (mu~ . p) q + omega (q . p) q + lambda p.
+// The sum over keys is one sweep_kernel launch per step (coefficients w_ij (k_j . p_i), tile = K); the vector part of a
+// step is the row-wise kernel below (one wave per query row).  A row whose residual norm is at or below eps when a
+// step starts is frozen (the paper's active mask).
+struct CgLayout {
+    Layout base;
+    size_t ktb, mut, om, x, r, p, sp, rr, it, total;
+};
+
+template <int DD>
+CgLayout make_cg_layout(int B, int H, int n)
+{
+    CgLayout C;
+    C.base = make_layout<DD>(B, H, n);
+    const size_t bh = (size_t)B * H, rows = bh * (size_t)n;
+    size_t off = C.base.total;
+    C.ktb = off; off += round_up(bh * C.base.npad * DD * 2, 256);        // K re-tiled as bf16 (tile operand of the sweeps)
+    C.mut = off; off += round_up(rows * DD * 4, 256);                      // mu~
+    C.om = off;  off += round_up(rows * 4, 256);                           // omega
+    C.x = off;   off += round_up(rows * DD * 4, 256);
+    C.r = off;   off += round_up(rows * DD * 4, 256);
+    C.p = off;   off += round_up(rows * Shape<DD>::YP * 4, 256);           // search direction, laid out like a y row
+    C.sp = off;  off += round_up(rows * DD * 4, 256);                      // sum_j w_j (k_j . p) k_j
+    C.rr = off;  off += round_up(rows * 4, 256);
+    C.it = off;  off += round_up(rows * 4, 256);                           // steps done; negative once frozen
+    C.total = off;
+    return C;
+}
+
+template <int DD>
+__device__ inline float wave_sum(float v)
+{
+#pragma unroll
+    for (int sft = 32; sft >= 1; sft >>= 1) v += __shfl_xor(v, sft);
+    return v;
+}
+
+// phase 0: start (mu = mu~ - omega q; X = 0, R = P = mu);  phase 1: one CG step;  phase 2: rho, delta -> y (+ outputs)
+template <int DD, int PHASE>
+__global__ __launch_bounds__(256) void cg_rows_kernel(const bf16_t *__restrict__ Qg, llla_strides sq, int H, int n,
+                                                      float lambda, float eps, const float *__restrict__ MUt,
+                                                      const float *__restrict__ OM, float *__restrict__ X,
+                                                      float *__restrict__ R, float *__restrict__ P,
+                                                      const float *__restrict__ SP, float *__restrict__ RR,
+                                                      int *__restrict__ IT, float *__restrict__ Yg,
+                                                      float *__restrict__ rho, float *__restrict__ delta,
+                                                      int32_t *__restrict__ iters)
+{
+    constexpr int YP = Shape<DD>::YP, PER = DD / 64;
+    const int lane = threadIdx.x % 64, i = blockIdx.x * 4 + threadIdx.x / 64, bh = blockIdx.y;
+    if (i >= n) return;
+    const size_t row = (size_t)bh * n + i;
+    const bf16_t *qrow = Qg + (bh / H) * sq.batch + (bh % H) * sq.head + (int64_t)i * sq.seq;
+    float q[PER], mut[PER];
+#pragma unroll
+    for (int t = 0; t < PER; ++t) {
+        q[t] = bf16_to_f32(qrow[lane + 64 * t]);
+        mut[t] = MUt[row * DD + lane + 64 * t];
+    }
+    const float om = OM[row];
+    if (PHASE == 0) {
+        float rr = 0.f;
+#pragma unroll
+        for (int t = 0; t < PER; ++t) {
+            const float mu = mut[t] - om * q[t];
+            X[row * DD + lane + 64 * t] = 0.f;
+            R[row * DD + lane + 64 * t] = mu;
+            P[row * YP + lane + 64 * t] = mu;
+            rr = fmaf(mu, mu, rr);
+        }
+        rr = wave_sum<DD>(rr);
+        if (lane == 0) { RR[row] = rr; IT[row] = 0; P[row * YP + DD] = 0.f; }
+    } else if (PHASE == 1) {
+        const int it = IT[row];
+        if (it < 0) return;                                     // frozen
+        const float rr = RR[row];
+        if (sqrtf(rr) <= eps) { if (lane == 0) IT[row] = -it - 1; return; }
+        float p[PER], sp[PER], qp = 0.f, mp = 0.f;
+#pragma unroll
+        for (int t = 0; t < PER; ++t) {
+            p[t] = P[row * YP + lane + 64 * t];
+            qp = fmaf(q[t], p[t], qp);
+            mp = fmaf(mut[t], p[t], mp);
+        }
+        qp = wave_sum<DD>(qp);
+        mp = wave_sum<DD>(mp);
+        float psp = 0.f;
+#pragma unroll
+        for (int t = 0; t < PER; ++t) {
+            sp[t] = SP[row * DD + lane + 64 * t] - qp * mut[t] - mp * q[t] + om * qp * q[t] + lambda * p[t];
+            psp = fmaf(p[t], sp[t], psp);
+        }
+        psp = wave_sum<DD>(psp);
+        const float alpha = rr / psp;
+        float r[PER], rr2 = 0.f;
+#pragma unroll
+        for (int t = 0; t < PER; ++t) {
+            X[row * DD + lane + 64 * t] += alpha * p[t];
+            r[t] = R[row * DD + lane + 64 * t] - alpha * sp[t];
+            R[row * DD + lane + 64 * t] = r[t];
+            rr2 = fmaf(r[t], r[t], rr2);
+        }
+        rr2 = wave_sum<DD>(rr2);
+        const float beta = rr2 / rr;
+#pragma unroll
+        for (int t = 0; t < PER; ++t) P[row * YP + lane + 64 * t] = r[t] + beta * p[t];
+        if (lane == 0) { RR[row] = rr2; IT[row] = it + 1; }
+    } else {
+        float x[PER], mx = 0.f, qx = 0.f;
+#pragma unroll
+        for (int t = 0; t < PER; ++t) {
+            x[t] = X[row * DD + lane + 64 * t];
+            mx = fmaf(mut[t] - om * q[t], x[t], mx);
+            qx = fmaf(q[t], x[t], qx);
+        }
+        mx = wave_sum<DD>(mx);
+        qx = wave_sum<DD>(qx);
+        const float dl = om - mx, inv = 1.f / dl;                // delta = omega - mu . rho
+#pragma unroll
+        for (int t = 0; t < PER; ++t) {
+            Yg[row * YP + lane + 64 * t] = -x[t] * inv;           // y1 = -rho / delta
+            if (rho != nullptr) rho[row * DD + lane + 64 * t] = x[t];
+        }
+        if (lane == 0) {
+            Yg[row * YP + DD] = (1.f + qx) * inv;                // y0 = (1 + q . rho) / delta
+            if (delta != nullptr) delta[row] = dl;
+            if (iters != nullptr) { const int it = IT[row]; iters[row] = it < 0 ? -it - 1 : it; }
+        }
+    }
+}
+
+template <int DD>
+hipError_t forward_cg_impl(const Problem &p, int T, float eps, int32_t *iters)
+{
+    using S = Shape<DD>;
+    const CgLayout C = make_cg_layout<DD>(p.B, p.H, p.n);
+    const Layout &L = C.base;
+    char *ws = static_cast<char *>(p.ws);
+    _Float16 *KT = reinterpret_cast<_Float16 *>(ws + L.kt);
+    bf16_t *VT = reinterpret_cast<bf16_t *>(ws + L.vt);
+    bf16_t *KTB = reinterpret_cast<bf16_t *>(ws + C.ktb);
+    float *M = reinterpret_cast<float *>(ws + L.m), *Y = reinterpret_cast<float *>(ws + L.y);
+    float *MUt = reinterpret_cast<float *>(ws + C.mut), *OM = reinterpret_cast<float *>(ws + C.om);
+    float *X = reinterpret_cast<float *>(ws + C.x), *R = reinterpret_cast<float *>(ws + C.r);
+    float *P = reinterpret_cast<float *>(ws + C.p), *SP = reinterpret_cast<float *>(ws + C.sp);
+    float *RR = reinterpret_cast<float *>(ws + C.rr);
+    int *IT = reinterpret_cast<int *>(ws + C.it);
+    const int bh = p.B * p.H, nq64 = (p.n + 63) / 64;
+    const float cscale = p.scale * LOG2E;
+    const bf16_t *Q = static_cast<const bf16_t *>(p.Q), *K = static_cast<const bf16_t *>(p.K),
+                 *V = static_cast<const bf16_t *>(p.V);
+    const llla_strides dense = {(int64_t)p.H * p.n * DD, (int64_t)p.n * DD, DD};     // [B,H,n,DD] fp32 scratch arrays
+    const dim3 rows_grid((p.n + 3) / 4, bh);
+
+    stage_mark(p.stream, "prep");
+    hipLaunchKernelGGL((prep_kernel<DD>), dim3(L.nkb, bh), dim3(256), 0, p.stream, K, V, p.sk, p.sv, p.H, p.n, L.nkb, KT, VT);
+    hipLaunchKernelGGL((prep_kernel<DD>), dim3(L.nkb, bh), dim3(256), 0, p.stream, K, K, p.sk, p.sk, p.H, p.n, L.nkb, KT, KTB);
+    stage_mark(p.stream, "rowmax");
+    hipLaunchKernelGGL((sweep_kernel<true, DD>), dim3(nq64, bh), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
+                       0, cscale, VT, M, Y, p.O, p.so, 0);
+    stage_mark(p.stream, "first_moment");       // omega = sum w, mu~ = sum w k: plain weights times the K tile
+    hipLaunchKernelGGL((sweep_kernel<false, DD>), dim3(nq64, bh), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
+                       0, cscale, KTB, M, (const float *)nullptr, (void *)MUt, dense, 0, OM);
+    hipLaunchKernelGGL((cg_rows_kernel<DD, 0>), rows_grid, dim3(256), 0, p.stream, Q, p.sq, p.H, p.n, p.lambda, eps, MUt, OM,
+                       X, R, P, SP, RR, IT, Y, p.rho, p.delta, iters);
+    stage_mark(p.stream, "cg_steps");
+    for (int t = 0; t < T; ++t) {
+        hipLaunchKernelGGL((sweep_kernel<false, DD>), dim3(nq64, bh), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n,
+                           L.nkb, 0, cscale, KTB, M, (const float *)P, (void *)SP, dense, 0, (float *)nullptr);
+        hipLaunchKernelGGL((cg_rows_kernel<DD, 1>), rows_grid, dim3(256), 0, p.stream, Q, p.sq, p.H, p.n, p.lambda, eps, MUt,
+                           OM, X, R, P, SP, RR, IT, Y, p.rho, p.delta, iters);
+    }
+    stage_mark(p.stream, "cg_finish");
+    hipLaunchKernelGGL((cg_rows_kernel<DD, 2>), rows_grid, dim3(256), 0, p.stream, Q, p.sq, p.H, p.n, p.lambda, eps, MUt, OM,
+                       X, R, P, SP, RR, IT, Y, p.rho, p.delta, iters);
+    const int first = S::EARLY_ROWS < p.n ? S::EARLY_ROWS : p.n;
+    stage_mark(p.stream, "output_early_rows");
+    hipError_t e = valu_forward_given(p, first, M, L.npad, Y, S::YP);
+    if (e != hipSuccess) return e;
+    if (first < p.n) {
+        stage_mark(p.stream, "output");
+        hipLaunchKernelGGL((sweep_kernel<false, DD>), dim3((p.n - first + 63) / 64, bh), dim3(256), 0, p.stream, Q, K, p.sq, p.sk,
+                           p.H, p.n, L.nkb, first, cscale, VT, M, (const float *)Y, p.O, p.so, p.out == LLLA_BF16 ? 1 : 0,
+                           (float *)nullptr);
+    }
+    return hipGetLastError();
+}
+
 }  // namespace
 
 bool mfma_forward_supported(int d, llla_dtype in, bool causal) { return (d == 64 || d == 128) && in == LLLA_BF16 && causal; }
@@ -731,5 +935,16 @@ size_t mfma_forward_workspace_bytes(int B, int H, int n, int d, llla_dtype in)
 }
 
 hipError_t mfma_forward(const Problem &p) { return p.d == 64 ? forward_impl<64>(p) : forward_impl<128>(p); }
+
+size_t mfma_forward_cg_workspace_bytes(int B, int H, int n, int d, llla_dtype in)
+{
+    if (!mfma_forward_supported(d, in, true)) return 0;
+    return d == 64 ? make_cg_layout<64>(B, H, n).total : make_cg_layout<128>(B, H, n).total;
+}
+
+hipError_t mfma_forward_cg(const Problem &p, int T, float eps, int32_t *iters)
+{
+    return p.d == 64 ? forward_cg_impl<64>(p, T, eps, iters) : forward_cg_impl<128>(p, T, eps, iters);
+}
 
 }  // namespace llla

@@ -71,6 +71,23 @@ def test_forward_ex_validation():
     assert ex(FAKE, FAKE, FAKE, FAKE, s, s, s, s, 1, 1, 64, 64, 1, 0, 1, 0.0, FAKE, 0.125, None, None, 2, 0, 0, 0) == 6
 
 
+def test_forward_cg_validation():
+    s = _Strides(64 * 64, 64 * 64, 64)
+    cg = llla.lib().llla_forward_cg
+
+    def call(din=1, d=64, T=4, eps=0.0, lam=1e-2, rho=None, ws=0, wsb=0):
+        return cg(FAKE, FAKE, FAKE, FAKE, s, s, s, s, 1, 1, 64, d, din, 0, lam, 0.125, T, eps, rho, None, None, ws, wsb, 0)
+
+    assert call(T=-1) == 4 and call(T=5000) == 4 and call(eps=-1.0) == 4 and call(eps=float("nan")) == 4
+    assert call(lam=0.0) == 4
+    assert call(rho=FAKE + 2) == 5
+    assert call(din=0) == 7            # fp32 inputs have no approximate mode
+    assert call(d=32) == 7
+    assert call() == 6                 # everything valid but no workspace
+    assert llla.lib().llla_forward_cg_workspace_bytes(1, 1, 64, 64, 1) > llla.lib().llla_forward_workspace_bytes(1, 1, 64, 64, 1)
+    assert llla.lib().llla_forward_cg_workspace_bytes(1, 1, 64, 64, 0) == 0
+
+
 @pytest.mark.parametrize("kw,code", [
     (dict(q=0), 1), (dict(L=0), 2), (dict(din=5), 3), (dict(lam=0.0), 4), (dict(K=FAKE + 2), 5), (dict(d=20), 7),
     (dict(sk=_Strides(64 * 64, 64 * 64, 8)), 2),

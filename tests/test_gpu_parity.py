@@ -293,3 +293,91 @@ def test_forward_ex_rejects_a_host_ridge_tensor():
     Q, K, V = [t.to(DEV) for t in workloads.make_inputs(w)]
     with pytest.raises(ValueError):
         llla.llla_forward(Q, K, V, torch.full((1, 1, 64), 0.01), w.scale)
+
+
+# ---- approximate mode: rho from T conjugate-gradient steps (Section 3.1 / Appendix C) ------------------------
+@pytest.mark.parametrize("n,d,T", [(333, 64, 0), (333, 64, 1), (333, 64, 2), (600, 64, 2), (290, 128, 1), (290, 128, 2)])
+def test_forward_cg_first_steps_match_the_cg_oracle(n, d, T):
+    """Element-wise against the fp64 CG oracle with the same number of steps.  Only the first steps can be compared
+    this way: CG iterates of an ill-conditioned system are not stable under rounding (two fp64 runs already drift
+    apart, see the SciPy pin), so later iterates are checked through their residuals instead (next test)."""
+    w = _small("cg", 1, 2, n, d, "bf16", index=800 + d + n + T)
+    Q, K, V = workloads.make_inputs(w)
+    O, R, Dl, steps = llla.llla_forward_cg(Q.to(DEV), K.to(DEV), V.to(DEV), w.lam, w.scale, T, 0.0, return_stats=True)
+    torch.cuda.synchronize()
+    O, R, Dl, steps = O.cpu().numpy(), R.cpu().numpy(), Dl.cpu().numpy(), steps.cpu().numpy()
+    rows = np.arange(n)
+    for h in range(2):
+        refO, refR, refD, used = oracle.forward_head_cg(Q[0, h], K[0, h], V[0, h], w.lam, w.scale, T, 0.0)
+        what = "cg T=%d n=%d d=%d head %d" % (T, n, d, h)
+        print(check(O[0:1, h:h + 1], refO[None, None], rows, d, w.tol, what))
+        assert np.array_equal(steps[0, h], used)
+        if T > 0:
+            print(check(R[0:1, h:h + 1], refR[None, None], rows, d, w.tol, what + " rho"))
+            # delta = omega - mu . rho is formed by cancellation in this mode (a row that has converged has
+            # delta << omega): fp32 holds it to a fraction of omega, not of delta
+            Qd, Kd = Q[0, h].double().numpy(), K[0, h].double().numpy()
+            omega = np.array([np.exp(w.scale * (Kd[: i + 1] @ Qd[i]) - (w.scale * (Kd[: i + 1] @ Qd[i])).max()).sum()
+                              for i in rows])
+            assert np.all(np.abs(Dl[0, h] - refD) <= w.tol * np.abs(refD) + 2e-4 * omega), what + " delta"
+
+
+@pytest.mark.parametrize("n,d,T,eps", [(333, 64, 4, 0.0), (333, 64, 12, 0.0), (600, 64, 40, 0.0), (290, 128, 8, 0.0),
+                                       (333, 64, 60, 1e-3)])
+def test_forward_cg_later_steps_reduce_the_residual_like_the_oracle(n, d, T, eps):
+    """What is well defined about a later CG iterate is how far it has brought the residual down.  For sampled rows
+    the residual of the GPU's rho, evaluated here in fp64 from the definitions of mu_i and Sigma_i, must be within a
+    small factor of the residual of the fp64 CG oracle after the same number of steps, or after two thirds of them
+    (down to the floor set by the 16-bit operand splits of the matrix-free product); delta must be
+    omega - mu . rho for that same rho."""
+    w = _small("cg", 1, 2, n, d, "bf16", index=800 + d + n + T)
+    Q, K, V = workloads.make_inputs(w)
+    O, R, Dl, steps = llla.llla_forward_cg(Q.to(DEV), K.to(DEV), V.to(DEV), w.lam, w.scale, T, eps, return_stats=True)
+    torch.cuda.synchronize()
+    R, Dl, steps = R.cpu().numpy().astype(np.float64), Dl.cpu().numpy().astype(np.float64), steps.cpu().numpy()
+    assert np.all(np.isfinite(O.cpu().numpy()))
+    rows = np.unique(np.concatenate([np.arange(0, n, 17), [1, 63, 64, 65, n - 1]]))
+    for h in range(2):
+        Qd, Kd = Q[0, h].double().numpy(), K[0, h].double().numpy()
+        _, refR, _, used = oracle.forward_head_cg(Q[0, h], K[0, h], V[0, h], w.lam, w.scale, T, eps, rows=rows)
+        # rounding delays CG (loss of orthogonality): allow the GPU run to lag the fp64 run by a third of the steps
+        _, lagR, _, _ = oracle.forward_head_cg(Q[0, h], K[0, h], V[0, h], w.lam, w.scale, max(1, (2 * T) // 3), eps, rows=rows)
+        for t, i in enumerate(rows):
+            sc = w.scale * (Kd[: i + 1] @ Qd[i])
+            wg = np.exp(sc - sc.max())
+            Z = Kd[: i + 1] - Qd[i]
+            omega, mu = wg.sum(), (wg[:, None] * Z).sum(0)
+            Sigma = (Z.T * wg) @ Z + w.lam * np.eye(d)
+            nmu = max(np.linalg.norm(mu), 1e-30)
+            res_gpu = np.linalg.norm(mu - Sigma @ R[0, h, i]) / nmu
+            res_ref = max(np.linalg.norm(mu - Sigma @ refR[t]), np.linalg.norm(mu - Sigma @ lagR[t])) / nmu
+            if eps == 0.0:
+                assert res_gpu <= 4.0 * res_ref + 1e-5, (h, i, res_gpu, res_ref)
+                # both run all T steps unless the residual became exactly zero (which fp32 reaches sooner)
+                assert steps[0, h, i] == used[t] or (used[t] < T and steps[0, h, i] <= T) or res_gpu <= 1e-5
+            else:       # frozen once the residual is at or below eps (the GPU judges it in fp32, one step of slack)
+                assert res_gpu * nmu <= 4.0 * eps or steps[0, h, i] == T, (h, i, res_gpu * nmu, steps[0, h, i])
+                assert int(used[t]) <= int(steps[0, h, i]) + 2 and int(steps[0, h, i]) <= (3 * int(used[t])) // 2 + 2, (h, i, steps[0, h, i], used[t])
+            # delta against the definition with the GPU's own rho: fp32 cancellation scales with omega
+            assert abs(Dl[0, h, i] - (omega - mu @ R[0, h, i])) <= 2e-4 * omega + 1e-6, (h, i)
+
+
+def test_forward_cg_zero_steps_is_softmax_attention():
+    w = _small("cg0", 1, 2, 300, 64, "bf16", index=850)
+    Q, K, V = workloads.make_inputs(w)
+    O = llla.llla_forward_cg(Q.to(DEV), K.to(DEV), V.to(DEV), w.lam, w.scale, 0).cpu()
+    ref = torch.nn.functional.scaled_dot_product_attention(Q.double(), K.double(), V.double(), is_causal=True, scale=w.scale)
+    err = (O.double() - ref).norm(dim=-1) / ref.norm(dim=-1)
+    assert float(err.max()) < 5e-3, float(err.max())
+
+
+def test_forward_cg_many_steps_approaches_the_exact_forward():
+    w = _small("cgx", 1, 2, 400, 64, "bf16", index=851)
+    Q, K, V = [t.to(DEV) for t in workloads.make_inputs(w)]
+    exact = llla.llla_forward(Q, K, V, w.lam, w.scale)
+    errs = []
+    for T in (2, 8, 32, 128):
+        O = llla.llla_forward_cg(Q, K, V, w.lam, w.scale, T, 1e-6)
+        errs.append(float(((O - exact)[:, :, 256:].norm(dim=-1) / exact[:, :, 256:].norm(dim=-1)).max()))
+    print("max rel. distance to the exact forward on rows >= 256 for T = 2, 8, 32, 128:", errs)
+    assert errs[-1] < 2e-2 and errs[-1] <= errs[0]
