@@ -31,10 +31,13 @@ class Workload:
     d: int
     dtype: str            # "f32" or "bf16"
     values: str           # "normal", "scaled" (Q,K * 1/sqrt(d)), "l2" (rows of Q,K normalised),
-                          # "regression" (V = K A^T + 0.1 noise)
+                          # "regression" (V = K A^T + 0.1 noise), "piecewise" (the piecewise-linear task:
+                          # keys from one cone per segment, one linear map per segment, Q = K)
     lam: float
     scale: float
     tol: float            # relative-error bound of the parity gate
+    segment: int = 0      # "piecewise" only: segment size S (n / S segments, a power of two of them)
+    noise: float = 0.1    # "piecewise" only: standard deviation of the value noise
 
     def with_shape(self, **kw) -> "Workload":
         return replace(self, **kw)
@@ -53,16 +56,60 @@ C3 = _w("C3_prefill_bf16_n4096_d64", 2, "forward", 4, 16, 4096, 64, "bf16", "nor
 C3B = _w("C3b_prefill_bf16_n8192_d64", 5, "forward", 2, 16, 8192, 64, "bf16", "normal")
 C4 = _w("C4_longctx_bf16_n8192_d128", 3, "forward", 1, 16, 8192, 128, "bf16", "regression")
 C5 = _w("C5_decode_bf16_L32768_d64", 4, "decode", 32, 16, 32768, 64, "bf16", "normal")
-ALL = {w.name.split("_")[0]: w for w in (C1, C2, C3, C3B, C4, C5)}
+# E2: the paper's test-time regression task (Section 4 and Appendix "Experiments": L = 1024, d = 64, S = 256), one
+# sequence per batch entry; E2S is the same task at a size the oracle finishes in seconds.
+E2 = replace(_w("E2_piecewise_bf16_L1024_d64", 6, "forward", 1024, 1, 1024, 64, "bf16", "piecewise"), segment=256)
+E2S = replace(_w("E2s_piecewise_f32_L256_d16", 7, "forward", 8, 1, 256, 16, "f32", "piecewise"), segment=32)
+ALL = {w.name.split("_")[0].upper(): w for w in (C1, C2, C3, C3B, C4, C5, E2, E2S)}
 
 
 def torch_dtype(w: Workload):
     return torch.float32 if w.dtype == "f32" else torch.bfloat16
 
 
+def cone_signs(n_segments: int) -> torch.Tensor:
+    """[n_segments, m] matrix of +-1, m = log2(n_segments): row c holds the m least-significant bits of c
+    (bit j set -> +1), the sign pattern of segment c's cone (Appendix "Piecewise Linear Data Generation")."""
+    m = n_segments.bit_length() - 1
+    if n_segments < 1 or (1 << m) != n_segments:
+        raise ValueError("the number of segments must be a power of two")
+    c = torch.arange(n_segments).unsqueeze(1)
+    return (((c >> torch.arange(m).unsqueeze(0)) & 1) * 2 - 1).to(torch.float32).reshape(n_segments, m)
+
+
+def piecewise_linear(w: Workload):
+    """The piecewise-linear regression task: every (batch, head) entry is one length-n sequence cut into n / S
+    segments; segment c draws Gaussian keys whose first m coordinates carry the cone's signs, and its values are
+    A_c k + noise with a Gaussian matrix A_c of its own.  The query at a position is that position's key.
+    Draw order: Z, A, noise.  Keys are cast to the workload dtype BEFORE the maps are applied, so the linear
+    relation holds for the stored keys.  Returns (Q, K, V, A, segment index of every position)."""
+    S = w.segment
+    if S <= 0 or w.n % S:
+        raise ValueError("segment size must divide the sequence length")
+    nseg = w.n // S
+    signs = cone_signs(nseg)
+    m = signs.shape[1]
+    if m > w.d:
+        raise ValueError("more sign coordinates than dimensions")
+    g = torch.Generator(device="cpu").manual_seed(SEED0 + w.index)
+    Z = torch.randn((w.B, w.H, w.n, w.d), generator=g, dtype=torch.float32)
+    A = torch.randn((w.B, w.H, nseg, w.d, w.d), generator=g, dtype=torch.float32)
+    E = torch.randn((w.B, w.H, w.n, w.d), generator=g, dtype=torch.float32)
+    seg = torch.arange(w.n) // S
+    K = Z.clone()
+    K[..., :m] = Z[..., :m].abs() * signs[seg]
+    dt = torch_dtype(w)
+    K = K.to(dt)
+    Kseg = K.float().reshape(w.B, w.H, nseg, S, w.d)
+    V = torch.matmul(Kseg, A.transpose(-1, -2)).reshape(w.B, w.H, w.n, w.d) + w.noise * E
+    return K.clone(), K, V.to(dt), A, seg
+
+
 def make_inputs(w: Workload):
     """Returns CPU tensors in the workload dtype.
     forward: (Q, K, V) each [B, H, n, d].   decode: (q [B, H, d], Kc, Vc [B, H, n, d])."""
+    if w.values == "piecewise":
+        return piecewise_linear(w)[:3]
     g = torch.Generator(device="cpu").manual_seed(SEED0 + w.index)
     shape = (w.B, w.H, w.n, w.d)
     qshape = shape if w.kind == "forward" else (w.B, w.H, w.d)
