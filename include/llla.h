@@ -139,6 +139,30 @@ llla_status llla_forward_cg(const void *Q, const void *K, const void *V, void *O
                             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * llla_backward -- Appendix D (backward derivation): the gradients of L = sum_i dO_i . o_i, o = the causal
+ * llla_forward_ex output, with respect to Q, K, V and the ridge of every row.  As in Appendix D the work per row is
+ * one more linear solve with the row's matrix (the paper's u_i) plus matrix products of the size of the forward's;
+ * the value gradient is S^T dO with S the output weights of Eq. (lla).  The forward here applies the ridge to
+ * max-normalised weights, so the output depends on the row maximum m_i; that dependence is differentiated too
+ * (it equals lambda_i dL/dlambda_i and flows into the logit of the key that attains the maximum; with several keys
+ * at the maximum, the first).  Nothing is kept from the forward call: the row statistics are recomputed.
+ *   Q, K, V, dO : device, [B, H, n, d] in dtype `in`, strides sq / sk / sv / sdo
+ *   dQ, dK, dV  : device float [B, H, n, d] contiguous, 16-byte aligned, fully overwritten
+ *   dlambda     : device float [B, H, n] contiguous or NULL; dL/dlambda_i of every row (sum them for a scalar ridge)
+ *   lambda, lambda_rows, scale : as in llla_forward_ex
+ * Causal only; every supported d and both dtypes; arithmetic in fp32 on the vector ALU.
+ * Workspace: llla_backward_workspace_bytes ((2d + 8) floats per row).
+ */
+size_t llla_backward_workspace_bytes(int B, int H, int n, int d, llla_dtype in);
+
+llla_status llla_backward(const void *Q, const void *K, const void *V, const void *dO,
+                          llla_strides sq, llla_strides sk, llla_strides sv, llla_strides sdo,
+                          float *dQ, float *dK, float *dV, float *dlambda,
+                          int B, int H, int n, int d, llla_dtype in,
+                          float lambda, const float *lambda_rows, float scale,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * llla_decode -- the inference step the paper mentions (Sections 1 and 2.3: LLA keeps a Theta(n d)
  * KV cache): one new query per (batch, head) against the cached keys and values, the new token's
  * own (k, v) already appended, i.e. the last row of a causal forward over seqlens[b] positions.

@@ -54,6 +54,11 @@ def lib():
     L.llla_forward_cg.argtypes = [vp, vp, vp, vp, _Strides, _Strides, _Strides, _Strides, i32, i32, i32, i32, i32, i32,
                                   f32, f32, i32, f32, vp, vp, vp, vp, sz, vp]
     L.llla_forward_cg.restype = i32
+    L.llla_backward_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
+    L.llla_backward_workspace_bytes.restype = sz
+    L.llla_backward.argtypes = [vp, vp, vp, vp, _Strides, _Strides, _Strides, _Strides, vp, vp, vp, vp, i32, i32, i32, i32,
+                                i32, f32, vp, f32, vp, sz, vp]
+    L.llla_backward.restype = i32
     dec = [vp, vp, vp, vp, _Strides, _Strides, vp, i32, i32, i32, i32, i32, i32, f32, f32]
     L.llla_decode.argtypes = dec + [vp, sz, vp]
     L.llla_decode.restype = i32
@@ -197,6 +202,41 @@ def llla_forward_cg(Q, K, V, lam: float, scale: float, max_steps: int, eps: floa
     if st != 0:
         raise LlaError(st, "llla_forward_cg")
     return (O, rho, delta, steps) if return_stats else O
+
+
+def backward_workspace_bytes(B, H, n, d, dtype) -> int:
+    return int(lib().llla_backward_workspace_bytes(B, H, n, d, _DTYPES[dtype]))
+
+
+def llla_backward(Q, K, V, dO, lam, scale: float, workspace=None, stream=None, return_dlambda: bool = False):
+    """Gradients of sum(dO * llla_forward(Q, K, V)) (causal): returns (dQ, dK, dV) as float32 [B, H, n, d], plus
+    dL/dlambda per row [B, H, n] with ``return_dlambda``.  ``lam`` as in ``llla_forward``; dO has the dtype of Q."""
+    if not (Q.is_cuda and K.is_cuda and V.is_cuda and dO.is_cuda):
+        raise ValueError("llla_backward needs device tensors; this library has no CPU path")
+    if not (Q.dtype == K.dtype == V.dtype == dO.dtype) or Q.dtype not in _DTYPES:
+        raise ValueError("Q, K, V, dO must share dtype float32 or bfloat16")
+    B, H, n, d = Q.shape
+    if K.shape != Q.shape or V.shape != Q.shape or dO.shape != Q.shape:
+        raise ValueError("Q, K, V, dO must have the same [B, H, n, d] shape")
+    lam_rows = None
+    if torch.is_tensor(lam):
+        lam_rows = lam
+        if not (lam_rows.is_cuda and lam_rows.dtype == torch.float32 and tuple(lam_rows.shape) == (B, H, n)
+                and lam_rows.is_contiguous()):
+            raise ValueError("a per-row ridge must be a contiguous device float32 tensor [B, H, n]")
+    dQ, dK, dV = (torch.empty((B, H, n, d), dtype=torch.float32, device=Q.device) for _ in range(3))
+    dlam = torch.empty((B, H, n), dtype=torch.float32, device=Q.device) if return_dlambda else None
+    need = backward_workspace_bytes(B, H, n, d, Q.dtype)
+    ws = _workspace(need, Q.device, workspace)
+    st = lib().llla_backward(Q.data_ptr(), K.data_ptr(), V.data_ptr(), dO.data_ptr(),
+                             _strides4(Q), _strides4(K), _strides4(V), _strides4(dO),
+                             dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), None if dlam is None else dlam.data_ptr(),
+                             B, H, n, d, _DTYPES[Q.dtype], 0.0 if lam_rows is not None else float(lam),
+                             None if lam_rows is None else lam_rows.data_ptr(), float(scale),
+                             ws.data_ptr(), ws.numel() * ws.element_size(), _stream_ptr(stream))
+    if st != 0:
+        raise LlaError(st, "llla_backward")
+    return (dQ, dK, dV, dlam) if return_dlambda else (dQ, dK, dV)
 
 
 def llla_decode(q, Kc, Vc, lam: float, scale: float, seqlens=None, out_dtype=None, path: str = "auto",

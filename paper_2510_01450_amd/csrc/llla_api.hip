@@ -223,6 +223,43 @@ llla_status llla_forward_cg(const void *Q, const void *K, const void *V, void *O
     return e == hipSuccess ? LLLA_OK : LLLA_ERR_LAUNCH;
 }
 
+size_t llla_backward_workspace_bytes(int B, int H, int n, int d, llla_dtype in)
+{
+    if (B <= 0 || H <= 0 || n <= 0 || !dim_supported(d) || !dtype_ok(in)) return 0;
+    return llla::valu_backward_workspace_bytes(B, H, n, d);
+}
+
+llla_status llla_backward(const void *Q, const void *K, const void *V, const void *dO, llla_strides sq, llla_strides sk,
+                          llla_strides sv, llla_strides sdo, float *dQ, float *dK, float *dV, float *dlambda, int B,
+                          int H, int n, int d, llla_dtype in, float lambda, const float *lambda_rows, float scale,
+                          void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!Q || !K || !V || !dO || !dQ || !dK || !dV) return LLLA_ERR_NULL;
+    llla_status st = check_common(B, H, n, d, in, LLLA_F32, lambda_rows ? 1.f : lambda, scale);
+    if (st != LLLA_OK) return st;
+    if (!strides_cover(sq, B, H, n, d) || !strides_cover(sk, B, H, n, d) || !strides_cover(sv, B, H, n, d) ||
+        !strides_cover(sdo, B, H, n, d))
+        return LLLA_ERR_SHAPE;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(dO) || !aligned16(dQ) || !aligned16(dK) ||
+        !aligned16(dV) || !strides_aligned(sq, in) || !strides_aligned(sk, in) || !strides_aligned(sv, in) ||
+        !strides_aligned(sdo, in) || (reinterpret_cast<uintptr_t>(dlambda) & 3u) ||
+        (reinterpret_cast<uintptr_t>(lambda_rows) & 3u))
+        return LLLA_ERR_ALIGN;
+    st = check_workspace(llla::valu_backward_workspace_bytes(B, H, n, d), workspace, workspace_bytes);
+    if (st != LLLA_OK) return st;
+
+    llla::BackwardProblem p{};
+    p.Q = Q; p.K = K; p.V = V; p.dO = dO;
+    p.sq = sq; p.sk = sk; p.sv = sv; p.sdo = sdo;
+    p.dQ = dQ; p.dK = dK; p.dV = dV; p.dlambda = dlambda;
+    p.B = B; p.H = H; p.n = n; p.d = d;
+    p.in = in;
+    p.lambda = lambda; p.lambda_rows = lambda_rows; p.scale = scale;
+    p.ws = workspace; p.ws_bytes = workspace_bytes;
+    p.stream = static_cast<hipStream_t>(stream);
+    return llla::valu_backward(p) == hipSuccess ? LLLA_OK : LLLA_ERR_LAUNCH;
+}
+
 size_t llla_decode_workspace_bytes(int B, int H, int L_max, int d, llla_dtype in)
 {
     if (B <= 0 || H <= 0 || L_max <= 0 || !dim_supported(d) || !dtype_ok(in)) return 0;

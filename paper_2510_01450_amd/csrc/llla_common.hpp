@@ -26,6 +26,21 @@ struct Problem {
     hipStream_t stream;
 };
 
+// One backward problem (causal), as validated by the C ABI layer.  Gradients are fp32, contiguous.
+struct BackwardProblem {
+    const void *Q, *K, *V, *dO;  // [B,H,n,d] in dtype `in`
+    llla_strides sq, sk, sv, sdo;
+    float *dQ, *dK, *dV;         // [B,H,n,d]
+    float *dlambda;              // [B,H,n] or nullptr
+    int B, H, n, d;
+    llla_dtype in;
+    float lambda, scale;
+    const float *lambda_rows;    // [B,H,n] or nullptr
+    void *ws;
+    size_t ws_bytes;
+    hipStream_t stream;
+};
+
 // Launchers return hipSuccess or the launch error.  Each lives in its own translation unit.
 hipError_t valu_forward(const Problem &p);
 // causal forward restricted to query rows [0, nrows); nrows must be a multiple of 16
@@ -34,6 +49,9 @@ hipError_t valu_forward_rows(const Problem &p, int nrows);
 // units) come from device memory
 hipError_t valu_forward_given(const Problem &p, int nrows, const float *M, int mpitch, const float *Y, int ypitch);
 hipError_t valu_decode(const Problem &p);
+
+size_t valu_backward_workspace_bytes(int B, int H, int n, int d);
+hipError_t valu_backward(const BackwardProblem &p);
 
 // MFMA (matrix-core) paths; *_supported() says whether one exists for the shape and dtype.
 bool mfma_forward_supported(int d, llla_dtype in, bool causal);

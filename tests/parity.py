@@ -59,3 +59,33 @@ def check(got, ref, rows, d, tol, what=""):
     assert np.all(err <= bound), "%s: row %d error %.3e exceeds %.1e (%s)" % (
         what, summary["worst_row"], err[worst], bound[worst[-1]], summary)
     return summary
+
+
+def check_grad(got, ref, d, tol, what="", floor=0.0):
+    """Gate for a gradient tensor.  got, ref: [B, H, n, c] (or [B, H, n] for per-row scalars).
+    Per (batch, head): Frobenius-relative error <= tol.  Per row i: ||got_i - ref_i|| <= f * tol * (||ref_i|| + rms),
+    rms = root-mean-square row norm of that head's reference (rows whose exact gradient is zero or tiny -- the first
+    row's dQ, keys no sampled row sees -- have no meaningful relative error of their own), f = 10 for rows i < 4d and 1
+    afterwards, as in the forward gate.  `floor`: the size of the terms a gradient is the sum of (the caller passes
+    ||dO|| * rms(V) of a head); a head whose exact gradient is smaller than that -- n = 1, where dQ and dK vanish
+    identically -- is measured against the floor instead of its own norm.  Returns a summary dict."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    assert np.all(np.isfinite(got)), what + ": non-finite gradient"
+    if got.ndim == 3:
+        got, ref = got[..., None], ref[..., None]
+    B, H, n = got.shape[:3]
+    rown = np.linalg.norm(ref, axis=-1)                                   # [B, H, n]
+    rms = np.maximum(np.sqrt(np.mean(rown ** 2, axis=-1, keepdims=True)), floor / np.sqrt(n))
+    err = np.linalg.norm(got - ref, axis=-1)
+    factor = np.where(np.arange(n) < 4 * d, 10.0, 1.0)
+    ratio = err / (factor * tol * (rown + rms) + 1e-300)
+    fro = np.array([[np.linalg.norm(got[b, h] - ref[b, h]) / max(np.linalg.norm(ref[b, h]), floor, 1e-300)
+                     for h in range(H)] for b in range(B)])
+    worst = np.unravel_index(np.argmax(ratio), ratio.shape)
+    summary = {"frobenius_max": float(fro.max()), "worst_row": int(worst[-1]),
+               "worst_row_ratio_to_bound": float(ratio.max())}
+    assert fro.max() <= tol, "%s: Frobenius error %.3e > %.1e (%s)" % (what, fro.max(), tol, summary)
+    assert ratio.max() <= 1.0, "%s: row %d off by %.2f x its bound (%s)" % (what, worst[-1], ratio.max(), summary)
+    return summary

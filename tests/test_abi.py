@@ -116,3 +116,32 @@ def test_product_has_no_cpu_fallback():
     x = torch.zeros(1, 1, 8, 16)
     with pytest.raises(ValueError):
         llla.llla_forward(x, x, x, 1e-2, 0.25)
+
+
+def _bwd(Q=FAKE, K=FAKE, V=FAKE, dO=FAKE, dQ=FAKE, dK=FAKE, dV=FAKE, dlam=None, s=None, B=1, H=1, n=64, d=64, din=0,
+         lam=1e-2, lam_rows=None, scale=0.125, ws=0, wsb=0):
+    s = _Strides(H * n * d, n * d, d) if s is None else s
+    return llla.lib().llla_backward(Q, K, V, dO, s, s, s, s, dQ, dK, dV, dlam, B, H, n, d, din, lam, lam_rows, scale,
+                                    ws, wsb, 0)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(dO=0), 1), (dict(dK=0), 1),
+    (dict(n=0), 2), (dict(s=_Strides(64 * 64, 64 * 64, 32)), 2),
+    (dict(din=5), 3),
+    (dict(lam=0.0), 4), (dict(scale=float("nan")), 4),
+    (dict(dQ=FAKE + 8), 5), (dict(dlam=FAKE + 2), 5), (dict(lam_rows=FAKE + 1), 5),
+    (dict(), 6), (dict(ws=FAKE + 16, wsb=1 << 30), 6), (dict(ws=FAKE, wsb=16), 6),
+    (dict(d=24), 7),
+])
+def test_backward_rejects_bad_arguments(kw, code):
+    """Every call fails a host-side check before anything is launched (the last valid-looking one for lack of a
+    workspace)."""
+    assert _bwd(**kw) == code
+
+
+def test_backward_workspace_size():
+    assert llla.backward_workspace_bytes(2, 3, 100, 64, __import__("torch").bfloat16) >= 2 * 3 * 100 * (2 * 64 + 8) * 4
+    assert llla.lib().llla_backward_workspace_bytes(1, 1, 0, 64, 0) == 0
+    # a bad scalar ridge is ignored when a ridge per row is given: the call gets as far as the workspace check
+    assert _bwd(lam=0.0, lam_rows=FAKE) == 6

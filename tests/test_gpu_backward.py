@@ -1,0 +1,157 @@
+"""Parity of llla_backward (through the C ABI) with the backward oracle (reverse-mode derivative of an fp64 forward
+typed from the objective).  Gate: parity.check_grad with tol = 1e-3 for fp32 inputs and 2e-2 for bf16 inputs.
+The gradient applies the inverse of a row's matrix to a right-hand side that is itself a cancelling sum, and then
+forms the differences gamma_ij - b_ij: one more factor of the system's condition number (1e2-1e4 on these inputs)
+than the forward, hence 1e-3 where the forward's fp32 gate is 1e-4.  All tests need a GPU."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2510_01450_amd as llla
+import workloads
+from oracle import backward as ob
+from parity import check_grad
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+NAMES = ("dQ", "dK", "dV", "dlambda")
+
+
+def _case(B, H, n, d, dtype, values=None, index=500, lam=1e-2):
+    base = workloads.C2 if dtype == "f32" else workloads.C3
+    values = ("l2" if dtype == "f32" else "normal") if values is None else values
+    return base.with_shape(name="bwd", B=B, H=H, n=n, d=d, dtype=dtype, values=values, index=index, lam=lam,
+                           scale=1 / math.sqrt(d), tol=1e-3 if dtype == "f32" else 2e-2)
+
+
+def _upstream(w, seed, rows=None):
+    g = torch.Generator(device="cpu").manual_seed(workloads.SEED0 + 9000 + seed)
+    G = torch.randn((w.B, w.H, w.n, w.d), generator=g, dtype=torch.float32)
+    if rows is not None:
+        keep = torch.zeros(w.n, dtype=torch.bool)
+        keep[torch.as_tensor(rows)] = True
+        G = G * keep[None, None, :, None]
+    return G.to(workloads.torch_dtype(w))
+
+
+def _backward(w, Q, K, V, G, lam):
+    lam_dev = lam.to(DEV) if torch.is_tensor(lam) else lam
+    out = llla.llla_backward(Q.to(DEV), K.to(DEV), V.to(DEV), G.to(DEV), lam_dev, w.scale, return_dlambda=True)
+    torch.cuda.synchronize()
+    return [t.cpu().numpy() for t in out]
+
+
+def _floor(V, G, lam):
+    """Size of the products dO.v every gradient term is proportional to (per head), for the gate's floor."""
+    heads = G.shape[0] * G.shape[1]
+    f = float(G.double().norm()) / math.sqrt(heads) * float(V.double().pow(2).mean().sqrt())
+    lam_typ = float(lam.double().mean()) if torch.is_tensor(lam) else float(lam)
+    return {"dQ": f, "dK": f, "dV": f, "dlambda": f / lam_typ}
+
+
+def _compare(w, got, ref, what, floor):
+    for name, g, r in zip(NAMES, got, ref):
+        print(name, check_grad(g, r, w.d, w.tol, "%s %s" % (what, name), floor=floor[name]))
+
+
+@pytest.mark.parametrize("n,d,dtype", [
+    (1, 16, "f32"), (2, 64, "f32"), (77, 16, "f32"), (130, 32, "f32"), (203, 64, "f32"), (150, 128, "f32"),
+    (77, 16, "bf16"), (131, 32, "bf16"), (333, 64, "bf16"), (257, 128, "bf16"),
+])
+def test_ragged_shapes_all_gradients(n, d, dtype):
+    w = _case(2, 3, n, d, dtype, index=500 + n + d)
+    Q, K, V = workloads.make_inputs(w)
+    G = _upstream(w, n + d)
+    ref = ob.backward(Q, K, V, G, w.lam, w.scale)
+    _compare(w, _backward(w, Q, K, V, G, w.lam), ref, "n=%d d=%d %s" % (n, d, dtype), _floor(V, G, w.lam))
+
+
+@pytest.mark.parametrize("n,d,dtype", [(203, 64, "f32"), (333, 64, "bf16"), (140, 128, "bf16"), (90, 32, "f32")])
+def test_ridge_per_row(n, d, dtype):
+    """lambda_i log-normal around 0.03 (Appendix C: the ridge is learnable per position); dL/dlambda_i is the
+    gradient such a parametrisation needs."""
+    w = _case(1, 2, n, d, dtype, index=600 + n + d)
+    Q, K, V = workloads.make_inputs(w)
+    G = _upstream(w, 1 + n + d)
+    g = torch.Generator(device="cpu").manual_seed(workloads.SEED0 + 9500 + n)
+    lam = (0.03 * torch.exp(0.7 * torch.randn((w.B, w.H, n), generator=g))).float()
+    ref = ob.backward(Q, K, V, G, lam.double().numpy(), w.scale)
+    _compare(w, _backward(w, Q, K, V, G, lam), ref, "lambda rows n=%d d=%d %s" % (n, d, dtype), _floor(V, G, lam))
+
+
+@pytest.mark.parametrize("values,lam", [("normal", 1e-2), ("scaled", 1e-2), ("l2", 0.5), ("regression", 0.1)])
+def test_other_value_distributions_and_ridges(values, lam):
+    w = _case(1, 2, 180, 32, "f32", values=values, index=700, lam=lam)
+    Q, K, V = workloads.make_inputs(w)
+    G = _upstream(w, 7)
+    ref = ob.backward(Q, K, V, G, w.lam, w.scale)
+    _compare(w, _backward(w, Q, K, V, G, w.lam), ref, values, _floor(V, G, w.lam))
+
+
+def test_piecewise_linear_task_gradients():
+    """The regression task's inputs (queries equal to keys: one dominant weight per row)."""
+    w = workloads.E2S.with_shape(B=2, tol=1e-3)
+    Q, K, V = workloads.make_inputs(w)
+    G = _upstream(w, 8)
+    ref = ob.backward(Q, K, V, G, w.lam, w.scale)
+    _compare(w, _backward(w, Q, K, V, G, w.lam), ref, w.name, _floor(V, G, w.lam))
+
+
+def test_strided_inputs():
+    """[B, n, H, d] memory viewed as [B, H, n, d] for Q, K, V and dO."""
+    w = _case(2, 4, 160, 64, "bf16", index=781)
+    Q, K, V = workloads.make_inputs(w)
+    G = _upstream(w, 9)
+    ref = ob.backward(Q, K, V, G, w.lam, w.scale)
+    dev = [t.to(DEV).permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (Q, K, V, G)]
+    assert not dev[0].is_contiguous()
+    got = llla.llla_backward(*dev, w.lam, w.scale, return_dlambda=True)
+    torch.cuda.synchronize()
+    _compare(w, [t.cpu().numpy() for t in got], ref, "strided", _floor(V, G, w.lam))
+
+
+def test_deterministic_and_inputs_untouched():
+    w = _case(1, 2, 300, 64, "bf16", index=790)
+    Q, K, V = workloads.make_inputs(w)
+    G = _upstream(w, 10)
+    dev = [t.to(DEV) for t in (Q, K, V, G)]
+    a = llla.llla_backward(*dev, w.lam, w.scale, return_dlambda=True)
+    b = llla.llla_backward(*dev, w.lam, w.scale, return_dlambda=True)
+    torch.cuda.synchronize()
+    assert all(torch.equal(x, y) for x, y in zip(a, b))
+    assert all(torch.equal(x.cpu(), y) for x, y in zip(dev, (Q, K, V, G)))
+
+
+def test_gradient_of_the_scalar_ridge_is_the_sum_over_rows_and_matches_a_difference_quotient_of_the_library():
+    """Consistency between the library's own forward and backward: d/dlambda sum(dO * O) by central differences of
+    llla_forward equals the sum of dlambda over rows (fp32 inputs, well-conditioned rows only: the first 4d rows
+    carry no upstream gradient)."""
+    w = _case(1, 1, 400, 16, "f32", index=795, lam=0.2)
+    Q, K, V = workloads.make_inputs(w)
+    G = _upstream(w, 11, rows=range(64, 400))
+    dev = [t.to(DEV) for t in (Q, K, V, G)]
+    dlam = llla.llla_backward(*dev, w.lam, w.scale, return_dlambda=True)[3]
+    h = 0.02
+    up = (llla.llla_forward(*dev[:3], w.lam + h, w.scale).double() * dev[3].double()).sum()
+    dn = (llla.llla_forward(*dev[:3], w.lam - h, w.scale).double() * dev[3].double()).sum()
+    fd = float((up - dn) / (2 * h))
+    assert abs(float(dlam.double().sum()) - fd) <= 2e-2 * abs(fd) + 1e-3, (float(dlam.sum()), fd)
+
+
+def test_c3_shape_sampled_rows():
+    """One batch entry of the prefill configuration (16 heads x 4096 x 64, bf16).  The upstream gradient is non-zero
+    on sampled rows only, so that the oracle can produce every gradient (dK and dV of a key sum over all later
+    rows) from those rows one by one; the kernels do the same work per row whatever the values of dO."""
+    w = workloads.C3.with_shape(B=1)
+    Q, K, V = workloads.make_inputs(w)
+    rows = workloads.sample_rows(w, n_random=40)[::3]
+    G = _upstream(w, 12, rows=rows)
+    got = _backward(w, Q, K, V, G, w.lam)
+    floor = _floor(V[:, :1], G[:, :1], w.lam)
+    for h in (0, 9):
+        ref = ob.backward_head(Q[0, h], K[0, h], V[0, h], G[0, h], w.lam, w.scale, rows=rows)
+        for name, g, r in zip(NAMES, got, ref):
+            print(name, check_grad(g[0, h][None, None], r[None, None], w.d, w.tol, "C3 head %d %s" % (h, name),
+                                   floor=floor[name]))
