@@ -40,6 +40,13 @@ def forward_flops(B, H, n, d):
     return B * H * (pairs * (d * d + 11 * d) + n * (d ** 3 / 3.0 + 4 * d * d))
 
 
+def backward_flops(B, H, n, d):
+    """Algorithmic flops of the backward: the forward's moments again, gamma, r, a, b, dV, dK (three terms), dQ per
+    causal pair; the elimination with two right-hand sides per row."""
+    pairs = n * (n + 1) // 2
+    return B * H * (pairs * (d * d + 22 * d) + n * (d ** 3 / 3.0 + 6 * d * d))
+
+
 def executed_mfma_flops(B, H, n, d):
     """What a full-square d x d second moment plus the small products issues per causal pair."""
     pairs = n * (n + 1) // 2
@@ -57,6 +64,8 @@ def main():
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--cg", type=int, default=None, metavar="T",
                     help="forward workloads: time llla_forward_cg, the paper's approximate mode with T conjugate-gradient steps")
+    ap.add_argument("--backward", action="store_true",
+                    help="forward workloads: time llla_backward (gradients w.r.t. Q, K, V and the ridge of every row)")
     ap.add_argument("--ex", action="store_true",
                     help="forward workloads: time llla_forward_ex with a ridge per row and the statistics rho, delta")
     args = ap.parse_args()
@@ -103,6 +112,14 @@ def main():
     ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
 
     ex = args.ex and not decode
+    bwd = args.backward and not decode
+    if bwd:
+        g = torch.Generator(device="cpu").manual_seed(workloads.SEED0 + 9000 + w.index)
+        dO_cpu = torch.randn((w.B, w.H, w.n, w.d), generator=g, dtype=torch.float32).to(dt)
+        dO = dO_cpu.to(dev)
+        ws = torch.empty(max(llla.backward_workspace_bytes(w.B, w.H, w.n, w.d, dt), 256), dtype=torch.uint8, device=dev)
+        grads = tuple(torch.empty((w.B, w.H, w.n, w.d), dtype=torch.float32, device=dev) for _ in range(3)) + (
+            torch.empty((w.B, w.H, w.n), dtype=torch.float32, device=dev),)
     # the per-row ridge is the workload's lambda in every row, so that the outputs stay those of the plain call
     lam_rows = torch.full((w.B, w.H, w.n), w.lam, dtype=torch.float32, device=dev) if ex else None
     stats = {}
@@ -111,6 +128,8 @@ def main():
         a, b, c = dev_in[i % n_rot]
         if decode:
             llla.llla_decode(a, b, c, w.lam, w.scale, path=args.path, workspace=ws, out=out)
+        elif bwd:
+            llla.llla_backward(a, b, c, dO, w.lam, w.scale, workspace=ws, out=grads)
         elif args.cg is not None:
             llla.llla_forward_cg(a, b, c, w.lam, w.scale, args.cg, 0.0, workspace=ws, out=out)
         elif ex:
@@ -157,7 +176,14 @@ def main():
         tokens = w.B * w.n
         pairs = w.n * (w.n + 1) // 2
         d = w.d
-        if dom == "cg_steps":
+        if bwd:
+            # rows kernel: half of the second moment, logits, mu~, gamma, r, a, b, dQ; keys kernel: logits, a, b,
+            # gamma, dV, the three terms of dK; per row the elimination with two right-hand sides
+            per_pair = {"backward_rows": d * d + 14 * d, "backward_keys": 16 * d}.get(dom, d * d + 22 * d)
+            per_row = (d ** 3 / 3.0 + 6 * d * d) if dom != "backward_keys" else 0.0
+            flops = w.B * w.H * (pairs * float(per_pair) + w.n * per_row)
+            bound, peak = "alu", PEAK_FP32_VALU
+        elif dom == "cg_steps":
             # per step and causal pair: logits (2d), k.p (2d), accumulate (2d); per row the vector updates (~12d)
             flops = args.cg * w.B * w.H * (pairs * 6.0 * d + w.n * 12.0 * d)
             bound, peak = "mfma", PEAK_MFMA_16BIT
@@ -172,7 +198,8 @@ def main():
         roof = {"bound": bound, "achieved": flops / (dom_ms * 1e-3) / 1e12, "peak": peak / 1e12,
                 "unit": "TFLOP/s", "traffic": None, "kernel": dom or "llla_forward (whole call)",
                 "algorithmic_flops_per_launch": flops, "kernel_ms": dom_ms,
-                "whole_call_algorithmic_tflops": forward_flops(w.B, w.H, w.n, d) / (float(np.mean(per)) * 1e-3) / 1e12}
+                "whole_call_algorithmic_tflops": (backward_flops(w.B, w.H, w.n, d) if bwd else
+                                                  forward_flops(w.B, w.H, w.n, d)) / (float(np.mean(per)) * 1e-3) / 1e12}
         if dom == "moments":
             # what the kernel really issues to the matrix cores (16x16x32 MFMA = 16384 flop, 16x16x4 fp32 = 2048):
             # per 64-key block and workgroup NW waves x (2 halves x QW x NTILE + 2) f16 MFMAs + 4 x NF bf16 ones
@@ -202,15 +229,17 @@ def main():
         roof["frac_of_sustained_probe"] = roof["achieved"] / roof["sustained_mfma_probe_tflops"]
 
     result = {
-        "metric": "LLA causal forward tokens/s" if not decode else "LLA decode generated tokens/s",
+        "metric": "LLA decode generated tokens/s" if decode else
+        ("LLA causal backward tokens/s" if bwd else "LLA causal forward tokens/s"),
         "value": tokens / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms, "ms_per_step_device_median": float(np.median(per)),
         "ms_per_step_device_min": float(per.min()), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32" if w.dtype == "f32" else "bf16 in, f16/f32 MFMA, f32 accumulate",
+        "vs_baseline": None, "dtype": "f32" if w.dtype == "f32" else
+        ("bf16 in, f32 vector arithmetic" if bwd else "bf16 in, f16/f32 MFMA, f32 accumulate"),
         "data": "synthetic (seeded, %s)" % w.values,
         "config": {"workload": w.name, "B": w.B, "H": w.H, "n": w.n, "d": w.d, "lambda": w.lam,
                    "scale": w.scale, "path": args.path, "input_setup_s": round(gen_s, 2),
-                   "entry": ("llla_forward_cg (approximate: %d conjugate-gradient steps)" % args.cg) if args.cg is not None
+                   "entry": "llla_backward" if bwd else ("llla_forward_cg (approximate: %d conjugate-gradient steps)" % args.cg) if args.cg is not None
                    and not decode else "llla_forward_ex (ridge per row, rho and delta written)" if ex else
                    ("llla_decode" if decode else "llla_forward")},
         "roofline": roof,
@@ -242,6 +271,35 @@ def main():
             result["cpu_baseline"] = {"value": w.B / full, "unit": "tokens/s", "cores": oracle.threads(),
                                       "kind": "oracle", "sample": "%d of %d (batch, head) pairs, %.1f s; scaled by count"
                                       % (nh, w.B * w.H, cpu_s)}
+        elif bwd:
+            # the upstream gradient is kept on sampled rows only, so that the oracle can produce every gradient of a
+            # head from those rows one by one; the kernels do the same work whatever dO holds
+            from oracle import backward as ob
+            from parity import check_grad
+            Q, K, V = cpu_in
+            rows = workloads.sample_rows(w, n_random=24)[::4] if w.n > 512 else list(range(w.n))
+            keep = torch.zeros(w.n, dtype=torch.bool)
+            keep[torch.as_tensor(rows)] = True
+            dO_s = dO_cpu * keep[None, None, :, None]
+            got = llla.llla_backward(dev_in[0][0], dev_in[0][1], dev_in[0][2], dO_s.to(dev), w.lam, w.scale, workspace=ws,
+                                     return_dlambda=True)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            ref = ob.backward_head(Q[0, 0], K[0, 0], V[0, 0], dO_s[0, 0], w.lam, w.scale, rows=rows)
+            cpu_s = time.perf_counter() - t1
+            tol = 1e-3 if w.dtype == "f32" else 2e-2
+            floor = float(dO_s[0, 0].double().norm()) * float(V[0, 0].double().pow(2).mean().sqrt())
+            summ = {}
+            for name, gq, rf in zip(("dQ", "dK", "dV", "dlambda"), got, ref):
+                summ[name] = check_grad(gq[0, 0].cpu().numpy()[None, None], rf[None, None], w.d, tol, "bench " + name,
+                                        floor=floor / (w.lam if name == "dlambda" else 1.0))
+            work_all = w.B * w.H * (w.n * (w.n + 1) / 2.0)
+            work_s = float(np.sum(np.asarray(rows) + 1.0))
+            full = cpu_s * work_all / work_s
+            result["cpu_baseline"] = {"value": w.B * w.n / full, "unit": "tokens/s", "cores": torch.get_num_threads(),
+                                      "kind": "oracle",
+                                      "sample": "%d sampled rows of one head in %.1f s; scaled by causal pairs (x%.0f)"
+                                      % (len(rows), cpu_s, work_all / work_s)}
         else:
             step(0)
             torch.cuda.synchronize()

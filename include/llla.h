@@ -150,8 +150,11 @@ llla_status llla_forward_cg(const void *Q, const void *K, const void *V, void *O
  *   dQ, dK, dV  : device float [B, H, n, d] contiguous, 16-byte aligned, fully overwritten
  *   dlambda     : device float [B, H, n] contiguous or NULL; dL/dlambda_i of every row (sum them for a scalar ridge)
  *   lambda, lambda_rows, scale : as in llla_forward_ex
- * Causal only; every supported d and both dtypes; arithmetic in fp32 on the vector ALU.
- * Workspace: llla_backward_workspace_bytes ((2d + 8) floats per row).
+ *   path        : LLLA_PATH_AUTO / VALU / MFMA as in llla_forward_path.  The vector path serves every supported d and
+ *                 both dtypes in fp32 arithmetic.  The matrix-core path (bf16, d = 64 or 128) recomputes the row
+ *                 moments and does both solves of a row with the forward's matrix-core kernel; the O(d)-per-pair
+ *                 sweeps around it run in fp32 on the vector ALU.
+ * Causal only.  Workspace: llla_backward_workspace_bytes (Theta(B H n d); enough for either path).
  */
 size_t llla_backward_workspace_bytes(int B, int H, int n, int d, llla_dtype in);
 
@@ -159,7 +162,7 @@ llla_status llla_backward(const void *Q, const void *K, const void *V, const voi
                           llla_strides sq, llla_strides sk, llla_strides sv, llla_strides sdo,
                           float *dQ, float *dK, float *dV, float *dlambda,
                           int B, int H, int n, int d, llla_dtype in,
-                          float lambda, const float *lambda_rows, float scale,
+                          float lambda, const float *lambda_rows, float scale, llla_path path,
                           void *workspace, size_t workspace_bytes, void *stream);
 
 /*

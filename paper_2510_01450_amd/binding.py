@@ -57,7 +57,7 @@ def lib():
     L.llla_backward_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
     L.llla_backward_workspace_bytes.restype = sz
     L.llla_backward.argtypes = [vp, vp, vp, vp, _Strides, _Strides, _Strides, _Strides, vp, vp, vp, vp, i32, i32, i32, i32,
-                                i32, f32, vp, f32, vp, sz, vp]
+                                i32, f32, vp, f32, i32, vp, sz, vp]
     L.llla_backward.restype = i32
     dec = [vp, vp, vp, vp, _Strides, _Strides, vp, i32, i32, i32, i32, i32, i32, f32, f32]
     L.llla_decode.argtypes = dec + [vp, sz, vp]
@@ -208,9 +208,11 @@ def backward_workspace_bytes(B, H, n, d, dtype) -> int:
     return int(lib().llla_backward_workspace_bytes(B, H, n, d, _DTYPES[dtype]))
 
 
-def llla_backward(Q, K, V, dO, lam, scale: float, workspace=None, stream=None, return_dlambda: bool = False):
+def llla_backward(Q, K, V, dO, lam, scale: float, path: str = "auto", workspace=None, stream=None,
+                  return_dlambda: bool = False, out=None):
     """Gradients of sum(dO * llla_forward(Q, K, V)) (causal): returns (dQ, dK, dV) as float32 [B, H, n, d], plus
-    dL/dlambda per row [B, H, n] with ``return_dlambda``.  ``lam`` as in ``llla_forward``; dO has the dtype of Q."""
+    dL/dlambda per row [B, H, n] with ``return_dlambda``.  ``lam`` as in ``llla_forward``; dO has the dtype of Q.
+    ``out``: optional (dQ, dK, dV) or (dQ, dK, dV, dlambda) tensors to write into."""
     if not (Q.is_cuda and K.is_cuda and V.is_cuda and dO.is_cuda):
         raise ValueError("llla_backward needs device tensors; this library has no CPU path")
     if not (Q.dtype == K.dtype == V.dtype == dO.dtype) or Q.dtype not in _DTYPES:
@@ -224,15 +226,26 @@ def llla_backward(Q, K, V, dO, lam, scale: float, workspace=None, stream=None, r
         if not (lam_rows.is_cuda and lam_rows.dtype == torch.float32 and tuple(lam_rows.shape) == (B, H, n)
                 and lam_rows.is_contiguous()):
             raise ValueError("a per-row ridge must be a contiguous device float32 tensor [B, H, n]")
-    dQ, dK, dV = (torch.empty((B, H, n, d), dtype=torch.float32, device=Q.device) for _ in range(3))
-    dlam = torch.empty((B, H, n), dtype=torch.float32, device=Q.device) if return_dlambda else None
+    if out is not None:
+        dQ, dK, dV = out[:3]
+        dlam = out[3] if len(out) > 3 else None
+        for t in (dQ, dK, dV):
+            if not (t.is_cuda and t.dtype == torch.float32 and tuple(t.shape) == (B, H, n, d) and t.is_contiguous()):
+                raise ValueError("gradient outputs must be contiguous device float32 tensors [B, H, n, d]")
+        if dlam is not None and not (dlam.is_cuda and dlam.dtype == torch.float32 and tuple(dlam.shape) == (B, H, n)
+                                     and dlam.is_contiguous()):
+            raise ValueError("dlambda must be a contiguous device float32 tensor [B, H, n]")
+        return_dlambda = dlam is not None
+    else:
+        dQ, dK, dV = (torch.empty((B, H, n, d), dtype=torch.float32, device=Q.device) for _ in range(3))
+        dlam = torch.empty((B, H, n), dtype=torch.float32, device=Q.device) if return_dlambda else None
     need = backward_workspace_bytes(B, H, n, d, Q.dtype)
     ws = _workspace(need, Q.device, workspace)
     st = lib().llla_backward(Q.data_ptr(), K.data_ptr(), V.data_ptr(), dO.data_ptr(),
                              _strides4(Q), _strides4(K), _strides4(V), _strides4(dO),
                              dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), None if dlam is None else dlam.data_ptr(),
                              B, H, n, d, _DTYPES[Q.dtype], 0.0 if lam_rows is not None else float(lam),
-                             None if lam_rows is None else lam_rows.data_ptr(), float(scale),
+                             None if lam_rows is None else lam_rows.data_ptr(), float(scale), PATHS[path],
                              ws.data_ptr(), ws.numel() * ws.element_size(), _stream_ptr(stream))
     if st != 0:
         raise LlaError(st, "llla_backward")

@@ -226,13 +226,13 @@ llla_status llla_forward_cg(const void *Q, const void *K, const void *V, void *O
 size_t llla_backward_workspace_bytes(int B, int H, int n, int d, llla_dtype in)
 {
     if (B <= 0 || H <= 0 || n <= 0 || !dim_supported(d) || !dtype_ok(in)) return 0;
-    return llla::valu_backward_workspace_bytes(B, H, n, d);
+    return llla::backward_workspace_bytes(B, H, n, d, in, LLLA_PATH_AUTO);
 }
 
 llla_status llla_backward(const void *Q, const void *K, const void *V, const void *dO, llla_strides sq, llla_strides sk,
                           llla_strides sv, llla_strides sdo, float *dQ, float *dK, float *dV, float *dlambda, int B,
                           int H, int n, int d, llla_dtype in, float lambda, const float *lambda_rows, float scale,
-                          void *workspace, size_t workspace_bytes, void *stream)
+                          llla_path path, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!Q || !K || !V || !dO || !dQ || !dK || !dV) return LLLA_ERR_NULL;
     llla_status st = check_common(B, H, n, d, in, LLLA_F32, lambda_rows ? 1.f : lambda, scale);
@@ -245,7 +245,9 @@ llla_status llla_backward(const void *Q, const void *K, const void *V, const voi
         !strides_aligned(sdo, in) || (reinterpret_cast<uintptr_t>(dlambda) & 3u) ||
         (reinterpret_cast<uintptr_t>(lambda_rows) & 3u))
         return LLLA_ERR_ALIGN;
-    st = check_workspace(llla::valu_backward_workspace_bytes(B, H, n, d), workspace, workspace_bytes);
+    if (path != LLLA_PATH_AUTO && path != LLLA_PATH_VALU && path != LLLA_PATH_MFMA) return LLLA_ERR_PARAM;
+    if (path == LLLA_PATH_MFMA && !llla::mfma_forward_supported(d, in, true)) return LLLA_ERR_UNSUPPORTED;
+    st = check_workspace(llla::backward_workspace_bytes(B, H, n, d, in, path), workspace, workspace_bytes);
     if (st != LLLA_OK) return st;
 
     llla::BackwardProblem p{};
@@ -257,7 +259,7 @@ llla_status llla_backward(const void *Q, const void *K, const void *V, const voi
     p.lambda = lambda; p.lambda_rows = lambda_rows; p.scale = scale;
     p.ws = workspace; p.ws_bytes = workspace_bytes;
     p.stream = static_cast<hipStream_t>(stream);
-    return llla::valu_backward(p) == hipSuccess ? LLLA_OK : LLLA_ERR_LAUNCH;
+    return llla::backward(p, path) == hipSuccess ? LLLA_OK : LLLA_ERR_LAUNCH;
 }
 
 size_t llla_decode_workspace_bytes(int B, int H, int L_max, int d, llla_dtype in)

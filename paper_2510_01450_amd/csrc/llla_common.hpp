@@ -52,6 +52,20 @@ hipError_t valu_decode(const Problem &p);
 
 size_t valu_backward_workspace_bytes(int B, int H, int n, int d);
 hipError_t valu_backward(const BackwardProblem &p);
+// backward with the matrix-core moments and solve (bf16, d = 64 / 128): workspace layout and the two MFMA stages
+struct BackwardLayout {
+    size_t fwd;        // the forward's workspace (re-tiled K, V; row maxima M; y rows)
+    size_t u, r, sc;   // u rows and r rows (pitch ypitch floats: vector then scalar), row scalars (8 floats per row)
+    size_t total;
+    int npad;          // pitch of the row maxima (log2 units), in floats
+    int ypitch;        // pitch of a y / u / r row, in floats
+    size_t m, y;       // offsets of M and of the y rows inside the forward's workspace
+};
+BackwardLayout mfma_backward_layout(int B, int H, int n, int d);
+hipError_t mfma_backward_rowmax(const BackwardProblem &p, const BackwardLayout &L);   // re-tiling and row maxima
+hipError_t mfma_backward_solve(const BackwardProblem &p, const BackwardLayout &L);    // moments, y and u of every row
+size_t backward_workspace_bytes(int B, int H, int n, int d, llla_dtype in, llla_path path);
+hipError_t backward(const BackwardProblem &p, llla_path path);
 
 // MFMA (matrix-core) paths; *_supported() says whether one exists for the shape and dtype.
 bool mfma_forward_supported(int d, llla_dtype in, bool causal);

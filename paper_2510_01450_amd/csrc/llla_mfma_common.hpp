@@ -44,6 +44,11 @@ __device__ inline float row_bcast(float x)   // value of lane C of the caller's 
 {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x150 + C, 0xf, 0xf, true));
 }
+template <int J>
+__device__ inline float quad_bcast(float x)   // value of lane (lane & ~3) + J
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), J * 0x55, 0xf, 0xf, true));
+}
 __device__ inline float lane_xor1(float x)   // value of lane ^ 1
 {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xf, 0xf, true));
@@ -290,11 +295,16 @@ __device__ inline void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memor
 // The matrix cores only add products, so everything that the textbook recursion subtracts is carried
 // negated instead: the trailing matrix (T), the inverse diagonal factors (N_P = -U_PP^{-1}), and the
 // partial right-hand sides; no tile is ever negated on the vector ALU.
-template <int DD, class BuildRhs>
+// WITH_U (the backward pass): build_rhs also puts -r1_q into column 2 and r0v[q] holds r0_q; a second system
+// [omega mu~^T; mu~ Sigma~ + lambda I] [u0; u1] = [r0; r1] is solved alongside at no extra matrix-core work (it
+// rides in a padding column of the right-hand-side tiles): on return column 1 (lanes nn == 1) = u1_q and
+// u0v[q] = u0_q (valid in lanes nn < 4).
+template <int DD, bool WITH_U = false, class BuildRhs>
 __device__ __forceinline__ void solve_wave(f32x4 (&acc)[Shape<DD>::QW][Shape<DD>::NTILE],
                                            f32x4 (&rhs)[Shape<DD>::QW][Shape<DD>::NB], float (&y0v)[Shape<DD>::QW],
                                            const float (&om4)[Shape<DD>::QW], float *scw, int g, int nn,
-                                           float pivot_floor, BuildRhs build_rhs)
+                                           float pivot_floor, BuildRhs build_rhs, const float *r0v = nullptr,
+                                           float *u0v = nullptr)
 {
     using S = Shape<DD>;
     constexpr int QW = S::QW, NB = S::NB;
@@ -366,6 +376,36 @@ __device__ __forceinline__ void solve_wave(f32x4 (&acc)[Shape<DD>::QW][Shape<DD>
     // y0 = (1 - a.c) / (omega - a.a);  y1 = U^{-1} (c - a y0), started below as z = a y0 - c
 #pragma unroll
     for (int q = 0; q < QW; ++q) {
+        if constexpr (WITH_U) {
+            // column 2 = e = U^{-T} r1:  u0 = (r0 - a.e) / (omega - a.a),  u1 = U^{-1} (e - a u0); every lane of the
+            // first quad of a row (nn < 4) sees a, c and e of that row
+            float saa = 0.f, sac = 0.f, sae = 0.f;
+#pragma unroll
+            for (int P = 0; P < NB; ++P)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const float v = rhs[q][P][t];
+                    const float av = quad_bcast<0>(v), cv = quad_bcast<1>(v), ev = quad_bcast<2>(v);
+                    saa = fmaf(av, av, saa);
+                    sac = fmaf(av, cv, sac);
+                    sae = fmaf(av, ev, sae);
+                }
+            saa += __shfl_xor(saa, 16); saa += __shfl_xor(saa, 32);
+            sac += __shfl_xor(sac, 16); sac += __shfl_xor(sac, 32);
+            sae += __shfl_xor(sae, 16); sae += __shfl_xor(sae, 32);
+            const float dinv = 1.f / (om4[q] - saa);
+            const float y0 = (1.f - sac) * dinv, u0 = (r0v[q] - sae) * dinv;       // valid in lanes nn < 4
+            y0v[q] = y0;
+            u0v[q] = u0;
+#pragma unroll
+            for (int P = 0; P < NB; ++P)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const float v = rhs[q][P][t];
+                    const float av = quad_bcast<0>(v), cv = quad_bcast<1>(v), ev = quad_bcast<2>(v);
+                    rhs[q][P][t] = (nn == 0) ? (av * y0 - cv) : ((nn == 1) ? (av * u0 - ev) : 0.f);
+                }
+        } else {
         float saa = 0.f, sac = 0.f;
 #pragma unroll
         for (int P = 0; P < NB; ++P)
@@ -388,6 +428,7 @@ __device__ __forceinline__ void solve_wave(f32x4 (&acc)[Shape<DD>::QW][Shape<DD>
                 const float cv = lane_xor1(av);
                 rhs[q][P][t] = (nn == 0) ? (av * y0 - cv) : 0.f;
             }
+        }
     }
 
     // ---- back substitution, block rows 3..0:  z_P += sum_{J>P} U(P,J) x_J,  x_P = N_P z_P.  C += A^T B needs

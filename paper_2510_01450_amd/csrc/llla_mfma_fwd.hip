@@ -288,12 +288,15 @@ __device__ inline int nat_swizzle(int key) { return CH == 8 ? ((key >> 1) & 7) :
 
 // PRECISE: fp32 weights and a two-term f16 split of the scaled operand w k, i.e. an fp32-accurate
 // second moment; used for the first rows of a sequence, whose systems are the worst conditioned.
-template <bool PRECISE, int DD>
+// WITH_U (the backward pass): Rg holds, per row, r1 (DD floats) and r0 at [DD] (pitch YP); the solve then also
+// returns u = M^{-1} [r0; r1] in Ug, laid out like Yg.
+template <bool PRECISE, int DD, bool WITH_U = false>
 __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t *__restrict__ Qg,
                                              const bf16_t *__restrict__ Kg, llla_strides sq, llla_strides sk, int H,
                                              int n, int nkb, float cscale, float lambda,
                                              const float *__restrict__ lam_rows, const _Float16 *__restrict__ KT,
-                                             const float *__restrict__ Mg, float *__restrict__ Yg)
+                                             const float *__restrict__ Mg, float *__restrict__ Yg,
+                                             const float *__restrict__ Rg = nullptr, float *__restrict__ Ug = nullptr)
 {
     using S = Shape<DD>;
     constexpr int NB = S::NB, NTILE = S::NTILE, NF = S::NF, QW = S::QW, NW = S::NW, QB = S::QB, YP = S::YP;
@@ -614,11 +617,17 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     for (int q = 0; q < QW; ++q) om4[q] = oms[QW * wave + q];
     const int gq_row = min(i0 + QW * wave + (g < QW ? g : QW - 1), n - 1);
     const float pivot_floor = 0.5f * (lam_rows ? lam_rows[(size_t)bh * n + gq_row] : lambda);
-    solve_wave<DD>(acc, rhs, y0v, om4, &sc[wave][0][0], g, nn, pivot_floor, [&](f32x4 (&r)[QW][NB]) {
+    float r0v[QW], u0v[QW];
+    if constexpr (WITH_U) {
+#pragma unroll
+        for (int q = 0; q < QW; ++q) r0v[q] = Rg[((size_t)bh * n + min(i0 + QW * wave + q, n - 1)) * YP + DD];
+    }
+    solve_wave<DD, WITH_U>(acc, rhs, y0v, om4, &sc[wave][0][0], g, nn, pivot_floor, [&](f32x4 (&r)[QW][NB]) {
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
             const int qi = QW * wave + q;
             const bf16_t *qrow = Qh + (int64_t)min(i0 + qi, n - 1) * sq.seq;
+            const float *rrow = WITH_U ? Rg + ((size_t)bh * n + min(i0 + qi, n - 1)) * YP : nullptr;
 #pragma unroll
             for (int P = 0; P < NB; ++P)
 #pragma unroll
@@ -627,10 +636,12 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
                     // would become a branch with its own wait per tile register
                     const int row = 16 * P + 4 * g + t;
                     const float mv = mus[qi][row], qv = bf16_to_f32(qrow[row]);
-                    r[q][P][t] = (nn == 0) ? mv : ((nn == 1) ? -qv : 0.f);      // mus holds -mu~
+                    float v = (nn == 0) ? mv : ((nn == 1) ? -qv : 0.f);         // mus holds -mu~
+                    if constexpr (WITH_U) v = (nn == 2) ? -rrow[row] : v;
+                    r[q][P][t] = v;
                 }
         }
-    });
+    }, r0v, u0v);
 
 #pragma unroll
     for (int q = 0; q < QW; ++q) {
@@ -640,6 +651,14 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
 #pragma unroll
             for (int P = 0; P < NB; ++P) *reinterpret_cast<f32x4 *>(yr + 16 * P + 4 * g) = rhs[q][P];
             if (g == 0) yr[DD] = y0v[q];
+        }
+        if constexpr (WITH_U) {
+            if (i < n && nn == 1) {
+                float *ur = Ug + ((size_t)bh * n + i) * YP;
+#pragma unroll
+                for (int P = 0; P < NB; ++P) *reinterpret_cast<f32x4 *>(ur + 16 * P + 4 * g) = rhs[q][P];
+                if (g == 0) ur[DD] = u0v[q];
+            }
         }
     }
 }
@@ -656,6 +675,21 @@ __global__ __launch_bounds__(Shape<DD>::NT, DD == 64 ? 2 : 1) void moments_kerne
     const int i0 = ((int)gridDim.x - 1 - (int)blockIdx.x) * Shape<DD>::QB;
     if (i0 < precise_rows) moments_body<true, DD>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg);
     else moments_body<false, DD>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg);
+}
+
+// The same with the backward's second system (see moments_body).
+template <int DD>
+__global__ __launch_bounds__(Shape<DD>::NT, DD == 64 ? 2 : 1) void moments_u_kernel(
+    const bf16_t *__restrict__ Qg, const bf16_t *__restrict__ Kg, llla_strides sq, llla_strides sk, int H, int n, int nkb,
+    int precise_rows, float cscale, float lambda, const float *__restrict__ lam_rows, const _Float16 *__restrict__ KT,
+    const float *__restrict__ Mg, float *__restrict__ Yg, const float *__restrict__ Rg, float *__restrict__ Ug)
+{
+    __shared__ __align__(16) MomentsShared<DD> sm;
+    const int i0 = ((int)gridDim.x - 1 - (int)blockIdx.x) * Shape<DD>::QB;
+    if (i0 < precise_rows)
+        moments_body<true, DD, true>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg, Rg, Ug);
+    else
+        moments_body<false, DD, true>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg, Rg, Ug);
 }
 
 // Optional statistics of Eq. (lla) from the solved y of every row: with y1 = -rho/delta and
@@ -924,7 +958,75 @@ hipError_t forward_cg_impl(const Problem &p, int T, float eps, int32_t *iters)
     return hipGetLastError();
 }
 
+template <int DD>
+hipError_t backward_rowmax_impl(const BackwardProblem &p, const BackwardLayout &BL)
+{
+    const Layout L = make_layout<DD>(p.B, p.H, p.n);
+    char *ws = static_cast<char *>(p.ws) + BL.fwd;
+    _Float16 *KT = reinterpret_cast<_Float16 *>(ws + L.kt);
+    bf16_t *VT = reinterpret_cast<bf16_t *>(ws + L.vt);
+    float *M = reinterpret_cast<float *>(ws + L.m);
+    float *Y = reinterpret_cast<float *>(ws + L.y);
+    const int bh = p.B * p.H;
+    const bf16_t *Q = static_cast<const bf16_t *>(p.Q), *K = static_cast<const bf16_t *>(p.K),
+                 *V = static_cast<const bf16_t *>(p.V);
+    stage_mark(p.stream, "prep");
+    hipLaunchKernelGGL((prep_kernel<DD>), dim3(L.nkb, bh), dim3(256), 0, p.stream, K, V, p.sk, p.sv, p.H, p.n, L.nkb, KT, VT);
+    stage_mark(p.stream, "rowmax");
+    hipLaunchKernelGGL((sweep_kernel<true, DD>), dim3((p.n + 63) / 64, bh), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H,
+                       p.n, L.nkb, 0, p.scale * LOG2E, VT, M, Y, (void *)nullptr, llla_strides{0, 0, 0}, 0, (float *)nullptr);
+    return hipGetLastError();
+}
+
+template <int DD>
+hipError_t backward_solve_impl(const BackwardProblem &p, const BackwardLayout &BL)
+{
+    using S = Shape<DD>;
+    const Layout L = make_layout<DD>(p.B, p.H, p.n);
+    char *base = static_cast<char *>(p.ws);
+    char *ws = base + BL.fwd;
+    _Float16 *KT = reinterpret_cast<_Float16 *>(ws + L.kt);
+    float *M = reinterpret_cast<float *>(ws + L.m);
+    float *Y = reinterpret_cast<float *>(ws + L.y);
+    const float *R = reinterpret_cast<const float *>(base + BL.r);
+    float *U = reinterpret_cast<float *>(base + BL.u);
+    const int first = S::EARLY_ROWS < p.n ? S::EARLY_ROWS : p.n;
+    stage_mark(p.stream, "moments_and_two_solves");
+    hipLaunchKernelGGL((moments_u_kernel<DD>), dim3((p.n + S::QB - 1) / S::QB, p.B * p.H), dim3(S::NT), 0, p.stream,
+                       static_cast<const bf16_t *>(p.Q), static_cast<const bf16_t *>(p.K), p.sq, p.sk, p.H, p.n, L.nkb, first,
+                       p.scale * LOG2E, p.lambda, p.lambda_rows, KT, M, Y, R, U);
+    return hipGetLastError();
+}
+
 }  // namespace
+
+BackwardLayout mfma_backward_layout(int B, int H, int n, int d)
+{
+    BackwardLayout BL{};
+    const Layout L = d == 64 ? make_layout<64>(B, H, n) : make_layout<128>(B, H, n);
+    const size_t rows = (size_t)B * H * n;
+    BL.ypitch = d + 4;
+    BL.npad = L.npad;
+    BL.m = L.m;
+    BL.y = L.y;
+    size_t off = 0;
+    BL.fwd = off; off += round_up(L.total, 256);
+    BL.u = off;   off += round_up(rows * BL.ypitch * 4, 256);
+    BL.r = off;   off += round_up(rows * BL.ypitch * 4, 256);
+    BL.sc = off;  off += round_up(rows * 8 * 4, 256);
+    BL.total = off;
+    return BL;
+}
+
+hipError_t mfma_backward_rowmax(const BackwardProblem &p, const BackwardLayout &L)
+{
+    return p.d == 64 ? backward_rowmax_impl<64>(p, L) : backward_rowmax_impl<128>(p, L);
+}
+
+hipError_t mfma_backward_solve(const BackwardProblem &p, const BackwardLayout &L)
+{
+    return p.d == 64 ? backward_solve_impl<64>(p, L) : backward_solve_impl<128>(p, L);
+}
 
 bool mfma_forward_supported(int d, llla_dtype in, bool causal) { return (d == 64 || d == 128) && in == LLLA_BF16 && causal; }
 

@@ -119,17 +119,18 @@ def test_product_has_no_cpu_fallback():
 
 
 def _bwd(Q=FAKE, K=FAKE, V=FAKE, dO=FAKE, dQ=FAKE, dK=FAKE, dV=FAKE, dlam=None, s=None, B=1, H=1, n=64, d=64, din=0,
-         lam=1e-2, lam_rows=None, scale=0.125, ws=0, wsb=0):
+         lam=1e-2, lam_rows=None, scale=0.125, path=0, ws=0, wsb=0):
     s = _Strides(H * n * d, n * d, d) if s is None else s
     return llla.lib().llla_backward(Q, K, V, dO, s, s, s, s, dQ, dK, dV, dlam, B, H, n, d, din, lam, lam_rows, scale,
-                                    ws, wsb, 0)
+                                    path, ws, wsb, 0)
 
 
 @pytest.mark.parametrize("kw,code", [
     (dict(dO=0), 1), (dict(dK=0), 1),
     (dict(n=0), 2), (dict(s=_Strides(64 * 64, 64 * 64, 32)), 2),
     (dict(din=5), 3),
-    (dict(lam=0.0), 4), (dict(scale=float("nan")), 4),
+    (dict(lam=0.0), 4), (dict(scale=float("nan")), 4), (dict(path=5), 4),
+    (dict(path=2), 7), (dict(path=2, din=1, d=32), 7),
     (dict(dQ=FAKE + 8), 5), (dict(dlam=FAKE + 2), 5), (dict(lam_rows=FAKE + 1), 5),
     (dict(), 6), (dict(ws=FAKE + 16, wsb=1 << 30), 6), (dict(ws=FAKE, wsb=16), 6),
     (dict(d=24), 7),

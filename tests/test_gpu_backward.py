@@ -36,9 +36,10 @@ def _upstream(w, seed, rows=None):
     return G.to(workloads.torch_dtype(w))
 
 
-def _backward(w, Q, K, V, G, lam):
+def _backward(w, Q, K, V, G, lam, path="auto"):
     lam_dev = lam.to(DEV) if torch.is_tensor(lam) else lam
-    out = llla.llla_backward(Q.to(DEV), K.to(DEV), V.to(DEV), G.to(DEV), lam_dev, w.scale, return_dlambda=True)
+    out = llla.llla_backward(Q.to(DEV), K.to(DEV), V.to(DEV), G.to(DEV), lam_dev, w.scale, path=path,
+                             return_dlambda=True)
     torch.cuda.synchronize()
     return [t.cpu().numpy() for t in out]
 
@@ -56,20 +57,25 @@ def _compare(w, got, ref, what, floor):
         print(name, check_grad(g, r, w.d, w.tol, "%s %s" % (what, name), floor=floor[name]))
 
 
-@pytest.mark.parametrize("n,d,dtype", [
-    (1, 16, "f32"), (2, 64, "f32"), (77, 16, "f32"), (130, 32, "f32"), (203, 64, "f32"), (150, 128, "f32"),
-    (77, 16, "bf16"), (131, 32, "bf16"), (333, 64, "bf16"), (257, 128, "bf16"),
+@pytest.mark.parametrize("n,d,dtype,path", [
+    (1, 16, "f32", "auto"), (2, 64, "f32", "auto"), (77, 16, "f32", "auto"), (130, 32, "f32", "auto"),
+    (203, 64, "f32", "auto"), (150, 128, "f32", "auto"), (77, 16, "bf16", "auto"), (131, 32, "bf16", "auto"),
+    (333, 64, "bf16", "valu"), (257, 128, "bf16", "valu"),
+    (1, 64, "bf16", "mfma"), (17, 64, "bf16", "mfma"), (333, 64, "bf16", "mfma"), (700, 64, "bf16", "mfma"),
+    (257, 128, "bf16", "mfma"), (530, 128, "bf16", "mfma"),
 ])
-def test_ragged_shapes_all_gradients(n, d, dtype):
+def test_ragged_shapes_all_gradients(n, d, dtype, path):
+    """Sizes that span several tiles with a ragged tail, both dtypes, every supported d, both kernel families."""
     w = _case(2, 3, n, d, dtype, index=500 + n + d)
     Q, K, V = workloads.make_inputs(w)
     G = _upstream(w, n + d)
     ref = ob.backward(Q, K, V, G, w.lam, w.scale)
-    _compare(w, _backward(w, Q, K, V, G, w.lam), ref, "n=%d d=%d %s" % (n, d, dtype), _floor(V, G, w.lam))
+    _compare(w, _backward(w, Q, K, V, G, w.lam, path), ref, "%s n=%d d=%d %s" % (path, n, d, dtype), _floor(V, G, w.lam))
 
 
-@pytest.mark.parametrize("n,d,dtype", [(203, 64, "f32"), (333, 64, "bf16"), (140, 128, "bf16"), (90, 32, "f32")])
-def test_ridge_per_row(n, d, dtype):
+@pytest.mark.parametrize("n,d,dtype,path", [(203, 64, "f32", "auto"), (333, 64, "bf16", "valu"), (333, 64, "bf16", "mfma"),
+                                            (140, 128, "bf16", "mfma"), (90, 32, "f32", "auto")])
+def test_ridge_per_row(n, d, dtype, path):
     """lambda_i log-normal around 0.03 (Appendix C: the ridge is learnable per position); dL/dlambda_i is the
     gradient such a parametrisation needs."""
     w = _case(1, 2, n, d, dtype, index=600 + n + d)
@@ -78,7 +84,8 @@ def test_ridge_per_row(n, d, dtype):
     g = torch.Generator(device="cpu").manual_seed(workloads.SEED0 + 9500 + n)
     lam = (0.03 * torch.exp(0.7 * torch.randn((w.B, w.H, n), generator=g))).float()
     ref = ob.backward(Q, K, V, G, lam.double().numpy(), w.scale)
-    _compare(w, _backward(w, Q, K, V, G, lam), ref, "lambda rows n=%d d=%d %s" % (n, d, dtype), _floor(V, G, lam))
+    _compare(w, _backward(w, Q, K, V, G, lam, path), ref, "lambda rows %s n=%d d=%d %s" % (path, n, d, dtype),
+             _floor(V, G, lam))
 
 
 @pytest.mark.parametrize("values,lam", [("normal", 1e-2), ("scaled", 1e-2), ("l2", 0.5), ("regression", 0.1)])
@@ -90,9 +97,10 @@ def test_other_value_distributions_and_ridges(values, lam):
     _compare(w, _backward(w, Q, K, V, G, w.lam), ref, values, _floor(V, G, w.lam))
 
 
-def test_piecewise_linear_task_gradients():
+@pytest.mark.parametrize("w", [workloads.E2S.with_shape(B=2, tol=1e-3),
+                               workloads.E2.with_shape(name="E2_2seq_n512", B=2, n=512, segment=128)], ids=lambda w: w.name)
+def test_piecewise_linear_task_gradients(w):
     """The regression task's inputs (queries equal to keys: one dominant weight per row)."""
-    w = workloads.E2S.with_shape(B=2, tol=1e-3)
     Q, K, V = workloads.make_inputs(w)
     G = _upstream(w, 8)
     ref = ob.backward(Q, K, V, G, w.lam, w.scale)
@@ -112,13 +120,14 @@ def test_strided_inputs():
     _compare(w, [t.cpu().numpy() for t in got], ref, "strided", _floor(V, G, w.lam))
 
 
-def test_deterministic_and_inputs_untouched():
+@pytest.mark.parametrize("path", ["valu", "mfma"])
+def test_deterministic_and_inputs_untouched(path):
     w = _case(1, 2, 300, 64, "bf16", index=790)
     Q, K, V = workloads.make_inputs(w)
     G = _upstream(w, 10)
     dev = [t.to(DEV) for t in (Q, K, V, G)]
-    a = llla.llla_backward(*dev, w.lam, w.scale, return_dlambda=True)
-    b = llla.llla_backward(*dev, w.lam, w.scale, return_dlambda=True)
+    a = llla.llla_backward(*dev, w.lam, w.scale, path=path, return_dlambda=True)
+    b = llla.llla_backward(*dev, w.lam, w.scale, path=path, return_dlambda=True)
     torch.cuda.synchronize()
     assert all(torch.equal(x, y) for x, y in zip(a, b))
     assert all(torch.equal(x.cpu(), y) for x, y in zip(dev, (Q, K, V, G)))
@@ -140,7 +149,15 @@ def test_gradient_of_the_scalar_ridge_is_the_sum_over_rows_and_matches_a_differe
     assert abs(float(dlam.double().sum()) - fd) <= 2e-2 * abs(fd) + 1e-3, (float(dlam.sum()), fd)
 
 
-def test_c3_shape_sampled_rows():
+def test_matrix_core_path_refuses_what_it_does_not_serve():
+    x = torch.zeros(1, 1, 64, 32, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(llla.LlaError) as e:
+        llla.llla_backward(x, x, x, x, 1e-2, 0.1, path="mfma")
+    assert e.value.code == 7
+
+
+@pytest.mark.parametrize("path", ["valu", "mfma"])
+def test_c3_shape_sampled_rows(path):
     """One batch entry of the prefill configuration (16 heads x 4096 x 64, bf16).  The upstream gradient is non-zero
     on sampled rows only, so that the oracle can produce every gradient (dK and dV of a key sum over all later
     rows) from those rows one by one; the kernels do the same work per row whatever the values of dO."""
@@ -148,7 +165,7 @@ def test_c3_shape_sampled_rows():
     Q, K, V = workloads.make_inputs(w)
     rows = workloads.sample_rows(w, n_random=40)[::3]
     G = _upstream(w, 12, rows=rows)
-    got = _backward(w, Q, K, V, G, w.lam)
+    got = _backward(w, Q, K, V, G, w.lam, path)
     floor = _floor(V[:, :1], G[:, :1], w.lam)
     for h in (0, 9):
         ref = ob.backward_head(Q[0, h], K[0, h], V[0, h], G[0, h], w.lam, w.scale, rows=rows)
