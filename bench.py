@@ -5,6 +5,7 @@ One "step" = one pass of the whole hot path (llla_forward, or llla_decode for th
 over one batch of seeded synthetic input that is already resident in HBM.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3|C3b|C4|C2|C1|C5|E2] [--path auto|valu|mfma]
+                  [--ex | --cg T | --backward]
 
 metric  : tokens/s of the causal forward (B*n / t)  -- or generated tokens/s for decode (B / t)
 roofline: the dominant kernel's algorithmic flops (forward; d^2+11d per causal pair plus
@@ -129,7 +130,7 @@ def main():
         if decode:
             llla.llla_decode(a, b, c, w.lam, w.scale, path=args.path, workspace=ws, out=out)
         elif bwd:
-            llla.llla_backward(a, b, c, dO, w.lam, w.scale, workspace=ws, out=grads)
+            llla.llla_backward(a, b, c, dO, w.lam, w.scale, path=args.path, workspace=ws, out=grads)
         elif args.cg is not None:
             llla.llla_forward_cg(a, b, c, w.lam, w.scale, args.cg, 0.0, workspace=ws, out=out)
         elif ex:
@@ -179,10 +180,12 @@ def main():
         if bwd:
             # rows kernel: half of the second moment, logits, mu~, gamma, r, a, b, dQ; keys kernel: logits, a, b,
             # gamma, dV, the three terms of dK; per row the elimination with two right-hand sides
-            per_pair = {"backward_rows": d * d + 14 * d, "backward_keys": 16 * d}.get(dom, d * d + 22 * d)
-            per_row = (d ** 3 / 3.0 + 6 * d * d) if dom != "backward_keys" else 0.0
+            # matrix-core flow: r sweep (logits, gamma, r), moments with both solves, dQ sweep (logits, a, b, gamma, dQ)
+            per_pair = {"backward_rows": d * d + 14 * d, "backward_keys": 16 * d, "backward_r": 6 * d,
+                        "backward_dq": 10 * d, "moments_and_two_solves": d * d + 5 * d}.get(dom, d * d + 22 * d)
+            per_row = (d ** 3 / 3.0 + 6 * d * d) if dom in ("backward_rows", "moments_and_two_solves") else 0.0
             flops = w.B * w.H * (pairs * float(per_pair) + w.n * per_row)
-            bound, peak = "alu", PEAK_FP32_VALU
+            bound, peak = ("mfma", PEAK_MFMA_16BIT) if dom == "moments_and_two_solves" else ("alu", PEAK_FP32_VALU)
         elif dom == "cg_steps":
             # per step and causal pair: logits (2d), k.p (2d), accumulate (2d); per row the vector updates (~12d)
             flops = args.cg * w.B * w.H * (pairs * 6.0 * d + w.n * 12.0 * d)
@@ -281,11 +284,17 @@ def main():
             keep = torch.zeros(w.n, dtype=torch.bool)
             keep[torch.as_tensor(rows)] = True
             dO_s = dO_cpu * keep[None, None, :, None]
-            got = llla.llla_backward(dev_in[0][0], dev_in[0][1], dev_in[0][2], dO_s.to(dev), w.lam, w.scale, workspace=ws,
-                                     return_dlambda=True)
+            got = llla.llla_backward(dev_in[0][0], dev_in[0][1], dev_in[0][2], dO_s.to(dev), w.lam, w.scale, path=args.path,
+                                     workspace=ws, return_dlambda=True)
             torch.cuda.synchronize()
             t1 = time.perf_counter()
             ref = ob.backward_head(Q[0, 0], K[0, 0], V[0, 0], dO_s[0, 0], w.lam, w.scale, rows=rows)
+            nrep = 1
+            while time.perf_counter() - t1 < 10.0:          # bounded sample: the same rows of further heads
+                hh = nrep % (w.B * w.H)
+                ob.backward_head(Q[hh // w.H, hh % w.H], K[hh // w.H, hh % w.H], V[hh // w.H, hh % w.H],
+                                 dO_s[hh // w.H, hh % w.H], w.lam, w.scale, rows=rows)
+                nrep += 1
             cpu_s = time.perf_counter() - t1
             tol = 1e-3 if w.dtype == "f32" else 2e-2
             floor = float(dO_s[0, 0].double().norm()) * float(V[0, 0].double().pow(2).mean().sqrt())
@@ -294,12 +303,12 @@ def main():
                 summ[name] = check_grad(gq[0, 0].cpu().numpy()[None, None], rf[None, None], w.d, tol, "bench " + name,
                                         floor=floor / (w.lam if name == "dlambda" else 1.0))
             work_all = w.B * w.H * (w.n * (w.n + 1) / 2.0)
-            work_s = float(np.sum(np.asarray(rows) + 1.0))
+            work_s = nrep * float(np.sum(np.asarray(rows) + 1.0))
             full = cpu_s * work_all / work_s
             result["cpu_baseline"] = {"value": w.B * w.n / full, "unit": "tokens/s", "cores": torch.get_num_threads(),
                                       "kind": "oracle",
-                                      "sample": "%d sampled rows of one head in %.1f s; scaled by causal pairs (x%.0f)"
-                                      % (len(rows), cpu_s, work_all / work_s)}
+                                      "sample": "%d sampled rows x %d heads in %.1f s; scaled by causal pairs (x%.0f)"
+                                      % (len(rows), nrep, cpu_s, work_all / work_s)}
         else:
             step(0)
             torch.cuda.synchronize()
