@@ -705,11 +705,7 @@ hipError_t launch_backward_mfma(const BackwardProblem &p)
     err = hipGetLastError();
     if (err != hipSuccess) return err;
     stage_mark(p.stream, "backward_keys");
-    dim3 grid_keys((p.n + KeyCfg<D>::KB - 1) / KeyCfg<D>::KB, p.B * p.H);
-    hipLaunchKernelGGL((bwd_keys_kernel<D, TI>), grid_keys, dim3(NT), 0, p.stream, (const TI *)p.Q, (const TI *)p.K,
-                       (const TI *)p.V, (const TI *)p.dO, p.sq, p.sk, p.sv, p.sdo, p.H, p.n, p.scale, (const float *)Y,
-                       (const float *)U, L.ypitch, (const float *)Sc, 8, p.dK, p.dV);
-    return hipGetLastError();
+    return mfma_backward_keys(p, L);
 }
 
 }  // namespace

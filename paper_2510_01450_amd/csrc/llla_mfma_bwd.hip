@@ -1,0 +1,222 @@
+// Matrix-core key sweep of the LLA backward pass (bf16 inputs, d = 64 / 128): dK_j and dV_j of a block of keys,
+// summed over the query rows at and after the block (Appendix D: Delta_V = S^T G and the key-side sums of the
+// w- and z-paths, here in the un-centred form described at the top of llla_bwd.hip).
+//
+// A wave owns 16 keys and walks over the query rows in steps of 32.  Per step, with C = A B on 16x16x32 bf16 MFMA:
+//   * four products of a [16 queries x d] row tile with the wave's key (or value) fragments give, in the accumulator
+//     layout (lane (g, nn): queries 4g..4g+3, key nn), the logits q_i.k_j, the linear forms y1_i.k_j and u1_i.k_j
+//     (y1, u1 as bf16 hi + lo) and gamma_ij = dO_i.v_j;
+//   * the vector ALU turns them into the three coefficient tiles s_ij, e_ij, scale p^_ij and splits each into
+//     bf16 hi + lo;
+//   * those registers are already the A operand of the second product family, whose contraction index is the query
+//     (slot 4s+r of lane group g <-> query 16s+4g+r): dV += S^T dO,  dK += E^T Y1 - S^T U1 + scale P^T Q.  The B operands
+//     are the same row tiles read transposed by ds_read_tr16_b64 (lane nn gets four consecutive queries of feature
+//     16J+nn), so no tile is stored twice.
+// Accumulators stay in registers for the whole sweep; every output element is written once (no atomics).
+#include "llla_mfma_common.hpp"
+
+namespace llla {
+namespace {
+
+using namespace mfma;
+
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) short4v *lds_short4_ptr;
+
+constexpr int QS = 32;        // query rows per step
+
+// transposed fragment of a natural [32 rows][pitch P halves] tile: for feature 16J + nn the rows 4g..4g+3 and
+// 16+4g..16+4g+3 -- addr is the lane's own address (row 4g + nn/4, features 16J + 4(nn%4)..) in halves
+__device__ inline bf16x8 tr_frag(const bf16_t *tile, int addr, int pitch)
+{
+    const short4v a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(tile + addr));
+    const short4v b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(tile + 16 * pitch + addr));
+    const uint2 au = __builtin_bit_cast(uint2, a), bu = __builtin_bit_cast(uint2, b);
+    return __builtin_bit_cast(bf16x8, make_uint4(au.x, au.y, bu.x, bu.y));
+}
+
+__device__ inline void split_bf16(float x, __bf16 &hi, __bf16 &lo)
+{
+    hi = (__bf16)x;
+    lo = (__bf16)(x - (float)hi);
+}
+
+template <int DD>
+__global__ __launch_bounds__(256, 2) void bwd_keys_mfma_kernel(
+    const bf16_t *__restrict__ Qg, const bf16_t *__restrict__ Kg, const bf16_t *__restrict__ Vg,
+    const bf16_t *__restrict__ Gg, llla_strides sq, llla_strides sk, llla_strides sv, llla_strides sg, int H, int n,
+    float scale, const float *__restrict__ Yg, const float *__restrict__ Ug, const float *__restrict__ Sc,
+    float *__restrict__ dK, float *__restrict__ dV)
+{
+    using S = Shape<DD>;
+    constexpr int NF = S::NF, NB = S::NB, YP = S::YP;
+    constexpr int P = DD + 8;                            // halves per row of an LDS tile (rows stay 16-byte aligned)
+    constexpr int CH = DD / 8;                           // 16-byte chunks per row
+    __shared__ __align__(16) bf16_t qt[QS * P], gt[QS * P], yh[QS * P], yl[QS * P], uh[QS * P], ul[QS * P];
+    __shared__ float rs[QS][8];                          // y0, u0, m, correction, argmax of the step's rows
+
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64, g = lane / 16, nn = lane % 16;
+    const int bh = blockIdx.y, b = bh / H, h = bh % H;
+    const int j0 = (int)blockIdx.x * 64;                 // low key blocks see the most rows: they go first
+    const int jk = j0 + 16 * wave + nn, jkc = min(jk, n - 1);
+    const bf16_t *Qh = Qg + b * sq.batch + h * sq.head;
+    const bf16_t *Gh = Gg + b * sg.batch + h * sg.head;
+    const float *Yh = Yg + (size_t)bh * n * YP, *Uh = Ug + (size_t)bh * n * YP, *Sh = Sc + (size_t)bh * n * 8;
+
+    bf16x8 kf[NF], vf[NF];
+    {
+        const bf16_t *krow = Kg + b * sk.batch + h * sk.head + (int64_t)jkc * sk.seq;
+        const bf16_t *vrow = Vg + b * sv.batch + h * sv.head + (int64_t)jkc * sv.seq;
+#pragma unroll
+        for (int f = 0; f < NF; ++f) {
+            kf[f] = *reinterpret_cast<const bf16x8 *>(krow + 32 * f + 8 * g);
+            vf[f] = *reinterpret_cast<const bf16x8 *>(vrow + 32 * f + 8 * g);
+        }
+    }
+    f32x4 dv[NB], dk[NB];
+#pragma unroll
+    for (int J = 0; J < NB; ++J) dv[J] = dk[J] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int tr_addr = (4 * g + (nn >> 2)) * P + 4 * (nn & 3);      // + 16 J
+
+    for (int it0 = j0; it0 < n; it0 += QS) {
+        __syncthreads();                                 // the previous step's tiles are consumed
+        for (int idx = tid; idx < QS * CH; idx += 256) {
+            const int row = idx / CH, ch = (idx % CH) * 8, i = it0 + row;
+            uint4 qv = make_uint4(0, 0, 0, 0), gv = qv;
+            bf16x8 y_hi, y_lo, u_hi, u_lo;
+            float yv[8], uv[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) yv[t] = uv[t] = 0.f;
+            if (i < n) {
+                qv = *reinterpret_cast<const uint4 *>(Qh + (int64_t)i * sq.seq + ch);
+                gv = *reinterpret_cast<const uint4 *>(Gh + (int64_t)i * sg.seq + ch);
+                const f32x4 ya = *reinterpret_cast<const f32x4 *>(Yh + (size_t)i * YP + ch);
+                const f32x4 yb = *reinterpret_cast<const f32x4 *>(Yh + (size_t)i * YP + ch + 4);
+                const f32x4 ua = *reinterpret_cast<const f32x4 *>(Uh + (size_t)i * YP + ch);
+                const f32x4 ub = *reinterpret_cast<const f32x4 *>(Uh + (size_t)i * YP + ch + 4);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    yv[t] = ya[t]; yv[4 + t] = yb[t];
+                    uv[t] = -ua[t]; uv[4 + t] = -ub[t];      // the tiles hold -u1: both uses subtract it
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                __bf16 hi, lo;
+                split_bf16(yv[t], hi, lo);
+                y_hi[t] = hi; y_lo[t] = lo;
+                split_bf16(uv[t], hi, lo);
+                u_hi[t] = hi; u_lo[t] = lo;
+            }
+            *reinterpret_cast<uint4 *>(&qt[row * P + ch]) = qv;
+            *reinterpret_cast<uint4 *>(&gt[row * P + ch]) = gv;
+            *reinterpret_cast<bf16x8 *>(&yh[row * P + ch]) = y_hi;
+            *reinterpret_cast<bf16x8 *>(&yl[row * P + ch]) = y_lo;
+            *reinterpret_cast<bf16x8 *>(&uh[row * P + ch]) = u_hi;
+            *reinterpret_cast<bf16x8 *>(&ul[row * P + ch]) = u_lo;
+        }
+        {
+            const int row = tid / 8, c = tid % 8;
+            rs[row][c] = (it0 + row < n && c < 5) ? Sh[(size_t)(it0 + row) * 8 + c] : 0.f;
+        }
+        __syncthreads();
+
+        // ---- coefficients: lane (g, nn) holds the pairs (query it0 + 16s + 4g + r, key jk) --------------------
+        bf16x8 s_hi, s_lo, e_hi, e_lo, p_hi, p_lo;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            f32x4 st = {0.f, 0.f, 0.f, 0.f}, at = st, bt = st, gm = st;
+            const int arow = (16 * s + nn) * P + 8 * g;
+#pragma unroll
+            for (int f = 0; f < NF; ++f) {
+                const bf16x8 qf = *reinterpret_cast<const bf16x8 *>(&qt[arow + 32 * f]);
+                const bf16x8 gf = *reinterpret_cast<const bf16x8 *>(&gt[arow + 32 * f]);
+                const bf16x8 yhf = *reinterpret_cast<const bf16x8 *>(&yh[arow + 32 * f]);
+                const bf16x8 ylf = *reinterpret_cast<const bf16x8 *>(&yl[arow + 32 * f]);
+                const bf16x8 uhf = *reinterpret_cast<const bf16x8 *>(&uh[arow + 32 * f]);
+                const bf16x8 ulf = *reinterpret_cast<const bf16x8 *>(&ul[arow + 32 * f]);
+                st = mfma_bf16(qf, kf[f], st);
+                gm = mfma_bf16(gf, vf[f], gm);
+                at = mfma_bf16(ylf, kf[f], at);
+                at = mfma_bf16(yhf, kf[f], at);
+                bt = mfma_bf16(ulf, kf[f], bt);
+                bt = mfma_bf16(uhf, kf[f], bt);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int qr = 16 * s + 4 * g + r, i = it0 + qr;
+                const float y0 = rs[qr][0], u0 = rs[qr][1], m = rs[qr][2], corr = rs[qr][3];
+                const int jstar = __float_as_int(rs[qr][4]);
+                const bool valid = (jk <= i) && (i < n);
+                const float w = __builtin_amdgcn_exp2f((scale * st[r] - m) * LOG2E);
+                const float a = y0 + at[r];
+                const float ev = w * (gm[r] - u0 + bt[r]);       // bt = -u1.k
+                float pv = a * ev;
+                pv = (jk == jstar) ? pv + corr : pv;
+                __bf16 hi, lo;
+                split_bf16(valid ? w * a : 0.f, hi, lo);
+                s_hi[4 * s + r] = hi; s_lo[4 * s + r] = lo;
+                split_bf16(valid ? ev : 0.f, hi, lo);
+                e_hi[4 * s + r] = hi; e_lo[4 * s + r] = lo;
+                split_bf16(valid ? scale * pv : 0.f, hi, lo);
+                p_hi[4 * s + r] = hi; p_lo[4 * s + r] = lo;
+            }
+        }
+
+        // ---- accumulate over the step's 32 queries --------------------------------------------------------------
+#pragma unroll
+        for (int J = 0; J < NB; ++J) {
+            const int ta = tr_addr + 16 * J;
+            const bf16x8 gT = tr_frag(gt, ta, P);
+            dv[J] = mfma_bf16(s_lo, gT, dv[J]);
+            dv[J] = mfma_bf16(s_hi, gT, dv[J]);
+            const bf16x8 yhT = tr_frag(yh, ta, P), ylT = tr_frag(yl, ta, P);
+            dk[J] = mfma_bf16(e_lo, yhT, dk[J]);
+            dk[J] = mfma_bf16(e_hi, ylT, dk[J]);
+            dk[J] = mfma_bf16(e_hi, yhT, dk[J]);
+            const bf16x8 uhT = tr_frag(uh, ta, P), ulT = tr_frag(ul, ta, P);
+            dk[J] = mfma_bf16(s_lo, uhT, dk[J]);
+            dk[J] = mfma_bf16(s_hi, ulT, dk[J]);
+            dk[J] = mfma_bf16(s_hi, uhT, dk[J]);
+            const bf16x8 qT = tr_frag(qt, ta, P);
+            dk[J] = mfma_bf16(p_lo, qT, dk[J]);
+            dk[J] = mfma_bf16(p_hi, qT, dk[J]);
+        }
+    }
+
+    // dv[J], dk[J]: lane (g, nn) reg r = gradient of key j0 + 16 wave + 4g + r, feature 16J + nn
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int key = j0 + 16 * wave + 4 * g + r;
+        if (key < n) {
+            const size_t off = ((size_t)bh * n + key) * DD + nn;
+#pragma unroll
+            for (int J = 0; J < NB; ++J) {
+                dK[off + 16 * J] = dk[J][r];
+                dV[off + 16 * J] = dv[J][r];
+            }
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t mfma_backward_keys(const BackwardProblem &p, const BackwardLayout &L)
+{
+    char *base = static_cast<char *>(p.ws);
+    const float *Y = reinterpret_cast<const float *>(base + L.fwd + L.y);
+    const float *U = reinterpret_cast<const float *>(base + L.u);
+    const float *Sc = reinterpret_cast<const float *>(base + L.sc);
+    const bf16_t *Q = static_cast<const bf16_t *>(p.Q), *K = static_cast<const bf16_t *>(p.K),
+                 *V = static_cast<const bf16_t *>(p.V), *G = static_cast<const bf16_t *>(p.dO);
+    dim3 grid((p.n + 63) / 64, p.B * p.H);
+    if (p.d == 64)
+        hipLaunchKernelGGL((bwd_keys_mfma_kernel<64>), grid, dim3(256), 0, p.stream, Q, K, V, G, p.sq, p.sk, p.sv, p.sdo,
+                           p.H, p.n, p.scale, Y, U, Sc, p.dK, p.dV);
+    else
+        hipLaunchKernelGGL((bwd_keys_mfma_kernel<128>), grid, dim3(256), 0, p.stream, Q, K, V, G, p.sq, p.sk, p.sv, p.sdo,
+                           p.H, p.n, p.scale, Y, U, Sc, p.dK, p.dV);
+    return hipGetLastError();
+}
+
+}  // namespace llla
