@@ -1,4 +1,4 @@
-// Matrix-core key sweep of the LLA backward pass (bf16 inputs, d = 64 / 128): dK_j and dV_j of a block of keys,
+// Matrix-core sweeps of the LLA backward pass (bf16 inputs, d = 64 / 128).  Key sweep: dK_j and dV_j of a block of keys,
 // summed over the query rows at and after the block (Appendix D: Delta_V = S^T G and the key-side sums of the
 // w- and z-paths, here in the un-centred form described at the top of llla_bwd.hip).
 //
@@ -199,7 +199,208 @@ __global__ __launch_bounds__(256, 2) void bwd_keys_mfma_kernel(
     }
 }
 
+
+// ---- row sweeps ---------------------------------------------------------------------------------------------
+// The mirror image of the key sweep: a wave owns 16 query rows (their fragments stay in registers) and walks over
+// the keys in steps of 32; the coefficient tiles come out as [key][query] (lane (g, nn): keys 4g..4g+3, query nn),
+// which is the A operand of a product that contracts over keys, with the K tile read transposed as B.
+//   MODE 0 (before the solve): c_ij = w_ij gamma_ij;  r1_i = sum_j c_ij k_j, r0_i = sum_j c_ij, and the first key that
+//                              attains the row maximum (the logits are produced exactly as in the row-maximum sweep);
+//   MODE 1 (after it):         dL/dlambda_i = -u1_i.y1_i, c_ij = p^_ij;  dQ_i = u1_i + scale sum_j c_ij k_j, and the row
+//                              scalars (y0, u0, m, correction, argmax) the key sweep reads.
+template <int DD, int MODE>
+__global__ __launch_bounds__(256, 2) void bwd_rows_mfma_kernel(
+    const bf16_t *__restrict__ Qg, const bf16_t *__restrict__ Kg, const bf16_t *__restrict__ Vg,
+    const bf16_t *__restrict__ Gg, llla_strides sq, llla_strides sk, llla_strides sv, llla_strides sg, int H, int n,
+    int mpitch, float scale, float lambda, const float *__restrict__ LamRows, const float *__restrict__ Mg,
+    const float *__restrict__ Yg, const float *__restrict__ Ug, float *__restrict__ Rv, float *__restrict__ Sc,
+    float *__restrict__ dQ, float *__restrict__ dLam)
+{
+    using S = Shape<DD>;
+    constexpr int NF = S::NF, NB = S::NB, YP = S::YP;
+    constexpr int P = DD + 8, CH = DD / 8;
+    __shared__ __align__(16) bf16_t kt[KB * P], vt[KB * P];
+
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64, g = lane / 16, nn = lane % 16;
+    const int bh = blockIdx.y, b = bh / H, h = bh % H;
+    const int i0 = ((int)gridDim.x - 1 - (int)blockIdx.x) * 64;          // long rows first
+    const int iq = i0 + 16 * wave + nn, iqc = min(iq, n - 1);
+    const size_t row = (size_t)bh * n + iqc;
+    const bf16_t *Kh = Kg + b * sk.batch + h * sk.head;
+    const bf16_t *Vh = Vg + b * sv.batch + h * sv.head;
+    const float cscale = scale * LOG2E;
+
+    bf16x8 qf[NF], gf[NF], yhf[NF], ylf[NF], uhf[NF], ulf[NF];
+    {
+        const bf16_t *qrow = Qg + b * sq.batch + h * sq.head + (int64_t)iqc * sq.seq;
+        const bf16_t *grow = Gg + b * sg.batch + h * sg.head + (int64_t)iqc * sg.seq;
+#pragma unroll
+        for (int f = 0; f < NF; ++f) {
+            qf[f] = *reinterpret_cast<const bf16x8 *>(qrow + 32 * f + 8 * g);
+            gf[f] = *reinterpret_cast<const bf16x8 *>(grow + 32 * f + 8 * g);
+        }
+    }
+    const float mrow = Mg[(size_t)bh * mpitch + iqc];                     // log2 units
+    float y0 = 0.f, u0 = 0.f, corr = 0.f;
+    int jstar = 0;
+    if (MODE == 1) {
+        const float *yr = Yg + row * YP, *ur = Ug + row * YP;
+        y0 = yr[DD];
+        u0 = ur[DD];
+        jstar = __float_as_int(Rv[row * YP + DD + 1]);
+        float dl = 0.f;
+#pragma unroll
+        for (int f = 0; f < NF; ++f)
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const float yv = yr[32 * f + 8 * g + t], uv = ur[32 * f + 8 * g + t];
+                dl = fmaf(-uv, yv, dl);
+                __bf16 hi, lo;
+                split_bf16(yv, hi, lo);
+                yhf[f][t] = hi; ylf[f][t] = lo;
+                split_bf16(uv, hi, lo);
+                uhf[f][t] = hi; ulf[f][t] = lo;
+            }
+        dl += __shfl_xor(dl, 16);
+        dl += __shfl_xor(dl, 32);
+        corr = (LamRows ? LamRows[row] : lambda) * dl;
+        if (g == 0 && iq < n) {
+            float *sc = Sc + row * 8;
+            sc[0] = y0; sc[1] = u0; sc[2] = mrow * 0.6931471805599453f; sc[3] = corr; sc[4] = __int_as_float(jstar);
+            if (dLam) dLam[row] = dl;
+        }
+    }
+    f32x4 acc[NB];
+#pragma unroll
+    for (int J = 0; J < NB; ++J) acc[J] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float csum = 0.f, best = -INFINITY;
+    int arg = 0;
+    const int tr_addr = (4 * g + (nn >> 2)) * P + 4 * (nn & 3);
+
+    const int nblk = min(i0 + 63, n - 1) / KB + 1;
+    for (int c = 0; c < nblk; ++c) {
+        __syncthreads();
+        for (int idx = tid; idx < KB * CH; idx += 256) {
+            const int key = idx / CH, ch = (idx % CH) * 8, j = c * KB + key;
+            uint4 kv = make_uint4(0, 0, 0, 0), vv = kv;
+            if (j < n) {
+                kv = *reinterpret_cast<const uint4 *>(Kh + (int64_t)j * sk.seq + ch);
+                vv = *reinterpret_cast<const uint4 *>(Vh + (int64_t)j * sv.seq + ch);
+            }
+            *reinterpret_cast<uint4 *>(&kt[key * P + ch]) = kv;
+            *reinterpret_cast<uint4 *>(&vt[key * P + ch]) = vv;
+        }
+        __syncthreads();
+        bf16x8 c_hi, c_lo;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            f32x4 st = {0.f, 0.f, 0.f, 0.f}, gm = st, at = st, bt = st;
+            const int arow = (16 * s + nn) * P + 8 * g;
+#pragma unroll
+            for (int f = 0; f < NF; ++f) {
+                const bf16x8 kfr = *reinterpret_cast<const bf16x8 *>(&kt[arow + 32 * f]);
+                const bf16x8 vfr = *reinterpret_cast<const bf16x8 *>(&vt[arow + 32 * f]);
+                st = mfma_bf16(kfr, qf[f], st);
+                gm = mfma_bf16(vfr, gf[f], gm);
+                if (MODE == 1) {
+                    at = mfma_bf16(kfr, ylf[f], at);
+                    at = mfma_bf16(kfr, yhf[f], at);
+                    bt = mfma_bf16(kfr, ulf[f], bt);
+                    bt = mfma_bf16(kfr, uhf[f], bt);
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int j = c * KB + 16 * s + 4 * g + r;
+                const bool valid = (j <= iq) && (iq < n);
+                const float lg = st[r] * cscale;
+                const float w = __builtin_amdgcn_exp2f(lg - mrow);
+                float cv;
+                if (MODE == 0) {
+                    if (valid && lg > best) {
+                        best = lg;
+                        arg = j;
+                    }
+                    cv = valid ? w * gm[r] : 0.f;
+                    csum += cv;
+                } else {
+                    cv = w * (y0 + at[r]) * (gm[r] - u0 - bt[r]);
+                    cv = (j == jstar) ? cv + corr : cv;
+                    cv = valid ? cv : 0.f;
+                }
+                __bf16 hi, lo;
+                split_bf16(cv, hi, lo);
+                c_hi[4 * s + r] = hi;
+                c_lo[4 * s + r] = lo;
+            }
+        }
+#pragma unroll
+        for (int J = 0; J < NB; ++J) {
+            const bf16x8 kT = tr_frag(kt, tr_addr + 16 * J, P);
+            acc[J] = mfma_bf16(c_lo, kT, acc[J]);
+            acc[J] = mfma_bf16(c_hi, kT, acc[J]);
+        }
+    }
+
+    if (MODE == 0) {
+        // lanes (g, nn), g = 0..3, hold query nn's partial sums and maxima over disjoint keys
+        csum += __shfl_xor(csum, 16);
+        csum += __shfl_xor(csum, 32);
+#pragma unroll
+        for (int sft = 16; sft <= 32; sft <<= 1) {
+            const float ob = __shfl_xor(best, sft);
+            const int oa = __shfl_xor(arg, sft);
+            const bool take = (ob > best) || (ob == best && oa < arg);
+            best = take ? ob : best;
+            arg = take ? oa : arg;
+        }
+        if (g == 0 && iq < n) {
+            Rv[row * YP + DD] = csum;
+            Rv[row * YP + DD + 1] = __int_as_float(arg);
+        }
+    }
+    // acc[J]: lane (g, nn) reg r = sum for query i0 + 16 wave + 4g + r, feature 16J + nn
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int i = i0 + 16 * wave + 4 * g + r;
+        if (i < n) {
+            const size_t ro = (size_t)bh * n + i;
+#pragma unroll
+            for (int J = 0; J < NB; ++J) {
+                if (MODE == 0) Rv[ro * YP + 16 * J + nn] = acc[J][r];
+                else dQ[ro * DD + 16 * J + nn] = fmaf(scale, acc[J][r], Ug[ro * YP + 16 * J + nn]);
+            }
+        }
+    }
+}
+
+template <int DD, int MODE>
+hipError_t launch_rows(const BackwardProblem &p, const BackwardLayout &L)
+{
+    char *base = static_cast<char *>(p.ws);
+    const float *M = reinterpret_cast<const float *>(base + L.fwd + L.m);
+    const float *Y = reinterpret_cast<const float *>(base + L.fwd + L.y);
+    const float *U = reinterpret_cast<const float *>(base + L.u);
+    float *R = reinterpret_cast<float *>(base + L.r);
+    float *Sc = reinterpret_cast<float *>(base + L.sc);
+    hipLaunchKernelGGL((bwd_rows_mfma_kernel<DD, MODE>), dim3((p.n + 63) / 64, p.B * p.H), dim3(256), 0, p.stream,
+                       static_cast<const bf16_t *>(p.Q), static_cast<const bf16_t *>(p.K), static_cast<const bf16_t *>(p.V),
+                       static_cast<const bf16_t *>(p.dO), p.sq, p.sk, p.sv, p.sdo, p.H, p.n, L.npad, p.scale, p.lambda,
+                       p.lambda_rows, M, Y, U, R, Sc, p.dQ, p.dlambda);
+    return hipGetLastError();
+}
+
 }  // namespace
+
+hipError_t mfma_backward_r(const BackwardProblem &p, const BackwardLayout &L)
+{
+    return p.d == 64 ? launch_rows<64, 0>(p, L) : launch_rows<128, 0>(p, L);
+}
+
+hipError_t mfma_backward_dq(const BackwardProblem &p, const BackwardLayout &L)
+{
+    return p.d == 64 ? launch_rows<64, 1>(p, L) : launch_rows<128, 1>(p, L);
+}
 
 hipError_t mfma_backward_keys(const BackwardProblem &p, const BackwardLayout &L)
 {
