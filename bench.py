@@ -72,7 +72,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures ONE GPU (one MI355X per box); --gpus %d is not run. "
-              "How the path would shard over several GPUs is described in DESIGN.md." % args.gpus,
+              "How the path would shard over several GPUs is described in the design notes of this repository." % args.gpus,
               file=sys.stderr)
         sys.exit(2)
 
