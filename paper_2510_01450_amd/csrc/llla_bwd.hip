@@ -306,6 +306,201 @@ __global__ __launch_bounds__(NT) void bwd_rows_kernel(const TI *__restrict__ Qg,
     if (slot_live && r < D) dQ[((size_t)bh * n + my_i) * D + r] = fmaf(scale, dq, u1s[slot * D + r]);
 }
 
+// ---- fp32 row sweeps for the first rows of the matrix-core flow -----------------------------------------------
+// With bf16 inputs and d = 64 / 128 the moments and both solves of a row run on the matrix cores, and so do the two
+// O(d)-per-pair sweeps over a row's keys -- except for the first 2d rows of a sequence: their systems are the worst
+// conditioned, u_i and the coefficients are large and cancel (dQ_0 is exactly 0 as the difference of two large
+// terms), and a 16-bit coefficient split is not enough there.  Those rows take these fp32 sweeps:
+//   MODE 0 (before the solve): r_i = sum_j w_ij gamma_ij [1; k_j] and the key that holds the row maximum;
+//   MODE 1 (after it):         dL/dlambda_i, the correction, dQ_i = u1_i + scale sum_j p^_ij k_j, and the row scalars
+//                              the key sweep reads.
+// The row maxima come from the matrix-core sweep (log2 units), so that all kernels normalise a row alike.
+template <int D>
+struct RowCfg {
+    static constexpr int QT = (D == 16) ? 64 : ((D >= 128) ? 16 : 32);   // query rows per workgroup
+    static constexpr int FPT = D * QT / NT;              // features per thread in the accumulation
+    static constexpr int TPR = NT / QT;                  // threads per row
+    static constexpr int KB = 32;                        // keys per tile
+    static constexpr int KPT = QT * KB / NT;             // keys per thread when the coefficients are formed
+    static constexpr int JG = KB / KPT;
+    static constexpr int CP = KB + 1;
+};
+
+template <int D, typename TI, int MODE>
+__global__ __launch_bounds__(NT) void bwd_rowsweep_kernel(const TI *__restrict__ Qg, const TI *__restrict__ Kg,
+                                                          const TI *__restrict__ Vg, const TI *__restrict__ Gg,
+                                                          llla_strides sq, llla_strides sk, llla_strides sv,
+                                                          llla_strides sg, int H, int n, int nrows, float scale,
+                                                          float lambda, const float *__restrict__ LamRows,
+                                                          const float *__restrict__ M, int mpitch,
+                                                          const float *__restrict__ Yv, const float *__restrict__ Uv,
+                                                          float *__restrict__ Rv, int vpitch, float *__restrict__ Sc,
+                                                          float *__restrict__ dQ, float *__restrict__ dLam)
+{
+    using C = RowCfg<D>;
+    constexpr int QT = C::QT, FPT = C::FPT, TPR = C::TPR, KB = C::KB, KPT = C::KPT, JG = C::JG, CP = C::CP;
+    constexpr int LDK = Cfg<D>::LDK;
+    constexpr int NROWT = (MODE == 1) ? 4 : 2;           // row-side tiles: q, g (, y1, u1)
+    static_assert(QT * JG == NT && QT * TPR == NT && FPT % 4 == 0, "thread maps");
+
+    __shared__ __align__(16) float smem[(2 * KB + NROWT * QT) * LDK + 2 * QT * CP + QT * 8];
+    float *ks = smem;                                     // [KB][LDK]
+    float *vs = ks + KB * LDK;                            // [KB][LDK]
+    float *qs = vs + KB * LDK;                            // [QT][LDK]
+    float *gs = qs + QT * LDK;                            // [QT][LDK]
+    float *y1s = gs + QT * LDK;                           // [QT][LDK]  (MODE 1)
+    float *u1s = y1s + QT * LDK;                          // [QT][LDK]  (MODE 1)
+    float *cs = smem + (2 * KB + NROWT * QT) * LDK;       // [QT][CP] coefficients
+    float *ss = cs + QT * CP;                             // [QT][CP] logits (MODE 0)
+    float *rs = ss + QT * CP;                             // [QT][8]  m, y0, u0, correction, argmax / running max
+
+    const int tid = threadIdx.x;
+    const int bh = blockIdx.y;
+    const int b = bh / H, h = bh % H;
+    const int i0 = ((int)gridDim.x - 1 - (int)blockIdx.x) * QT;          // long rows first
+    const int kend = min(nrows, i0 + QT);                                // rows [0, nrows) only; nrows <= n
+    const TI *Kh = Kg + b * sk.batch + h * sk.head;
+    const TI *Vh = Vg + b * sv.batch + h * sv.head;
+
+    load_tile<D, TI>(qs, Qg + b * sq.batch + h * sq.head, sq.seq, i0, QT, n, tid);
+    load_tile<D, TI>(gs, Gg + b * sg.batch + h * sg.head, sg.seq, i0, QT, n, tid);
+    if (MODE == 1) {
+        load_tile<D, float>(y1s, Yv + (size_t)bh * n * vpitch, vpitch, i0, QT, n, tid);
+        load_tile<D, float>(u1s, Uv + (size_t)bh * n * vpitch, vpitch, i0, QT, n, tid);
+    }
+    __syncthreads();
+    if (tid < QT) {
+        const int i = min(i0 + tid, n - 1);
+        const size_t row = (size_t)bh * n + i;
+        const float m = M[(size_t)bh * mpitch + i] * 0.6931471805599453f;
+        rs[tid * 8 + 0] = m;
+        if (MODE == 1) {
+            const float y0 = Yv[row * vpitch + D], u0 = Uv[row * vpitch + D];
+            const float jbits = Rv[row * vpitch + D + 1];
+            float dl = 0.f;
+            for (int c = 0; c < D; ++c) dl = fmaf(-u1s[tid * LDK + c], y1s[tid * LDK + c], dl);
+            const float corr = (LamRows ? LamRows[row] : lambda) * dl;
+            rs[tid * 8 + 1] = y0;
+            rs[tid * 8 + 2] = u0;
+            rs[tid * 8 + 3] = corr;
+            rs[tid * 8 + 4] = jbits;
+            if (i0 + tid < nrows) {
+                float *sc = Sc + row * 8;
+                sc[0] = y0; sc[1] = u0; sc[2] = m; sc[3] = corr; sc[4] = jbits;
+                if (dLam) dLam[row] = dl;
+            }
+        } else {
+            rs[tid * 8 + 5] = -INFINITY;                  // running maximum of the fp32 logits
+            rs[tid * 8 + 6] = __int_as_float(0);          // and the first key that attains it
+        }
+    }
+
+    const int ai = tid / JG, ajg = tid % JG;             // coefficient phase: row and key group
+    const int bi = tid / TPR, bc = (tid % TPR) * FPT;    // accumulation phase: row and feature chunk
+    float acc[FPT];
+    float r0 = 0.f;
+#pragma unroll
+    for (int x = 0; x < FPT; ++x) acc[x] = 0.f;
+
+    for (int kt0 = 0; kt0 < kend; kt0 += KB) {
+        __syncthreads();
+        load_tile<D, TI>(ks, Kh, sk.seq, kt0, KB, n, tid);
+        load_tile<D, TI>(vs, Vh, sv.seq, kt0, KB, n, tid);
+        __syncthreads();
+        {
+            const int ig = i0 + ai;
+            float ds[KPT], da[KPT], db[KPT], dg[KPT];
+#pragma unroll
+            for (int k = 0; k < KPT; ++k) ds[k] = da[k] = db[k] = dg[k] = 0.f;
+            for (int c = 0; c < D; c += 4) {
+                const float4 q4 = *reinterpret_cast<const float4 *>(qs + ai * LDK + c);
+                const float4 g4 = *reinterpret_cast<const float4 *>(gs + ai * LDK + c);
+                float4 y4 = make_float4(0.f, 0.f, 0.f, 0.f), u4 = y4;
+                if (MODE == 1) {
+                    y4 = *reinterpret_cast<const float4 *>(y1s + ai * LDK + c);
+                    u4 = *reinterpret_cast<const float4 *>(u1s + ai * LDK + c);
+                }
+#pragma unroll
+                for (int k = 0; k < KPT; ++k) {
+                    const int j = ajg + k * JG;
+                    const float4 k4 = *reinterpret_cast<const float4 *>(ks + j * LDK + c);
+                    const float4 v4 = *reinterpret_cast<const float4 *>(vs + j * LDK + c);
+                    ds[k] = fmaf(q4.x, k4.x, fmaf(q4.y, k4.y, fmaf(q4.z, k4.z, fmaf(q4.w, k4.w, ds[k]))));
+                    dg[k] = fmaf(g4.x, v4.x, fmaf(g4.y, v4.y, fmaf(g4.z, v4.z, fmaf(g4.w, v4.w, dg[k]))));
+                    if (MODE == 1) {
+                        da[k] = fmaf(y4.x, k4.x, fmaf(y4.y, k4.y, fmaf(y4.z, k4.z, fmaf(y4.w, k4.w, da[k]))));
+                        db[k] = fmaf(u4.x, k4.x, fmaf(u4.y, k4.y, fmaf(u4.z, k4.z, fmaf(u4.w, k4.w, db[k]))));
+                    }
+                }
+            }
+            const float m = rs[ai * 8 + 0];
+#pragma unroll
+            for (int k = 0; k < KPT; ++k) {
+                const int j = ajg + k * JG;
+                const bool valid = (kt0 + j <= ig) && (ig < nrows);
+                float cv = 0.f;
+                if (MODE == 0) {
+                    const float lg = scale * ds[k];
+                    if (valid) cv = __expf(lg - m) * dg[k];
+                    ss[ai * CP + j] = valid ? lg : -INFINITY;
+                } else if (valid) {
+                    const float w = __expf(scale * ds[k] - m);
+                    cv = w * (rs[ai * 8 + 1] + da[k]) * (dg[k] - (rs[ai * 8 + 2] + db[k]));
+                    if (kt0 + j == __float_as_int(rs[ai * 8 + 4])) cv += rs[ai * 8 + 3];
+                }
+                cs[ai * CP + j] = cv;
+            }
+        }
+        __syncthreads();
+        if (MODE == 0 && tid < QT) {                         // first key with the largest logit so far
+            float mx = rs[tid * 8 + 5];
+            int arg = __float_as_int(rs[tid * 8 + 6]);
+            for (int j = 0; j < KB; ++j) {
+                const float v = ss[tid * CP + j];
+                if (v > mx) {
+                    mx = v;
+                    arg = kt0 + j;
+                }
+            }
+            rs[tid * 8 + 5] = mx;
+            rs[tid * 8 + 6] = __int_as_float(arg);
+        }
+        for (int j = 0; j < KB; ++j) {
+            const float cv = cs[bi * CP + j];
+            r0 += cv;
+#pragma unroll
+            for (int x = 0; x < FPT; x += 4) {
+                const float4 k4 = *reinterpret_cast<const float4 *>(ks + j * LDK + bc + x);
+                acc[x] = fmaf(cv, k4.x, acc[x]);
+                acc[x + 1] = fmaf(cv, k4.y, acc[x + 1]);
+                acc[x + 2] = fmaf(cv, k4.z, acc[x + 2]);
+                acc[x + 3] = fmaf(cv, k4.w, acc[x + 3]);
+            }
+        }
+    }
+    __syncthreads();
+    if (i0 + bi < nrows) {
+        const size_t row = (size_t)bh * n + i0 + bi;
+        if (MODE == 0) {
+            float *rr = Rv + row * vpitch;
+#pragma unroll
+            for (int x = 0; x < FPT; x += 4)
+                *reinterpret_cast<float4 *>(rr + bc + x) = make_float4(acc[x], acc[x + 1], acc[x + 2], acc[x + 3]);
+            if (bc == 0) {
+                rr[D] = r0;
+                rr[D + 1] = rs[bi * 8 + 6];
+            }
+        } else {
+            float *qr = dQ + row * D;
+#pragma unroll
+            for (int x = 0; x < FPT; x += 4)
+                *reinterpret_cast<float4 *>(qr + bc + x) =
+                    make_float4(fmaf(scale, acc[x], u1s[bi * LDK + bc + x]), fmaf(scale, acc[x + 1], u1s[bi * LDK + bc + x + 1]),
+                                fmaf(scale, acc[x + 2], u1s[bi * LDK + bc + x + 2]), fmaf(scale, acc[x + 3], u1s[bi * LDK + bc + x + 3]));
+        }
+    }
+}
+
 // ---- key sweep ------------------------------------------------------------------------------------------
 template <int D>
 struct KeyCfg {
@@ -480,19 +675,43 @@ hipError_t backward_by_dtype(const BackwardProblem &p)
     return p.in == LLLA_F32 ? launch_backward<D, float>(p) : launch_backward<D, bf16_t>(p);
 }
 
+template <int D, int MODE>
+hipError_t launch_early_rows(const BackwardProblem &p, const BackwardLayout &L, int first)
+{
+    using TI = bf16_t;
+    char *base = static_cast<char *>(p.ws);
+    const float *M = reinterpret_cast<const float *>(base + L.fwd + L.m);
+    const float *Y = reinterpret_cast<const float *>(base + L.fwd + L.y);
+    const float *U = reinterpret_cast<const float *>(base + L.u);
+    float *R = reinterpret_cast<float *>(base + L.r);
+    float *Sc = reinterpret_cast<float *>(base + L.sc);
+    dim3 grid((first + RowCfg<D>::QT - 1) / RowCfg<D>::QT, p.B * p.H);
+    hipLaunchKernelGGL((bwd_rowsweep_kernel<D, TI, MODE>), grid, dim3(NT), 0, p.stream, (const TI *)p.Q, (const TI *)p.K,
+                       (const TI *)p.V, (const TI *)p.dO, p.sq, p.sk, p.sv, p.sdo, p.H, p.n, first, p.scale, p.lambda,
+                       p.lambda_rows, M, L.npad, MODE == 1 ? Y : nullptr, MODE == 1 ? U : nullptr, R, L.ypitch,
+                       MODE == 1 ? Sc : nullptr, MODE == 1 ? p.dQ : nullptr, MODE == 1 ? p.dlambda : nullptr);
+    return hipGetLastError();
+}
+
 // matrix-core flow (bf16, d = 64 / 128): row maxima, r sweep, moments with both solves, dQ sweep, key sweep
 hipError_t launch_backward_mfma(const BackwardProblem &p)
 {
     const BackwardLayout L = mfma_backward_layout(p.B, p.H, p.n, p.d);
     hipError_t err = mfma_backward_rowmax(p, L);
     if (err != hipSuccess) return err;
+    // the first 2d rows: fp32 sweeps (see bwd_rowsweep_kernel); the matrix-core sweeps start after them
+    const int first = p.n < 2 * p.d ? p.n : 2 * p.d;
     stage_mark(p.stream, "backward_r");
-    err = mfma_backward_r(p, L);
+    err = p.d == 64 ? launch_early_rows<64, 0>(p, L, first) : launch_early_rows<128, 0>(p, L, first);
+    if (err != hipSuccess) return err;
+    if (first < p.n) err = mfma_backward_r(p, L, first);
     if (err != hipSuccess) return err;
     err = mfma_backward_solve(p, L);
     if (err != hipSuccess) return err;
     stage_mark(p.stream, "backward_dq");
-    err = mfma_backward_dq(p, L);
+    err = p.d == 64 ? launch_early_rows<64, 1>(p, L, first) : launch_early_rows<128, 1>(p, L, first);
+    if (err != hipSuccess) return err;
+    if (first < p.n) err = mfma_backward_dq(p, L, first);
     if (err != hipSuccess) return err;
     stage_mark(p.stream, "backward_keys");
     return mfma_backward_keys(p, L);

@@ -64,8 +64,8 @@ struct BackwardLayout {
 BackwardLayout mfma_backward_layout(int B, int H, int n, int d);
 hipError_t mfma_backward_rowmax(const BackwardProblem &p, const BackwardLayout &L);   // re-tiling and row maxima
 hipError_t mfma_backward_solve(const BackwardProblem &p, const BackwardLayout &L);    // moments, y and u of every row
-hipError_t mfma_backward_r(const BackwardProblem &p, const BackwardLayout &L);        // r rows and the argmax of every row
-hipError_t mfma_backward_dq(const BackwardProblem &p, const BackwardLayout &L);       // dQ, dlambda and the row scalars
+hipError_t mfma_backward_r(const BackwardProblem &p, const BackwardLayout &L, int first_row);   // r rows, argmax; rows >= first_row
+hipError_t mfma_backward_dq(const BackwardProblem &p, const BackwardLayout &L, int first_row);  // dQ, dlambda, row scalars; rows >= first_row
 hipError_t mfma_backward_keys(const BackwardProblem &p, const BackwardLayout &L);     // dK, dV from y, u and the row scalars
 size_t backward_workspace_bytes(int B, int H, int n, int d, llla_dtype in, llla_path path);
 hipError_t backward(const BackwardProblem &p, llla_path path);

@@ -22,6 +22,7 @@ using namespace mfma;
 
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) short4v *lds_short4_ptr;
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int QS = 32;        // query rows per step
 
@@ -78,48 +79,56 @@ __global__ __launch_bounds__(256, 2) void bwd_keys_mfma_kernel(
     for (int J = 0; J < NB; ++J) dv[J] = dk[J] = f32x4{0.f, 0.f, 0.f, 0.f};
     const int tr_addr = (4 * g + (nn >> 2)) * P + 4 * (nn & 3);      // + 16 J
 
+    // The rows of the next step travel from global memory into registers while the current step is computed; they
+    // are split and stored to LDS after the barrier that retires the current tiles.
+    constexpr int NIT = QS * CH / 256;                   // 16-byte chunks per thread and tile
+    u32x4 pq[NIT], pg[NIT];
+    f32x4 pya[NIT], pyb[NIT], pua[NIT], pub[NIT];
+    float psc = 0.f;
+    auto fetch = [&](int it0) {
+#pragma unroll
+        for (int k = 0; k < NIT; ++k) {
+            const int idx = tid + 256 * k, row = idx / CH, ch = (idx % CH) * 8, i = it0 + row;
+            pq[k] = pg[k] = u32x4{0u, 0u, 0u, 0u};
+            pya[k] = pyb[k] = pua[k] = pub[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (i < n) {
+                pq[k] = *reinterpret_cast<const u32x4 *>(Qh + (int64_t)i * sq.seq + ch);
+                pg[k] = *reinterpret_cast<const u32x4 *>(Gh + (int64_t)i * sg.seq + ch);
+                pya[k] = *reinterpret_cast<const f32x4 *>(Yh + (size_t)i * YP + ch);
+                pyb[k] = *reinterpret_cast<const f32x4 *>(Yh + (size_t)i * YP + ch + 4);
+                pua[k] = *reinterpret_cast<const f32x4 *>(Uh + (size_t)i * YP + ch);
+                pub[k] = *reinterpret_cast<const f32x4 *>(Uh + (size_t)i * YP + ch + 4);
+            }
+        }
+        const int row = tid / 8, c = tid % 8;
+        psc = (it0 + row < n && c < 5) ? Sh[(size_t)(it0 + row) * 8 + c] : 0.f;
+    };
+    fetch(j0);
+
     for (int it0 = j0; it0 < n; it0 += QS) {
         __syncthreads();                                 // the previous step's tiles are consumed
-        for (int idx = tid; idx < QS * CH; idx += 256) {
-            const int row = idx / CH, ch = (idx % CH) * 8, i = it0 + row;
-            uint4 qv = make_uint4(0, 0, 0, 0), gv = qv;
+#pragma unroll
+        for (int k = 0; k < NIT; ++k) {
+            const int idx = tid + 256 * k, row = idx / CH, ch = (idx % CH) * 8;
             bf16x8 y_hi, y_lo, u_hi, u_lo;
-            float yv[8], uv[8];
-#pragma unroll
-            for (int t = 0; t < 8; ++t) yv[t] = uv[t] = 0.f;
-            if (i < n) {
-                qv = *reinterpret_cast<const uint4 *>(Qh + (int64_t)i * sq.seq + ch);
-                gv = *reinterpret_cast<const uint4 *>(Gh + (int64_t)i * sg.seq + ch);
-                const f32x4 ya = *reinterpret_cast<const f32x4 *>(Yh + (size_t)i * YP + ch);
-                const f32x4 yb = *reinterpret_cast<const f32x4 *>(Yh + (size_t)i * YP + ch + 4);
-                const f32x4 ua = *reinterpret_cast<const f32x4 *>(Uh + (size_t)i * YP + ch);
-                const f32x4 ub = *reinterpret_cast<const f32x4 *>(Uh + (size_t)i * YP + ch + 4);
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    yv[t] = ya[t]; yv[4 + t] = yb[t];
-                    uv[t] = -ua[t]; uv[4 + t] = -ub[t];      // the tiles hold -u1: both uses subtract it
-                }
-            }
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
                 __bf16 hi, lo;
-                split_bf16(yv[t], hi, lo);
+                split_bf16(t < 4 ? pya[k][t & 3] : pyb[k][t & 3], hi, lo);
                 y_hi[t] = hi; y_lo[t] = lo;
-                split_bf16(uv[t], hi, lo);
+                split_bf16(-(t < 4 ? pua[k][t & 3] : pub[k][t & 3]), hi, lo);      // the tiles hold -u1: both uses subtract it
                 u_hi[t] = hi; u_lo[t] = lo;
             }
-            *reinterpret_cast<uint4 *>(&qt[row * P + ch]) = qv;
-            *reinterpret_cast<uint4 *>(&gt[row * P + ch]) = gv;
+            *reinterpret_cast<u32x4 *>(&qt[row * P + ch]) = pq[k];
+            *reinterpret_cast<u32x4 *>(&gt[row * P + ch]) = pg[k];
             *reinterpret_cast<bf16x8 *>(&yh[row * P + ch]) = y_hi;
             *reinterpret_cast<bf16x8 *>(&yl[row * P + ch]) = y_lo;
             *reinterpret_cast<bf16x8 *>(&uh[row * P + ch]) = u_hi;
             *reinterpret_cast<bf16x8 *>(&ul[row * P + ch]) = u_lo;
         }
-        {
-            const int row = tid / 8, c = tid % 8;
-            rs[row][c] = (it0 + row < n && c < 5) ? Sh[(size_t)(it0 + row) * 8 + c] : 0.f;
-        }
+        rs[tid / 8][tid % 8] = psc;
         __syncthreads();
+        if (it0 + QS < n) fetch(it0 + QS);
 
         // ---- coefficients: lane (g, nn) holds the pairs (query it0 + 16s + 4g + r, key jk) --------------------
         bf16x8 s_hi, s_lo, e_hi, e_lo, p_hi, p_lo;
@@ -208,11 +217,13 @@ __global__ __launch_bounds__(256, 2) void bwd_keys_mfma_kernel(
 //                              attains the row maximum (the logits are produced exactly as in the row-maximum sweep);
 //   MODE 1 (after it):         dL/dlambda_i = -u1_i.y1_i, c_ij = p^_ij;  dQ_i = u1_i + scale sum_j c_ij k_j, and the row
 //                              scalars (y0, u0, m, correction, argmax) the key sweep reads.
+// Rows [first_row, n) only: the first rows of a sequence take fp32 sweeps (their coefficients cancel too strongly for
+// a 16-bit split).
 template <int DD, int MODE>
 __global__ __launch_bounds__(256, 2) void bwd_rows_mfma_kernel(
     const bf16_t *__restrict__ Qg, const bf16_t *__restrict__ Kg, const bf16_t *__restrict__ Vg,
     const bf16_t *__restrict__ Gg, llla_strides sq, llla_strides sk, llla_strides sv, llla_strides sg, int H, int n,
-    int mpitch, float scale, float lambda, const float *__restrict__ LamRows, const float *__restrict__ Mg,
+    int first_row, int mpitch, float scale, float lambda, const float *__restrict__ LamRows, const float *__restrict__ Mg,
     const float *__restrict__ Yg, const float *__restrict__ Ug, float *__restrict__ Rv, float *__restrict__ Sc,
     float *__restrict__ dQ, float *__restrict__ dLam)
 {
@@ -223,7 +234,7 @@ __global__ __launch_bounds__(256, 2) void bwd_rows_mfma_kernel(
 
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64, g = lane / 16, nn = lane % 16;
     const int bh = blockIdx.y, b = bh / H, h = bh % H;
-    const int i0 = ((int)gridDim.x - 1 - (int)blockIdx.x) * 64;          // long rows first
+    const int i0 = first_row + ((int)gridDim.x - 1 - (int)blockIdx.x) * 64;          // long rows first
     const int iq = i0 + 16 * wave + nn, iqc = min(iq, n - 1);
     const size_t row = (size_t)bh * n + iqc;
     const bf16_t *Kh = Kg + b * sk.batch + h * sk.head;
@@ -278,19 +289,31 @@ __global__ __launch_bounds__(256, 2) void bwd_rows_mfma_kernel(
     const int tr_addr = (4 * g + (nn >> 2)) * P + 4 * (nn & 3);
 
     const int nblk = min(i0 + 63, n - 1) / KB + 1;
+    // the next key tile travels from global memory into registers while the current one is consumed
+    constexpr int NIT = KB * CH / 256;
+    u32x4 pk[NIT], pv[NIT];
+    auto fetch = [&](int c) {
+#pragma unroll
+        for (int k = 0; k < NIT; ++k) {
+            const int idx = tid + 256 * k, key = idx / CH, ch = (idx % CH) * 8, j = c * KB + key;
+            pk[k] = pv[k] = u32x4{0u, 0u, 0u, 0u};
+            if (j < n) {
+                pk[k] = *reinterpret_cast<const u32x4 *>(Kh + (int64_t)j * sk.seq + ch);
+                pv[k] = *reinterpret_cast<const u32x4 *>(Vh + (int64_t)j * sv.seq + ch);
+            }
+        }
+    };
+    fetch(0);
     for (int c = 0; c < nblk; ++c) {
         __syncthreads();
-        for (int idx = tid; idx < KB * CH; idx += 256) {
-            const int key = idx / CH, ch = (idx % CH) * 8, j = c * KB + key;
-            uint4 kv = make_uint4(0, 0, 0, 0), vv = kv;
-            if (j < n) {
-                kv = *reinterpret_cast<const uint4 *>(Kh + (int64_t)j * sk.seq + ch);
-                vv = *reinterpret_cast<const uint4 *>(Vh + (int64_t)j * sv.seq + ch);
-            }
-            *reinterpret_cast<uint4 *>(&kt[key * P + ch]) = kv;
-            *reinterpret_cast<uint4 *>(&vt[key * P + ch]) = vv;
+#pragma unroll
+        for (int k = 0; k < NIT; ++k) {
+            const int idx = tid + 256 * k, key = idx / CH, ch = (idx % CH) * 8;
+            *reinterpret_cast<u32x4 *>(&kt[key * P + ch]) = pk[k];
+            *reinterpret_cast<u32x4 *>(&vt[key * P + ch]) = pv[k];
         }
         __syncthreads();
+        if (c + 1 < nblk) fetch(c + 1);
         bf16x8 c_hi, c_lo;
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
@@ -375,7 +398,7 @@ __global__ __launch_bounds__(256, 2) void bwd_rows_mfma_kernel(
 }
 
 template <int DD, int MODE>
-hipError_t launch_rows(const BackwardProblem &p, const BackwardLayout &L)
+hipError_t launch_rows(const BackwardProblem &p, const BackwardLayout &L, int first_row)
 {
     char *base = static_cast<char *>(p.ws);
     const float *M = reinterpret_cast<const float *>(base + L.fwd + L.m);
@@ -383,23 +406,24 @@ hipError_t launch_rows(const BackwardProblem &p, const BackwardLayout &L)
     const float *U = reinterpret_cast<const float *>(base + L.u);
     float *R = reinterpret_cast<float *>(base + L.r);
     float *Sc = reinterpret_cast<float *>(base + L.sc);
-    hipLaunchKernelGGL((bwd_rows_mfma_kernel<DD, MODE>), dim3((p.n + 63) / 64, p.B * p.H), dim3(256), 0, p.stream,
+    hipLaunchKernelGGL((bwd_rows_mfma_kernel<DD, MODE>), dim3((p.n - first_row + 63) / 64, p.B * p.H), dim3(256), 0, p.stream,
                        static_cast<const bf16_t *>(p.Q), static_cast<const bf16_t *>(p.K), static_cast<const bf16_t *>(p.V),
-                       static_cast<const bf16_t *>(p.dO), p.sq, p.sk, p.sv, p.sdo, p.H, p.n, L.npad, p.scale, p.lambda,
-                       p.lambda_rows, M, Y, U, R, Sc, p.dQ, p.dlambda);
+                       static_cast<const bf16_t *>(p.dO), p.sq, p.sk, p.sv, p.sdo, p.H, p.n, first_row, L.npad, p.scale,
+                       p.lambda, p.lambda_rows, M, Y, U, R, Sc, p.dQ, p.dlambda);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t mfma_backward_r(const BackwardProblem &p, const BackwardLayout &L)
+// rows [first_row, n); first_row must be a multiple of 64
+hipError_t mfma_backward_r(const BackwardProblem &p, const BackwardLayout &L, int first_row)
 {
-    return p.d == 64 ? launch_rows<64, 0>(p, L) : launch_rows<128, 0>(p, L);
+    return p.d == 64 ? launch_rows<64, 0>(p, L, first_row) : launch_rows<128, 0>(p, L, first_row);
 }
 
-hipError_t mfma_backward_dq(const BackwardProblem &p, const BackwardLayout &L)
+hipError_t mfma_backward_dq(const BackwardProblem &p, const BackwardLayout &L, int first_row)
 {
-    return p.d == 64 ? launch_rows<64, 1>(p, L) : launch_rows<128, 1>(p, L);
+    return p.d == 64 ? launch_rows<64, 1>(p, L, first_row) : launch_rows<128, 1>(p, L, first_row);
 }
 
 hipError_t mfma_backward_keys(const BackwardProblem &p, const BackwardLayout &L)

@@ -172,3 +172,20 @@ def test_c3_shape_sampled_rows(path):
         for name, g, r in zip(NAMES, got, ref):
             print(name, check_grad(g[0, h][None, None], r[None, None], w.d, w.tol, "C3 head %d %s" % (h, name),
                                    floor=floor[name]))
+
+
+def test_c4_shape_sampled_rows():
+    """Two heads of the long-context configuration (8192 x 128, bf16, regression-shaped values) on the matrix-core
+    path; the first rows, where the exact dQ_0 = 0 is the difference of two large terms, are among the sampled ones."""
+    w = workloads.C4.with_shape(H=2)
+    Q, K, V = workloads.make_inputs(w)
+    rows = workloads.sample_rows(w, n_random=24)[::4]
+    assert 0 in rows
+    G = _upstream(w, 13, rows=rows)
+    got = _backward(w, Q, K, V, G, w.lam, "mfma")
+    floor = _floor(V[:, :1], G[:, :1], w.lam)
+    for h in (0, 1):
+        ref = ob.backward_head(Q[0, h], K[0, h], V[0, h], G[0, h], w.lam, w.scale, rows=rows)
+        for name, g, r in zip(NAMES, got, ref):
+            print(name, check_grad(g[0, h][None, None], r[None, None], w.d, w.tol, "C4 head %d %s" % (h, name),
+                                   floor=floor[name]))
