@@ -43,7 +43,7 @@ __device__ inline void split_bf16(float x, __bf16 &hi, __bf16 &lo)
 }
 
 template <int DD>
-__global__ __launch_bounds__(256, 2) void bwd_keys_mfma_kernel(
+__global__ __launch_bounds__(256, DD == 64 ? 3 : 2) void bwd_keys_mfma_kernel(
     const bf16_t *__restrict__ Qg, const bf16_t *__restrict__ Kg, const bf16_t *__restrict__ Vg,
     const bf16_t *__restrict__ Gg, llla_strides sq, llla_strides sk, llla_strides sv, llla_strides sg, int H, int n,
     float scale, const float *__restrict__ Yg, const float *__restrict__ Ug, const float *__restrict__ Sc,
@@ -54,11 +54,14 @@ __global__ __launch_bounds__(256, 2) void bwd_keys_mfma_kernel(
     constexpr int P = DD + 8;                            // halves per row of an LDS tile (rows stay 16-byte aligned)
     constexpr int CH = DD / 8;                           // 16-byte chunks per row
     __shared__ __align__(16) bf16_t qt[QS * P], gt[QS * P], yh[QS * P], yl[QS * P], uh[QS * P], ul[QS * P];
-    __shared__ float rs[QS][8];                          // y0, u0, m, correction, argmax of the step's rows
+    __shared__ float rs[QS][9];                          // y0, u0, m, correction, argmax of the step's rows (odd pitch)
 
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64, g = lane / 16, nn = lane % 16;
-    const int bh = blockIdx.y, b = bh / H, h = bh % H;
-    const int j0 = (int)blockIdx.x * 64;                 // low key blocks see the most rows: they go first
+    // A low key block sees the most rows (up to n/32 steps), the last one two steps.  Workgroups are dispatched
+    // with blockIdx.x running fastest, so the head is put there: all heads' longest blocks start first and the
+    // shortest ones fill the tail, instead of the last head's longest block running alone at the end.
+    const int bh = blockIdx.x, b = bh / H, h = bh % H;
+    const int j0 = (int)blockIdx.y * 64;
     const int jk = j0 + 16 * wave + nn, jkc = min(jk, n - 1);
     const bf16_t *Qh = Qg + b * sq.batch + h * sq.head;
     const bf16_t *Gh = Gg + b * sg.batch + h * sg.head;
@@ -79,56 +82,41 @@ __global__ __launch_bounds__(256, 2) void bwd_keys_mfma_kernel(
     for (int J = 0; J < NB; ++J) dv[J] = dk[J] = f32x4{0.f, 0.f, 0.f, 0.f};
     const int tr_addr = (4 * g + (nn >> 2)) * P + 4 * (nn & 3);      // + 16 J
 
-    // The rows of the next step travel from global memory into registers while the current step is computed; they
-    // are split and stored to LDS after the barrier that retires the current tiles.
-    constexpr int NIT = QS * CH / 256;                   // 16-byte chunks per thread and tile
-    u32x4 pq[NIT], pg[NIT];
-    f32x4 pya[NIT], pyb[NIT], pua[NIT], pub[NIT];
-    float psc = 0.f;
-    auto fetch = [&](int it0) {
-#pragma unroll
-        for (int k = 0; k < NIT; ++k) {
-            const int idx = tid + 256 * k, row = idx / CH, ch = (idx % CH) * 8, i = it0 + row;
-            pq[k] = pg[k] = u32x4{0u, 0u, 0u, 0u};
-            pya[k] = pyb[k] = pua[k] = pub[k] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (i < n) {
-                pq[k] = *reinterpret_cast<const u32x4 *>(Qh + (int64_t)i * sq.seq + ch);
-                pg[k] = *reinterpret_cast<const u32x4 *>(Gh + (int64_t)i * sg.seq + ch);
-                pya[k] = *reinterpret_cast<const f32x4 *>(Yh + (size_t)i * YP + ch);
-                pyb[k] = *reinterpret_cast<const f32x4 *>(Yh + (size_t)i * YP + ch + 4);
-                pua[k] = *reinterpret_cast<const f32x4 *>(Uh + (size_t)i * YP + ch);
-                pub[k] = *reinterpret_cast<const f32x4 *>(Uh + (size_t)i * YP + ch + 4);
-            }
-        }
-        const int row = tid / 8, c = tid % 8;
-        psc = (it0 + row < n && c < 5) ? Sh[(size_t)(it0 + row) * 8 + c] : 0.f;
-    };
-    fetch(j0);
-
     for (int it0 = j0; it0 < n; it0 += QS) {
         __syncthreads();                                 // the previous step's tiles are consumed
-#pragma unroll
-        for (int k = 0; k < NIT; ++k) {
-            const int idx = tid + 256 * k, row = idx / CH, ch = (idx % CH) * 8;
+        for (int idx = tid; idx < QS * CH; idx += 256) {
+            const int row = idx / CH, ch = (idx % CH) * 8, i = it0 + row;
+            u32x4 qv = {0u, 0u, 0u, 0u}, gv = qv;
+            f32x4 ya = {0.f, 0.f, 0.f, 0.f}, yb = ya, ua = ya, ub = ya;
+            if (i < n) {
+                qv = *reinterpret_cast<const u32x4 *>(Qh + (int64_t)i * sq.seq + ch);
+                gv = *reinterpret_cast<const u32x4 *>(Gh + (int64_t)i * sg.seq + ch);
+                ya = *reinterpret_cast<const f32x4 *>(Yh + (size_t)i * YP + ch);
+                yb = *reinterpret_cast<const f32x4 *>(Yh + (size_t)i * YP + ch + 4);
+                ua = *reinterpret_cast<const f32x4 *>(Uh + (size_t)i * YP + ch);
+                ub = *reinterpret_cast<const f32x4 *>(Uh + (size_t)i * YP + ch + 4);
+            }
             bf16x8 y_hi, y_lo, u_hi, u_lo;
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
                 __bf16 hi, lo;
-                split_bf16(t < 4 ? pya[k][t & 3] : pyb[k][t & 3], hi, lo);
+                split_bf16(t < 4 ? ya[t & 3] : yb[t & 3], hi, lo);
                 y_hi[t] = hi; y_lo[t] = lo;
-                split_bf16(-(t < 4 ? pua[k][t & 3] : pub[k][t & 3]), hi, lo);      // the tiles hold -u1: both uses subtract it
+                split_bf16(-(t < 4 ? ua[t & 3] : ub[t & 3]), hi, lo);      // the tiles hold -u1: both uses subtract it
                 u_hi[t] = hi; u_lo[t] = lo;
             }
-            *reinterpret_cast<u32x4 *>(&qt[row * P + ch]) = pq[k];
-            *reinterpret_cast<u32x4 *>(&gt[row * P + ch]) = pg[k];
+            *reinterpret_cast<u32x4 *>(&qt[row * P + ch]) = qv;
+            *reinterpret_cast<u32x4 *>(&gt[row * P + ch]) = gv;
             *reinterpret_cast<bf16x8 *>(&yh[row * P + ch]) = y_hi;
             *reinterpret_cast<bf16x8 *>(&yl[row * P + ch]) = y_lo;
             *reinterpret_cast<bf16x8 *>(&uh[row * P + ch]) = u_hi;
             *reinterpret_cast<bf16x8 *>(&ul[row * P + ch]) = u_lo;
         }
-        rs[tid / 8][tid % 8] = psc;
+        {
+            const int row = tid / 8, c = tid % 8;
+            rs[row][c] = (it0 + row < n && c < 5) ? Sh[(size_t)(it0 + row) * 8 + c] : 0.f;
+        }
         __syncthreads();
-        if (it0 + QS < n) fetch(it0 + QS);
 
         // ---- coefficients: lane (g, nn) holds the pairs (query it0 + 16s + 4g + r, key jk) --------------------
         bf16x8 s_hi, s_lo, e_hi, e_lo, p_hi, p_lo;
@@ -233,8 +221,9 @@ __global__ __launch_bounds__(256, 2) void bwd_rows_mfma_kernel(
     __shared__ __align__(16) bf16_t kt[KB * P], vt[KB * P];
 
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64, g = lane / 16, nn = lane % 16;
-    const int bh = blockIdx.y, b = bh / H, h = bh % H;
-    const int i0 = first_row + ((int)gridDim.x - 1 - (int)blockIdx.x) * 64;          // long rows first
+    // head on blockIdx.x (dispatched fastest), row block on y, longest rows first: see bwd_keys_mfma_kernel
+    const int bh = blockIdx.x, b = bh / H, h = bh % H;
+    const int i0 = first_row + ((int)gridDim.y - 1 - (int)blockIdx.y) * 64;
     const int iq = i0 + 16 * wave + nn, iqc = min(iq, n - 1);
     const size_t row = (size_t)bh * n + iqc;
     const bf16_t *Kh = Kg + b * sk.batch + h * sk.head;
@@ -406,7 +395,7 @@ hipError_t launch_rows(const BackwardProblem &p, const BackwardLayout &L, int fi
     const float *U = reinterpret_cast<const float *>(base + L.u);
     float *R = reinterpret_cast<float *>(base + L.r);
     float *Sc = reinterpret_cast<float *>(base + L.sc);
-    hipLaunchKernelGGL((bwd_rows_mfma_kernel<DD, MODE>), dim3((p.n - first_row + 63) / 64, p.B * p.H), dim3(256), 0, p.stream,
+    hipLaunchKernelGGL((bwd_rows_mfma_kernel<DD, MODE>), dim3(p.B * p.H, (p.n - first_row + 63) / 64), dim3(256), 0, p.stream,
                        static_cast<const bf16_t *>(p.Q), static_cast<const bf16_t *>(p.K), static_cast<const bf16_t *>(p.V),
                        static_cast<const bf16_t *>(p.dO), p.sq, p.sk, p.sv, p.sdo, p.H, p.n, first_row, L.npad, p.scale,
                        p.lambda, p.lambda_rows, M, Y, U, R, Sc, p.dQ, p.dlambda);
@@ -434,7 +423,7 @@ hipError_t mfma_backward_keys(const BackwardProblem &p, const BackwardLayout &L)
     const float *Sc = reinterpret_cast<const float *>(base + L.sc);
     const bf16_t *Q = static_cast<const bf16_t *>(p.Q), *K = static_cast<const bf16_t *>(p.K),
                  *V = static_cast<const bf16_t *>(p.V), *G = static_cast<const bf16_t *>(p.dO);
-    dim3 grid((p.n + 63) / 64, p.B * p.H);
+    dim3 grid(p.B * p.H, (p.n + 63) / 64);
     if (p.d == 64)
         hipLaunchKernelGGL((bwd_keys_mfma_kernel<64>), grid, dim3(256), 0, p.stream, Q, K, V, G, p.sq, p.sk, p.sv, p.sdo,
                            p.H, p.n, p.scale, Y, U, Sc, p.dK, p.dV);
