@@ -136,7 +136,8 @@ llla_status llla_forward_ex(const void *Q, const void *K, const void *V, void *O
         !strides_aligned(sk, in) || !strides_aligned(sv, in) || !strides_aligned(so, out))
         return LLLA_ERR_ALIGN;
 
-    const bool has_mfma = llla::mfma_forward_supported(d, in, causal != 0);
+    // the matrix-core sweeps put their 64-row blocks on grid.y: at most 65535 of them
+    const bool has_mfma = llla::mfma_forward_supported(d, in, causal != 0) && (n + 63) / 64 <= kMaxGridY;
     if (path == LLLA_PATH_MFMA && !has_mfma) return LLLA_ERR_UNSUPPORTED;
     const bool use_mfma = has_mfma && path != LLLA_PATH_VALU;
     if (use_mfma) {
@@ -203,7 +204,7 @@ llla_status llla_forward_cg(const void *Q, const void *K, const void *V, void *O
         (reinterpret_cast<uintptr_t>(rho) & 3u) || (reinterpret_cast<uintptr_t>(delta) & 3u) ||
         (reinterpret_cast<uintptr_t>(steps) & 3u))
         return LLLA_ERR_ALIGN;
-    if (!llla::mfma_forward_supported(d, in, true)) return LLLA_ERR_UNSUPPORTED;
+    if (!llla::mfma_forward_supported(d, in, true) || (n + 63) / 64 > kMaxGridY) return LLLA_ERR_UNSUPPORTED;
     st = check_workspace(llla::mfma_forward_cg_workspace_bytes(B, H, n, d, in), workspace, workspace_bytes);
     if (st != LLLA_OK) return st;
 
@@ -246,7 +247,8 @@ llla_status llla_backward(const void *Q, const void *K, const void *V, const voi
         (reinterpret_cast<uintptr_t>(lambda_rows) & 3u))
         return LLLA_ERR_ALIGN;
     if (path != LLLA_PATH_AUTO && path != LLLA_PATH_VALU && path != LLLA_PATH_MFMA) return LLLA_ERR_PARAM;
-    if (path == LLLA_PATH_MFMA && !llla::mfma_forward_supported(d, in, true)) return LLLA_ERR_UNSUPPORTED;
+    if (path == LLLA_PATH_MFMA && (!llla::mfma_forward_supported(d, in, true) || (n + 63) / 64 > kMaxGridY))
+        return LLLA_ERR_UNSUPPORTED;
     st = check_workspace(llla::backward_workspace_bytes(B, H, n, d, in, path), workspace, workspace_bytes);
     if (st != LLLA_OK) return st;
 

@@ -113,9 +113,11 @@ __global__ __launch_bounds__(256) void sweep_kernel(const bf16_t *__restrict__ Q
     __shared__ __align__(16) bf16_t kn[KB * KN_PITCH];
     __shared__ __align__(16) bf16_t vt[MAXONLY ? 8 : DD * VT_PITCH];
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64, g = lane / 16, nn = lane % 16;
-    const int bh = blockIdx.y, b = bh / H, h = bh % H;
-    const int nqb = gridDim.x;
-    const int i0 = first_row + (nqb - 1 - (int)blockIdx.x) * 64;      // long rows first
+    // head on blockIdx.x (dispatched fastest), query block on y, longest rows first: every head's longest blocks
+    // start first and the short ones fill the tail (with the head on y the last head's longest block ran alone)
+    const int bh = blockIdx.x, b = bh / H, h = bh % H;
+    const int nqb = gridDim.y;
+    const int i0 = first_row + (nqb - 1 - (int)blockIdx.y) * 64;
     const int iq = i0 + wave * 16 + nn;                                // this lane's query
     const int iqc = min(iq, n - 1);
     const bf16_t *Kh = Kg + b * sk.batch + h * sk.head;
@@ -741,7 +743,7 @@ hipError_t forward_impl(const Problem &p)
     hipLaunchKernelGGL((prep_kernel<DD>), dim3(L.nkb, bh), dim3(256), 0, p.stream, K, V, p.sk, p.sv, p.H, p.n, L.nkb, KT, VT);
     const int nq64 = (p.n + 63) / 64;
     stage_mark(p.stream, "rowmax");
-    hipLaunchKernelGGL((sweep_kernel<true, DD>), dim3(nq64, bh), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
+    hipLaunchKernelGGL((sweep_kernel<true, DD>), dim3(bh, nq64), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
                        0, cscale, VT, M, Y, p.O, p.so, 0);
     const int nqb = (p.n + S::QB - 1) / S::QB;
     stage_mark(p.stream, "moments");
@@ -760,7 +762,7 @@ hipError_t forward_impl(const Problem &p)
     if (first < p.n) {
         const int nq64b = (p.n - first + 63) / 64;
         stage_mark(p.stream, "output");
-        hipLaunchKernelGGL((sweep_kernel<false, DD>), dim3(nq64b, bh), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n,
+        hipLaunchKernelGGL((sweep_kernel<false, DD>), dim3(bh, nq64b), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n,
                            L.nkb, first, cscale, VT, M, Y, p.O, p.so, p.out == LLLA_BF16 ? 1 : 0);
     }
     return hipGetLastError();
@@ -928,16 +930,16 @@ hipError_t forward_cg_impl(const Problem &p, int T, float eps, int32_t *iters)
     hipLaunchKernelGGL((prep_kernel<DD>), dim3(L.nkb, bh), dim3(256), 0, p.stream, K, V, p.sk, p.sv, p.H, p.n, L.nkb, KT, VT);
     hipLaunchKernelGGL((prep_kernel<DD>), dim3(L.nkb, bh), dim3(256), 0, p.stream, K, K, p.sk, p.sk, p.H, p.n, L.nkb, KT, KTB);
     stage_mark(p.stream, "rowmax");
-    hipLaunchKernelGGL((sweep_kernel<true, DD>), dim3(nq64, bh), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
+    hipLaunchKernelGGL((sweep_kernel<true, DD>), dim3(bh, nq64), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
                        0, cscale, VT, M, Y, p.O, p.so, 0);
     stage_mark(p.stream, "first_moment");       // omega = sum w, mu~ = sum w k: plain weights times the K tile
-    hipLaunchKernelGGL((sweep_kernel<false, DD>), dim3(nq64, bh), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
+    hipLaunchKernelGGL((sweep_kernel<false, DD>), dim3(bh, nq64), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
                        0, cscale, KTB, M, (const float *)nullptr, (void *)MUt, dense, 0, OM);
     hipLaunchKernelGGL((cg_rows_kernel<DD, 0>), rows_grid, dim3(256), 0, p.stream, Q, p.sq, p.H, p.n, p.lambda, eps, MUt, OM,
                        X, R, P, SP, RR, IT, Y, p.rho, p.delta, iters);
     stage_mark(p.stream, "cg_steps");
     for (int t = 0; t < T; ++t) {
-        hipLaunchKernelGGL((sweep_kernel<false, DD>), dim3(nq64, bh), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n,
+        hipLaunchKernelGGL((sweep_kernel<false, DD>), dim3(bh, nq64), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n,
                            L.nkb, 0, cscale, KTB, M, (const float *)P, (void *)SP, dense, 0, (float *)nullptr);
         hipLaunchKernelGGL((cg_rows_kernel<DD, 1>), rows_grid, dim3(256), 0, p.stream, Q, p.sq, p.H, p.n, p.lambda, eps, MUt,
                            OM, X, R, P, SP, RR, IT, Y, p.rho, p.delta, iters);
@@ -951,7 +953,7 @@ hipError_t forward_cg_impl(const Problem &p, int T, float eps, int32_t *iters)
     if (e != hipSuccess) return e;
     if (first < p.n) {
         stage_mark(p.stream, "output");
-        hipLaunchKernelGGL((sweep_kernel<false, DD>), dim3((p.n - first + 63) / 64, bh), dim3(256), 0, p.stream, Q, K, p.sq, p.sk,
+        hipLaunchKernelGGL((sweep_kernel<false, DD>), dim3(bh, (p.n - first + 63) / 64), dim3(256), 0, p.stream, Q, K, p.sq, p.sk,
                            p.H, p.n, L.nkb, first, cscale, VT, M, (const float *)Y, p.O, p.so, p.out == LLLA_BF16 ? 1 : 0,
                            (float *)nullptr);
     }
@@ -973,7 +975,7 @@ hipError_t backward_rowmax_impl(const BackwardProblem &p, const BackwardLayout &
     stage_mark(p.stream, "prep");
     hipLaunchKernelGGL((prep_kernel<DD>), dim3(L.nkb, bh), dim3(256), 0, p.stream, K, V, p.sk, p.sv, p.H, p.n, L.nkb, KT, VT);
     stage_mark(p.stream, "rowmax");
-    hipLaunchKernelGGL((sweep_kernel<true, DD>), dim3((p.n + 63) / 64, bh), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H,
+    hipLaunchKernelGGL((sweep_kernel<true, DD>), dim3(bh, (p.n + 63) / 64), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H,
                        p.n, L.nkb, 0, p.scale * LOG2E, VT, M, Y, (void *)nullptr, llla_strides{0, 0, 0}, 0, (float *)nullptr);
     return hipGetLastError();
 }
