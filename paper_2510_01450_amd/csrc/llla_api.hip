@@ -37,6 +37,7 @@ llla_status check_common(int B, int H, int n, int d, llla_dtype in, llla_dtype o
     if (!dtype_ok(in) || !dtype_ok(out)) return LLLA_ERR_DTYPE;
     if (!dim_supported(d)) return LLLA_ERR_UNSUPPORTED;
     if ((int64_t)B * H > kMaxGridY) return LLLA_ERR_SHAPE;
+    if ((int64_t)B * H * n > 2147483647LL) return LLLA_ERR_SHAPE;       // one-dimensional grids index (head, row block) pairs
     if (!(lambda > 0.f) || !std::isfinite(lambda) || !std::isfinite(scale)) return LLLA_ERR_PARAM;
     return LLLA_OK;
 }

@@ -38,7 +38,7 @@ template <int D, typename TI>
 __global__ __launch_bounds__(NT) void bwd_rows_kernel(const TI *__restrict__ Qg, const TI *__restrict__ Kg,
                                                       const TI *__restrict__ Vg, const TI *__restrict__ Gg,
                                                       llla_strides sq, llla_strides sk, llla_strides sv,
-                                                      llla_strides sg, int H, int n, float lambda,
+                                                      llla_strides sg, int H, int nbh, int n, float lambda,
                                                       const float *__restrict__ LamRows, float scale,
                                                       float *__restrict__ Rec, float *__restrict__ dQ,
                                                       float *__restrict__ dLam)
@@ -73,14 +73,15 @@ __global__ __launch_bounds__(NT) void bwd_rows_kernel(const TI *__restrict__ Qg,
     const int slot = tid / TPQ;
     const int r = tid % TPQ;
     const int ta = r / TG, tb = r % TG;
-    const int bh = blockIdx.y;
+    // one-dimensional grid, (batch, head) index fastest: the longest query blocks of every head are dispatched first
+    const int bh = (int)(blockIdx.x % (unsigned)nbh);
     const int b = bh / H, h = bh % H;
 
     const TI *Kh = Kg + b * sk.batch + h * sk.head;
     const TI *Vh = Vg + b * sv.batch + h * sv.head;
 
-    const int nqb = gridDim.x;
-    const int i0 = (nqb - 1 - (int)blockIdx.x) * QB;    // long rows are scheduled first
+    const int nqb = (int)(gridDim.x / (unsigned)nbh);
+    const int i0 = (nqb - 1 - (int)(blockIdx.x / (unsigned)nbh)) * QB;
     const int my_i = i0 + slot;
     const bool slot_live = my_i < n;
     const int kend = min(n, i0 + QB);
@@ -517,7 +518,7 @@ template <int D, typename TI>
 __global__ __launch_bounds__(NT) void bwd_keys_kernel(const TI *__restrict__ Qg, const TI *__restrict__ Kg,
                                                       const TI *__restrict__ Vg, const TI *__restrict__ Gg,
                                                       llla_strides sq, llla_strides sk, llla_strides sv,
-                                                      llla_strides sg, int H, int n, float scale,
+                                                      llla_strides sg, int H, int nbh, int n, float scale,
                                                       const float *__restrict__ Y1, const float *__restrict__ U1,
                                                       int vpitch, const float *__restrict__ Sc, int spitch,
                                                       float *__restrict__ dK, float *__restrict__ dV)
@@ -542,9 +543,10 @@ __global__ __launch_bounds__(NT) void bwd_keys_kernel(const TI *__restrict__ Qg,
     float *rs = cp + QT * CP;                             // [QT][8]  y0, u0, m, correction, argmax
 
     const int tid = threadIdx.x;
-    const int bh = blockIdx.y;
+    // one-dimensional grid, (batch, head) index fastest; low key blocks see the most rows: they go first for every head
+    const int bh = (int)(blockIdx.x % (unsigned)nbh);
     const int b = bh / H, h = bh % H;
-    const int j0 = (int)blockIdx.x * KB;                 // low key blocks see the most rows: they go first
+    const int j0 = (int)(blockIdx.x / (unsigned)nbh) * KB;
     const TI *Qh = Qg + b * sq.batch + h * sq.head;
     const TI *Gh = Gg + b * sg.batch + h * sg.head;
     const float *Y1h = Y1 + (size_t)bh * n * vpitch, *U1h = U1 + (size_t)bh * n * vpitch;
@@ -655,16 +657,16 @@ hipError_t launch_backward(const BackwardProblem &p)
     constexpr int REC = rec_floats<D>();
     float *rec = static_cast<float *>(p.ws);
     stage_mark(p.stream, "backward_rows");
-    dim3 grid_rows((p.n + Cfg<D>::QB - 1) / Cfg<D>::QB, p.B * p.H);
+    dim3 grid_rows((p.n + Cfg<D>::QB - 1) / Cfg<D>::QB * p.B * p.H);
     hipLaunchKernelGGL((bwd_rows_kernel<D, TI>), grid_rows, dim3(NT), 0, p.stream, (const TI *)p.Q, (const TI *)p.K,
-                       (const TI *)p.V, (const TI *)p.dO, p.sq, p.sk, p.sv, p.sdo, p.H, p.n, p.lambda, p.lambda_rows,
+                       (const TI *)p.V, (const TI *)p.dO, p.sq, p.sk, p.sv, p.sdo, p.H, p.B * p.H, p.n, p.lambda, p.lambda_rows,
                        p.scale, rec, p.dQ, p.dlambda);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     stage_mark(p.stream, "backward_keys");
-    dim3 grid_keys((p.n + KeyCfg<D>::KB - 1) / KeyCfg<D>::KB, p.B * p.H);
+    dim3 grid_keys((p.n + KeyCfg<D>::KB - 1) / KeyCfg<D>::KB * p.B * p.H);
     hipLaunchKernelGGL((bwd_keys_kernel<D, TI>), grid_keys, dim3(NT), 0, p.stream, (const TI *)p.Q, (const TI *)p.K,
-                       (const TI *)p.V, (const TI *)p.dO, p.sq, p.sk, p.sv, p.sdo, p.H, p.n, p.scale, (const float *)rec,
+                       (const TI *)p.V, (const TI *)p.dO, p.sq, p.sk, p.sv, p.sdo, p.H, p.B * p.H, p.n, p.scale, (const float *)rec,
                        (const float *)rec + D, REC, (const float *)rec + 2 * D, REC, p.dK, p.dV);
     return hipGetLastError();
 }

@@ -23,8 +23,8 @@ namespace {
 
 using namespace valu;
 
-// Kernel.  DECODE = false: grid.x = ceil(n/QB) query blocks (heaviest first), grid.y = B*H.
-//          DECODE = true : grid.x = 1, grid.y = B*H; all slots share the query and split the keys.
+// Kernel.  DECODE = false: grid.x = ceil(n/QB) query blocks (heaviest first) x B*H, the (batch, head) index fastest.
+//          DECODE = true : grid.x = B*H; all slots share the query and split the keys.
 //          GIVEN  = true : (forward only) the per-row solution y and row maximum are read from
 //                          device memory (written by the MFMA moments kernel); only sweep 3 runs.
 template <int D, typename TI, typename TO, bool DECODE, bool GIVEN = false>
@@ -32,7 +32,7 @@ __global__ __launch_bounds__(NT) void valu_kernel(const TI *__restrict__ Qg, con
                                                   const TI *__restrict__ Vg, TO *__restrict__ Og,
                                                   llla_strides sq, llla_strides sk, llla_strides sv,
                                                   llla_strides so, const int32_t *__restrict__ seqlens,
-                                                  int H, int n, int causal, float lambda, float scale,
+                                                  int H, int nbh, int n, int causal, float lambda, float scale,
                                                   const float *__restrict__ Mg = nullptr, int mpitch = 0,
                                                   const float *__restrict__ Yg = nullptr, int ypitch = 0,
                                                   const float *__restrict__ LamRows = nullptr,
@@ -64,7 +64,9 @@ __global__ __launch_bounds__(NT) void valu_kernel(const TI *__restrict__ Qg, con
     const int slot = tid / TPQ;
     const int r = tid % TPQ;
     const int ta = r / TG, tb = r % TG;
-    const int bh = blockIdx.y;
+    // one-dimensional grid, (batch, head) index fastest: blocks are dispatched in that order, so the longest query
+    // blocks of every head start first and the short ones fill the tail
+    const int bh = (int)(blockIdx.x % (unsigned)nbh);
     const int b = bh / H, h = bh % H;
 
     const TI *Kh = Kg + b * sk.batch + h * sk.head;
@@ -77,8 +79,8 @@ __global__ __launch_bounds__(NT) void valu_kernel(const TI *__restrict__ Qg, con
         nkeys = nkeys < 1 ? 1 : (nkeys > n ? n : nkeys);
     } else {
         nkeys = n;
-        const int nqb = gridDim.x;
-        i0 = (nqb - 1 - (int)blockIdx.x) * QB;          // long rows are scheduled first
+        const int nqb = (int)(gridDim.x / (unsigned)nbh);
+        i0 = (nqb - 1 - (int)(blockIdx.x / (unsigned)nbh)) * QB;          // long rows are scheduled first
     }
     const int my_i = DECODE ? nkeys - 1 : i0 + slot;    // query row of this slot
     const bool slot_live = DECODE ? true : (my_i < n);
@@ -337,10 +339,10 @@ template <int D, typename TI, typename TO, bool DECODE>
 hipError_t launch(const Problem &p, int nrows)
 {
     using C = Cfg<D>;
-    dim3 grid(DECODE ? 1 : (nrows + C::QB - 1) / C::QB, p.B * p.H);
+    dim3 grid((DECODE ? 1 : (nrows + C::QB - 1) / C::QB) * p.B * p.H);
     hipLaunchKernelGGL((valu_kernel<D, TI, TO, DECODE>), grid, dim3(NT), 0, p.stream,
                        (const TI *)p.Q, (const TI *)p.K, (const TI *)p.V, (TO *)p.O, p.sq, p.sk, p.sv,
-                       p.so, p.seqlens, p.H, p.n, p.causal, p.lambda, p.scale, (const float *)nullptr, 0,
+                       p.so, p.seqlens, p.H, p.B * p.H, p.n, p.causal, p.lambda, p.scale, (const float *)nullptr, 0,
                        (const float *)nullptr, 0, DECODE ? nullptr : p.lambda_rows, DECODE ? nullptr : p.rho,
                        DECODE ? nullptr : p.delta);
     return hipGetLastError();
@@ -371,16 +373,16 @@ hipError_t launch_given(const Problem &p, int nrows, const float *M, int mpitch,
 {
     using C = Cfg<D>;
     nrows = nrows < p.n ? nrows : p.n;
-    dim3 grid((nrows + C::QB - 1) / C::QB, p.B * p.H);
+    dim3 grid((nrows + C::QB - 1) / C::QB * p.B * p.H);
     if (p.out == LLLA_F32)
         hipLaunchKernelGGL((valu_kernel<D, bf16_t, float, false, true>), grid, dim3(NT), 0, p.stream,
                            (const bf16_t *)p.Q, (const bf16_t *)p.K, (const bf16_t *)p.V, (float *)p.O, p.sq, p.sk,
-                           p.sv, p.so, nullptr, p.H, p.n, 1, p.lambda, p.scale, M, mpitch, Y, ypitch, (const float *)nullptr,
+                           p.sv, p.so, nullptr, p.H, p.B * p.H, p.n, 1, p.lambda, p.scale, M, mpitch, Y, ypitch, (const float *)nullptr,
                            (float *)nullptr, (float *)nullptr);
     else
         hipLaunchKernelGGL((valu_kernel<D, bf16_t, bf16_t, false, true>), grid, dim3(NT), 0, p.stream,
                            (const bf16_t *)p.Q, (const bf16_t *)p.K, (const bf16_t *)p.V, (bf16_t *)p.O, p.sq, p.sk,
-                           p.sv, p.so, nullptr, p.H, p.n, 1, p.lambda, p.scale, M, mpitch, Y, ypitch, (const float *)nullptr,
+                           p.sv, p.so, nullptr, p.H, p.B * p.H, p.n, 1, p.lambda, p.scale, M, mpitch, Y, ypitch, (const float *)nullptr,
                            (float *)nullptr, (float *)nullptr);
     return hipGetLastError();
 }
