@@ -30,7 +30,7 @@ PEAK_HBM = 8.0e12             # B/s
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # same command, scaled with a copy kernel of known size (profiles/*_hbm_traffic.md, *_mfma_counters.md).
 MEASURED_TRAFFIC = {
-    ("C5_decode_bf16_L32768_d64", "decode_partial"): 4.329e9 + 0.111e9,
+    ("C5_decode_bf16_L32768_d64", "decode_partial"): 4.310e9 + 0.056e9,
     ("C3_prefill_bf16_n4096_d64", "moments"): 0.712e9 + 0.339e9,
 }
 

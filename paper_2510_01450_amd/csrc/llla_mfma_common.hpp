@@ -277,6 +277,18 @@ __device__ inline void dma16_base(const void *sbase, unsigned voff, void *lds_ba
     const unsigned lds = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void_ptr)lds_base);
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds) : "memory", "m0");
 }
+// The same two transfers with the non-temporal hint, for data that is read exactly once (the decode kernel's cache
+// stream): without it the stream stays about 10 % below what plain streaming loads reach on this part.
+__device__ inline void dma16_nt(const void *gsrc, void *lds_base)
+{
+    const unsigned lds = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void_ptr)lds_base);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt" ::"v"(gsrc), "s"(lds) : "memory", "m0");
+}
+__device__ inline void dma16_base_nt(const void *sbase, unsigned voff, void *lds_base)
+{
+    const unsigned lds = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void_ptr)lds_base);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt" ::"v"(voff), "s"(sbase), "s"(lds) : "memory", "m0");
+}
 #pragma clang diagnostic pop
 __device__ inline void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 

@@ -43,7 +43,9 @@ struct Split {
 Split make_split(int bh, int L)
 {
     Split s;
-    int want = (1024 + bh - 1) / bh;                 // aim at >= 1024 workgroups
+    // two workgroups per compute unit fit: with 512 (batch, head) pairs or more one workgroup per pair fills the GPU
+    // in a single round (a second round of equally long workgroups cost 5 % at the changeover)
+    int want = (512 + bh - 1) / bh;
     int most = L / (4 * 8 * STEP);                   // at least 8 steps per wave
     if (most < 1) most = 1;
     s.nsplit = want < 1 ? 1 : (want > most ? most : want);
@@ -133,7 +135,7 @@ __global__ __launch_bounds__(NT, 2) void decode_partial_kernel(const bf16_t *__r
     const int rot = nsteps > 0 ? (int)((part * 7u + bh * 13u) % (unsigned)nsteps) : 0;
     auto step_pos = [&](int step) { const int t = step + rot; return t >= nsteps ? t - nsteps : t; };
     // addresses: a scalar base per step (row j0 of the head) plus per-lane byte offsets that never change, so a
-    // transfer costs no vector-ALU work; only a step that reaches past the sequence clamps its rows per lane
+    // transfer costs no vector-ALU work; the transfers carry the non-temporal hint (the cache is read once); only a step that reaches past the sequence clamps its rows per lane
     // (to the last valid row: their weights are 0)
     unsigned koff[4], voff[4];
 #pragma unroll
@@ -148,15 +150,15 @@ __global__ __launch_bounds__(NT, 2) void decode_partial_kernel(const bf16_t *__r
             const bf16_t *kb = Kh + (int64_t)j0 * sk.seq, *vb = Vh + (int64_t)j0 * sv.seq;
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                dma16_base(kb, koff[t], dst + 512 * t);
-                dma16_base(vb, voff[t], dst + TILE_H + 512 * t);
+                dma16_base_nt(kb, koff[t], dst + 512 * t);
+                dma16_base_nt(vb, voff[t], dst + TILE_H + 512 * t);
             }
         } else {
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const int j = min(j0 + dma_key[t], L - 1);
-                dma16(Kh + (int64_t)j * sk.seq + dma_col[t], dst + 512 * t);
-                dma16(Vh + (int64_t)j * sv.seq + dma_col[t], dst + TILE_H + 512 * t);
+                dma16_nt(Kh + (int64_t)j * sk.seq + dma_col[t], dst + 512 * t);
+                dma16_nt(Vh + (int64_t)j * sv.seq + dma_col[t], dst + TILE_H + 512 * t);
             }
         }
     };
