@@ -288,6 +288,24 @@ struct MomentsShared {
 template <int CH>
 __device__ inline int nat_swizzle(int key) { return CH == 8 ? ((key >> 1) & 7) : (key & 15); }
 
+// Which (batch-head, query block) a workgroup of the moments kernels serves.  Workgroups are handed to the 8 XCDs
+// (each with an L2 of its own) round-robin in dispatch order, blockIdx.x fastest.  With the plain mapping
+// (x = query block, y = head) the neighbouring query blocks of one head land on all 8 XCDs and every L2 fetches that
+// head's K tiles from memory for itself.  Here a group of 8 heads is spread over the 8 XCDs instead, one head per XCD,
+// and an XCD walks through the query blocks of its head (longest first) before the next group of heads starts: each
+// head's tiles are fetched by one L2 only.  Heads beyond the last full group of 8 keep the plain mapping.
+struct BlockMap { int bh, qblk; };
+__device__ inline BlockMap moments_block_map()
+{
+    const int nqb = (int)gridDim.x, nbh = (int)gridDim.y;
+    const long long lin = (long long)blockIdx.y * nqb + blockIdx.x;
+    const long long grouped = (long long)(nbh & ~7) * nqb;
+    if (lin >= grouped) return BlockMap{(int)blockIdx.y, (int)blockIdx.x};
+    const int xcd = (int)(lin & 7);
+    const long long k = lin >> 3;
+    return BlockMap{(int)(k / nqb) * 8 + xcd, (int)(k % nqb)};
+}
+
 // PRECISE: fp32 weights and a two-term f16 split of the scaled operand w k, i.e. an fp32-accurate
 // second moment; used for the first rows of a sequence, whose systems are the worst conditioned.
 // WITH_U (the backward pass): Rg holds, per row, r1 (DD floats) and r0 at [DD] (pitch YP); the solve then also
@@ -318,9 +336,10 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     auto &sc = sm.sc;
 
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64, g = lane / 16, nn = lane % 16;
-    const int bh = blockIdx.y, b = bh / H, h = bh % H;
+    const BlockMap bm = moments_block_map();
+    const int bh = bm.bh, b = bh / H, h = bh % H;
     const int nqb = gridDim.x;
-    const int i0 = (nqb - 1 - (int)blockIdx.x) * QB;                   // long rows first
+    const int i0 = (nqb - 1 - bm.qblk) * QB;                           // long rows first
     const int ilast = min(i0 + QB - 1, n - 1);
     const int nblk = ilast / KB2 + 1;                                  // blocks of 64 keys
     const int mpitch = nkb * KB;
@@ -674,7 +693,7 @@ __global__ __launch_bounds__(Shape<DD>::NT, DD == 64 ? 2 : 1) void moments_kerne
     const float *__restrict__ Mg, float *__restrict__ Yg)
 {
     __shared__ __align__(16) MomentsShared<DD> sm;
-    const int i0 = ((int)gridDim.x - 1 - (int)blockIdx.x) * Shape<DD>::QB;
+    const int i0 = ((int)gridDim.x - 1 - moments_block_map().qblk) * Shape<DD>::QB;
     if (i0 < precise_rows) moments_body<true, DD>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg);
     else moments_body<false, DD>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg);
 }
@@ -687,7 +706,7 @@ __global__ __launch_bounds__(Shape<DD>::NT, DD == 64 ? 2 : 1) void moments_u_ker
     const float *__restrict__ Mg, float *__restrict__ Yg, const float *__restrict__ Rg, float *__restrict__ Ug)
 {
     __shared__ __align__(16) MomentsShared<DD> sm;
-    const int i0 = ((int)gridDim.x - 1 - (int)blockIdx.x) * Shape<DD>::QB;
+    const int i0 = ((int)gridDim.x - 1 - moments_block_map().qblk) * Shape<DD>::QB;
     if (i0 < precise_rows)
         moments_body<true, DD, true>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg, Rg, Ug);
     else
