@@ -747,7 +747,7 @@ size_t backward_workspace_bytes(int B, int H, int n, int d, llla_dtype in, llla_
 
 hipError_t backward(const BackwardProblem &p, llla_path path)
 {
-    // the matrix-core key sweep puts its key blocks on grid.y (at most 65535 of them, i.e. n <= 4 194 240)
+    // the matrix-core sweeps put their 64-row blocks on grid.y (at most 65535 of them, i.e. n <= 4 194 240)
     const bool use_mfma = path != LLLA_PATH_VALU && mfma_forward_supported(p.d, p.in, true) && (p.n + 63) / 64 <= 65535;
     stage_begin(p.stream);
     hipError_t err;

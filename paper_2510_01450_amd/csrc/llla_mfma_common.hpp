@@ -33,6 +33,26 @@ struct Shape {
     __host__ __device__ static constexpr int tix(int I, int J) { return I * NB - I * (I - 1) / 2 + (J - I); }
 };
 
+// Which (batch-head, block) a workgroup serves in a grid (blocks, heads).  Workgroups are handed to the 8 XCDs (each
+// with an L2 of its own) round-robin in dispatch order, blockIdx.x fastest.  With the plain mapping the neighbouring
+// blocks of one head land on all 8 XCDs and every L2 fetches that head's tiles for itself.  Here a group of 8 heads
+// is spread over the 8 XCDs, one head per XCD, and an XCD walks through the blocks of its head in the order given
+// (callers put the longest first) before the next group of heads starts: each head's tiles are fetched by one L2
+// only.  Heads beyond the last full group of 8 keep the plain mapping.  Used by the moments kernels (16 or 8 rows per
+// workgroup, hundreds of workgroups per head).  The 64-row sweeps do not use it: all blocks of a head fit an XCD at
+// once, they would start together and the XCD would wait for the longest; those kernels put the head on blockIdx.x.
+struct BlockMap { int bh, blk; };
+__device__ inline BlockMap xcd_block_map()
+{
+    const int nblk = (int)gridDim.x, nbh = (int)gridDim.y;
+    const long long lin = (long long)blockIdx.y * nblk + blockIdx.x;
+    const long long grouped = (long long)(nbh & ~7) * nblk;
+    if (lin >= grouped) return BlockMap{(int)blockIdx.y, (int)blockIdx.x};
+    const int xcd = (int)(lin & 7);
+    const long long k = lin >> 3;
+    return BlockMap{(int)(k / nblk) * 8 + xcd, (int)(k % nblk)};
+}
+
 __device__ inline void wave_sync()
 {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");

@@ -114,7 +114,9 @@ __global__ __launch_bounds__(256) void sweep_kernel(const bf16_t *__restrict__ Q
     __shared__ __align__(16) bf16_t vt[MAXONLY ? 8 : DD * VT_PITCH];
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64, g = lane / 16, nn = lane % 16;
     // head on blockIdx.x (dispatched fastest), query block on y, longest rows first: every head's longest blocks
-    // start first and the short ones fill the tail (with the head on y the last head's longest block ran alone)
+    // start first and the short ones fill the tail.  (With the head on y the last head's longest block ran alone at the
+    // end; with the XCD-grouped mapping of the moments kernel a head's 64-row blocks all start at once and the XCD
+    // waits for the longest: both measured slower.)  Heads that are a multiple of 8 apart share an XCD and its L2.
     const int bh = blockIdx.x, b = bh / H, h = bh % H;
     const int nqb = gridDim.y;
     const int i0 = first_row + (nqb - 1 - (int)blockIdx.y) * 64;
@@ -288,22 +290,14 @@ struct MomentsShared {
 template <int CH>
 __device__ inline int nat_swizzle(int key) { return CH == 8 ? ((key >> 1) & 7) : (key & 15); }
 
-// Which (batch-head, query block) a workgroup of the moments kernels serves.  Workgroups are handed to the 8 XCDs
-// (each with an L2 of its own) round-robin in dispatch order, blockIdx.x fastest.  With the plain mapping
-// (x = query block, y = head) the neighbouring query blocks of one head land on all 8 XCDs and every L2 fetches that
-// head's K tiles from memory for itself.  Here a group of 8 heads is spread over the 8 XCDs instead, one head per XCD,
-// and an XCD walks through the query blocks of its head (longest first) before the next group of heads starts: each
-// head's tiles are fetched by one L2 only.  Heads beyond the last full group of 8 keep the plain mapping.
-struct BlockMap { int bh, qblk; };
-__device__ inline BlockMap moments_block_map()
+// (head, query block) of a workgroup of the moments kernels: XCD-aware at d = 64 (see xcd_block_map; HBM reads of the
+// kernel 0.71 -> 0.14 GB at [4,16,4096,64], 3 % faster there and 10 % with 1024 short heads); at d = 128 the plain
+// mapping (x = query block, y = head) measured 2 % faster and is kept.
+template <int DD>
+__device__ inline BlockMap moments_block()
 {
-    const int nqb = (int)gridDim.x, nbh = (int)gridDim.y;
-    const long long lin = (long long)blockIdx.y * nqb + blockIdx.x;
-    const long long grouped = (long long)(nbh & ~7) * nqb;
-    if (lin >= grouped) return BlockMap{(int)blockIdx.y, (int)blockIdx.x};
-    const int xcd = (int)(lin & 7);
-    const long long k = lin >> 3;
-    return BlockMap{(int)(k / nqb) * 8 + xcd, (int)(k % nqb)};
+    if (DD == 64) return xcd_block_map();
+    return BlockMap{(int)blockIdx.y, (int)blockIdx.x};
 }
 
 // PRECISE: fp32 weights and a two-term f16 split of the scaled operand w k, i.e. an fp32-accurate
@@ -336,10 +330,10 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     auto &sc = sm.sc;
 
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64, g = lane / 16, nn = lane % 16;
-    const BlockMap bm = moments_block_map();
+    const BlockMap bm = moments_block<DD>();
     const int bh = bm.bh, b = bh / H, h = bh % H;
     const int nqb = gridDim.x;
-    const int i0 = (nqb - 1 - bm.qblk) * QB;                           // long rows first
+    const int i0 = (nqb - 1 - bm.blk) * QB;                           // long rows first
     const int ilast = min(i0 + QB - 1, n - 1);
     const int nblk = ilast / KB2 + 1;                                  // blocks of 64 keys
     const int mpitch = nkb * KB;
@@ -693,7 +687,7 @@ __global__ __launch_bounds__(Shape<DD>::NT, DD == 64 ? 2 : 1) void moments_kerne
     const float *__restrict__ Mg, float *__restrict__ Yg)
 {
     __shared__ __align__(16) MomentsShared<DD> sm;
-    const int i0 = ((int)gridDim.x - 1 - moments_block_map().qblk) * Shape<DD>::QB;
+    const int i0 = ((int)gridDim.x - 1 - moments_block<DD>().blk) * Shape<DD>::QB;
     if (i0 < precise_rows) moments_body<true, DD>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg);
     else moments_body<false, DD>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg);
 }
@@ -706,7 +700,7 @@ __global__ __launch_bounds__(Shape<DD>::NT, DD == 64 ? 2 : 1) void moments_u_ker
     const float *__restrict__ Mg, float *__restrict__ Yg, const float *__restrict__ Rg, float *__restrict__ Ug)
 {
     __shared__ __align__(16) MomentsShared<DD> sm;
-    const int i0 = ((int)gridDim.x - 1 - moments_block_map().qblk) * Shape<DD>::QB;
+    const int i0 = ((int)gridDim.x - 1 - moments_block<DD>().blk) * Shape<DD>::QB;
     if (i0 < precise_rows)
         moments_body<true, DD, true>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg, Rg, Ug);
     else
