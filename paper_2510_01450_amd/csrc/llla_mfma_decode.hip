@@ -38,6 +38,8 @@ struct Split {
     int nsplit;          // workgroups per head
     int keys_per_wave;   // multiple of STEP
     int nparts;          // partials per head = 4 * nsplit
+    int group;           // partials merged by one wave of the combine stage (0: no combine stage)
+    int ngroups;         // partials per head that reach the merge kernel
 };
 
 Split make_split(int bh, int L)
@@ -49,10 +51,18 @@ Split make_split(int bh, int L)
     int most = L / (4 * 8 * STEP);                   // at least 8 steps per wave
     if (most < 1) most = 1;
     s.nsplit = want < 1 ? 1 : (want > most ? most : want);
-    if (s.nsplit > 8) s.nsplit = 8;
+    if (s.nsplit > 16) s.nsplit = 16;
     const int waves = 4 * s.nsplit;
     s.keys_per_wave = ((L + waves - 1) / waves + STEP - 1) / STEP * STEP;
     s.nparts = waves;
+    // few heads with long caches are cut into many partials; the merge kernel sums a head's partials one after the
+    // other, so beyond 16 of them a combine stage first merges groups of about sqrt(nparts) in parallel
+    s.group = 0;
+    s.ngroups = s.nparts;
+    if (s.nparts > 16) {
+        s.group = s.nparts >= 64 ? 8 : 6;
+        s.ngroups = (s.nparts + s.group - 1) / s.group;
+    }
     return s;
 }
 
@@ -258,6 +268,44 @@ __global__ __launch_bounds__(NT, 2) void decode_partial_kernel(const bf16_t *__r
     for (int t = 0; t < 16; ++t) *reinterpret_cast<f32x4 *>(P + 192 + (10 + t) * 256 + lane * 4) = gt[t];
 }
 
+// Combine stage for heads with many partials: one wave merges partials [g * group, (g + 1) * group) of a head into a
+// single record of the same format (the merge step of Algorithm 1's running maximum), so that the merge kernel's
+// sequential sum over a head's partials stays short.  grid.x = groups, grid.y = heads, 4 waves = 4 groups per block.
+// (at most two waves per SIMD: the scheduler otherwise keeps the register count low for occupancy and waits for every
+// load before it issues the next)
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 2))) void decode_combine_kernel(const float *__restrict__ parts, float *__restrict__ parts2,
+                                                            int nparts, int group, int ngroups)
+{
+    // the wave index as a scalar: the loop bounds below are then uniform and the loads of an iteration are issued together
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64), lane = threadIdx.x % 64;
+    const int gi = (int)blockIdx.x * 4 + wave, bh = blockIdx.y;
+    if (gi >= ngroups) return;
+    const int p0 = gi * group, p1 = min(p0 + group, nparts);
+    const float *P0 = parts + (size_t)bh * nparts * PART_F;
+    float mstar = -INFINITY;
+    for (int p = p0; p < p1; ++p) mstar = fmaxf(mstar, P0[(size_t)p * PART_F]);
+    float om = 0.f, mu = 0.f, yv = 0.f;
+    f32x4 acc[NTILES];
+#pragma unroll
+    for (int t = 0; t < NTILES; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int p = p0; p < p1; ++p) {
+        const float *P = P0 + (size_t)p * PART_F;
+        const float mp = P[0];
+        const float f = (mp == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mp - mstar);
+        om = fmaf(f, P[1], om);
+        mu = fmaf(f, P[64 + lane], mu);
+        yv = fmaf(f, P[128 + lane], yv);
+#pragma unroll
+        for (int t = 0; t < NTILES; ++t) acc[t] += f * *reinterpret_cast<const f32x4 *>(P + 192 + t * 256 + lane * 4);
+    }
+    float *R = parts2 + ((size_t)bh * ngroups + gi) * PART_F;
+    if (lane == 0) { R[0] = mstar; R[1] = om; }
+    R[64 + lane] = mu;
+    R[128 + lane] = yv;
+#pragma unroll
+    for (int t = 0; t < NTILES; ++t) *reinterpret_cast<f32x4 *>(R + 192 + t * 256 + lane * 4) = acc[t];
+}
+
 // Merge, solve, output for 4 heads per workgroup (4 waves):
 //   phase 1  wave w sums the partial moments of head 4*block + w with the max-rescale factors
 //            2^(m_p - m*) into LDS (the merge step of Algorithm 1's running maximum);
@@ -370,7 +418,8 @@ size_t mfma_decode_workspace_bytes(int B, int H, int L_max, int d, llla_dtype in
 {
     if (!mfma_decode_supported(d, in) || L_max < MIN_L) return 0;
     const Split s = make_split(B * H, L_max);
-    return round_up((size_t)B * H * s.nparts * PART_F * sizeof(float), 256);
+    const size_t records = (size_t)s.nparts + (s.group ? s.ngroups : 0);
+    return round_up((size_t)B * H * records * PART_F * sizeof(float), 256);
 }
 
 bool mfma_decode_takes(const Problem &p)
@@ -389,9 +438,17 @@ hipError_t mfma_decode(const Problem &p)
     stage_mark(p.stream, "decode_partial");
     hipLaunchKernelGGL(decode_partial_kernel, dim3(s.nsplit, bh), dim3(NT), 0, p.stream, (const bf16_t *)p.Q,
                        (const bf16_t *)p.K, (const bf16_t *)p.V, p.sk, p.sv, p.seqlens, p.H, p.n, s.nparts, cscale, parts);
+    const float *merge_in = parts;
+    if (s.group) {
+        float *parts2 = parts + (size_t)bh * s.nparts * PART_F;
+        stage_mark(p.stream, "decode_combine");
+        hipLaunchKernelGGL(decode_combine_kernel, dim3((s.ngroups + 3) / 4, bh), dim3(NT), 0, p.stream, (const float *)parts,
+                           parts2, s.nparts, s.group, s.ngroups);
+        merge_in = parts2;
+    }
     stage_mark(p.stream, "decode_merge");
     hipLaunchKernelGGL(decode_merge_kernel, dim3((bh + QW - 1) / QW), dim3(NT), 0, p.stream, (const bf16_t *)p.Q,
-                       parts, bh, s.nparts, p.lambda, p.O, p.out == LLLA_BF16 ? 1 : 0);
+                       merge_in, bh, s.ngroups, p.lambda, p.O, p.out == LLLA_BF16 ? 1 : 0);
     return hipGetLastError();
 }
 

@@ -163,9 +163,10 @@ def test_decode_matches_oracle(L, d, dtype, path):
     print(check(got[:, :, None, :], ref[:, :, None, :], rows, d, w.tol, "decode L=%d d=%d %s" % (L, d, dtype)))
 
 
-@pytest.mark.parametrize("B,H,L", [(1, 2, 4096), (2, 3, 5000), (4, 8, 1024)])
+@pytest.mark.parametrize("B,H,L", [(1, 2, 4096), (2, 3, 5000), (4, 8, 1024), (1, 2, 20000), (1, 1, 40000), (3, 1, 16384)])
 def test_decode_mfma_splits_and_bf16_output(B, H, L):
-    """The single-pass matrix-core decode with several cache splits per head and a ragged last step."""
+    """The single-pass matrix-core decode with several cache splits per head and a ragged last step; the long caches
+    with few heads are cut into more than 16 partials per head and take the combine stage before the merge."""
     w = _small("decm", B, H, L, 64, "bf16", index=400 + L).with_shape(kind="decode")
     q, Kc, Vc = workloads.make_inputs(w)
     ref = oracle.decode(q, Kc, Vc, w.lam, w.scale)
@@ -193,6 +194,24 @@ def test_decode_seqlens_and_forward_last_row():
     fwd = llla.llla_forward(Qf.to(DEV), Kc[0:1].to(DEV), Vc[0:1].to(DEV), w.lam, w.scale).cpu().numpy()
     err = np.linalg.norm(fwd[0, :, -1] - got[0]) / np.linalg.norm(got[0])
     assert err < 1e-3, err
+
+
+def test_decode_seqlens_with_many_partials():
+    """Few heads, long cache, short and long sequences: partials beyond a sequence's length are empty and the combine
+    stage has to carry them (all-empty groups included)."""
+    w = _small("decsl3", 3, 1, 20000, 64, "bf16", index=122).with_shape(kind="decode")
+    q, Kc, Vc = workloads.make_inputs(w)
+    lens = [20000, 700, 9000]
+    ref = oracle.decode(q, Kc, Vc, w.lam, w.scale, seqlens=lens)
+    Kp, Vp = Kc.clone(), Vc.clone()
+    for b, L in enumerate(lens):
+        Kp[b, :, L:] = float("nan")
+        Vp[b, :, L:] = float("nan")
+    sl = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    got = llla.llla_decode(q.to(DEV), Kp.to(DEV), Vp.to(DEV), w.lam, w.scale, seqlens=sl, path="mfma").cpu().numpy()
+    for b, L in enumerate(lens):
+        print(check(got[b:b + 1, :, None, :], ref[b:b + 1, :, None, :], np.array([L - 1]), w.d, w.tol,
+                    "decode seqlen %d of 20000" % L))
 
 
 @pytest.mark.parametrize("path", ["mfma", "valu"])
