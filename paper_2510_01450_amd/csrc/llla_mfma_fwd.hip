@@ -644,17 +644,24 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
             const bf16_t *qrow = Qh + (int64_t)min(i0 + qi, n - 1) * sq.seq;
             const float *rrow = WITH_U ? Rg + ((size_t)bh * n + min(i0 + qi, n - 1)) * YP : nullptr;
 #pragma unroll
-            for (int P = 0; P < NB; ++P)
+            for (int P = 0; P < NB; ++P) {
+                // every lane loads all values and selects: a load under a lane-dependent condition would become a
+                // branch with its own wait per tile register; four consecutive rows per load, so that a tile costs
+                // one load per source instead of four that the compiler waits for one by one
+                const int row0 = 16 * P + 4 * g;
+                const f32x4 mv = *reinterpret_cast<const f32x4 *>(&mus[qi][row0]);
+                const uint2 qb = *reinterpret_cast<const uint2 *>(qrow + row0);
+                const float qv[4] = {__uint_as_float(qb.x << 16), __uint_as_float(qb.x & 0xffff0000u),
+                                     __uint_as_float(qb.y << 16), __uint_as_float(qb.y & 0xffff0000u)};
+                f32x4 rv = {0.f, 0.f, 0.f, 0.f};
+                if constexpr (WITH_U) rv = *reinterpret_cast<const f32x4 *>(rrow + row0);
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
-                    // every lane loads both values and selects: a load under a lane-dependent condition
-                    // would become a branch with its own wait per tile register
-                    const int row = 16 * P + 4 * g + t;
-                    const float mv = mus[qi][row], qv = bf16_to_f32(qrow[row]);
-                    float v = (nn == 0) ? mv : ((nn == 1) ? -qv : 0.f);         // mus holds -mu~
-                    if constexpr (WITH_U) v = (nn == 2) ? -rrow[row] : v;
+                    float v = (nn == 0) ? mv[t] : ((nn == 1) ? -qv[t] : 0.f);   // mus holds -mu~
+                    if constexpr (WITH_U) v = (nn == 2) ? -rv[t] : v;
                     r[q][P][t] = v;
                 }
+            }
         }
     }, r0v, u0v);
 
