@@ -43,8 +43,6 @@ struct BackwardProblem {
 
 // Launchers return hipSuccess or the launch error.  Each lives in its own translation unit.
 hipError_t valu_forward(const Problem &p);
-// causal forward restricted to query rows [0, nrows); nrows must be a multiple of 16
-hipError_t valu_forward_rows(const Problem &p, int nrows);
 // sweep 3 only, for query rows [0, nrows): y (pitch ypitch floats: y1 then y0) and the row maxima (log2
 // units) come from device memory
 hipError_t valu_forward_given(const Problem &p, int nrows, const float *M, int mpitch, const float *Y, int ypitch);
@@ -82,6 +80,9 @@ size_t mfma_decode_workspace_bytes(int B, int H, int L_max, int d, llla_dtype in
 // whether the MFMA decode path serves this call (it needs the full cache length for every sequence)
 bool mfma_decode_takes(const Problem &p);
 hipError_t mfma_decode(const Problem &p);
+// the d = 128 kernels behind the two functions above (a translation unit of their own)
+size_t mfma_decode128_workspace_bytes(int B, int H, int L_max);
+hipError_t mfma_decode128(const Problem &p);
 
 // ---- stage profiling (measurement aid, off by default) ------------------------------------------
 // stage_mark(stream, name) records an event and labels the work enqueued AFTER it, up to the next

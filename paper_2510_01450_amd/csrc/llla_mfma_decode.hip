@@ -412,11 +412,12 @@ __global__ __launch_bounds__(NT, 1) void decode_merge_kernel(const bf16_t *__res
 
 }  // namespace
 
-bool mfma_decode_supported(int d, llla_dtype in) { return d == D && in == LLLA_BF16; }
+bool mfma_decode_supported(int d, llla_dtype in) { return (d == D || d == 128) && in == LLLA_BF16; }
 
 size_t mfma_decode_workspace_bytes(int B, int H, int L_max, int d, llla_dtype in)
 {
     if (!mfma_decode_supported(d, in) || L_max < MIN_L) return 0;
+    if (d == 128) return mfma_decode128_workspace_bytes(B, H, L_max);
     const Split s = make_split(B * H, L_max);
     const size_t records = (size_t)s.nparts + (s.group ? s.ngroups : 0);
     return round_up((size_t)B * H * records * PART_F * sizeof(float), 256);
@@ -426,11 +427,13 @@ bool mfma_decode_takes(const Problem &p)
 {
     // per-lane byte offsets inside one 32-key step are kept in 32 bits
     const int64_t reach = 2 * 32 * (p.sk.seq > p.sv.seq ? p.sk.seq : p.sv.seq);
-    return p.n >= MIN_L && reach < (int64_t(1) << 31);
+    // (batch, head) is the y dimension of the grid
+    return p.n >= MIN_L && reach < (int64_t(1) << 31) && (int64_t)p.B * p.H <= 65535;
 }
 
 hipError_t mfma_decode(const Problem &p)
 {
+    if (p.d == 128) return mfma_decode128(p);
     const int bh = p.B * p.H;
     const Split s = make_split(bh, p.n);
     float *parts = static_cast<float *>(p.ws);

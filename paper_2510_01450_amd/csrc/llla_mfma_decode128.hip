@@ -1,0 +1,470 @@
+// Matrix-core decode path of Local Linear Attention for gfx950 at head dimension 128: bf16 caches, cache
+// capacity L_max >= 1024, optional per-sequence lengths.  The method is the one of the d = 64 kernel (a single
+// pass over the cache that accumulates omega, mu~, Sigma~ of Eq. (tilded_form) and the value moments sum w v,
+// G~ = sum w k v^T relative to a running maximum as in Algorithm 1, then one solve per head and
+// o = y0 * sum w v + G~^T y1, which is Eq. (lla) with the sum over keys taken first).
+//
+// What differs is who holds the moments.  At d = 128 they are 36 + 64 upper-triangular / full 16x16 tiles plus
+// 16 broadcast tiles for mu~ and sum w v: 464 accumulator registers, more than one wave owns.  The four waves of
+// a workgroup therefore walk ONE key stream together and split the tiles: wave (a, b) owns the rows 64a..64a+63
+// of Sigma~ and G~ restricted to the columns 64b..64b+63 (the lower-left quarter of Sigma~ is not needed), and
+// the two broadcast moments are dealt out so that the waves carry 30 / 32 / 24 / 30 tiles.  Every wave computes
+// the 32 logits of a step itself (8 MFMAs) so that weights, running maximum and rescaling decisions are
+// bit-identical in the four waves without any exchange.  A step's K and V tiles (16 KB) are brought into LDS
+// by all four waves (a quarter each) and three stages rotate with one workgroup barrier per step.
+#include "llla_mfma_common.hpp"
+
+namespace llla {
+namespace {
+
+using namespace mfma;
+
+using S128 = Shape<128>;
+constexpr int D = 128, NB = 8, NT = 256;
+constexpr int STEP = 32;                       // keys per MFMA step
+constexpr int NSTAGE = 3;                      // LDS stages per workgroup; two are in flight while one is read
+constexpr int TILE_H = STEP * D;               // halves of one natural [32 keys][128] tile (8 KB)
+constexpr int STAGE_H = 2 * TILE_H;            // K tile + V tile
+constexpr int DMA_PER_WAVE = 4;                // transfers one wave issues per stage (2 for K, 2 for V)
+constexpr int NSIG = 36, NTILES = 100;         // Sigma~ upper triangle, then G~ row-major [I][J]
+constexpr int HDR = 3 * D;                     // [m, omega, ..pad], mu~ at [D, 2D), sum w v at [2D, 3D)
+constexpr int PART_F = HDR + NTILES * 256;     // floats per partial record
+constexpr int MIN_L = 1024;                    // shorter caches go to the vector path
+constexpr int MAX_SPLIT = 32;
+constexpr int PRECISE_L = 4 * D;               // sequences up to this length take the two-term weights
+
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) short4v *lds_short4_ptr;
+
+struct Split {
+    int nsplit;          // workgroups (= partial records) per head
+};
+
+Split make_split(int bh, int L)
+{
+    Split s;
+    int want = (512 + bh - 1) / bh;                  // two workgroups per compute unit are resident
+    int most = L / (8 * STEP);                       // at least 8 steps per workgroup
+    if (most < 1) most = 1;
+    s.nsplit = want < 1 ? 1 : (want > most ? most : want);
+    if (s.nsplit > MAX_SPLIT) s.nsplit = MAX_SPLIT;
+    return s;
+}
+
+// two bf16 packed in a dword -> two f16 packed (exact for values in the f16 range)
+__device__ inline unsigned bf16x2_to_f16x2(unsigned u)
+{
+    const float lo = __uint_as_float(u << 16), hi = __uint_as_float(u & 0xffff0000u);
+    return __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(lo, hi));
+}
+
+template <int N>
+__device__ inline void dma_wait_pending() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+// A natural tile is [key][16 chunks of 8 features], 256 B per key, which is exactly one pass over the LDS banks;
+// chunk c of key k is stored at chunk position c ^ swz(k).  Bits 1..3 of the position take k mod 8, so that the
+// 8 keys that half a wave reads transposed (two neighbouring chunks each) cover all banks once; bit 0 takes bit 3
+// of k, so that the 16 keys a quarter wave reads as natural rows (one chunk each) do too.
+__device__ inline int swz(int key) { return ((key & 7) << 1) ^ ((key >> 3) & 1); }
+
+// Transposed fragment of 16 features x 32 keys as an MFMA operand (bf16 -> f16): slot t < 4 = key 4g + t,
+// slot t >= 4 = key 16 + 4g + t - 4, feature 16 I + nn.  addr: the lane's address for feature block I.
+__device__ inline half8 tr_frag(const bf16_t *tile, int addr)
+{
+    const short4v a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(tile + addr));
+    const short4v b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(tile + 16 * D + addr));
+    const uint2 au = __builtin_bit_cast(uint2, a), bu = __builtin_bit_cast(uint2, b);
+    const uint4 p = make_uint4(bf16x2_to_f16x2(au.x), bf16x2_to_f16x2(au.y), bf16x2_to_f16x2(bu.x), bf16x2_to_f16x2(bu.y));
+    return __builtin_bit_cast(half8, p);
+}
+
+__host__ __device__ constexpr int tix4(int i, int j) { return i * 4 - i * (i - 1) / 2 + (j - i); }   // 4x4 upper triangle
+
+struct PartialArgs {
+    const bf16_t *qg, *Kg, *Vg;
+    llla_strides sk, sv;
+    const int32_t *seqlens;
+    int H, L_max, nparts;
+    float cscale;
+    float *parts;
+};
+
+// The share of wave (WA, WB): rows 4 WA .. 4 WA + 3 (feature blocks), columns 4 WB .. 4 WB + 3.
+template <int WA, int WB, bool PRECISE>
+__device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage, int wave, int lane)
+{
+    constexpr bool SIG_DIAG = (WA == WB);                 // 10 tiles of a diagonal quarter of Sigma~
+    constexpr bool SIG_FULL = (WA == 0 && WB == 1);       // the 16 tiles of the upper-right quarter
+    constexpr int NS = SIG_DIAG ? 10 : (SIG_FULL ? 16 : 1);
+    constexpr bool HAS_MU = (WB == 0);                    // mu~ blocks 4 WA .. 4 WA + 3
+    constexpr bool HAS_YV = (WA == 1);                    // (sum w v) blocks 4 WB .. 4 WB + 3
+
+    const int g = lane / 16, nn = lane % 16;
+    const int bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
+    const int part = blockIdx.x;
+    // the sequence's own length decides the share of each workgroup; rows at and beyond L are never read
+    const int L = a.seqlens ? min(max(a.seqlens[b], 1), a.L_max) : a.L_max;
+    const int keys_per_part = ((L + a.nparts - 1) / a.nparts + STEP - 1) / STEP * STEP;
+    const int r0 = part * keys_per_part;
+    const int r1 = min(r0 + keys_per_part, L);
+    const int nsteps = __builtin_amdgcn_readfirstlane(r1 > r0 ? (r1 - r0 + STEP - 1) / STEP : 0);
+    // Short sequences are the ill-conditioned ones (fewer keys than features leave directions that only the ridge
+    // holds, and a relative error of 2^-11 in w k is then not small against the ridge): they take the weights in
+    // fp32 and hand w and w k to the matrix cores as two f16 terms each.  Long ones round w to f16 once and use
+    // that same rounded weight in every moment.  (PRECISE is chosen per sequence by the kernel.)
+    constexpr bool precise = PRECISE;
+    const bf16_t *Kh = a.Kg + b * a.sk.batch + h * a.sk.head;
+    const bf16_t *Vh = a.Vg + b * a.sv.batch + h * a.sv.head;
+
+    // query fragments, the same for every column of the B operand: lane (g, *) holds q[32 c + 8 g ..+7]
+    bf16x8 qf[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) qf[c] = *reinterpret_cast<const bf16x8 *>(a.qg + (size_t)bh * D + 32 * c + 8 * g);
+
+    // this wave's part of a stage: LDS chunk slots [128 wave, 128 wave + 128) of the K tile and of the V tile
+    int dma_key[2], dma_col[2];
+    unsigned koff[2], voff[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int sl = 128 * wave + 64 * t + lane;
+        dma_key[t] = sl >> 4;
+        dma_col[t] = ((sl & 15) ^ swz(dma_key[t])) * 8;
+        koff[t] = 2u * (unsigned)(dma_key[t] * (int)a.sk.seq + dma_col[t]);
+        voff[t] = 2u * (unsigned)(dma_key[t] * (int)a.sv.seq + dma_col[t]);
+    }
+    // logits operand (natural rows): key 16 sub + nn, chunks 4 c + g
+    int nat[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) nat[c] = nn * D + (((4 * c + g) ^ swz(nn)) * 8);
+    // transposed operand: inside a 16-lane group, lane j addresses 4 features (16 I + 4 (j % 4) ..) of key
+    // 4 g + j / 4; the instruction hands lane i the 4 keys 4g .. 4g+3 of feature 16 I + i
+    int tr_addr[NB];
+    {
+        const int key = 4 * g + (nn >> 2);
+#pragma unroll
+        for (int I = 0; I < NB; ++I) {
+            const int c = 2 * I + ((nn & 3) >> 1);
+            tr_addr[I] = key * D + ((c ^ swz(key)) * 8) + (nn & 1) * 4;
+        }
+    }
+
+    f32x4 sig[NS], gt[16], muacc[4], yvacc[4];
+#pragma unroll
+    for (int t = 0; t < NS; ++t) sig[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < 16; ++t) gt[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < 4; ++t) { muacc[t] = f32x4{0.f, 0.f, 0.f, 0.f}; yvacc[t] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    float om = 0.f, m = -INFINITY;
+
+    // workgroups that start together on equally spaced addresses would keep hitting the same memory channels in
+    // step; each sweeps its share from a different starting step and wraps around (the moments do not depend on
+    // the order of the keys)
+    const int rot = nsteps > 0 ? (int)((part * 7u + bh * 13u) % (unsigned)nsteps) : 0;
+    auto step_pos = [&](int step) { const int t = step + rot; return t >= nsteps ? t - nsteps : t; };
+    auto issue_dma = [&](int step) {
+        bf16_t *dst = stage + (step % NSTAGE) * STAGE_H + 1024 * wave;
+        const int j0 = r0 + step_pos(step < nsteps ? step : 0) * STEP;
+        if (j0 + STEP <= L) {
+            const bf16_t *kb = Kh + (int64_t)j0 * a.sk.seq, *vb = Vh + (int64_t)j0 * a.sv.seq;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                dma16_base_nt(kb, koff[t], dst + 512 * t);
+                dma16_base_nt(vb, voff[t], dst + TILE_H + 512 * t);
+            }
+        } else {      // a step that reaches past the sequence (or an idle workgroup): rows clamped to the last valid one
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int j = max(min(j0 + dma_key[t], L - 1), 0);
+                dma16_nt(Kh + (int64_t)j * a.sk.seq + dma_col[t], dst + 512 * t);
+                dma16_nt(Vh + (int64_t)j * a.sv.seq + dma_col[t], dst + TILE_H + 512 * t);
+            }
+        }
+    };
+
+    // Two stages are in flight.  Every step first waits for this wave's transfers of the step, then meets the
+    // other waves (now the whole stage has landed, and everybody has finished reading the stage of the step
+    // before), and only then refills that older stage.  Every step issues exactly one stage (clamped past the
+    // end), so "at most DMA_PER_WAVE transfers pending" always means "this step's have landed".
+    issue_dma(0);
+    issue_dma(1);
+    for (int s = 0; s < nsteps; ++s) {
+        dma_wait_pending<DMA_PER_WAVE>();
+        __syncthreads();
+        issue_dma(s + 2);
+        const bf16_t *kt = stage + (s % NSTAGE) * STAGE_H;
+        const bf16_t *vt = kt + TILE_H;
+        const int j0 = r0 + step_pos(s) * STEP;
+
+        // logits of the 32 keys: lane (g, *) gets keys 4g..4g+3 (sub-tile 0) and 16+4g.. (sub-tile 1)
+        float tl[8];
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            f32x4 z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                z = mfma_bf16(*reinterpret_cast<const bf16x8 *>(kt + sub * 16 * D + nat[c]), qf[c], z);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int j = j0 + 16 * sub + 4 * g + r;
+                tl[4 * sub + r] = (j < r1) ? z[r] * a.cscale : -INFINITY;
+            }
+        }
+        // running maximum over the workgroup's keys; the accumulators are rescaled only when it moves
+        float mx = fmaxf(fmaxf(fmaxf(tl[0], tl[1]), fmaxf(tl[2], tl[3])), fmaxf(fmaxf(tl[4], tl[5]), fmaxf(tl[6], tl[7])));
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        if (__builtin_amdgcn_readfirstlane(mx > m ? 1 : 0)) {
+            const float alpha = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - mx);
+            m = mx;
+            om *= alpha;
+#pragma unroll
+            for (int t = 0; t < NS; ++t) sig[t] *= alpha;
+#pragma unroll
+            for (int t = 0; t < 16; ++t) gt[t] *= alpha;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) { muacc[t] *= alpha; yvacc[t] *= alpha; }
+        }
+        float wf[8];
+        half8 wq, wl;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            wf[t] = __builtin_amdgcn_exp2f(tl[t] - m);                // exp2(-inf) = 0 masks the tail
+            wq[t] = (_Float16)wf[t];
+        }
+        if constexpr (precise) {
+#pragma unroll
+            for (int t = 0; t < 8; ++t) { wl[t] = (_Float16)(wf[t] - (float)wq[t]); om += wf[t]; }
+        } else {
+#pragma unroll
+            for (int t = 0; t < 8; ++t) om += (float)wq[t];
+        }
+
+        half8 kA[4], vB[4], kB[SIG_FULL ? 4 : 1];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            kA[i] = tr_frag(kt, tr_addr[4 * WA + i]);
+            vB[i] = tr_frag(vt, tr_addr[4 * WB + i]);
+            if constexpr (SIG_FULL) kB[i] = tr_frag(kt, tr_addr[4 + i]);
+        }
+        auto row_mfmas = [&](int i, const half8 &af) {
+            if constexpr (SIG_DIAG) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (j >= i) sig[tix4(i, j)] = mfma_f16(af, kA[j], sig[tix4(i, j)]);
+            }
+            if constexpr (SIG_FULL) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) sig[4 * i + j] = mfma_f16(af, kB[j], sig[4 * i + j]);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) gt[4 * i + j] = mfma_f16(af, vB[j], gt[4 * i + j]);
+        };
+        auto bcast_mfmas = [&](const half8 &wv) {
+            if constexpr (HAS_MU) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) muacc[j] = mfma_f16(wv, kA[j], muacc[j]);      // every row = mu~[64 WA + 16 j + nn]
+            }
+            if constexpr (HAS_YV) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) yvacc[j] = mfma_f16(wv, vB[j], yvacc[j]);      // every row = (sum w v)[64 WB + 16 j + nn]
+            }
+        };
+        if constexpr (!precise) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) row_mfmas(i, kA[i] * wq);
+            bcast_mfmas(wq);
+        } else {
+            // w k in fp32 (exact up to the rounding of w), handed to the matrix cores as an f16 head plus an f16 tail
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                half8 ah, al;
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    const float pr = (float)kA[i][t] * wf[t];
+                    ah[t] = (_Float16)pr;
+                    al[t] = (_Float16)(pr - (float)ah[t]);
+                }
+                row_mfmas(i, ah);
+                row_mfmas(i, al);
+            }
+            bcast_mfmas(wq);
+            bcast_mfmas(wl);
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // drain the clamped tail transfers before the wave ends
+
+    om += __shfl_xor(om, 16);
+    om += __shfl_xor(om, 32);
+    float *P = a.parts + ((size_t)bh * a.nparts + part) * PART_F;
+    if (WA == 0 && WB == 0 && lane == 0) { P[0] = m; P[1] = om; }
+    if (g == 0) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if constexpr (HAS_MU) P[D + 64 * WA + 16 * j + nn] = muacc[j][0];
+            if constexpr (HAS_YV) P[2 * D + 64 * WB + 16 * j + nn] = yvacc[j][0];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int I = 4 * WA + i, J = 4 * WB + j;
+            if constexpr (SIG_DIAG) {
+                if (j >= i) *reinterpret_cast<f32x4 *>(P + HDR + S128::tix(I, J) * 256 + lane * 4) = sig[tix4(i, j)];
+            }
+            if constexpr (SIG_FULL) *reinterpret_cast<f32x4 *>(P + HDR + S128::tix(I, J) * 256 + lane * 4) = sig[4 * i + j];
+            *reinterpret_cast<f32x4 *>(P + HDR + (NSIG + NB * I + J) * 256 + lane * 4) = gt[4 * i + j];
+        }
+    }
+}
+
+__global__ __launch_bounds__(NT, 2) void decode128_partial_kernel(PartialArgs a)
+{
+    __shared__ __align__(16) bf16_t stage[NSTAGE * STAGE_H];       // 3 stages x 16 KB
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64), lane = threadIdx.x % 64;
+    // scalar branches: each wave runs the loop of its own share; all of them meet at the same barriers
+    const int b = (int)blockIdx.y / a.H;
+    const int L = a.seqlens ? min(max(a.seqlens[b], 1), a.L_max) : a.L_max;
+    if (__builtin_amdgcn_readfirstlane(L <= PRECISE_L ? 1 : 0)) {
+        if (wave == 0) partial_body<0, 0, true>(a, stage, 0, lane);
+        else if (wave == 1) partial_body<0, 1, true>(a, stage, 1, lane);
+        else if (wave == 2) partial_body<1, 0, true>(a, stage, 2, lane);
+        else partial_body<1, 1, true>(a, stage, 3, lane);
+    } else {
+        if (wave == 0) partial_body<0, 0, false>(a, stage, 0, lane);
+        else if (wave == 1) partial_body<0, 1, false>(a, stage, 1, lane);
+        else if (wave == 2) partial_body<1, 0, false>(a, stage, 2, lane);
+        else partial_body<1, 1, false>(a, stage, 3, lane);
+    }
+}
+
+// Merge, solve, output for one head per workgroup (4 waves):
+//   phase 1  wave w sums tiles w, w + 4, .. of the head's partial records with the max-rescale factors
+//            2^(m_p - m*) into LDS (the merge step of Algorithm 1's running maximum);
+//   phase 2  wave 0 solves the augmented system;
+//   phase 3  wave w forms o = y0 * (sum w v) + G~^T y1 for the value blocks 2w and 2w + 1.
+__global__ __launch_bounds__(NT, 1) void decode128_merge_kernel(const bf16_t *__restrict__ qg, const float *__restrict__ parts,
+                                                                int nparts, float lambda, void *__restrict__ og, int out_bf16)
+{
+    constexpr int TPW = NTILES / 4;                                 // tiles per wave in phase 1
+    __shared__ __align__(16) float merged[NTILES][256];
+    __shared__ __align__(16) float scw[16 * SC_PITCH];
+    __shared__ __align__(16) float mus[D], yvs[D], ys[D + 4];
+    __shared__ float oms;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64, g = lane / 16,
+              nn = lane % 16;
+    const int bh = blockIdx.x;
+    const float *P0 = parts + (size_t)bh * nparts * PART_F;
+
+    {   // phase 1
+        float mstar = -INFINITY;
+        for (int p = 0; p < nparts; ++p) mstar = fmaxf(mstar, P0[(size_t)p * PART_F]);
+        float om = 0.f, hv = 0.f;
+        f32x4 acc[TPW];
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int p = 0; p < nparts; ++p) {
+            const float *P = P0 + (size_t)p * PART_F;
+            const float mp = P[0];
+            const float f = (mp == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mp - mstar);
+            om = fmaf(f, P[1], om);
+            hv = fmaf(f, P[D + tid], hv);                           // mu~ (threads 0..127), sum w v (128..255)
+#pragma unroll
+            for (int t = 0; t < TPW; ++t)
+                acc[t] += f * *reinterpret_cast<const f32x4 *>(P + HDR + (4 * t + wave) * 256 + lane * 4);
+        }
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) *reinterpret_cast<f32x4 *>(&merged[4 * t + wave][lane * 4]) = acc[t];
+        if (tid < D) mus[tid] = hv; else yvs[tid - D] = hv;
+        if (tid == 0) oms = om;
+    }
+    __syncthreads();
+
+    if (wave == 0) {   // phase 2 (scalar branch: the block contains MFMAs)
+        f32x4 acc[1][NSIG], rhs[1][NB];
+        float om4[1] = {oms}, y0v[1];
+#pragma unroll
+        for (int t = 0; t < NSIG; ++t) acc[0][t] = -*reinterpret_cast<const f32x4 *>(&merged[t][lane * 4]);
+#pragma unroll
+        for (int P = 0; P < NB; ++P)        // solve_wave takes -(Sigma~ + lambda I)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc[0][S128::tix(P, P)][t] -= (nn == 4 * g + t) ? lambda : 0.f;
+        solve_wave<128>(acc, rhs, y0v, om4, scw, g, nn, 0.5f * lambda, [&](f32x4 (&r)[1][NB]) {
+#pragma unroll
+            for (int P = 0; P < NB; ++P) {
+                const int row0 = 16 * P + 4 * g;
+                const f32x4 mv = *reinterpret_cast<const f32x4 *>(&mus[row0]);
+                const uint2 qb = *reinterpret_cast<const uint2 *>(qg + (size_t)bh * D + row0);
+                const float qv[4] = {__uint_as_float(qb.x << 16), __uint_as_float(qb.x & 0xffff0000u),
+                                     __uint_as_float(qb.y << 16), __uint_as_float(qb.y & 0xffff0000u)};
+#pragma unroll
+                for (int t = 0; t < 4; ++t) r[0][P][t] = (nn == 0) ? -mv[t] : ((nn == 1) ? -qv[t] : 0.f);
+            }
+        });
+        if (nn == 0) {
+#pragma unroll
+            for (int P = 0; P < NB; ++P) *reinterpret_cast<f32x4 *>(&ys[16 * P + 4 * g]) = rhs[0][P];
+            if (g == 0) ys[D] = y0v[0];
+        }
+    }
+    __syncthreads();
+
+    {   // phase 3
+        const float y0 = ys[D];
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const int J = 2 * wave + jj;
+            float s = 0.f;
+#pragma unroll
+            for (int I = 0; I < NB; ++I) {
+                const f32x4 gv = *reinterpret_cast<const f32x4 *>(&merged[NSIG + NB * I + J][lane * 4]);
+                const f32x4 y1 = *reinterpret_cast<const f32x4 *>(&ys[16 * I + 4 * g]);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) s = fmaf(gv[t], y1[t], s);      // G~[16I+4g+t][16J+nn] y1[16I+4g+t]
+            }
+            s += __shfl_xor(s, 16);
+            s += __shfl_xor(s, 32);
+            const float o = fmaf(y0, yvs[16 * J + nn], s);
+            if (g == 0) {
+                if (out_bf16) ((bf16_t *)og)[(size_t)bh * D + 16 * J + nn] = f32_to_bf16(o);
+                else ((float *)og)[(size_t)bh * D + 16 * J + nn] = o;
+            }
+        }
+    }
+}
+
+}  // namespace
+
+size_t mfma_decode128_workspace_bytes(int B, int H, int L_max)
+{
+    if (L_max < MIN_L) return 0;
+    const Split s = make_split(B * H, L_max);
+    return round_up((size_t)B * H * s.nsplit * PART_F * sizeof(float), 256);
+}
+
+hipError_t mfma_decode128(const Problem &p)
+{
+    const int bh = p.B * p.H;
+    const Split s = make_split(bh, p.n);
+    PartialArgs a;
+    a.qg = (const bf16_t *)p.Q;
+    a.Kg = (const bf16_t *)p.K;
+    a.Vg = (const bf16_t *)p.V;
+    a.sk = p.sk;
+    a.sv = p.sv;
+    a.seqlens = p.seqlens;
+    a.H = p.H;
+    a.L_max = p.n;
+    a.nparts = s.nsplit;
+    a.cscale = p.scale * LOG2E;
+    a.parts = static_cast<float *>(p.ws);
+    stage_mark(p.stream, "decode_partial");
+    hipLaunchKernelGGL(decode128_partial_kernel, dim3(s.nsplit, bh), dim3(NT), 0, p.stream, a);
+    stage_mark(p.stream, "decode_merge");
+    hipLaunchKernelGGL(decode128_merge_kernel, dim3(bh), dim3(NT), 0, p.stream, (const bf16_t *)p.Q, (const float *)a.parts,
+                       s.nsplit, p.lambda, p.O, p.out == LLLA_BF16 ? 1 : 0);
+    return hipGetLastError();
+}
+
+}  // namespace llla

@@ -398,7 +398,6 @@ hipError_t valu_forward_given(const Problem &p, int nrows, const float *M, int m
 }
 
 hipError_t valu_forward(const Problem &p) { return by_dim<false>(p, p.n); }
-hipError_t valu_forward_rows(const Problem &p, int nrows) { return by_dim<false>(p, nrows < p.n ? nrows : p.n); }
 hipError_t valu_decode(const Problem &p) { return by_dim<true>(p, 1); }
 
 }  // namespace llla

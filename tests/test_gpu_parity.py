@@ -178,6 +178,58 @@ def test_decode_mfma_splits_and_bf16_output(B, H, L):
     assert np.linalg.norm(got - valu) / np.linalg.norm(valu) < 1e-2
 
 
+@pytest.mark.parametrize("B,H,L", [(1, 2, 4096), (2, 3, 5000), (4, 8, 1024), (1, 1, 40000), (3, 1, 16384), (70, 8, 1500)])
+def test_decode_mfma_d128_splits_and_bf16_output(B, H, L):
+    """d = 128: the four waves of a workgroup share one key stream and each owns a quarter of the moment tiles; 1 to
+    32 workgroups per head, ragged last steps, both output types."""
+    w = _small("decm128", B, H, L, 128, "bf16", index=500 + L).with_shape(kind="decode")
+    q, Kc, Vc = workloads.make_inputs(w)
+    ref = oracle.decode(q, Kc, Vc, w.lam, w.scale)
+    for od in (torch.float32, torch.bfloat16):
+        got = llla.llla_decode(q.to(DEV), Kc.to(DEV), Vc.to(DEV), w.lam, w.scale, path="mfma", out_dtype=od)
+        got = got.float().cpu().numpy()
+        print(check(got[:, :, None, :], ref[:, :, None, :], np.array([L - 1]), 128, w.tol, "decode mfma d=128 L=%d" % L))
+    valu = llla.llla_decode(q.to(DEV), Kc.to(DEV), Vc.to(DEV), w.lam, w.scale, path="valu").cpu().numpy()
+    assert np.linalg.norm(got - valu) / np.linalg.norm(valu) < 1e-2
+
+
+def test_decode_mfma_d128_seqlens_ignore_the_tail_and_strided_cache():
+    """d = 128 with per-sequence lengths (a sequence of one key, idle workgroups beyond a short sequence, a ragged
+    last step) on a cache whose tail is poisoned with NaN; the cache is a view with a row pitch of 2 d."""
+    w = _small("decsl128", 5, 2, 9000, 128, "bf16", index=123).with_shape(kind="decode")
+    q, Kc, Vc = workloads.make_inputs(w)
+    lens = [9000, 1, 33, 1024, 8999]
+    ref = oracle.decode(q, Kc, Vc, w.lam, w.scale, seqlens=lens)
+    Kw = torch.full((5, 2, 9000, 256), float("nan"), dtype=torch.bfloat16)
+    Vw = torch.full((5, 2, 9000, 256), float("nan"), dtype=torch.bfloat16)
+    Kw[..., :128] = Kc
+    Vw[..., 128:] = Vc
+    for b, L in enumerate(lens):
+        Kw[b, :, L:] = float("nan")
+        Vw[b, :, L:] = float("nan")
+    Kd, Vd = Kw.to(DEV)[..., :128], Vw.to(DEV)[..., 128:]
+    sl = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    got = llla.llla_decode(q.to(DEV), Kd, Vd, w.lam, w.scale, seqlens=sl, path="mfma").cpu().numpy()
+    for b, L in enumerate(lens):
+        print(check(got[b:b + 1, :, None, :], ref[b:b + 1, :, None, :], np.array([L - 1]), w.d, w.tol,
+                    "decode d=128 seqlen %d of 9000" % L))
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_decode_mfma_short_sequences_in_a_long_cache(d):
+    """Sequences with fewer keys than features, about as many, and a few times as many (the ill-conditioned range,
+    where only the ridge holds some directions) in a cache long enough for the matrix-core path."""
+    lens = [17, 100, 127, 128, 129, 200, 256, 400, 512, 513, 700, 1024]
+    w = _small("decshort", len(lens), 2, 1024, d, "bf16", index=124 + d).with_shape(kind="decode")
+    q, Kc, Vc = workloads.make_inputs(w)
+    ref = oracle.decode(q, Kc, Vc, w.lam, w.scale, seqlens=lens)
+    sl = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    got = llla.llla_decode(q.to(DEV), Kc.to(DEV), Vc.to(DEV), w.lam, w.scale, seqlens=sl, path="mfma").cpu().numpy()
+    for b, L in enumerate(lens):
+        print(L, check(got[b:b + 1, :, None, :], ref[b:b + 1, :, None, :], np.array([L - 1]), w.d, w.tol,
+                       "decode d=%d seqlen %d of 1024" % (d, L)))
+
+
 def test_decode_seqlens_and_forward_last_row():
     w = _small("decsl", 4, 2, 600, 64, "bf16", index=120).with_shape(kind="decode")
     q, Kc, Vc = workloads.make_inputs(w)
