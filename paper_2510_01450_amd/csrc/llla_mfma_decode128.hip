@@ -22,7 +22,7 @@ using namespace mfma;
 using S128 = Shape<128>;
 constexpr int D = 128, NB = 8, NT = 256;
 constexpr int STEP = 32;                       // keys per MFMA step
-constexpr int NSTAGE = 3;                      // LDS stages per workgroup; two are in flight while one is read
+constexpr int NSTAGE = 4;                      // LDS stages per workgroup: two being read, two in flight
 constexpr int TILE_H = STEP * D;               // halves of one natural [32 keys][128] tile (8 KB)
 constexpr int STAGE_H = 2 * TILE_H;            // K tile + V tile
 constexpr int DMA_PER_WAVE = 4;                // transfers one wave issues per stage (2 for K, 2 for V)
@@ -35,6 +35,7 @@ constexpr int PRECISE_L = 4 * D;               // sequences up to this length ta
 
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) short4v *lds_short4_ptr;
+typedef __attribute__((address_space(3))) const bf16x8 *lds_bf16x8_ptr;
 
 struct Split {
     int nsplit;          // workgroups (= partial records) per head
@@ -68,11 +69,12 @@ __device__ inline void dma_wait_pending() { asm volatile("s_waitcnt vmcnt(%0)" :
 __device__ inline int swz(int key) { return ((key & 7) << 1) ^ ((key >> 3) & 1); }
 
 // Transposed fragment of 16 features x 32 keys as an MFMA operand (bf16 -> f16): slot t < 4 = key 4g + t,
-// slot t >= 4 = key 16 + 4g + t - 4, feature 16 I + nn.  addr: the lane's address for feature block I.
-__device__ inline half8 tr_frag(const bf16_t *tile, int addr)
+// slot t >= 4 = key 16 + 4g + t - 4, feature 16 I + nn.  The argument is the lane's LDS byte address for feature
+// block I of the tile; the second half of the keys lies a constant 16 rows further on.
+__device__ inline half8 tr_frag(unsigned lds_byte_addr)
 {
-    const short4v a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(tile + addr));
-    const short4v b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(tile + 16 * D + addr));
+    const short4v a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(uintptr_t)lds_byte_addr);
+    const short4v b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(uintptr_t)(lds_byte_addr + 16 * D * 2));
     const uint2 au = __builtin_bit_cast(uint2, a), bu = __builtin_bit_cast(uint2, b);
     const uint4 p = make_uint4(bf16x2_to_f16x2(au.x), bf16x2_to_f16x2(au.y), bf16x2_to_f16x2(bu.x), bf16x2_to_f16x2(bu.y));
     return __builtin_bit_cast(half8, p);
@@ -133,18 +135,20 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
         voff[t] = 2u * (unsigned)(dma_key[t] * (int)a.sv.seq + dma_col[t]);
     }
     // logits operand (natural rows): key 16 sub + nn, chunks 4 c + g
-    int nat[4];
+    // (LDS byte addresses relative to the start of a stage: a step adds the stage's scalar base once per address,
+    // everything else is an immediate offset of the read)
+    unsigned nat[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) nat[c] = nn * D + (((4 * c + g) ^ swz(nn)) * 8);
+    for (int c = 0; c < 4; ++c) nat[c] = 2u * (unsigned)(nn * D + (((4 * c + g) ^ swz(nn)) * 8));
     // transposed operand: inside a 16-lane group, lane j addresses 4 features (16 I + 4 (j % 4) ..) of key
     // 4 g + j / 4; the instruction hands lane i the 4 keys 4g .. 4g+3 of feature 16 I + i
-    int tr_addr[NB];
+    unsigned tr_addr[NB];
     {
         const int key = 4 * g + (nn >> 2);
 #pragma unroll
         for (int I = 0; I < NB; ++I) {
             const int c = 2 * I + ((nn & 3) >> 1);
-            tr_addr[I] = key * D + ((c ^ swz(key)) * 8) + (nn & 1) * 4;
+            tr_addr[I] = 2u * (unsigned)(key * D + ((c ^ swz(key)) * 8) + (nn & 1) * 4);
         }
     }
 
@@ -156,6 +160,7 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
 #pragma unroll
     for (int t = 0; t < 4; ++t) { muacc[t] = f32x4{0.f, 0.f, 0.f, 0.f}; yvacc[t] = f32x4{0.f, 0.f, 0.f, 0.f}; }
     float om = 0.f, m = -INFINITY;
+    const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void_ptr)stage);
 
     // workgroups that start together on equally spaced addresses would keep hitting the same memory channels in
     // step; each sweeps its share from a different starting step and wraps around (the moments do not depend on
@@ -182,38 +187,31 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
         }
     };
 
-    // Two stages are in flight.  Every step first waits for this wave's transfers of the step, then meets the
-    // other waves (now the whole stage has landed, and everybody has finished reading the stage of the step
-    // before), and only then refills that older stage.  Every step issues exactly one stage (clamped past the
-    // end), so "at most DMA_PER_WAVE transfers pending" always means "this step's have landed".
-    issue_dma(0);
-    issue_dma(1);
-    for (int s = 0; s < nsteps; ++s) {
-        dma_wait_pending<DMA_PER_WAVE>();
-        __syncthreads();
-        issue_dma(s + 2);
-        const bf16_t *kt = stage + (s % NSTAGE) * STAGE_H;
-        const bf16_t *vt = kt + TILE_H;
-        const int j0 = r0 + step_pos(s) * STEP;
-
-        // logits of the 32 keys: lane (g, *) gets keys 4g..4g+3 (sub-tile 0) and 16+4g.. (sub-tile 1)
-        float tl[8];
+    // logits of the 32 keys of a step whose K tile lies at LDS byte address kt: lane (g, *) gets keys 4g..4g+3
+    // (sub-tile 0) and 16+4g.. (sub-tile 1); returns their maximum over the wave
+    auto logits = [&](unsigned kt, int step, float (&tl)[8]) {
+        const int j0 = r0 + step_pos(step) * STEP;
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             f32x4 z = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int c = 0; c < 4; ++c)
-                z = mfma_bf16(*reinterpret_cast<const bf16x8 *>(kt + sub * 16 * D + nat[c]), qf[c], z);
+                z = mfma_bf16(*(lds_bf16x8_ptr)(uintptr_t)(kt + nat[c] + sub * 16 * D * 2), qf[c], z);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int j = j0 + 16 * sub + 4 * g + r;
-                tl[4 * sub + r] = (j < r1) ? z[r] * a.cscale : -INFINITY;
+                tl[4 * sub + r] = (j < r1 && step < nsteps) ? z[r] * a.cscale : -INFINITY;
             }
         }
-        // running maximum over the workgroup's keys; the accumulators are rescaled only when it moves
         float mx = fmaxf(fmaxf(fmaxf(tl[0], tl[1]), fmaxf(tl[2], tl[3])), fmaxf(fmaxf(tl[4], tl[5]), fmaxf(tl[6], tl[7])));
         mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        return fmaxf(mx, __shfl_xor(mx, 32));
+    };
+    // running maximum over the workgroup's keys (the accumulators are rescaled only when it moves), then the weights
+    // of the step: wq (f16), and for short sequences the fp32 weights and their f16 tail as well
+    float wf[8];
+    half8 wq, wl;
+    auto weights = [&](float mx, const float (&tl)[8]) {
         if (__builtin_amdgcn_readfirstlane(mx > m ? 1 : 0)) {
             const float alpha = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - mx);
             m = mx;
@@ -225,11 +223,10 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
 #pragma unroll
             for (int t = 0; t < 4; ++t) { muacc[t] *= alpha; yvacc[t] *= alpha; }
         }
-        float wf[8];
-        half8 wq, wl;
+        const float mref = (m == -INFINITY) ? 0.f : m;                // an idle workgroup has no maximum yet
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-            wf[t] = __builtin_amdgcn_exp2f(tl[t] - m);                // exp2(-inf) = 0 masks the tail
+            wf[t] = __builtin_amdgcn_exp2f(tl[t] - mref);             // exp2(-inf) = 0 masks the tail
             wq[t] = (_Float16)wf[t];
         }
         if constexpr (precise) {
@@ -239,13 +236,44 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
 #pragma unroll
             for (int t = 0; t < 8; ++t) om += (float)wq[t];
         }
+    };
+
+    // NSTAGE - 1 stages are issued ahead.  Iteration s multiplies step s into the moments and, independently of
+    // that, forms the logits and weights of step s + 1, so that the chain "LDS read, logits, maximum over the wave,
+    // exponentials" of one step lies beside the matrix-core work of the step before instead of in front of it.
+    // An iteration therefore reads stages s and s + 1: it first waits for this wave's transfers of step s + 1,
+    // then meets the other waves (now the whole stage s + 1 has landed, and everybody has finished reading stage
+    // s - 1), and only then refills that oldest stage with step s + NSTAGE - 1.  Every iteration issues exactly
+    // one stage (clamped past the end), so "at most DMA_PER_WAVE (NSTAGE - 3) transfers pending" always means
+    // "step s + 1 has landed".
+#pragma unroll
+    for (int st = 0; st < NSTAGE - 1; ++st) issue_dma(st);
+    dma_wait_pending<DMA_PER_WAVE *(NSTAGE - 2)>();
+    __syncthreads();
+    {
+        float tl[8];
+        const float mx = logits(lds0, 0, tl);
+        weights(mx, tl);
+    }
+    unsigned read_off = 0;
+    for (int s = 0; s < nsteps; ++s) {
+        dma_wait_pending<DMA_PER_WAVE *(NSTAGE - 3)>();
+        __syncthreads();
+        issue_dma(s + NSTAGE - 1);
+        // LDS byte addresses of the two stages, kept as scalars that the optimiser cannot take apart (it would
+        // otherwise carry one induction register per read and spend two vector-ALU operations on each)
+        const unsigned next_off = (read_off == (NSTAGE - 1) * STAGE_H * 2) ? 0u : read_off + STAGE_H * 2;
+        unsigned kt = lds0 + read_off, kn = lds0 + next_off;
+        asm volatile("" : "+s"(kt), "+s"(kn));
+        const unsigned vt = kt + TILE_H * 2;
+        read_off = next_off;
 
         half8 kA[4], vB[4], kB[SIG_FULL ? 4 : 1];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            kA[i] = tr_frag(kt, tr_addr[4 * WA + i]);
-            vB[i] = tr_frag(vt, tr_addr[4 * WB + i]);
-            if constexpr (SIG_FULL) kB[i] = tr_frag(kt, tr_addr[4 + i]);
+            kA[i] = tr_frag(kt + tr_addr[4 * WA + i]);
+            vB[i] = tr_frag(vt + tr_addr[4 * WB + i]);
+            if constexpr (SIG_FULL) kB[i] = tr_frag(kt + tr_addr[4 + i]);
         }
         auto row_mfmas = [&](int i, const half8 &af) {
             if constexpr (SIG_DIAG) {
@@ -270,6 +298,8 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
                 for (int j = 0; j < 4; ++j) yvacc[j] = mfma_f16(wv, vB[j], yvacc[j]);      // every row = (sum w v)[64 WB + 16 j + nn]
             }
         };
+        float tln[8];
+        const float mxn = logits(kn, s + 1, tln);
         if constexpr (!precise) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) row_mfmas(i, kA[i] * wq);
@@ -291,6 +321,7 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
             bcast_mfmas(wq);
             bcast_mfmas(wl);
         }
+        weights(mxn, tln);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // drain the clamped tail transfers before the wave ends
 
@@ -321,21 +352,24 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
 
 __global__ __launch_bounds__(NT, 2) void decode128_partial_kernel(PartialArgs a)
 {
-    __shared__ __align__(16) bf16_t stage[NSTAGE * STAGE_H];       // 3 stages x 16 KB
+    __shared__ __align__(16) bf16_t stage[NSTAGE * STAGE_H];       // 4 stages x 16 KB
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64), lane = threadIdx.x % 64;
-    // scalar branches: each wave runs the loop of its own share; all of them meet at the same barriers
+    // Scalar branches: each wave runs the loop of its own share; all of them meet at the same barriers.  The shares
+    // differ in work (24 to 32 tiles), and wave w of every workgroup runs on SIMD w of its compute unit; the shares
+    // therefore rotate with the workgroup index, so that no SIMD gets the heaviest share from both of its workgroups.
     const int b = (int)blockIdx.y / a.H;
     const int L = a.seqlens ? min(max(a.seqlens[b], 1), a.L_max) : a.L_max;
+    const int role = (wave + (int)blockIdx.x + (int)blockIdx.y) & 3;
     if (__builtin_amdgcn_readfirstlane(L <= PRECISE_L ? 1 : 0)) {
-        if (wave == 0) partial_body<0, 0, true>(a, stage, 0, lane);
-        else if (wave == 1) partial_body<0, 1, true>(a, stage, 1, lane);
-        else if (wave == 2) partial_body<1, 0, true>(a, stage, 2, lane);
-        else partial_body<1, 1, true>(a, stage, 3, lane);
+        if (role == 0) partial_body<0, 0, true>(a, stage, wave, lane);
+        else if (role == 1) partial_body<0, 1, true>(a, stage, wave, lane);
+        else if (role == 2) partial_body<1, 0, true>(a, stage, wave, lane);
+        else partial_body<1, 1, true>(a, stage, wave, lane);
     } else {
-        if (wave == 0) partial_body<0, 0, false>(a, stage, 0, lane);
-        else if (wave == 1) partial_body<0, 1, false>(a, stage, 1, lane);
-        else if (wave == 2) partial_body<1, 0, false>(a, stage, 2, lane);
-        else partial_body<1, 1, false>(a, stage, 3, lane);
+        if (role == 0) partial_body<0, 0, false>(a, stage, wave, lane);
+        else if (role == 1) partial_body<0, 1, false>(a, stage, wave, lane);
+        else if (role == 2) partial_body<1, 0, false>(a, stage, wave, lane);
+        else partial_body<1, 1, false>(a, stage, wave, lane);
     }
 }
 
