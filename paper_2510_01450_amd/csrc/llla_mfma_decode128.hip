@@ -35,7 +35,9 @@ constexpr int PRECISE_L = 4 * D;               // sequences up to this length ta
 
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) short4v *lds_short4_ptr;
-typedef __attribute__((address_space(3))) const bf16x8 *lds_bf16x8_ptr;
+typedef __attribute__((address_space(3))) const half8 *lds_half8_ptr;
+typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) uint4v *lds_uint4_ptr;
 
 struct Split {
     int nsplit;          // workgroups (= partial records) per head
@@ -59,6 +61,19 @@ __device__ inline unsigned bf16x2_to_f16x2(unsigned u)
     return __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(lo, hi));
 }
 
+// Row broadcasts across the 16-lane rows of a wave: rows 1 and 3 receive lane 15 of rows 0 and 2 (the other rows
+// keep x); rows 2 and 3 receive lane 31, the last lane of row 1 (rows 0 and 1 keep x).
+__device__ inline float rows_1_3_from_rows_0_2(float x)
+{
+    const int v = __builtin_bit_cast(int, x);
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(v, v, 0x142, 0xa, 0xf, false));
+}
+__device__ inline float rows_2_3_from_row_1(float x)
+{
+    const int v = __builtin_bit_cast(int, x);
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(v, v, 0x143, 0xc, 0xf, false));
+}
+
 template <int N>
 __device__ inline void dma_wait_pending() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
@@ -68,7 +83,7 @@ __device__ inline void dma_wait_pending() { asm volatile("s_waitcnt vmcnt(%0)" :
 // of k, so that the 16 keys a quarter wave reads as natural rows (one chunk each) do too.
 __device__ inline int swz(int key) { return ((key & 7) << 1) ^ ((key >> 3) & 1); }
 
-// Transposed fragment of 16 features x 32 keys as an MFMA operand (bf16 -> f16): slot t < 4 = key 4g + t,
+// Transposed fragment of 16 features x 32 keys as an MFMA operand (the tile already holds f16): slot t < 4 = key 4g + t,
 // slot t >= 4 = key 16 + 4g + t - 4, feature 16 I + nn.  The argument is the lane's LDS byte address for feature
 // block I of the tile; the second half of the keys lies a constant 16 rows further on.
 __device__ inline half8 tr_frag(unsigned lds_byte_addr)
@@ -76,8 +91,7 @@ __device__ inline half8 tr_frag(unsigned lds_byte_addr)
     const short4v a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(uintptr_t)lds_byte_addr);
     const short4v b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(uintptr_t)(lds_byte_addr + 16 * D * 2));
     const uint2 au = __builtin_bit_cast(uint2, a), bu = __builtin_bit_cast(uint2, b);
-    const uint4 p = make_uint4(bf16x2_to_f16x2(au.x), bf16x2_to_f16x2(au.y), bf16x2_to_f16x2(bu.x), bf16x2_to_f16x2(bu.y));
-    return __builtin_bit_cast(half8, p);
+    return __builtin_bit_cast(half8, make_uint4(au.x, au.y, bu.x, bu.y));
 }
 
 __host__ __device__ constexpr int tix4(int i, int j) { return i * 4 - i * (i - 1) / 2 + (j - i); }   // 4x4 upper triangle
@@ -119,9 +133,13 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
     const bf16_t *Vh = a.Vg + b * a.sv.batch + h * a.sv.head;
 
     // query fragments, the same for every column of the B operand: lane (g, *) holds q[32 c + 8 g ..+7]
-    bf16x8 qf[4];
+    // (as f16, like the tiles: exact for values in the f16 range)
+    half8 qf[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) qf[c] = *reinterpret_cast<const bf16x8 *>(a.qg + (size_t)bh * D + 32 * c + 8 * g);
+    for (int c = 0; c < 4; ++c) {
+        const uint4 u = *reinterpret_cast<const uint4 *>(a.qg + (size_t)bh * D + 32 * c + 8 * g);
+        qf[c] = __builtin_bit_cast(half8, make_uint4(bf16x2_to_f16x2(u.x), bf16x2_to_f16x2(u.y), bf16x2_to_f16x2(u.z), bf16x2_to_f16x2(u.w)));
+    }
 
     // this wave's part of a stage: LDS chunk slots [128 wave, 128 wave + 128) of the K tile and of the V tile
     int dma_key[2], dma_col[2];
@@ -187,6 +205,17 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
         }
     };
 
+    // bf16 -> f16 in place for the part of a stage that this wave's own transfers brought in (so only the wave's own
+    // wait is needed before it): every element is converted once per workgroup, not once per wave that uses it
+    auto convert_own = [&](unsigned st) {
+        const unsigned base = st + 2048u * (unsigned)wave + 16u * (unsigned)lane;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const lds_uint4_ptr ptr = (lds_uint4_ptr)(uintptr_t)(base + 1024u * (t & 1) + (t >> 1) * (TILE_H * 2));
+            const uint4v u = *ptr;
+            *ptr = uint4v{bf16x2_to_f16x2(u.x), bf16x2_to_f16x2(u.y), bf16x2_to_f16x2(u.z), bf16x2_to_f16x2(u.w)};
+        }
+    };
     // logits of the 32 keys of a step whose K tile lies at LDS byte address kt: lane (g, *) gets keys 4g..4g+3
     // (sub-tile 0) and 16+4g.. (sub-tile 1); returns their maximum over the wave
     auto logits = [&](unsigned kt, int step, float (&tl)[8]) {
@@ -196,23 +225,26 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
             f32x4 z = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int c = 0; c < 4; ++c)
-                z = mfma_bf16(*(lds_bf16x8_ptr)(uintptr_t)(kt + nat[c] + sub * 16 * D * 2), qf[c], z);
+                z = mfma_f16(*(lds_half8_ptr)(uintptr_t)(kt + nat[c] + sub * 16 * D * 2), qf[c], z);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int j = j0 + 16 * sub + 4 * g + r;
                 tl[4 * sub + r] = (j < r1 && step < nsteps) ? z[r] * a.cscale : -INFINITY;
             }
         }
+        // all 16 lanes of a row hold the same 8 logits; the maximum over the four rows goes through two row
+        // broadcasts of the data-parallel primitives (no LDS round trips) and ends up in the last row
         float mx = fmaxf(fmaxf(fmaxf(tl[0], tl[1]), fmaxf(tl[2], tl[3])), fmaxf(fmaxf(tl[4], tl[5]), fmaxf(tl[6], tl[7])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        return fmaxf(mx, __shfl_xor(mx, 32));
+        mx = fmaxf(mx, rows_1_3_from_rows_0_2(mx));
+        mx = fmaxf(mx, rows_2_3_from_row_1(mx));
+        return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mx), 63));
     };
     // running maximum over the workgroup's keys (the accumulators are rescaled only when it moves), then the weights
     // of the step: wq (f16), and for short sequences the fp32 weights and their f16 tail as well
     float wf[8];
     half8 wq, wl;
     auto weights = [&](float mx, const float (&tl)[8]) {
-        if (__builtin_amdgcn_readfirstlane(mx > m ? 1 : 0)) {
+        if (mx > m) {      // both are wave-uniform
             const float alpha = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - mx);
             m = mx;
             om *= alpha;
@@ -241,14 +273,15 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
     // NSTAGE - 1 stages are issued ahead.  Iteration s multiplies step s into the moments and, independently of
     // that, forms the logits and weights of step s + 1, so that the chain "LDS read, logits, maximum over the wave,
     // exponentials" of one step lies beside the matrix-core work of the step before instead of in front of it.
-    // An iteration therefore reads stages s and s + 1: it first waits for this wave's transfers of step s + 1,
-    // then meets the other waves (now the whole stage s + 1 has landed, and everybody has finished reading stage
-    // s - 1), and only then refills that oldest stage with step s + NSTAGE - 1.  Every iteration issues exactly
+    // An iteration therefore reads stages s and s + 1: it first waits for this wave's transfers of step s + 1 and
+    // converts what they brought, then meets the other waves (now the whole stage s + 1 is there as f16, and
+    // everybody has finished reading stage s - 1), and only then refills that oldest stage with step s + NSTAGE - 1.  Every iteration issues exactly
     // one stage (clamped past the end), so "at most DMA_PER_WAVE (NSTAGE - 3) transfers pending" always means
     // "step s + 1 has landed".
 #pragma unroll
     for (int st = 0; st < NSTAGE - 1; ++st) issue_dma(st);
     dma_wait_pending<DMA_PER_WAVE *(NSTAGE - 2)>();
+    convert_own(lds0);
     __syncthreads();
     {
         float tl[8];
@@ -257,14 +290,15 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
     }
     unsigned read_off = 0;
     for (int s = 0; s < nsteps; ++s) {
-        dma_wait_pending<DMA_PER_WAVE *(NSTAGE - 3)>();
-        __syncthreads();
-        issue_dma(s + NSTAGE - 1);
         // LDS byte addresses of the two stages, kept as scalars that the optimiser cannot take apart (it would
         // otherwise carry one induction register per read and spend two vector-ALU operations on each)
         const unsigned next_off = (read_off == (NSTAGE - 1) * STAGE_H * 2) ? 0u : read_off + STAGE_H * 2;
         unsigned kt = lds0 + read_off, kn = lds0 + next_off;
         asm volatile("" : "+s"(kt), "+s"(kn));
+        dma_wait_pending<DMA_PER_WAVE *(NSTAGE - 3)>();
+        convert_own(kn);
+        __syncthreads();
+        issue_dma(s + NSTAGE - 1);
         const unsigned vt = kt + TILE_H * 2;
         read_off = next_off;
 
@@ -350,7 +384,7 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
     }
 }
 
-__global__ __launch_bounds__(NT, 2) void decode128_partial_kernel(PartialArgs a)
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void decode128_partial_kernel(PartialArgs a)
 {
     __shared__ __align__(16) bf16_t stage[NSTAGE * STAGE_H];       // 4 stages x 16 KB
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64), lane = threadIdx.x % 64;
