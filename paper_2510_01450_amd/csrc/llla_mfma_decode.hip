@@ -200,10 +200,13 @@ __global__ __launch_bounds__(NT, 2) void decode_partial_kernel(const bf16_t *__r
             }
         }
         // running maximum over the wave's keys; the accumulators are rescaled only when it moves
+        // (all 16 lanes of a row hold the same 8 logits; the maximum over the four rows goes through two row
+        // broadcasts of the data-parallel primitives, without LDS round trips, and is read from the last row)
         float mx = fmaxf(fmaxf(fmaxf(tl[0], tl[1]), fmaxf(tl[2], tl[3])), fmaxf(fmaxf(tl[4], tl[5]), fmaxf(tl[6], tl[7])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        if (__builtin_amdgcn_readfirstlane(mx > m ? 1 : 0)) {
+        mx = fmaxf(mx, rows_1_3_from_rows_0_2(mx));
+        mx = fmaxf(mx, rows_2_3_from_row_1(mx));
+        mx = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mx), 63));
+        if (mx > m) {      // both are wave-uniform
             const float alpha = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - mx);
             m = mx;
             om *= alpha;

@@ -61,19 +61,6 @@ __device__ inline unsigned bf16x2_to_f16x2(unsigned u)
     return __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(lo, hi));
 }
 
-// Row broadcasts across the 16-lane rows of a wave: rows 1 and 3 receive lane 15 of rows 0 and 2 (the other rows
-// keep x); rows 2 and 3 receive lane 31, the last lane of row 1 (rows 0 and 1 keep x).
-__device__ inline float rows_1_3_from_rows_0_2(float x)
-{
-    const int v = __builtin_bit_cast(int, x);
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(v, v, 0x142, 0xa, 0xf, false));
-}
-__device__ inline float rows_2_3_from_row_1(float x)
-{
-    const int v = __builtin_bit_cast(int, x);
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(v, v, 0x143, 0xc, 0xf, false));
-}
-
 template <int N>
 __device__ inline void dma_wait_pending() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
