@@ -31,6 +31,7 @@ PEAK_HBM = 8.0e12             # B/s
 # same command, scaled with a copy kernel of known size (profiles/*_hbm_traffic.md, *_mfma_counters.md).
 MEASURED_TRAFFIC = {
     ("C5_decode_bf16_L32768_d64", "decode_partial"): 4.310e9 + 0.056e9,
+    ("C5d128_decode_bf16_L32768_d128", "decode_partial"): 4.310e9 + 0.053e9,
     ("C3_prefill_bf16_n4096_d64", "moments"): 0.141e9 + 0.250e9,
     ("C3b_prefill_bf16_n8192_d64", "moments"): 0.140e9 + 0.289e9,
 }
