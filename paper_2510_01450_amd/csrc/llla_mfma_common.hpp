@@ -66,6 +66,17 @@ __device__ inline float rows_2_3_from_row_1(float x)
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(v, v, 0x143, 0xc, 0xf, false));
 }
 
+// Maximum of x[p * pitch], p in [p0, p1), over a wave: lane l takes p0 + l, p0 + l + 64, .., so the loads of a
+// wave are in flight together (a loop over p in every lane would wait for each load in turn).
+__device__ inline float wave_max_strided(const float *x, int p0, int p1, size_t pitch, int lane)
+{
+    float mv = -INFINITY;
+    for (int p = p0 + lane; p < p1; p += 64) mv = fmaxf(mv, x[(size_t)p * pitch]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mv = fmaxf(mv, __shfl_xor(mv, off));
+    return mv;
+}
+
 __device__ inline void wave_sync()
 {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");

@@ -285,8 +285,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 2))) void
     if (gi >= ngroups) return;
     const int p0 = gi * group, p1 = min(p0 + group, nparts);
     const float *P0 = parts + (size_t)bh * nparts * PART_F;
-    float mstar = -INFINITY;
-    for (int p = p0; p < p1; ++p) mstar = fmaxf(mstar, P0[(size_t)p * PART_F]);
+    const float mstar = wave_max_strided(P0, p0, p1, PART_F, lane);
     float om = 0.f, mu = 0.f, yv = 0.f;
     f32x4 acc[NTILES];
 #pragma unroll
@@ -327,8 +326,7 @@ __global__ __launch_bounds__(NT, 1) void decode_merge_kernel(const bf16_t *__res
     {   // phase 1
         const int hq = min((int)blockIdx.x * QW + wave, BH - 1);
         const float *P0 = parts + (size_t)hq * nparts * PART_F;
-        float mstar = -INFINITY;
-        for (int p = 0; p < nparts; ++p) mstar = fmaxf(mstar, P0[(size_t)p * PART_F]);
+        const float mstar = wave_max_strided(P0, 0, nparts, PART_F, lane);
         float om = 0.f, mu = 0.f, yv = 0.f;
         f32x4 acc[NTILES];
 #pragma unroll

@@ -413,8 +413,7 @@ __global__ __launch_bounds__(NT, 1) void decode128_merge_kernel(const bf16_t *__
     const float *P0 = parts + (size_t)bh * nparts * PART_F;
 
     {   // phase 1
-        float mstar = -INFINITY;
-        for (int p = 0; p < nparts; ++p) mstar = fmaxf(mstar, P0[(size_t)p * PART_F]);
+        const float mstar = wave_max_strided(P0, 0, nparts, PART_F, lane);
         float om = 0.f, hv = 0.f;
         f32x4 acc[TPW];
 #pragma unroll
