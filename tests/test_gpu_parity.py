@@ -300,18 +300,18 @@ def _sampled(w, heads):
 
 def test_c3_prefill_sampled_rows():
     w = workloads.C3
-    _sampled(w, [(0, h) for h in range(0, w.H, 4)] + [(3, 7), (2, 15)])
+    _sampled(w, [(0, h) for h in range(w.H)] + [(3, 7), (2, 15)])
 
 
 def test_c3b_prefill_n8192_sampled_rows():
     """The shape the matrix-core utilisation target is quoted for (d = 64, n = 8192)."""
     w = workloads.C3B
-    _sampled(w, [(0, 0), (0, 9), (1, 15)])
+    _sampled(w, [(0, h) for h in range(w.H)] + [(1, 15), (1, 6)])
 
 
 def test_c4_long_context_sampled_rows():
     w = workloads.C4
-    _sampled(w, [(0, 0), (0, 5), (0, 15)])
+    _sampled(w, [(0, h) for h in range(w.H)])
 
 
 def test_c5_decode_sampled_heads():
@@ -321,11 +321,25 @@ def test_c5_decode_sampled_heads():
     torch.cuda.synchronize()
     got = got.cpu().numpy()
     assert np.all(np.isfinite(got))
-    pick = [(0, 0), (0, 15), (7, 3), (16, 8), (31, 15), (31, 0), (12, 12), (25, 1)]
+    pick = [(0, 0), (0, 15), (7, 3), (16, 8), (31, 15), (31, 0), (12, 12), (25, 1)] + [(b, (5 * b + 2 + 8 * k) % 16) for b in range(32) for k in range(2)]
     for (b, h) in pick:
         ref = oracle.decode(q[b:b + 1, h:h + 1], Kc[b:b + 1, h:h + 1], Vc[b:b + 1, h:h + 1], w.lam, w.scale)
         print((b, h), check(got[b:b + 1, h:h + 1, None, :], ref[:, :, None, :], np.array([w.n - 1]), w.d, w.tol,
                             "C5 head %s" % ((b, h),)))
+
+
+def test_c5d128_decode_sampled_heads():
+    """The d = 128 decode shape that bench.py times (256 heads x 32768 cached keys), sampled heads."""
+    w = workloads.C5D128
+    q, Kc, Vc = workloads.make_inputs(w)
+    got = llla.llla_decode(q.to(DEV), Kc.to(DEV), Vc.to(DEV), w.lam, w.scale)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    assert np.all(np.isfinite(got))
+    for (b, h) in [(0, 0), (0, 15), (7, 3), (15, 15), (15, 0), (12, 12), (3, 9), (9, 1)]:
+        ref = oracle.decode(q[b:b + 1, h:h + 1], Kc[b:b + 1, h:h + 1], Vc[b:b + 1, h:h + 1], w.lam, w.scale)
+        print((b, h), check(got[b:b + 1, h:h + 1, None, :], ref[:, :, None, :], np.array([w.n - 1]), w.d, w.tol,
+                            "C5d128 head %s" % ((b, h),)))
 
 
 # ---- extended forward: a ridge per row (Appendix C) and the statistics rho, delta of Eq. (lla) -----------
