@@ -230,6 +230,43 @@ def test_decode_mfma_short_sequences_in_a_long_cache(d):
                        "decode d=%d seqlen %d of 1024" % (d, L)))
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_decode_mfma_is_deterministic_and_independent_of_order_and_split(d):
+    """The decode moments are sums over a set of keys: the output may not depend on the order of the cache rows, on
+    the number of workgroups a head is cut into (set by the cache capacity and the batch), or on the run."""
+    L = 6000
+    w = _small("decinv", 2, 2, L, d, "bf16", index=130 + d).with_shape(kind="decode")
+    q, Kc, Vc = workloads.make_inputs(w)
+    ref = oracle.decode(q, Kc, Vc, w.lam, w.scale)
+    qd, Kd, Vd = q.to(DEV), Kc.to(DEV), Vc.to(DEV)
+    a = llla.llla_decode(qd, Kd, Vd, w.lam, w.scale, path="mfma")
+    b = llla.llla_decode(qd, Kd, Vd, w.lam, w.scale, path="mfma")
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    a = a.cpu().numpy()
+    print(check(a[:, :, None, :], ref[:, :, None, :], np.array([L - 1]), d, w.tol, "decode d=%d" % d))
+    # the same keys in another order
+    perm = torch.randperm(L, generator=torch.Generator().manual_seed(7))
+    p = llla.llla_decode(qd, Kc[:, :, perm].contiguous().to(DEV), Vc[:, :, perm].contiguous().to(DEV), w.lam, w.scale,
+                         path="mfma").cpu().numpy()
+    print(check(p[:, :, None, :], ref[:, :, None, :], np.array([L - 1]), d, w.tol, "decode d=%d, permuted cache" % d))
+    assert np.linalg.norm(p - a) / np.linalg.norm(a) < 1e-3
+    # the same sequences in a cache of four times the capacity (more workgroups per head), and in a batch large
+    # enough that every head gets a single workgroup
+    big = torch.zeros(2, 2, 4 * L, d, dtype=torch.bfloat16)
+    Kb, Vb = big.clone(), big.clone()
+    Kb[:, :, :L], Vb[:, :, :L] = Kc, Vc
+    sl = torch.full((2,), L, dtype=torch.int32, device=DEV)
+    c = llla.llla_decode(qd, Kb.to(DEV), Vb.to(DEV), w.lam, w.scale, seqlens=sl, path="mfma").cpu().numpy()
+    assert np.linalg.norm(c - a) / np.linalg.norm(a) < 1e-3
+    rep = 160
+    e = llla.llla_decode(qd.repeat(rep, 1, 1), Kd.repeat(rep, 1, 1, 1), Vd.repeat(rep, 1, 1, 1), w.lam, w.scale,
+                         path="mfma").cpu().numpy()
+    # (copies of a head in different batch entries sweep their keys from different starting points: equal up to
+    # rounding, not bit by bit)
+    assert np.linalg.norm(e[:2] - a) / np.linalg.norm(a) < 1e-3 and np.linalg.norm(e[-2:] - a) / np.linalg.norm(a) < 1e-3
+
+
 def test_decode_seqlens_and_forward_last_row():
     w = _small("decsl", 4, 2, 600, 64, "bf16", index=120).with_shape(kind="decode")
     q, Kc, Vc = workloads.make_inputs(w)

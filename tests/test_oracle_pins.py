@@ -208,6 +208,23 @@ def test_P9_decode_equals_last_row_and_prefix_property():
     assert np.abs(od[0, 0] - O[19]).max() <= 1e-12 and np.abs(od[1, 0] - O[-1]).max() <= 1e-12
 
 
+def test_decode_is_invariant_under_a_permutation_of_the_cache():
+    """A decode step is a weighted least-squares fit over a SET of (key, value) pairs (Eq. (lla_obj): a sum over j
+    with weights that depend on q and k_j only), so reordering the cache rows, keys and values together, cannot
+    change it.  (A forward row sees a prefix and is not invariant; this pins that the decode oracle uses nothing
+    positional.)"""
+    n, d = 40, 8
+    Q, K, V = _rand(n, d, d, 21)
+    scale = 1.0 / math.sqrt(d)
+    o = oracle.decode(Q[None, None, -1], K[None, None], V[None, None], LAM, scale)[0, 0]
+    perm = np.random.default_rng(5).permutation(n)
+    op = oracle.decode(Q[None, None, -1], K[None, None, perm], V[None, None, perm], LAM, scale)[0, 0]
+    assert np.abs(o - op).max() <= 1e-12
+    # and it is NOT invariant when only the keys are permuted (a mistake that pairs k_j with the wrong v_j shows)
+    ow = oracle.decode(Q[None, None, -1], K[None, None, perm], V[None, None], LAM, scale)[0, 0]
+    assert np.abs(o - ow).max() > 1e-3
+
+
 def test_P10_uncentred_augmented_identity():
     """Second algebraic route: with phi_j = [1; k_j], At = sum w phi phi^T + lam diag(0, I) and
     y = At^{-1} [1; q_i], the output is sum_j w_j (phi_j . y) v_j (the fit c + W x evaluated at q_i
