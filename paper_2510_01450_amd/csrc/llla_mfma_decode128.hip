@@ -214,9 +214,14 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
             for (int c = 0; c < 4; ++c)
                 z = mfma_f16(*(lds_half8_ptr)(uintptr_t)(kt + nat[c] + sub * 16 * D * 2), qf[c], z);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int j = j0 + 16 * sub + 4 * g + r;
-                tl[4 * sub + r] = (j < r1 && step < nsteps) ? z[r] * a.cscale : -INFINITY;
+            for (int r = 0; r < 4; ++r) tl[4 * sub + r] = z[r] * a.cscale;
+        }
+        // only a step that reaches past the wave's share (or lies past its last step) masks keys
+        if (__builtin_amdgcn_readfirstlane((j0 + STEP > r1 || step >= nsteps) ? 1 : 0)) {
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const int j = j0 + 16 * (t >> 2) + 4 * g + (t & 3);
+                if (!(j < r1 && step < nsteps)) tl[t] = -INFINITY;
             }
         }
         // all 16 lanes of a row hold the same 8 logits; the maximum over the four rows goes through two row
@@ -248,12 +253,14 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
             wf[t] = __builtin_amdgcn_exp2f(tl[t] - mref);             // exp2(-inf) = 0 masks the tail
             wq[t] = (_Float16)wf[t];
         }
+        // omega sums the weights exactly as the matrix cores see them; only the wave that writes it keeps it
         if constexpr (precise) {
 #pragma unroll
-            for (int t = 0; t < 8; ++t) { wl[t] = (_Float16)(wf[t] - (float)wq[t]); om += wf[t]; }
-        } else {
+            for (int t = 0; t < 8; ++t) wl[t] = (_Float16)(wf[t] - (float)wq[t]);
+        }
+        if constexpr (WA == 0 && WB == 0) {
 #pragma unroll
-            for (int t = 0; t < 8; ++t) om += (float)wq[t];
+            for (int t = 0; t < 8; ++t) om += precise ? wf[t] : (float)wq[t];
         }
     };
 
