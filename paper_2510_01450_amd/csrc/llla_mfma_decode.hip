@@ -30,6 +30,7 @@ constexpr int DMA_PER_STAGE = 8;
 constexpr int NTILES = 26;                     // 10 (Sigma~ upper) + 16 (G~)
 constexpr int PART_F = 192 + NTILES * 256;     // floats per partial: [m, omega, ..], mu~[64], y0v[64], tiles
 constexpr int MIN_L = 1024;                    // shorter caches go to the vector path
+constexpr int PRECISE_L = 4 * D;               // sequences up to this length take the two-term weights
 
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) short4v *lds_short4_ptr;
@@ -76,15 +77,17 @@ __device__ inline unsigned bf16x2_to_f16x2(unsigned u)
 template <int N>
 __device__ inline void dma_wait_pending() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-__global__ __launch_bounds__(NT, 2) void decode_partial_kernel(const bf16_t *__restrict__ qg,
-                                                               const bf16_t *__restrict__ Kg,
-                                                               const bf16_t *__restrict__ Vg, llla_strides sk,
-                                                               llla_strides sv, const int32_t *__restrict__ seqlens,
-                                                               int H, int L_max, int nparts, float cscale,
-                                                               float *__restrict__ parts)
+// PRECISE (short sequences, chosen per sequence by the kernel): with fewer keys than features only the ridge holds
+// some directions, and the 2^-11 rounding of w k is then not small against it.  Such sequences take the weights in
+// fp32 and hand w and w k to the matrix cores as an f16 head plus an f16 tail.  Long ones round w to f16 once and
+// use that same rounded weight in every moment.
+template <bool PRECISE>
+__device__ __forceinline__ void decode_partial_body(bf16_t (&stage)[4][NSTAGE][STAGE_H], const bf16_t *__restrict__ qg,
+                                                    const bf16_t *__restrict__ Kg, const bf16_t *__restrict__ Vg,
+                                                    llla_strides sk, llla_strides sv,
+                                                    const int32_t *__restrict__ seqlens, int H, int L_max, int nparts,
+                                                    float cscale, float *__restrict__ parts)
 {
-    __shared__ __align__(16) bf16_t stage[4][NSTAGE][STAGE_H];     // 4 waves x NSTAGE stages x 8 KB
-
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64, g = lane / 16,
               nn = lane % 16;
     const int bh = blockIdx.y, b = bh / H, h = bh % H;
@@ -217,11 +220,18 @@ __global__ __launch_bounds__(NT, 2) void decode_partial_kernel(const bf16_t *__r
 #pragma unroll
             for (int t = 0; t < 4; ++t) { muacc[t] *= alpha; yvacc[t] *= alpha; }
         }
-        half8 wq;
+        float wf[8];
+        half8 wq, wl;
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-            wq[t] = (_Float16)__builtin_amdgcn_exp2f(tl[t] - m);      // exp2(-inf) = 0 masks the tail
-            om += (float)wq[t];
+            wf[t] = __builtin_amdgcn_exp2f(tl[t] - m);                // exp2(-inf) = 0 masks the tail
+            wq[t] = (_Float16)wf[t];
+            if (PRECISE) {
+                wl[t] = (_Float16)(wf[t] - (float)wq[t]);
+                om += wf[t];
+            } else {
+                om += (float)wq[t];                                   // omega sums the weights as the MFMAs see them
+            }
         }
 
         // transposed K and V fragments (bf16 -> f16, exact): slot t < 4 = key 4g+t, t >= 4 = key 16+4g+t-4
@@ -241,18 +251,40 @@ __global__ __launch_bounds__(NT, 2) void decode_partial_kernel(const bf16_t *__r
             kf[I] = __builtin_bit_cast(half8, kp);
             vf[I] = __builtin_bit_cast(half8, vp);
         }
+        auto row_mfmas = [&](int I, const half8 &af) {
 #pragma unroll
-        for (int I = 0; I < 4; ++I) {
-            const half8 af = kf[I] * wq;
-#pragma unroll
-            for (int J = I; J < 4; ++J) sig[tix(I, J)] = mfma_f16(af, kf[J], sig[tix(I, J)]);
+            for (int J = 0; J < 4; ++J)
+                if (J >= I) sig[tix(I, J)] = mfma_f16(af, kf[J], sig[tix(I, J)]);
 #pragma unroll
             for (int J = 0; J < 4; ++J) gt[4 * I + J] = mfma_f16(af, vf[J], gt[4 * I + J]);
-        }
+        };
+        auto bcast_mfmas = [&](const half8 &wv) {
 #pragma unroll
-        for (int J = 0; J < 4; ++J) {
-            muacc[J] = mfma_f16(wq, kf[J], muacc[J]);       // every row of the tile = mu~[16J + nn]
-            yvacc[J] = mfma_f16(wq, vf[J], yvacc[J]);       // every row = (sum w v)[16J + nn]
+            for (int J = 0; J < 4; ++J) {
+                muacc[J] = mfma_f16(wv, kf[J], muacc[J]);       // every row of the tile = mu~[16J + nn]
+                yvacc[J] = mfma_f16(wv, vf[J], yvacc[J]);       // every row = (sum w v)[16J + nn]
+            }
+        };
+        if (!PRECISE) {
+#pragma unroll
+            for (int I = 0; I < 4; ++I) row_mfmas(I, kf[I] * wq);
+            bcast_mfmas(wq);
+        } else {
+            // w k in fp32 (exact up to the rounding of w), handed to the matrix cores as an f16 head plus an f16 tail
+#pragma unroll
+            for (int I = 0; I < 4; ++I) {
+                half8 ah, al;
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    const float pr = (float)kf[I][t] * wf[t];
+                    ah[t] = (_Float16)pr;
+                    al[t] = (_Float16)(pr - (float)ah[t]);
+                }
+                row_mfmas(I, ah);
+                row_mfmas(I, al);
+            }
+            bcast_mfmas(wq);
+            bcast_mfmas(wl);
         }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // drain the clamped tail DMAs before the wave ends
@@ -269,6 +301,22 @@ __global__ __launch_bounds__(NT, 2) void decode_partial_kernel(const bf16_t *__r
     for (int t = 0; t < 10; ++t) *reinterpret_cast<f32x4 *>(P + 192 + t * 256 + lane * 4) = sig[t];
 #pragma unroll
     for (int t = 0; t < 16; ++t) *reinterpret_cast<f32x4 *>(P + 192 + (10 + t) * 256 + lane * 4) = gt[t];
+}
+
+__global__ __launch_bounds__(NT, 2) void decode_partial_kernel(const bf16_t *__restrict__ qg,
+                                                               const bf16_t *__restrict__ Kg,
+                                                               const bf16_t *__restrict__ Vg, llla_strides sk,
+                                                               llla_strides sv, const int32_t *__restrict__ seqlens,
+                                                               int H, int L_max, int nparts, float cscale,
+                                                               float *__restrict__ parts)
+{
+    __shared__ __align__(16) bf16_t stage[4][NSTAGE][STAGE_H];     // 4 waves x NSTAGE stages x 8 KB
+    const int b = (int)blockIdx.y / H;
+    const int L = seqlens ? min(max(seqlens[b], 1), L_max) : L_max;
+    if (__builtin_amdgcn_readfirstlane(L <= PRECISE_L ? 1 : 0))
+        decode_partial_body<true>(stage, qg, Kg, Vg, sk, sv, seqlens, H, L_max, nparts, cscale, parts);
+    else
+        decode_partial_body<false>(stage, qg, Kg, Vg, sk, sv, seqlens, H, L_max, nparts, cscale, parts);
 }
 
 // Combine stage for heads with many partials: one wave merges partials [g * group, (g + 1) * group) of a head into a
