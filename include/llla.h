@@ -184,7 +184,7 @@ llla_status llla_decode(const void *q, const void *Kc, const void *Vc, void *o,
                         void *workspace, size_t workspace_bytes, void *stream);
 
 /* Same as llla_decode with the kernel family chosen by the caller.  The matrix-core kernels serve bf16 caches with
- * d = 64 or 128, L_max >= 1024 and B * H <= 65535 (keys and values must be representable in f16, |x| <= 65504);
+ * d = 64 or 128, L_max >= 1024 and B * H <= 65535 (queries, keys and values must lie in the f16 range, |x| <= 65504);
  * LLLA_PATH_MFMA on any other call returns LLLA_ERR_UNSUPPORTED, LLLA_PATH_AUTO takes the vector kernels there. */
 llla_status llla_decode_path(const void *q, const void *Kc, const void *Vc, void *o,
                              llla_strides sk, llla_strides sv, const int32_t *seqlens,

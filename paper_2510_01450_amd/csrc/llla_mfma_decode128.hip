@@ -11,7 +11,8 @@
 // the two broadcast moments are dealt out so that the waves carry 30 / 32 / 24 / 30 tiles.  Every wave computes
 // the 32 logits of a step itself (8 MFMAs) so that weights, running maximum and rescaling decisions are
 // bit-identical in the four waves without any exchange.  A step's K and V tiles (16 KB) are brought into LDS
-// by all four waves (a quarter each) and three stages rotate with one workgroup barrier per step.
+// by all four waves (a quarter each, which the same wave then converts from bf16 to f16 in place) and four
+// stages rotate with one workgroup barrier per step.
 #include "llla_mfma_common.hpp"
 
 namespace llla {
@@ -22,7 +23,7 @@ using namespace mfma;
 using S128 = Shape<128>;
 constexpr int D = 128, NB = 8, NT = 256;
 constexpr int STEP = 32;                       // keys per MFMA step
-constexpr int NSTAGE = 4;                      // LDS stages per workgroup: two being read, two in flight
+constexpr int NSTAGE = 4;                      // LDS stages per workgroup: two being read, two being filled
 constexpr int TILE_H = STEP * D;               // halves of one natural [32 keys][128] tile (8 KB)
 constexpr int STAGE_H = 2 * TILE_H;            // K tile + V tile
 constexpr int DMA_PER_WAVE = 4;                // transfers one wave issues per stage (2 for K, 2 for V)
