@@ -193,30 +193,48 @@ __global__ __launch_bounds__(256) void sweep_kernel(const bf16_t *__restrict__ Q
                 ut[s] = u;
             }
         }
-        // lane (g, nn): st[s][r] = <k_j, q_iq> for key j = 32c + 16s + 4g + r
+        // lane (g, nn): st[s][r] = <k_j, q_iq> for key j = 32c + 16s + 4g + r.  Only the blocks that reach past the
+        // wave's first query need the causal mask (a scalar condition): the others skip the compares and selects,
+        // which are most of the vector work of this sweep.
+        const bool masked = c * KB + KB - 1 > i0 + wave * 16;
         if (MAXONLY) {
+            if (!masked) {
 #pragma unroll
-            for (int s = 0; s < 2; ++s)
+                for (int s = 0; s < 2; ++s)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int j = c * KB + 16 * s + 4 * g + r;
-                    const float t = st[s][r] * cscale;
-                    mx[s][r] = (j <= iq) ? fmaxf(mx[s][r], t) : mx[s][r];
-                }
+                    for (int r = 0; r < 4; ++r) mx[s][r] = fmaxf(mx[s][r], st[s][r] * cscale);
+            } else {
+#pragma unroll
+                for (int s = 0; s < 2; ++s)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int j = c * KB + 16 * s + 4 * g + r;
+                        const float t = st[s][r] * cscale;
+                        mx[s][r] = (j <= iq) ? fmaxf(mx[s][r], t) : mx[s][r];
+                    }
+            }
         } else {
             bf16x8 ch, cl;      // output weights as bf16 hi + lo; slot t<4: key 4g+t, t>=4: key 16+4g+t-4
+            float cv[8];
 #pragma unroll
             for (int s = 0; s < 2; ++s)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int j = c * KB + 16 * s + 4 * g + r;
-                    const float wgt = __builtin_amdgcn_exp2f(st[s][r] * cscale - mrow);
-                    const float cv = (j <= iq) ? wgt * (y0 + ut[s][r]) : 0.f;
-                    csum += cv;
-                    const __bf16 hi = (__bf16)cv;
-                    ch[4 * s + r] = hi;
-                    cl[4 * s + r] = (__bf16)(cv - (float)hi);
+                for (int r = 0; r < 4; ++r)
+                    cv[4 * s + r] = __builtin_amdgcn_exp2f(st[s][r] * cscale - mrow) * (y0 + ut[s][r]);
+            if (masked) {
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    const int j = c * KB + 16 * (t >> 2) + 4 * g + (t & 3);
+                    cv[t] = (j <= iq) ? cv[t] : 0.f;
                 }
+            }
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                csum += cv[t];
+                const __bf16 hi = (__bf16)cv[t];
+                ch[t] = hi;
+                cl[t] = (__bf16)(cv[t] - (float)hi);
+            }
 #pragma unroll
             for (int J = 0; J < NB; ++J) {
                 bf16x8 vf;
