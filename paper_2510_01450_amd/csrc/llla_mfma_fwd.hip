@@ -458,11 +458,18 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     };
     auto weights_store = [&](int blk, int buf, f32x4 z) {
         float wf[4];
+        // stored negated: the tiles accumulate -(w k) k^T.  A block that lies wholly before the workgroup's first
+        // query needs no causal mask (a scalar condition; most blocks of a long row)
+        if (blk * KB2 + KB2 - 1 <= i0 && QB == 16) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int j = blk * KB2 + 16 * wave + 4 * g + r;
-            const float wgt = __builtin_amdgcn_exp2f(z[r] * cscale - mrow);
-            wf[r] = (q_live && j <= iq) ? -wgt : 0.f;     // stored negated: the tiles accumulate -(w k) k^T
+            for (int r = 0; r < 4; ++r) wf[r] = -__builtin_amdgcn_exp2f(z[r] * cscale - mrow);
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int j = blk * KB2 + 16 * wave + 4 * g + r;
+                const float wgt = __builtin_amdgcn_exp2f(z[r] * cscale - mrow);
+                wf[r] = (q_live && j <= iq) ? -wgt : 0.f;
+            }
         }
         if (PRECISE) {
             *reinterpret_cast<f32x4 *>(&wt32[buf][nn * WT32_PITCH + 16 * wave + 4 * g]) = f32x4{wf[0], wf[1], wf[2], wf[3]};
