@@ -422,21 +422,36 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     // second-moment operand reads of a transposed sub-tile: feature row 16 I + nn, key chunk g
     const int kt_r = (nn * 4 + (g ^ ((nn >> 2) & 3))) * 8;  // + I * 16 * 32 halves
 
+    // Transfers take a scalar base address per block plus per-lane byte offsets that never change, so that a
+    // transfer costs no vector-ALU address arithmetic (every vector instruction of this loop competes with the
+    // MFMAs for the issue port); only the last, ragged block of natural rows clamps its rows per lane.
+    unsigned tr_boff[TR_INSTR], kn_boff[NAT_INSTR];
+#pragma unroll
+    for (int t = 0; t < TR_INSTR; ++t) tr_boff[t] = 2u * (unsigned)tr_goff[t];
+#pragma unroll
+    for (int t = 0; t < NAT_INSTR; ++t) kn_boff[t] = 2u * (unsigned)(kn_key[t] * (int)sk.seq + kn_gcol[t]);
+    const bool small_pitch = sk.seq < (int64_t(1) << 23);       // the offsets above fit 32 bits
     auto issue_dma = [&](int blk) {     // block blk -> LDS buffer blk & 1
         const int buf = blk & 1;
         if (t_wave) {
             const _Float16 *src = KTh + (size_t)blk * (2 * KT_SUB);
 #pragma unroll
             for (int t = 0; t < TR_INSTR; ++t) {
-                dma16(src + tr_goff[t], &kt[buf][0][(tw * TR_SLOTS + 64 * t) * 8]);
-                dma16(src + KT_SUB + tr_goff[t], &kt[buf][1][(tw * TR_SLOTS + 64 * t) * 8]);
+                dma16_base(src, tr_boff[t], &kt[buf][0][(tw * TR_SLOTS + 64 * t) * 8]);
+                dma16_base(src + KT_SUB, tr_boff[t], &kt[buf][1][(tw * TR_SLOTS + 64 * t) * 8]);
             }
         }
         if (w_wave) {
+            if (small_pitch && blk * KB2 + KB2 <= n) {
+                const bf16_t *src = Kh + (int64_t)blk * KB2 * sk.seq;
 #pragma unroll
-            for (int t = 0; t < NAT_INSTR; ++t) {
-                const int j = min(blk * KB2 + kn_key[t], n - 1);
-                dma16(Kh + (int64_t)j * sk.seq + kn_gcol[t], &kn[buf][(16 * CH * wave + 64 * t) * 8]);
+                for (int t = 0; t < NAT_INSTR; ++t) dma16_base(src, kn_boff[t], &kn[buf][(16 * CH * wave + 64 * t) * 8]);
+            } else {
+#pragma unroll
+                for (int t = 0; t < NAT_INSTR; ++t) {
+                    const int j = min(blk * KB2 + kn_key[t], n - 1);
+                    dma16(Kh + (int64_t)j * sk.seq + kn_gcol[t], &kn[buf][(16 * CH * wave + 64 * t) * 8]);
+                }
             }
         }
     };
