@@ -342,7 +342,6 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     auto &kn = sm.kn;
     auto &wt = sm.w.h;
     auto &wt32 = sm.w.f;
-    auto &omp = sm.omp;
     auto &mus = sm.mus;
     auto &oms = sm.oms;
     auto &sc = sm.sc;
@@ -397,7 +396,11 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
             for (int t = 0; t < 4; ++t) acc[q][S::tix(P, P)][t] = (nn == 4 * g + t) ? -lq : 0.f;
     }
     f32x4 mu_acc = {0.f, 0.f, 0.f, 0.f};
-    float om_part = 0.f;            // this lane's share of omega for query i0 + nn
+    // omega: at d = 64 one wave sums it on the matrix cores (see mu_mfma); at d = 128, where the registers for that are
+    // not there (measured 5 % slower), every weight wave sums its own keys on the vector ALU
+    constexpr bool OM_MFMA = (DD == 64);
+    f32x4 om_acc = {0.f, 0.f, 0.f, 0.f};      // OM_MFMA, one wave: -omega of query 4g + r in every column
+    float om_part = 0.f;                      // otherwise: this lane's share of omega for query i0 + nn
 
     // ---- per-lane constants of the staging and of the operand reads ------------------------------
     int tr_goff[TR_INSTR];                                  // halves inside a [feature][32 key] sub-tile
@@ -488,13 +491,13 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
         }
         if (PRECISE) {
             *reinterpret_cast<f32x4 *>(&wt32[buf][nn * WT32_PITCH + 16 * wave + 4 * g]) = f32x4{wf[0], wf[1], wf[2], wf[3]};
-            om_part -= (wf[0] + wf[1]) + (wf[2] + wf[3]);
+            if (!OM_MFMA) om_part -= (wf[0] + wf[1]) + (wf[2] + wf[3]);
         } else {
             half4 wv;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 wv[r] = (_Float16)wf[r];
-                om_part -= (float)wv[r];        // omega sums the weights exactly as the MFMAs see them
+                if (!OM_MFMA) om_part -= (float)wv[r];      // omega sums the weights exactly as the MFMAs see them
             }
             *reinterpret_cast<half4 *>(&wt[buf][nn * WT_PITCH + 16 * wave + 4 * g]) = wv;
         }
@@ -564,9 +567,20 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
             split_f16(wv, mu_a, mu_a2);
         }
     };
+    // omega rides on the same A operand with a tile of ones as B: it sums the weights exactly as the MFMAs of the
+    // other moments see them, and costs one wave one MFMA per half instead of every weight wave eight vector
+    // instructions per block (which compete with the MFMAs for the issue port)
+    constexpr int OM_WAVE = NW - 1;
+    half8 ones;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) ones[t] = (_Float16)1.f;
     auto mu_mfma = [&]() {
         if (PRECISE) mu_acc = mfma_f16(mu_a2, mu_b, mu_acc);
         mu_acc = mfma_f16(mu_a, mu_b, mu_acc);          // -mu~[row 4g + r][feature 16 wave + nn]
+        if (OM_MFMA && wave == OM_WAVE) {
+            if (PRECISE) om_acc = mfma_f16(mu_a2, ones, om_acc);
+            om_acc = mfma_f16(mu_a, ones, om_acc);      // -omega[row 4g + r] in every column
+        }
     };
 
     // Software pipeline over blocks of 64 keys, one barrier per block, placed between its two halves:
@@ -653,17 +667,25 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
         }
     }
 
-    // omega: lanes (g, nn) of the four weight waves hold partial sums for query row nn
-    om_part += __shfl_xor(om_part, 16);
-    om_part += __shfl_xor(om_part, 32);
-    if (w_wave && g == 0) omp[wave][nn] = om_part;
 
     // ---- hand mu~ and omega to the waves that own the queries ---------------------------------------
 #pragma unroll
     for (int r = 0; r < 4; ++r) mus[4 * g + r][16 * wave + nn] = mu_acc[r];   // -mu~ (negated weights)
-    __syncthreads();
-    if (tid < 16) oms[tid] = (omp[0][tid] + omp[1][tid]) + (omp[2][tid] + omp[3][tid]);
-    __syncthreads();
+    if (OM_MFMA) {
+        if (wave == OM_WAVE && nn == 0) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) oms[4 * g + r] = -om_acc[r];
+        }
+        __syncthreads();
+    } else {
+        // lanes (g, nn) of the four weight waves hold partial sums for query row nn
+        om_part += __shfl_xor(om_part, 16);
+        om_part += __shfl_xor(om_part, 32);
+        if (w_wave && g == 0) sm.omp[wave][nn] = om_part;
+        __syncthreads();
+        if (tid < 16) oms[tid] = (sm.omp[0][tid] + sm.omp[1][tid]) + (sm.omp[2][tid] + sm.omp[3][tid]);
+        __syncthreads();
+    }
 
     // ---- per-query solve (see solve_wave); the right-hand sides [mu~ q] are built inside it ----------
     f32x4 rhs[QW][NB];
