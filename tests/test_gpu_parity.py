@@ -139,6 +139,18 @@ def test_large_logits_do_not_overflow():
     print(check(got, ref, np.arange(w.n), w.d, 1e-4, "large logits"))
 
 
+@pytest.mark.parametrize("path,d", [("mfma", 64), ("mfma", 128), ("valu", 64)])
+def test_negative_and_zero_scale(path, d):
+    """scale only has to be finite: a negative one turns the nearest keys into the farthest (the row maximum is then
+    the scaled MINIMUM of the products), zero makes all weights equal."""
+    for scale in (-0.11, 0.0):
+        w = _small("negscale", 1, 2, 333, d, "bf16", index=140 + d).with_shape(scale=scale)
+        Q, K, V = workloads.make_inputs(w)
+        ref = oracle.forward(Q, K, V, w.lam, scale)
+        got = llla.llla_forward(Q.to(DEV), K.to(DEV), V.to(DEV), w.lam, scale, path=path).cpu().numpy()
+        print(scale, check(got, ref, np.arange(w.n), d, w.tol, "scale %g %s d=%d" % (scale, path, d)))
+
+
 def test_deterministic():
     w = _small("det", 2, 2, 300, 64, "bf16", index=92)
     Q, K, V = [t.to(DEV) for t in workloads.make_inputs(w)]
