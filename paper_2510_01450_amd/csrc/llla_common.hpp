@@ -48,6 +48,15 @@ hipError_t valu_forward(const Problem &p);
 hipError_t valu_forward_given(const Problem &p, int nrows, const float *M, int mpitch, const float *Y, int ypitch);
 hipError_t valu_decode(const Problem &p);
 
+// Queries that see at most dual_max_keys(d) = min(d, DUAL_MAX_KEYS) keys: fp64, key-space form of the same minimiser
+// (llla_dual.hip).  dual_forward() serves rows [0, dual_forward_rows(p)) of a forward call (O, and rho / delta when
+// asked for); dual_decode() serves the sequences of a decode call that are short enough and leaves the others alone.
+constexpr int DUAL_MAX_KEYS = 64;
+int dual_max_keys(int d);
+int dual_forward_rows(const Problem &p);
+hipError_t dual_forward(const Problem &p);
+hipError_t dual_decode(const Problem &p);
+
 size_t valu_backward_workspace_bytes(int B, int H, int n, int d);
 hipError_t valu_backward(const BackwardProblem &p);
 // backward with the matrix-core moments and solve (bf16, d = 64 / 128): workspace layout and the two MFMA stages

@@ -397,7 +397,25 @@ hipError_t valu_forward_given(const Problem &p, int nrows, const float *M, int m
     return hipErrorInvalidValue;
 }
 
-hipError_t valu_forward(const Problem &p) { return by_dim<false>(p, p.n); }
-hipError_t valu_decode(const Problem &p) { return by_dim<true>(p, 1); }
+// Rows that see at most dual_max_keys(d) keys are rewritten afterwards by the fp64 key-space kernel (the output
+// weights of such a row cancel to three digits in fp32); a call that consists of such rows only skips the sweep.
+hipError_t valu_forward(const Problem &p)
+{
+    if (dual_forward_rows(p) < p.n) {
+        const hipError_t e = by_dim<false>(p, p.n);
+        if (e != hipSuccess) return e;
+    }
+    return dual_forward(p);
+}
+
+hipError_t valu_decode(const Problem &p)
+{
+    const bool all_short = p.n <= dual_max_keys(p.d);
+    if (!all_short) {
+        const hipError_t e = by_dim<true>(p, 1);
+        if (e != hipSuccess || p.seqlens == nullptr) return e;      // without lengths every sequence is long
+    }
+    return dual_decode(p);
+}
 
 }  // namespace llla

@@ -134,14 +134,14 @@ def make_inputs(w: Workload):
     return Q.to(dt), K.to(dt), V.to(dt)
 
 
-def sample_rows(w: Workload, n_random: int = 256):
+def sample_rows(w: Workload, n_random: int = 96):
     """Rows checked one by one against the oracle when the full output is too expensive:
-    0..4d, every multiple of 64/128/256 with both neighbours, n_random uniform rows, the last."""
+    0..4d, every multiple of 64 (hence of 128 and 256: the tile boundaries of every kernel) with both
+    neighbours, n_random uniform rows, the last."""
     n, d = w.n, w.d
     rows = set(range(min(n, 4 * d + 1)))
-    for step in (64, 128, 256):
-        for r in range(step, n, step * 8):
-            rows.update(x for x in (r - 1, r, r + 1) if 0 <= x < n)
+    for r in range(64, n, 64):
+        rows.update(x for x in (r - 1, r, r + 1) if 0 <= x < n)
     g = torch.Generator(device="cpu").manual_seed(SEED0 + 1000 + w.index)
     rows.update(int(x) for x in torch.randint(0, n, (n_random,), generator=g))
     rows.add(n - 1)
