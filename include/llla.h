@@ -25,9 +25,9 @@
  *
  * Memory and execution contract (all entry points):
  *   - every data pointer is a DEVICE pointer owned by the caller; the library never allocates or
- *     frees device memory, never synchronises the device (llla_profile_last excepted), and enqueues
- *     all work on `stream`
- *     (a hipStream_t passed as void*; NULL = the default stream);
+ *     frees device memory, never synchronises the device, keeps no state between calls (it is
+ *     thread-safe), and enqueues all work on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream);
  *   - tensors are [batch, head, seq, d] with the innermost (d) stride equal to 1; the other strides
  *     are given in elements in an llla_strides;
  *   - inputs are never modified, outputs are fully overwritten, results are deterministic;
@@ -37,6 +37,15 @@
  *     (256-byte aligned); it holds Theta(B*H*n*d) data only -- no per-query d x d matrix and no
  *     n x n matrix is ever written to device memory.  Calls that share a workspace must be
  *     ordered on one stream.
+ *
+ * Value range of the matrix-core kernels.  LLLA_PATH_AUTO serves bf16 inputs with d = 64 or 128 on
+ * the matrix cores (llla_forward, llla_forward_ex, llla_forward_cg, llla_backward, and llla_decode
+ * with a cache capacity of at least 1024 rows).  Those kernels hand the keys (and, in decode, queries and
+ * values) to the MFMA units as f16: every |x| must be at most 65504 (larger ones become
+ * infinite and the affected rows NaN; no status is returned, the data being device memory), and
+ * magnitudes below 6.1e-5 lose bits to the f16 subnormal range.  bf16 values of ordinary size
+ * (8 significant bits, |x| in [6.1e-5, 65504]) convert exactly.  LLLA_PATH_VALU computes in fp32
+ * throughout and has no such limit.
  */
 #ifndef LLLA_H
 #define LLLA_H
@@ -191,27 +200,6 @@ llla_status llla_decode_path(const void *q, const void *Kc, const void *Vc, void
                              int B, int H, int L_max, int d, llla_dtype in, llla_dtype out,
                              float lambda, float scale, llla_path path,
                              void *workspace, size_t workspace_bytes, void *stream);
-
-/*
- * Measurement aid (used by bench.py; not part of the method).  After llla_profile_enable(1) every
- * forward / decode call records HIP events around each kernel it enqueues, on the caller's stream.
- * llla_profile_last() waits for the events of the most recent call and writes up to `max` stage
- * durations in milliseconds to ms[] and pointers to static stage names to names[]; it returns
- * the number of stages (0 if profiling is off or nothing was recorded).  This is the library's only
- * process-wide state: it is not thread-safe and must stay off (the default) in production use.
- */
-void llla_profile_enable(int on);
-int llla_profile_last(float *ms, const char **names, int max);
-
-/*
- * Measurement aid (used by bench.py; not part of the method).  Enqueues one launch of nothing but
- * independent v_mfma_f32_16x16x32_f16 instructions on every compute unit, `iters` x 8 per wavefront, and
- * writes the number of floating-point operations of that launch to *flops (host).  Timing the launch
- * on `stream` gives the 16-bit matrix-core rate the GPU sustains at the clock it settles to under such a
- * load, the practical ceiling beside the published peak.  `scratch` is a device buffer of >= 4 bytes that
- * is never written in practice (it only keeps the arithmetic alive).  1 <= iters <= 2^20.
- */
-llla_status llla_probe_mfma_f16(int iters, void *scratch, double *flops, void *stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char *llla_status_string(llla_status status);

@@ -2,13 +2,16 @@
 from __future__ import annotations
 
 import ctypes
+import functools
 import os
 
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libllla.so")
-_lib = None
+_MEASURE_PATH = os.path.join(_HERE, "libllla_measure.so")
+_libs = {}
+_use_measure = False
 
 PATHS = {"auto": 0, "valu": 1, "mfma": 2}
 _DTYPES = {torch.float32: 0, torch.bfloat16: 1}
@@ -28,15 +31,18 @@ def lib_path() -> str:
     return _LIB_PATH
 
 
-def lib():
-    """The loaded C-ABI library.  Builds it with hipcc only if no built library exists."""
-    global _lib
-    if _lib is not None:
-        return _lib
-    if not os.path.exists(_LIB_PATH):
-        from . import build as _build
-        _build.build()
-    L = ctypes.CDLL(_LIB_PATH)
+def measure_lib_path() -> str:
+    return _MEASURE_PATH
+
+
+def use_measure_library(on: bool) -> None:
+    """Benchmark aid: route the calls of this module through libllla_measure.so (the same sources compiled with
+    per-kernel HIP events, see include/llla_measure.h) instead of the production library."""
+    global _use_measure
+    _use_measure = bool(on)
+
+
+def _declare(L, measure: bool):
     vp, sz, i32, f32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_float
     L.llla_forward_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
     L.llla_forward_workspace_bytes.restype = sz
@@ -67,14 +73,40 @@ def lib():
     L.llla_status_string.argtypes = [i32]
     L.llla_status_string.restype = ctypes.c_char_p
     L.llla_version.restype = ctypes.c_char_p
-    L.llla_profile_enable.argtypes = [i32]
-    L.llla_profile_enable.restype = None
-    L.llla_profile_last.argtypes = [ctypes.POINTER(f32), ctypes.POINTER(ctypes.c_char_p), i32]
-    L.llla_profile_last.restype = i32
-    L.llla_probe_mfma_f16.argtypes = [i32, vp, ctypes.POINTER(ctypes.c_double), vp]
-    L.llla_probe_mfma_f16.restype = i32
-    _lib = L
+    if measure:
+        L.llla_profile_enable.argtypes = [i32]
+        L.llla_profile_enable.restype = None
+        L.llla_profile_last.argtypes = [ctypes.POINTER(f32), ctypes.POINTER(ctypes.c_char_p), i32]
+        L.llla_profile_last.restype = i32
+        L.llla_probe_mfma_f16.argtypes = [i32, vp, ctypes.POINTER(ctypes.c_double), vp]
+        L.llla_probe_mfma_f16.restype = i32
+
+
+def _load(measure: bool):
+    """Loads a built library.  A library that is missing, or whose stamp says it was built from other sources than
+    the ones in the tree now, is rebuilt first (hipcc cross-compiles without a GPU); without a compiler that is an
+    error -- a stale library is never loaded silently."""
+    if measure in _libs:
+        return _libs[measure]
+    from . import build as _build
+    path = _MEASURE_PATH if measure else _LIB_PATH
+    if not _build.is_current(path, measure):
+        if not os.path.exists(_build.HIPCC):
+            raise RuntimeError("%s is missing or older than its sources and there is no hipcc to rebuild it" % path)
+        _build._build_one(path, measure, False, ())
+    L = ctypes.CDLL(path)
+    _declare(L, measure)
+    _libs[measure] = L
     return L
+
+
+def lib():
+    """The loaded C-ABI library (the production one unless use_measure_library(True) is in effect)."""
+    return _load(_use_measure)
+
+
+def measure_lib():
+    return _load(True)
 
 
 def status_string(code: int) -> str:
@@ -86,23 +118,23 @@ def version() -> str:
 
 
 def profile_enable(on: bool) -> None:
-    """Measurement aid: record HIP events around every kernel of the following calls."""
-    lib().llla_profile_enable(1 if on else 0)
+    """Measurement library only: record HIP events around every kernel of the following calls."""
+    measure_lib().llla_profile_enable(1 if on else 0)
 
 
 def profile_last() -> dict:
-    """Stage name -> milliseconds of the most recent profiled call (waits for it to finish)."""
+    """Measurement library only: stage name -> milliseconds of the most recent profiled call (waits for it)."""
     ms = (ctypes.c_float * 16)()
     names = (ctypes.c_char_p * 16)()
-    k = lib().llla_profile_last(ms, names, 16)
+    k = measure_lib().llla_profile_last(ms, names, 16)
     return {names[i].decode(): float(ms[i]) for i in range(k)}
 
 
 def probe_mfma_f16(iters: int, scratch) -> float:
-    """Measurement aid: enqueue the pure-MFMA probe on the current stream; returns its flop count."""
+    """Measurement library only: enqueue the pure-MFMA probe on the current stream; returns its flop count."""
     flops = ctypes.c_double(0.0)
-    st = lib().llla_probe_mfma_f16(int(iters), ctypes.c_void_p(scratch.data_ptr()), ctypes.byref(flops),
-                                   ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    st = measure_lib().llla_probe_mfma_f16(int(iters), ctypes.c_void_p(scratch.data_ptr()), ctypes.byref(flops),
+                                           ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
     if st != 0:
         raise LlaError(st, status_string(st))
     return float(flops.value)
@@ -133,6 +165,22 @@ def _workspace(nbytes: int, device, workspace):
     return workspace
 
 
+def _on_callers_stream(fn):
+    """Runs `fn` with its ``stream`` argument as torch's current stream.  The scratch and output tensors it allocates
+    then belong to that stream: torch's caching allocator hands a freed block only to later work of the stream it was
+    allocated on, so the scratch is not reused while the library's kernels, enqueued on that same stream, still
+    touch it."""
+    @functools.wraps(fn)
+    def wrapped(*args, **kw):
+        stream = kw.get("stream")
+        if stream is None:
+            return fn(*args, **kw)
+        with torch.cuda.stream(stream):
+            return fn(*args, **kw)
+    return wrapped
+
+
+@_on_callers_stream
 def llla_forward(Q, K, V, lam, scale: float, causal: bool = True, out_dtype=None, path: str = "auto",
                  workspace=None, out=None, stream=None, return_stats: bool = False):
     """O = LLA(Q, K, V) for [B, H, n, d] device tensors (f32 or bf16).  ``lam`` is a float or a device float32
@@ -174,6 +222,7 @@ def forward_cg_workspace_bytes(B, H, n, d, dtype) -> int:
     return int(lib().llla_forward_cg_workspace_bytes(B, H, n, d, _DTYPES[dtype]))
 
 
+@_on_callers_stream
 def llla_forward_cg(Q, K, V, lam: float, scale: float, max_steps: int, eps: float = 0.0, out_dtype=None,
                     workspace=None, out=None, stream=None, return_stats: bool = False):
     """The paper's approximate forward: rho from at most ``max_steps`` conjugate-gradient steps (bf16, d = 64 / 128,
@@ -208,6 +257,7 @@ def backward_workspace_bytes(B, H, n, d, dtype) -> int:
     return int(lib().llla_backward_workspace_bytes(B, H, n, d, _DTYPES[dtype]))
 
 
+@_on_callers_stream
 def llla_backward(Q, K, V, dO, lam, scale: float, path: str = "auto", workspace=None, stream=None,
                   return_dlambda: bool = False, out=None):
     """Gradients of sum(dO * llla_forward(Q, K, V)) (causal): returns (dQ, dK, dV) as float32 [B, H, n, d], plus
@@ -252,6 +302,7 @@ def llla_backward(Q, K, V, dO, lam, scale: float, path: str = "auto", workspace=
     return (dQ, dK, dV, dlam) if return_dlambda else (dQ, dK, dV)
 
 
+@_on_callers_stream
 def llla_decode(q, Kc, Vc, lam: float, scale: float, seqlens=None, out_dtype=None, path: str = "auto",
                 workspace=None, out=None, stream=None):
     """One query per (batch, head) against [B, H, L_max, d] caches.  q: [B, H, d].  Returns [B, H, d]."""
@@ -278,3 +329,4 @@ def llla_decode(q, Kc, Vc, lam: float, scale: float, seqlens=None, out_dtype=Non
     if st != 0:
         raise LlaError(st, "llla_decode")
     return o
+

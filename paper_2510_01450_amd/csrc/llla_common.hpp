@@ -93,12 +93,19 @@ hipError_t mfma_decode(const Problem &p);
 size_t mfma_decode128_workspace_bytes(int B, int H, int L_max);
 hipError_t mfma_decode128(const Problem &p);
 
-// ---- stage profiling (measurement aid, off by default) ------------------------------------------
-// stage_mark(stream, name) records an event and labels the work enqueued AFTER it, up to the next
-// mark; stage_begin() starts a new call, stage_end() closes the last stage.
+// ---- stage hooks ---------------------------------------------------------------------------------
+// stage_mark(stream, name) labels the work enqueued AFTER it, up to the next mark; stage_begin() starts a new call,
+// stage_end() closes the last stage.  In the production library they compile to nothing.  The measurement build
+// (-DLLLA_MEASURE, a library of its own) records HIP events there so that a benchmark can time each kernel of a call.
+#ifdef LLLA_MEASURE
 void stage_begin(hipStream_t stream);
 void stage_mark(hipStream_t stream, const char *name);
 void stage_end(hipStream_t stream);
+#else
+inline void stage_begin(hipStream_t) {}
+inline void stage_mark(hipStream_t, const char *) {}
+inline void stage_end(hipStream_t) {}
+#endif
 
 // ---- storage types -----------------------------------------------------------------------------
 // bf16 is handled as raw uint16_t bits; conversions are written out so that rounding is explicit.

@@ -3,6 +3,7 @@
 // the second-moment kernel is made of (v_mfma_f32_16x16x32_f16, independent accumulators, two waves per
 // SIMD on every compute unit) and nothing else, so its rate is the ceiling that kernel can approach.
 #include "llla_common.hpp"
+#include "llla_measure.h"
 
 namespace llla {
 namespace {

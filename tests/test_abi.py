@@ -13,19 +13,51 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 FAKE = 0x10000          # never dereferenced: every call below fails validation first
 
 
-def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "llla.h")).read()
+def _declared_symbols(header="llla.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(llla_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(llla_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported():
     names = _declared_symbols()
     assert {"llla_forward", "llla_decode", "llla_forward_workspace_bytes", "llla_decode_workspace_bytes",
             "llla_status_string", "llla_version"} <= set(names)
+    llla.lib()                                  # builds the library if the tree has none
     L = ctypes.CDLL(llla.lib_path())
     for name in names:
         assert hasattr(L, name), name
+
+
+def test_measurement_aids_live_in_a_library_of_their_own():
+    """The production library exports the method only; the profiling hooks and the MFMA probe exist in the
+    measurement build, which also exports everything llla.h declares."""
+    aids = _declared_symbols("llla_measure.h")
+    assert set(aids) == {"llla_profile_enable", "llla_profile_last", "llla_probe_mfma_f16"}
+    assert not set(aids) & set(_declared_symbols())
+    llla.lib()
+    P = ctypes.CDLL(llla.lib_path())
+    for name in aids:
+        assert not hasattr(P, name), name + " leaked into the production library"
+    llla.measure_lib()
+    M = ctypes.CDLL(llla.measure_lib_path())
+    for name in aids + _declared_symbols():
+        assert hasattr(M, name), name
+
+
+def test_a_stale_library_is_detected():
+    """The binding compares a hash of the sources with the stamp the build left beside the library."""
+    from paper_2510_01450_amd import build
+    llla.lib()
+    assert build.is_current(build.LIB)
+    stamp = build.stamp_path(build.LIB)
+    good = open(stamp).read()
+    try:
+        open(stamp, "w").write("0" * 64 + "\n")
+        assert not build.is_current(build.LIB)
+    finally:
+        open(stamp, "w").write(good)
+    assert build.is_current(build.LIB)
 
 
 def _fwd(Q=FAKE, K=FAKE, V=FAKE, O=FAKE, sq=None, B=1, H=1, n=64, d=64, din=0, dout=0, causal=1, lam=1e-2,
