@@ -201,6 +201,25 @@ llla_status llla_decode_path(const void *q, const void *Kc, const void *Vc, void
                              float lambda, float scale, llla_path path,
                              void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * llla_decode_static -- llla_decode for callers that cannot allocate device memory and therefore have no workspace
+ * to pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and bit-identical results; the partial-moment records that llla_decode keeps in `workspace` live in a
+ * device array of LLLA_STATIC_SCRATCH_BYTES inside the library instead (one copy per GPU, held from the moment the
+ * library is loaded on that GPU until the process ends).  The call allocates and frees nothing and does not
+ * synchronise.  A call whose llla_decode_workspace_bytes() exceeds LLLA_STATIC_SCRATCH_BYTES returns
+ * LLLA_ERR_WORKSPACE (the decode configuration of 32 x 16 heads x 32768 keys at d = 64 needs 56 MB and fits);
+ * LLLA_ERR_LAUNCH if the runtime cannot report the array's address.  Every call on a GPU uses that GPU's one array:
+ * calls on the same stream are ordered and safe, calls that overlap on one GPU (different streams, different
+ * threads) race on it -- unlike every other entry point, this one is not re-entrant per device.
+ */
+#define LLLA_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+
+llla_status llla_decode_static(const void *q, const void *Kc, const void *Vc, void *o,
+                               llla_strides sk, llla_strides sv, const int32_t *seqlens,
+                               int B, int H, int L_max, int d, llla_dtype in, llla_dtype out,
+                               float lambda, float scale, void *stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char *llla_status_string(llla_status status);
 

@@ -70,6 +70,8 @@ def _declare(L, measure: bool):
     L.llla_decode.restype = i32
     L.llla_decode_path.argtypes = dec + [i32, vp, sz, vp]
     L.llla_decode_path.restype = i32
+    L.llla_decode_static.argtypes = dec + [vp]
+    L.llla_decode_static.restype = i32
     L.llla_status_string.argtypes = [i32]
     L.llla_status_string.restype = ctypes.c_char_p
     L.llla_version.restype = ctypes.c_char_p
@@ -330,3 +332,25 @@ def llla_decode(q, Kc, Vc, lam: float, scale: float, seqlens=None, out_dtype=Non
         raise LlaError(st, "llla_decode")
     return o
 
+
+def llla_decode_static(q, Kc, Vc, lam: float, scale: float, out, seqlens=None, stream=None):
+    """llla_decode without a workspace (the library's own fixed device array holds the partial records): for callers
+    that may not allocate.  Nothing is allocated here either: ``out`` ([B, H, d], float32 or bfloat16) is required."""
+    if not (q.is_cuda and Kc.is_cuda and Vc.is_cuda and out.is_cuda):
+        raise ValueError("llla_decode_static needs device tensors; this library has no CPU path")
+    if not (q.dtype == Kc.dtype == Vc.dtype) or q.dtype not in _DTYPES or out.dtype not in _DTYPES:
+        raise ValueError("q, Kc, Vc must share dtype float32 or bfloat16")
+    B, H, Lmax, d = Kc.shape
+    if tuple(q.shape) != (B, H, d) or Vc.shape != Kc.shape or not q.is_contiguous():
+        raise ValueError("q must be contiguous [B, H, d]; caches [B, H, L_max, d]")
+    if tuple(out.shape) != (B, H, d) or not out.is_contiguous():
+        raise ValueError("out must be contiguous [B, H, d]")
+    if seqlens is not None and (seqlens.dtype != torch.int32 or not seqlens.is_cuda or seqlens.numel() != B):
+        raise ValueError("seqlens must be a device int32 tensor of B entries")
+    st = lib().llla_decode_static(q.data_ptr(), Kc.data_ptr(), Vc.data_ptr(), out.data_ptr(),
+                                  _strides4(Kc), _strides4(Vc), 0 if seqlens is None else seqlens.data_ptr(),
+                                  B, H, Lmax, d, _DTYPES[q.dtype], _DTYPES[out.dtype], float(lam), float(scale),
+                                  _stream_ptr(stream))
+    if st != 0:
+        raise LlaError(st, "llla_decode_static")
+    return out
