@@ -17,6 +17,7 @@
 #include <type_traits>
 
 #include "llla_mfma_common.hpp"
+#include "llla_mfma_solve64.hpp"
 
 namespace llla {
 namespace {
@@ -687,7 +688,37 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
         __syncthreads();
     }
 
-    // ---- per-query solve (see solve_wave); the right-hand sides [mu~ q] are built inside it ----------
+    // ---- per-query solve ---------------------------------------------------------------------------------------
+    if constexpr (DD == 64) {
+        // four queries per wave: blocked factorisation on the matrix cores, substitutions on the vector ALU with lane
+        // (q, r) = (g, nn) holding element r of every 16-block of query q's vectors (see solve_wave_q4)
+        const int qi = QW * wave + g;
+        const int row = min(i0 + qi, n - 1);
+        const bf16_t *qrow = Qh + (int64_t)row * sq.seq;
+        const float pivot_floor = 0.5f * (lam_rows ? lam_rows[(size_t)bh * n + row] : lambda);
+        float tmu[4], tq[4], te[4], y1[4], u1[4], y0 = 0.f, u0 = 0.f, r0 = 0.f;
+#pragma unroll
+        for (int P = 0; P < NB; ++P) {
+            tmu[P] = mus[qi][16 * P + nn];                               // mus holds -mu~
+            tq[P] = -bf16_to_f32(qrow[16 * P + nn]);
+            te[P] = 0.f; y1[P] = 0.f; u1[P] = 0.f;
+            if constexpr (WITH_U) te[P] = -Rg[((size_t)bh * n + row) * YP + 16 * P + nn];
+        }
+        if constexpr (WITH_U) r0 = Rg[((size_t)bh * n + row) * YP + DD];
+        solve_wave_q4<WITH_U>(acc, tmu, tq, te, r0, oms[qi], &sc[wave][0][0], g, nn, pivot_floor, y1, y0, u1, u0);
+        if (i0 + qi < n) {
+            float *yr = Yg + ((size_t)bh * n + row) * YP;
+#pragma unroll
+            for (int P = 0; P < NB; ++P) yr[16 * P + nn] = y1[P];
+            if (nn == 0) yr[DD] = y0;
+            if constexpr (WITH_U) {
+                float *ur = Ug + ((size_t)bh * n + row) * YP;
+#pragma unroll
+                for (int P = 0; P < NB; ++P) ur[16 * P + nn] = u1[P];
+                if (nn == 0) ur[DD] = u0;
+            }
+        }
+    } else {
     f32x4 rhs[QW][NB];
     float y0v[QW], om4[QW];
 #pragma unroll
@@ -744,6 +775,7 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
                 if (g == 0) ur[DD] = u0v[q];
             }
         }
+    }
     }
 }
 
