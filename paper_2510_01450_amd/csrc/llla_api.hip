@@ -57,6 +57,7 @@ extern "C" {
 size_t llla_forward_workspace_bytes(int B, int H, int n, int d, llla_dtype in)
 {
     if (B <= 0 || H <= 0 || n <= 0 || !dim_supported(d) || !dtype_ok(in)) return 0;
+    if (in == LLLA_F32) return llla::mfma_forward_f32_supported(d, true) ? llla::mfma_forward_f32_workspace_bytes(B, H, n) : 0;
     return llla::mfma_forward_workspace_bytes(B, H, n, d, in);
 }
 
@@ -82,11 +83,13 @@ llla_status llla_forward_ex(const void *Q, const void *K, const void *V, void *O
         return LLLA_ERR_ALIGN;
 
     // the matrix-core sweeps put their 64-row blocks on grid.y: at most 65535 of them
-    const bool has_mfma = llla::mfma_forward_supported(d, in, causal != 0) && (n + 63) / 64 <= kMaxGridY;
+    const bool f32_mfma = in == LLLA_F32 && llla::mfma_forward_f32_supported(d, causal != 0);
+    const bool has_mfma = (f32_mfma || llla::mfma_forward_supported(d, in, causal != 0)) && (n + 63) / 64 <= kMaxGridY;
     if (path == LLLA_PATH_MFMA && !has_mfma) return LLLA_ERR_UNSUPPORTED;
     const bool use_mfma = has_mfma && path != LLLA_PATH_VALU;
     if (use_mfma) {
-        st = check_workspace(llla::mfma_forward_workspace_bytes(B, H, n, d, in), workspace, workspace_bytes);
+        st = check_workspace(f32_mfma ? llla::mfma_forward_f32_workspace_bytes(B, H, n)
+                                      : llla::mfma_forward_workspace_bytes(B, H, n, d, in), workspace, workspace_bytes);
         if (st != LLLA_OK) return st;
     }
 
@@ -103,7 +106,7 @@ llla_status llla_forward_ex(const void *Q, const void *K, const void *V, void *O
     p.stream = static_cast<hipStream_t>(stream);
     llla::stage_begin(p.stream);
     if (!use_mfma) llla::stage_mark(p.stream, "valu_forward");
-    const hipError_t e = use_mfma ? llla::mfma_forward(p) : llla::valu_forward(p);
+    const hipError_t e = use_mfma ? (f32_mfma ? llla::mfma_forward_f32(p) : llla::mfma_forward(p)) : llla::valu_forward(p);
     llla::stage_end(p.stream);
     return e == hipSuccess ? LLLA_OK : LLLA_ERR_LAUNCH;
 }

@@ -81,6 +81,10 @@ hipError_t backward(const BackwardProblem &p, llla_path path);
 bool mfma_forward_supported(int d, llla_dtype in, bool causal);
 size_t mfma_forward_workspace_bytes(int B, int H, int n, int d, llla_dtype in);
 hipError_t mfma_forward(const Problem &p);
+// the same for fp32 inputs (d = 64, causal): fp32 MFMA throughout (llla_mfma_fwd_f32.hip)
+bool mfma_forward_f32_supported(int d, bool causal);
+size_t mfma_forward_f32_workspace_bytes(int B, int H, int n);
+hipError_t mfma_forward_f32(const Problem &p);
 // approximate mode: T conjugate-gradient steps per row (bf16, d = 64 / 128, causal); iters: [B,H,n] steps done, or nullptr
 size_t mfma_forward_cg_workspace_bytes(int B, int H, int n, int d, llla_dtype in);
 hipError_t mfma_forward_cg(const Problem &p, int T, float eps, int32_t *iters);

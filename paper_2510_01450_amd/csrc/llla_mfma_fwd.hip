@@ -128,6 +128,18 @@ __global__ __launch_bounds__(256) void sweep_kernel(const bf16_t *__restrict__ Q
     bf16x8 qf[NF];
 #pragma unroll
     for (int f = 0; f < NF; ++f) qf[f] = *reinterpret_cast<const bf16x8 *>(qrow + 32 * f + 8 * g);
+    // Row maxima: max_j c <q, k_j> = |c| max_j <sign(c) q, k_j>, so the sign of the scale goes into the query operand
+    // once (a flip of the bf16 sign bits) and the sweep keeps the maximum of the RAW products, one three-input maximum
+    // per two logits; |c| is applied to the result.  (Scaling every logit first was two vector instructions per logit
+    // in a sweep that the vector ALU bounds.)
+    if (MAXONLY && cscale < 0.f) {
+#pragma unroll
+        for (int f = 0; f < NF; ++f) {
+            uint4 u = __builtin_bit_cast(uint4, qf[f]);
+            u.x ^= 0x80008000u; u.y ^= 0x80008000u; u.z ^= 0x80008000u; u.w ^= 0x80008000u;
+            qf[f] = __builtin_bit_cast(bf16x8, u);
+        }
+    }
 
     float mrow = -INFINITY, y0 = 0.f;
     bf16x8 yh[NF], yl[NF];
@@ -201,17 +213,14 @@ __global__ __launch_bounds__(256) void sweep_kernel(const bf16_t *__restrict__ Q
         if (MAXONLY) {
             if (!masked) {
 #pragma unroll
-                for (int s = 0; s < 2; ++s)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) mx[s][r] = fmaxf(mx[s][r], st[s][r] * cscale);
+                for (int r = 0; r < 4; ++r) mx[0][r] = __builtin_fmaxf(__builtin_fmaxf(mx[0][r], st[0][r]), st[1][r]);   // v_max3_f32
             } else {
 #pragma unroll
                 for (int s = 0; s < 2; ++s)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int j = c * KB + 16 * s + 4 * g + r;
-                        const float t = st[s][r] * cscale;
-                        mx[s][r] = (j <= iq) ? fmaxf(mx[s][r], t) : mx[s][r];
+                        mx[0][r] = (j <= iq) ? fmaxf(mx[0][r], st[s][r]) : mx[0][r];
                     }
             }
         } else {
@@ -250,14 +259,11 @@ __global__ __launch_bounds__(256) void sweep_kernel(const bf16_t *__restrict__ Q
     }
 
     if (MAXONLY) {
-        float m = -INFINITY;
-#pragma unroll
-        for (int s = 0; s < 2; ++s)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) m = fmaxf(m, mx[s][r]);
+        float m = fmaxf(fmaxf(mx[0][0], mx[0][1]), fmaxf(mx[0][2], mx[0][3]));
         m = fmaxf(m, __shfl_xor(m, 16));
         m = fmaxf(m, __shfl_xor(m, 32));
-        if (g == 0 && iq < n) Mg[(size_t)bh * (nkb * KB) + iq] = m;
+        // every row sees at least its own key, so m is finite; a zero scale gives 0 (not 0 times a product)
+        if (g == 0 && iq < n) Mg[(size_t)bh * (nkb * KB) + iq] = cscale == 0.f ? 0.f : m * fabsf(cscale);
     } else {
         if (Csum != nullptr) {      // lanes (g, nn), g = 0..3, hold the coefficients of query nn for disjoint keys
             csum += __shfl_xor(csum, 16);

@@ -368,20 +368,20 @@ hipError_t by_dim(const Problem &p, int nrows)
     }
 }
 
-template <int D>
+template <int D, typename TI>
 hipError_t launch_given(const Problem &p, int nrows, const float *M, int mpitch, const float *Y, int ypitch)
 {
     using C = Cfg<D>;
     nrows = nrows < p.n ? nrows : p.n;
     dim3 grid((nrows + C::QB - 1) / C::QB * p.B * p.H);
     if (p.out == LLLA_F32)
-        hipLaunchKernelGGL((valu_kernel<D, bf16_t, float, false, true>), grid, dim3(NT), 0, p.stream,
-                           (const bf16_t *)p.Q, (const bf16_t *)p.K, (const bf16_t *)p.V, (float *)p.O, p.sq, p.sk,
+        hipLaunchKernelGGL((valu_kernel<D, TI, float, false, true>), grid, dim3(NT), 0, p.stream,
+                           (const TI *)p.Q, (const TI *)p.K, (const TI *)p.V, (float *)p.O, p.sq, p.sk,
                            p.sv, p.so, nullptr, p.H, p.B * p.H, p.n, 1, p.lambda, p.scale, M, mpitch, Y, ypitch, (const float *)nullptr,
                            (float *)nullptr, (float *)nullptr);
     else
-        hipLaunchKernelGGL((valu_kernel<D, bf16_t, bf16_t, false, true>), grid, dim3(NT), 0, p.stream,
-                           (const bf16_t *)p.Q, (const bf16_t *)p.K, (const bf16_t *)p.V, (bf16_t *)p.O, p.sq, p.sk,
+        hipLaunchKernelGGL((valu_kernel<D, TI, bf16_t, false, true>), grid, dim3(NT), 0, p.stream,
+                           (const TI *)p.Q, (const TI *)p.K, (const TI *)p.V, (bf16_t *)p.O, p.sq, p.sk,
                            p.sv, p.so, nullptr, p.H, p.B * p.H, p.n, 1, p.lambda, p.scale, M, mpitch, Y, ypitch, (const float *)nullptr,
                            (float *)nullptr, (float *)nullptr);
     return hipGetLastError();
@@ -392,13 +392,11 @@ hipError_t launch_given(const Problem &p, int nrows, const float *M, int mpitch,
 hipError_t valu_forward_given(const Problem &p, int nrows, const float *M, int mpitch, const float *Y, int ypitch)
 {
     if (p.in != LLLA_BF16) return hipErrorInvalidValue;
-    if (p.d == 64) return launch_given<64>(p, nrows, M, mpitch, Y, ypitch);
-    if (p.d == 128) return launch_given<128>(p, nrows, M, mpitch, Y, ypitch);
+    if (p.d == 64) return launch_given<64, bf16_t>(p, nrows, M, mpitch, Y, ypitch);
+    if (p.d == 128) return launch_given<128, bf16_t>(p, nrows, M, mpitch, Y, ypitch);
     return hipErrorInvalidValue;
 }
 
-// Rows that see at most dual_max_keys(d) keys are rewritten afterwards by the fp64 key-space kernel (the output
-// weights of such a row cancel to three digits in fp32); a call that consists of such rows only skips the sweep.
 hipError_t valu_forward(const Problem &p)
 {
     if (dual_forward_rows(p) < p.n) {

@@ -153,14 +153,40 @@ def test_mfma_path_all_outputs_and_bf16_output(n, d):
     assert err < 2e-3, err          # the two kernel families agree far inside the tolerance
 
 
+@pytest.mark.parametrize("n,values,scale", [(1024, "l2", None), (700, "normal", None), (333, "l2", 60.0), (333, "l2", -45.0),
+                                            (130, "normal", 0.0)])
+def test_f32_matrix_core_path_all_outputs(n, values, scale):
+    """fp32 inputs at d = 64 on the matrix cores (fp32 MFMA), forced with path='mfma': all outputs, rho and delta against
+    the oracle.  The logits of the scale-60 cases span more than 2^64, so the reference exponent of the weights moves
+    during the sweep and the accumulated moments are rescaled (the lazy form of Algorithm 1's running maximum)."""
+    w = _small("f32mfma", 2, 2, n, 64, "f32", values=values, index=1500 + n, scale=scale)
+    Q, K, V = workloads.make_inputs(w)
+    refO, refR, refD = oracle.forward_ex(Q, K, V, w.lam, w.scale)
+    O, R, Dl = llla.llla_forward(Q.to(DEV), K.to(DEV), V.to(DEV), w.lam, w.scale, path="mfma", return_stats=True)
+    torch.cuda.synchronize()
+    rows = np.arange(n)
+    what = "f32 mfma n=%d %s scale=%s" % (n, values, scale)
+    print(check(O.cpu().numpy(), refO, rows, 64, w.tol, what))
+    print(check(R.cpu().numpy(), refR, rows, 64, w.tol, what + " rho"))
+    print(check(Dl.cpu().numpy()[..., None], refD[..., None], rows, 64, w.tol, what + " delta"))
+    valu = llla.llla_forward(Q.to(DEV), K.to(DEV), V.to(DEV), w.lam, w.scale, path="valu").cpu().numpy()
+    late = rows >= 256
+    if late.any():
+        assert np.linalg.norm(O.cpu().numpy()[..., late, :] - valu[..., late, :]) / np.linalg.norm(valu[..., late, :]) < 1e-4
+
+
 def test_mfma_path_refuses_what_it_does_not_serve():
     x = torch.zeros(1, 1, 64, 32, dtype=torch.bfloat16, device=DEV)
     with pytest.raises(llla.LlaError) as e:
         llla.llla_forward(x, x, x, 1e-2, 0.2, path="mfma")          # d = 32 has no matrix-core path
     assert e.value.code == 7
+    y = torch.zeros(1, 1, 64, 128, dtype=torch.float32, device=DEV)
+    with pytest.raises(llla.LlaError) as e:
+        llla.llla_forward(y, y, y, 1e-2, 0.2, path="mfma")          # fp32 inputs at d = 128 neither
+    assert e.value.code == 7
     y = torch.zeros(1, 1, 64, 64, dtype=torch.float32, device=DEV)
     with pytest.raises(llla.LlaError) as e:
-        llla.llla_forward(y, y, y, 1e-2, 0.2, path="mfma")          # fp32 inputs neither
+        llla.llla_forward(y, y, y, 1e-2, 0.2, path="mfma", causal=False)      # the fp32 matrix-core path is causal only
     assert e.value.code == 7
     z = torch.zeros(1, 1, 512, 64, dtype=torch.bfloat16, device=DEV)
     with pytest.raises(llla.LlaError) as e:
