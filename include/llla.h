@@ -40,7 +40,7 @@
  *
  * Value range of the matrix-core kernels.  LLLA_PATH_AUTO serves bf16 inputs with d = 64 or 128 on
  * the matrix cores (llla_forward, llla_forward_ex, llla_forward_cg, llla_backward, and llla_decode
- * with a cache capacity of at least 1024 rows).  Those kernels hand the keys (and, in decode, queries and
+ * with a cache capacity of at least 256 rows).  Those kernels hand the keys (and, in decode, queries and
  * values) to the MFMA units as f16: every |x| must be at most 65504 (larger ones become
  * infinite and the affected rows NaN; no status is returned, the data being device memory), and
  * magnitudes below 6.1e-5 lose bits to the f16 subnormal range.  bf16 values of ordinary size
@@ -65,7 +65,7 @@ typedef enum {
     LLLA_ERR_PARAM = 4,       /* lambda <= 0 or not finite, scale not finite */
     LLLA_ERR_ALIGN = 5,       /* base pointer or stride not 16-byte compatible */
     LLLA_ERR_WORKSPACE = 6,   /* workspace NULL/unaligned or smaller than *_workspace_bytes() */
-    LLLA_ERR_UNSUPPORTED = 7, /* d not in {16, 32, 64, 128}, or causal == 0 with a path lacking it */
+    LLLA_ERR_UNSUPPORTED = 7, /* d not in {16, 32, 64, 128}, or a path forced that does not serve the call */
     LLLA_ERR_LAUNCH = 8       /* the HIP runtime refused a launch */
 } llla_status;
 
@@ -193,7 +193,7 @@ llla_status llla_decode(const void *q, const void *Kc, const void *Vc, void *o,
                         void *workspace, size_t workspace_bytes, void *stream);
 
 /* Same as llla_decode with the kernel family chosen by the caller.  The matrix-core kernels serve bf16 caches with
- * d = 64 or 128, L_max >= 1024 and B * H <= 65535 (queries, keys and values must lie in the f16 range, |x| <= 65504);
+ * d = 64 or 128, L_max >= 256 and B * H <= 65535 (queries, keys and values must lie in the f16 range, |x| <= 65504);
  * LLLA_PATH_MFMA on any other call returns LLLA_ERR_UNSUPPORTED, LLLA_PATH_AUTO takes the vector kernels there. */
 llla_status llla_decode_path(const void *q, const void *Kc, const void *Vc, void *o,
                              llla_strides sk, llla_strides sv, const int32_t *seqlens,

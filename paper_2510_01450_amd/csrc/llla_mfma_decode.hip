@@ -29,7 +29,7 @@ constexpr int STAGE_H = 2 * TILE_H;            // K tile + V tile
 constexpr int DMA_PER_STAGE = 8;
 constexpr int NTILES = 26;                     // 10 (Sigma~ upper) + 16 (G~)
 constexpr int PART_F = 192 + NTILES * 256;     // floats per partial: [m, omega, ..], mu~[64], y0v[64], tiles
-constexpr int MIN_L = 1024;                    // shorter caches go to the vector path
+constexpr int MIN_L = 256;                     // shorter caches go to the vector path
 constexpr int PRECISE_L = 4 * D;               // sequences up to this length take the two-term weights
 
 typedef short short4v __attribute__((ext_vector_type(4)));

@@ -30,7 +30,7 @@ constexpr int DMA_PER_WAVE = 4;                // transfers one wave issues per 
 constexpr int NSIG = 36, NTILES = 100;         // Sigma~ upper triangle, then G~ row-major [I][J]
 constexpr int HDR = 3 * D;                     // [m, omega, ..pad], mu~ at [D, 2D), sum w v at [2D, 3D)
 constexpr int PART_F = HDR + NTILES * 256;     // floats per partial record
-constexpr int MIN_L = 1024;                    // shorter caches go to the vector path
+constexpr int MIN_L = 256;                     // shorter caches go to the vector path
 constexpr int MAX_SPLIT = 32;
 constexpr int PRECISE_L = 4 * D;               // sequences up to this length take the two-term weights
 

@@ -12,8 +12,8 @@
 //           products run on fp32 MFMA; only y_i (d+1 floats) and m_i leave the chip;
 //   output  s_ij = w_ij (y0_i + k_j . y1_i), O = S V  (Eq. (lla) with y1 = -rho/delta,
 //           y0 = (1 + q.rho)/delta), a flash-style sweep.
-// The first 4d rows of every sequence, whose systems are the worst conditioned, are served by the
-// fp32 vector-ALU kernel instead (same result, higher-precision second moment).
+// The first 2d rows of every sequence, whose systems are the worst conditioned, take the "precise" variant of the
+// moments kernel (fp32 weights, the scaled operand as two f16 terms) and an fp32 output sweep on the vector ALU.
 #include <type_traits>
 
 #include "llla_mfma_common.hpp"
@@ -102,7 +102,7 @@ __global__ __launch_bounds__(256) void sweep_kernel(const bf16_t *__restrict__ Q
                                                     int first_row, float cscale, const bf16_t *__restrict__ VT,
                                                     float *__restrict__ Mg, const float *__restrict__ Yg,
                                                     void *__restrict__ Og, llla_strides so, int out_bf16,
-                                                    float *__restrict__ Csum = nullptr)
+                                                    float *__restrict__ Csum = nullptr, int causal = 1)
 {
     // !MAXONLY is a general "coefficients times a tile" sweep: O_i = sum_j w_ij (y0_i + k_j . y1_i) t_j with the rows t_j
     // of whatever VT holds (V for the output; K for the first moment and for the matrix-free product of the
@@ -123,6 +123,7 @@ __global__ __launch_bounds__(256) void sweep_kernel(const bf16_t *__restrict__ Q
     const int i0 = first_row + (nqb - 1 - (int)blockIdx.y) * 64;
     const int iq = i0 + wave * 16 + nn;                                // this lane's query
     const int iqc = min(iq, n - 1);
+    const int jlim = causal ? iq : n - 1;                              // last key this lane's query sees
     const bf16_t *Kh = Kg + b * sk.batch + h * sk.head;
     const bf16_t *qrow = Qg + b * sq.batch + h * sq.head + (int64_t)iqc * sq.seq;
     bf16x8 qf[NF];
@@ -168,7 +169,7 @@ __global__ __launch_bounds__(256) void sweep_kernel(const bf16_t *__restrict__ Q
     float csum = 0.f;
 
     const int ilast = min(i0 + 63, n - 1);
-    const int nblk = ilast / KB + 1;
+    const int nblk = causal ? ilast / KB + 1 : (n + KB - 1) / KB;
     for (int c = 0; c < nblk; ++c) {
         __syncthreads();
         // stage K (natural) and V^T tiles
@@ -209,7 +210,7 @@ __global__ __launch_bounds__(256) void sweep_kernel(const bf16_t *__restrict__ Q
         // lane (g, nn): st[s][r] = <k_j, q_iq> for key j = 32c + 16s + 4g + r.  Only the blocks that reach past the
         // wave's first query need the causal mask (a scalar condition): the others skip the compares and selects,
         // which are most of the vector work of this sweep.
-        const bool masked = c * KB + KB - 1 > i0 + wave * 16;
+        const bool masked = causal ? (c * KB + KB - 1 > i0 + wave * 16) : (c * KB + KB > n);
         if (MAXONLY) {
             if (!masked) {
 #pragma unroll
@@ -220,7 +221,7 @@ __global__ __launch_bounds__(256) void sweep_kernel(const bf16_t *__restrict__ Q
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int j = c * KB + 16 * s + 4 * g + r;
-                        mx[0][r] = (j <= iq) ? fmaxf(mx[0][r], st[s][r]) : mx[0][r];
+                        mx[0][r] = (j <= jlim) ? fmaxf(mx[0][r], st[s][r]) : mx[0][r];
                     }
             }
         } else {
@@ -235,7 +236,7 @@ __global__ __launch_bounds__(256) void sweep_kernel(const bf16_t *__restrict__ Q
 #pragma unroll
                 for (int t = 0; t < 8; ++t) {
                     const int j = c * KB + 16 * (t >> 2) + 4 * g + (t & 3);
-                    cv[t] = (j <= iq) ? cv[t] : 0.f;
+                    cv[t] = (j <= jlim) ? cv[t] : 0.f;
                 }
             }
 #pragma unroll
@@ -335,7 +336,8 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
                                              int n, int nkb, float cscale, float lambda,
                                              const float *__restrict__ lam_rows, const _Float16 *__restrict__ KT,
                                              const float *__restrict__ Mg, float *__restrict__ Yg,
-                                             const float *__restrict__ Rg = nullptr, float *__restrict__ Ug = nullptr)
+                                             const float *__restrict__ Rg = nullptr, float *__restrict__ Ug = nullptr,
+                                             int causal = 1)
 {
     using S = Shape<DD>;
     constexpr int NB = S::NB, NTILE = S::NTILE, NF = S::NF, QW = S::QW, NW = S::NW, QB = S::QB, YP = S::YP;
@@ -359,7 +361,7 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     const int nqb = gridDim.x;
     const int i0 = (nqb - 1 - bm.blk) * QB;                           // long rows first
     const int ilast = min(i0 + QB - 1, n - 1);
-    const int nblk = ilast / KB2 + 1;                                  // blocks of 64 keys
+    const int nblk = causal ? ilast / KB2 + 1 : (n + KB2 - 1) / KB2;   // blocks of 64 keys
     const int mpitch = nkb * KB;
     const bf16_t *Kh = Kg + b * sk.batch + h * sk.head;
     const bf16_t *Qh = Qg + b * sq.batch + h * sq.head;
@@ -370,6 +372,7 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
 
     // weight role: lane (g, nn) of wave w < 4 serves query i0 + nn (nn < QB) and keys 16w + 4g + r
     const int iq = i0 + nn, iqc = min(iq, n - 1);
+    const int jlim = causal ? iq : n - 1;                   // last key the lane's query sees
     const bool q_live = nn < QB;
     // The query operand of the logits: d = 64 re-reads it from LDS for every block (its registers go to the second
     // fragment set), d = 128 keeps it in registers.
@@ -485,7 +488,7 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
         float wf[4];
         // stored negated: the tiles accumulate -(w k) k^T.  A block that lies wholly before the workgroup's first
         // query needs no causal mask (a scalar condition; most blocks of a long row)
-        if (blk * KB2 + KB2 - 1 <= i0 && QB == 16) {
+        if ((causal ? blk * KB2 + KB2 - 1 <= i0 : blk * KB2 + KB2 <= n) && QB == 16) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) wf[r] = -__builtin_amdgcn_exp2f(z[r] * cscale - mrow);
         } else {
@@ -493,7 +496,7 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
             for (int r = 0; r < 4; ++r) {
                 const int j = blk * KB2 + 16 * wave + 4 * g + r;
                 const float wgt = __builtin_amdgcn_exp2f(z[r] * cscale - mrow);
-                wf[r] = (q_live && j <= iq) ? -wgt : 0.f;
+                wf[r] = (q_live && j <= jlim) ? -wgt : 0.f;
             }
         }
         if (PRECISE) {
@@ -791,12 +794,14 @@ template <int DD>
 __global__ __launch_bounds__(Shape<DD>::NT, DD == 64 ? 2 : 1) void moments_kernel(
     const bf16_t *__restrict__ Qg, const bf16_t *__restrict__ Kg, llla_strides sq, llla_strides sk, int H, int n, int nkb,
     int precise_rows, float cscale, float lambda, const float *__restrict__ lam_rows, const _Float16 *__restrict__ KT,
-    const float *__restrict__ Mg, float *__restrict__ Yg)
+    const float *__restrict__ Mg, float *__restrict__ Yg, int causal)
 {
     __shared__ __align__(16) MomentsShared<DD> sm;
     const int i0 = ((int)gridDim.x - 1 - moments_block<DD>().blk) * Shape<DD>::QB;
-    if (i0 < precise_rows) moments_body<true, DD>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg);
-    else moments_body<false, DD>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg);
+    if (i0 < precise_rows)
+        moments_body<true, DD>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg, nullptr, nullptr, causal);
+    else
+        moments_body<false, DD>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg, nullptr, nullptr, causal);
 }
 
 // The same with the backward's second system (see moments_body).
@@ -855,7 +860,9 @@ hipError_t forward_impl(const Problem &p)
     float *Y = reinterpret_cast<float *>(ws + L.y);
     const int bh = p.B * p.H;
     const float cscale = p.scale * LOG2E;
-    const int first = S::EARLY_ROWS < p.n ? S::EARLY_ROWS : p.n;
+    // rows whose visible keys number at most 2 d take the precise moments and the fp32 output sweep: the first 2 d
+    // rows of a causal call; every row of a non-causal call over at most 2 d keys, none of a longer one
+    const int first = p.causal ? (S::EARLY_ROWS < p.n ? S::EARLY_ROWS : p.n) : (p.n <= S::EARLY_ROWS ? p.n : 0);
 
     const bf16_t *Q = static_cast<const bf16_t *>(p.Q), *K = static_cast<const bf16_t *>(p.K),
                  *V = static_cast<const bf16_t *>(p.V);
@@ -864,26 +871,28 @@ hipError_t forward_impl(const Problem &p)
     const int nq64 = (p.n + 63) / 64;
     stage_mark(p.stream, "rowmax");
     hipLaunchKernelGGL((sweep_kernel<true, DD>), dim3(bh, nq64), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
-                       0, cscale, VT, M, Y, p.O, p.so, 0);
+                       0, cscale, VT, M, Y, p.O, p.so, 0, (float *)nullptr, p.causal);
     const int nqb = (p.n + S::QB - 1) / S::QB;
     stage_mark(p.stream, "moments");
     hipLaunchKernelGGL((moments_kernel<DD>), dim3(nqb, bh), dim3(S::NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
-                       first, cscale, p.lambda, p.lambda_rows, KT, M, Y);
+                       first, cscale, p.lambda, p.lambda_rows, KT, M, Y, p.causal);
     if (p.rho != nullptr || p.delta != nullptr) {
         stage_mark(p.stream, "statistics");
         hipLaunchKernelGGL((stats_kernel<DD>), dim3((p.n + 3) / 4, bh), dim3(256), 0, p.stream, Q, p.sq, p.H, p.n, Y, p.rho,
                            p.delta);
     }
-    // output: the first rows are evaluated in fp32 on the vector ALUs (their weights y0 + k.y1 cancel
+    // output: those rows are evaluated in fp32 on the vector ALUs (their weights y0 + k.y1 cancel
     // to a few digits), the rest by the MFMA sweep
-    stage_mark(p.stream, "output_early_rows");
-    hipError_t e = valu_forward_given(p, first, M, L.npad, Y, S::YP);
-    if (e != hipSuccess) return e;
+    if (first > 0) {
+        stage_mark(p.stream, "output_early_rows");
+        const hipError_t e = valu_forward_given(p, first, M, L.npad, Y, S::YP);
+        if (e != hipSuccess) return e;
+    }
     if (first < p.n) {
         const int nq64b = (p.n - first + 63) / 64;
         stage_mark(p.stream, "output");
         hipLaunchKernelGGL((sweep_kernel<false, DD>), dim3(bh, nq64b), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n,
-                           L.nkb, first, cscale, VT, M, Y, p.O, p.so, p.out == LLLA_BF16 ? 1 : 0);
+                           L.nkb, first, cscale, VT, M, Y, p.O, p.so, p.out == LLLA_BF16 ? 1 : 0, (float *)nullptr, p.causal);
     }
     return hipGetLastError();
 }
@@ -1150,7 +1159,9 @@ hipError_t mfma_backward_solve(const BackwardProblem &p, const BackwardLayout &L
     return p.d == 64 ? backward_solve_impl<64>(p, L) : backward_solve_impl<128>(p, L);
 }
 
-bool mfma_forward_supported(int d, llla_dtype in, bool causal) { return (d == 64 || d == 128) && in == LLLA_BF16 && causal; }
+// (the exact forward serves causal and non-causal calls; the approximate mode and the backward, which ask with
+// causal = true, are causal by definition)
+bool mfma_forward_supported(int d, llla_dtype in, bool causal) { (void)causal; return (d == 64 || d == 128) && in == LLLA_BF16; }
 
 size_t mfma_forward_workspace_bytes(int B, int H, int n, int d, llla_dtype in)
 {

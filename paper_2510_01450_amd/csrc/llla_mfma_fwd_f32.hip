@@ -1,4 +1,4 @@
-// Matrix-core forward path for fp32 inputs, d = 64, causal: the contractions of Algorithm 1 (Section 3.2) -- logits,
+// Matrix-core forward path for fp32 inputs, d = 64: the contractions of Algorithm 1 (Section 3.2) -- logits,
 // first moment, second moment -- on v_mfma_f32_16x16x4_f32, fp32 operands and fp32 accumulation throughout, so the
 // path has the accuracy of the vector kernels and no value-range condition.
 //
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(256, 2) void moments_f32_kernel(const float *__rest
                                                             llla_strides sq, llla_strides sk, int H, int n, int npad,
                                                             float cscale, float lambda, const float *__restrict__ lam_rows,
                                                             float *__restrict__ Mg, float *__restrict__ LFg,
-                                                            float *__restrict__ Yg)
+                                                            float *__restrict__ Yg, int causal)
 {
     using S = Shape<FD>;
     constexpr int NB = 4, QW = 4, QB = 16, YP = S::YP;
@@ -78,12 +78,13 @@ __global__ __launch_bounds__(256, 2) void moments_f32_kernel(const float *__rest
     const int nqb = gridDim.x;
     const int i0 = (nqb - 1 - bm.blk) * QB;                           // long rows first
     const int ilast = min(i0 + QB - 1, n - 1);
-    const int nblk = ilast / FKB + 1;
+    const int nblk = causal ? ilast / FKB + 1 : (n + FKB - 1) / FKB;
     const float *Kh = Kg + b * sk.batch + h * sk.head;
     const float *Qh = Qg + b * sq.batch + h * sq.head;
 
     // weight role: lane (g, nn) of wave w serves query i0 + nn and keys 16 w + 4 g + r of a block
     const int iq = i0 + nn, iqc = min(iq, n - 1);
+    const int jlim = causal ? iq : n - 1;                              // last key the lane's query sees
     const bool q_live = iq < n;
     float qreg[16];                                                    // Q[query nn][16 g + s], s = 0..15
     {
@@ -142,7 +143,7 @@ __global__ __launch_bounds__(256, 2) void moments_f32_kernel(const float *__rest
         for (int r = 0; r < 4; ++r) {
             const int j = c * FKB + 16 * wave + 4 * g + r;
             zs[r] = z[r] * cscale;
-            pmx = (q_live && j <= iq) ? fmaxf(pmx, zs[r]) : pmx;
+            pmx = (q_live && j <= jlim) ? fmaxf(pmx, zs[r]) : pmx;
         }
         pmx = fmaxf(pmx, __shfl_xor(pmx, 16));
         pmx = fmaxf(pmx, __shfl_xor(pmx, 32));
@@ -163,7 +164,7 @@ __global__ __launch_bounds__(256, 2) void moments_f32_kernel(const float *__rest
             for (int r = 0; r < 4; ++r) {
                 const int j = c * FKB + 16 * wave + 4 * g + r;
                 const float wgt = __builtin_amdgcn_exp2f(zs[r] - mh);
-                wf[r] = (q_live && j <= iq) ? -wgt : 0.f;             // stored negated: the tiles accumulate -(w k) k^T
+                wf[r] = (q_live && j <= jlim) ? -wgt : 0.f;           // stored negated: the tiles accumulate -(w k) k^T
                 sm.wt[nn * FWP + r * 16 + 4 * wave + g] = wf[r];
             }
             om_part += (wf[0] + wf[1]) + (wf[2] + wf[3]);
@@ -281,7 +282,7 @@ __global__ __launch_bounds__(256) void output_f32_kernel(const float *__restrict
                                                          const float *__restrict__ Vg, llla_strides sq, llla_strides sk,
                                                          llla_strides sv, int H, int n, int npad, float cscale,
                                                          const float *__restrict__ Mg, const float *__restrict__ Yg,
-                                                         void *__restrict__ Og, llla_strides so, int out_bf16)
+                                                         void *__restrict__ Og, llla_strides so, int out_bf16, int causal)
 {
     constexpr int YP = Shape<FD>::YP, NB = 4;
     __shared__ __align__(16) OutShared sm;
@@ -290,6 +291,7 @@ __global__ __launch_bounds__(256) void output_f32_kernel(const float *__restrict
     const int bh = blockIdx.x, b = bh / H, h = bh % H;
     const int i0 = ((int)gridDim.y - 1 - (int)blockIdx.y) * 64;
     const int iq = i0 + wave * 16 + nn, iqc = min(iq, n - 1);
+    const int jlim = causal ? iq : n - 1;
     const float *Kh = Kg + b * sk.batch + h * sk.head;
     const float *Vh = Vg + b * sv.batch + h * sv.head;
     float qreg[16], yreg[16];                                       // Q and y1' of query nn, features 16 g + s
@@ -310,7 +312,7 @@ __global__ __launch_bounds__(256) void output_f32_kernel(const float *__restrict
     for (int J = 0; J < NB; ++J) oacc[J] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const int ilast = min(i0 + 63, n - 1);
-    const int nblk = ilast / FKB + 1;
+    const int nblk = causal ? ilast / FKB + 1 : (n + FKB - 1) / FKB;
     for (int c = 0; c < nblk; ++c) {
         __syncthreads();                                            // everybody is done with the previous tiles
 #pragma unroll
@@ -324,7 +326,7 @@ __global__ __launch_bounds__(256) void output_f32_kernel(const float *__restrict
         dma_wait();
         __syncthreads();
         // blocks that lie wholly before the wave's first query need no causal mask (a scalar condition)
-        const bool masked = c * FKB + FKB - 1 > i0 + wave * 16;
+        const bool masked = causal ? (c * FKB + FKB - 1 > i0 + wave * 16) : (c * FKB + FKB > n);
 #pragma unroll
         for (int sub = 0; sub < 4; ++sub) {
             f32x4 z = {0.f, 0.f, 0.f, 0.f}, u = {0.f, 0.f, 0.f, 0.f};
@@ -347,7 +349,7 @@ __global__ __launch_bounds__(256) void output_f32_kernel(const float *__restrict
                 cf[r] = __builtin_amdgcn_exp2f(z[r] * cscale - mh) * (y0 + u[r]);
                 if (masked) {
                     const int j = c * FKB + 16 * sub + 4 * g + r;
-                    cf[r] = (j <= iq) ? cf[r] : 0.f;
+                    cf[r] = (j <= jlim) ? cf[r] : 0.f;
                 }
             }
 #pragma unroll
@@ -397,7 +399,7 @@ __global__ __launch_bounds__(256) void stats_f32_kernel(const float *__restrict_
 
 }  // namespace
 
-bool mfma_forward_f32_supported(int d, bool causal) { return d == FD && causal; }
+bool mfma_forward_f32_supported(int d, bool causal) { (void)causal; return d == FD; }
 
 size_t mfma_forward_f32_workspace_bytes(int B, int H, int n) { return make_f32_layout(B, H, n).total; }
 
@@ -412,7 +414,7 @@ hipError_t mfma_forward_f32(const Problem &p)
     const float *Q = static_cast<const float *>(p.Q), *K = static_cast<const float *>(p.K);
     stage_mark(p.stream, "moments");
     hipLaunchKernelGGL(moments_f32_kernel, dim3((p.n + S::QB - 1) / S::QB, bh), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H,
-                       p.n, L.npad, p.scale * LOG2E, p.lambda, p.lambda_rows, M, LF, Y);
+                       p.n, L.npad, p.scale * LOG2E, p.lambda, p.lambda_rows, M, LF, Y, p.causal);
     if (p.rho != nullptr || p.delta != nullptr) {
         stage_mark(p.stream, "statistics");
         hipLaunchKernelGGL(stats_f32_kernel, dim3((p.n + 3) / 4, bh), dim3(256), 0, p.stream, Q, p.sq, p.H, p.n, L.npad,
@@ -421,7 +423,7 @@ hipError_t mfma_forward_f32(const Problem &p)
     stage_mark(p.stream, "output");
     hipLaunchKernelGGL(output_f32_kernel, dim3(bh, (p.n + 63) / 64), dim3(256), 0, p.stream, Q, K, static_cast<const float *>(p.V),
                        p.sq, p.sk, p.sv, p.H, p.n, L.npad, p.scale * LOG2E, (const float *)M, (const float *)Y, p.O, p.so,
-                       p.out == LLLA_BF16 ? 1 : 0);
+                       p.out == LLLA_BF16 ? 1 : 0, p.causal);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // rows that see at most 64 keys: fp64 in key space (their output weights cancel to three digits in fp32)

@@ -377,12 +377,12 @@ hipError_t launch_given(const Problem &p, int nrows, const float *M, int mpitch,
     if (p.out == LLLA_F32)
         hipLaunchKernelGGL((valu_kernel<D, TI, float, false, true>), grid, dim3(NT), 0, p.stream,
                            (const TI *)p.Q, (const TI *)p.K, (const TI *)p.V, (float *)p.O, p.sq, p.sk,
-                           p.sv, p.so, nullptr, p.H, p.B * p.H, p.n, 1, p.lambda, p.scale, M, mpitch, Y, ypitch, (const float *)nullptr,
+                           p.sv, p.so, nullptr, p.H, p.B * p.H, p.n, p.causal, p.lambda, p.scale, M, mpitch, Y, ypitch, (const float *)nullptr,
                            (float *)nullptr, (float *)nullptr);
     else
         hipLaunchKernelGGL((valu_kernel<D, TI, bf16_t, false, true>), grid, dim3(NT), 0, p.stream,
                            (const TI *)p.Q, (const TI *)p.K, (const TI *)p.V, (bf16_t *)p.O, p.sq, p.sk,
-                           p.sv, p.so, nullptr, p.H, p.B * p.H, p.n, 1, p.lambda, p.scale, M, mpitch, Y, ypitch, (const float *)nullptr,
+                           p.sv, p.so, nullptr, p.H, p.B * p.H, p.n, p.causal, p.lambda, p.scale, M, mpitch, Y, ypitch, (const float *)nullptr,
                            (float *)nullptr, (float *)nullptr);
     return hipGetLastError();
 }

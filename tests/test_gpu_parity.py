@@ -112,14 +112,24 @@ def test_unnormalised_f32_statistics_and_ridge_per_row():
     print(check(Dl.cpu().numpy()[..., None], refD[..., None], rows, d, w.tol, "unnormalised ex delta"))
 
 
-@pytest.mark.parametrize("d,dtype", [(16, "f32"), (64, "f32"), (64, "bf16"), (128, "bf16")])
-def test_non_causal(d, dtype):
-    w = _small("noncausal", 1, 2, 150, d, dtype, index=70 + d)
+@pytest.mark.parametrize("n,d,dtype,path", [
+    (150, 16, "f32", "auto"), (150, 64, "f32", "valu"), (150, 64, "bf16", "valu"), (150, 128, "bf16", "valu"),
+    (40, 64, "f32", "mfma"), (150, 64, "f32", "mfma"), (700, 64, "f32", "mfma"),
+    (100, 64, "bf16", "mfma"), (150, 64, "bf16", "mfma"), (700, 64, "bf16", "mfma"),
+    (150, 128, "bf16", "mfma"), (257, 128, "bf16", "mfma"), (600, 128, "bf16", "mfma"),
+])
+def test_non_causal(n, d, dtype, path):
+    """causal = 0: every row sees all n keys (the matrix form of Section 3.2 without its tril mask), on the vector
+    kernels and on the matrix-core kernels, below and above the row count at which the latter change variant."""
+    w = _small("noncausal", 1, 2, n, d, dtype, index=70 + d + n)
     Q, K, V = workloads.make_inputs(w)
     ref = oracle.forward(Q, K, V, w.lam, w.scale, causal=False)
-    got = _run_forward(w, Q, K, V, causal=False)
-    # every row sees all 150 keys; rows are "late" rows in the sense of the gate only if 150 >= 4d
-    print(check(got, ref, np.full(w.n, w.n - 1), d, w.tol, "noncausal d=%d %s" % (d, dtype)))
+    got = _run_forward(w, Q, K, V, causal=False, path=path)
+    # every row sees all n keys; rows are "late" rows in the sense of the gate only if n > 4d
+    print(check(got, ref, np.full(w.n, w.n - 1), d, w.tol, "noncausal %s n=%d d=%d %s" % (path, n, d, dtype)))
+    if path == "mfma":
+        got16 = _run_forward(w, Q, K, V, causal=False, path=path, out_dtype=torch.bfloat16)
+        print(check(got16, ref, np.full(w.n, w.n - 1), d, max(w.tol, 2e-2), "noncausal bf16 out"))
 
 
 def test_strided_inputs_and_bf16_output():
@@ -183,10 +193,6 @@ def test_mfma_path_refuses_what_it_does_not_serve():
     y = torch.zeros(1, 1, 64, 128, dtype=torch.float32, device=DEV)
     with pytest.raises(llla.LlaError) as e:
         llla.llla_forward(y, y, y, 1e-2, 0.2, path="mfma")          # fp32 inputs at d = 128 neither
-    assert e.value.code == 7
-    y = torch.zeros(1, 1, 64, 64, dtype=torch.float32, device=DEV)
-    with pytest.raises(llla.LlaError) as e:
-        llla.llla_forward(y, y, y, 1e-2, 0.2, path="mfma", causal=False)      # the fp32 matrix-core path is causal only
     assert e.value.code == 7
     z = torch.zeros(1, 1, 512, 64, dtype=torch.bfloat16, device=DEV)
     with pytest.raises(llla.LlaError) as e:
@@ -277,6 +283,29 @@ def test_decode_mfma_d128_splits_and_bf16_output(B, H, L):
         print(check(got[:, :, None, :], ref[:, :, None, :], np.array([L - 1]), 128, w.tol, "decode mfma d=128 L=%d" % L))
     valu = llla.llla_decode(q.to(DEV), Kc.to(DEV), Vc.to(DEV), w.lam, w.scale, path="valu").cpu().numpy()
     assert np.linalg.norm(got - valu) / np.linalg.norm(valu) < 1e-2
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_decode_mfma_short_caches(d):
+    """Cache capacities from 256 rows up on the matrix-core decode (a wave then has as little as two 32-key steps),
+    with the full length and with shorter per-sequence lengths; below 256 rows the matrix-core path does not serve."""
+    for L in (256, 300, 511, 777, 1023):
+        w = _small("decshortcache", 3, 2, L, d, "bf16", index=1600 + d + L).with_shape(kind="decode")
+        q, Kc, Vc = workloads.make_inputs(w)
+        ref = oracle.decode(q, Kc, Vc, w.lam, w.scale)
+        got = llla.llla_decode(q.to(DEV), Kc.to(DEV), Vc.to(DEV), w.lam, w.scale, path="mfma").cpu().numpy()
+        print(L, check(got[:, :, None, :], ref[:, :, None, :], np.array([L - 1]), d, w.tol, "decode mfma d=%d L=%d" % (d, L)))
+        lens = [L, 1, L // 2 + 1]
+        ref = oracle.decode(q, Kc, Vc, w.lam, w.scale, seqlens=lens)
+        sl = torch.tensor(lens, dtype=torch.int32, device=DEV)
+        got = llla.llla_decode(q.to(DEV), Kc.to(DEV), Vc.to(DEV), w.lam, w.scale, seqlens=sl, path="mfma").cpu().numpy()
+        for b, Lb in enumerate(lens):
+            print(check(got[b:b + 1, :, None, :], ref[b:b + 1, :, None, :], np.array([Lb - 1]), d, w.tol,
+                        "decode mfma d=%d seqlen %d of %d" % (d, Lb, L)))
+    x = torch.zeros(1, 1, 255, d, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(llla.LlaError) as e:
+        llla.llla_decode(x[:, :, 0], x, x, 1e-2, 0.1, path="mfma")
+    assert e.value.code == 7
 
 
 def test_decode_mfma_d128_seqlens_ignore_the_tail_and_strided_cache():
