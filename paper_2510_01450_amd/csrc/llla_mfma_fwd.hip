@@ -462,8 +462,14 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
             } else {
 #pragma unroll
                 for (int t = 0; t < NAT_INSTR; ++t) {
-                    const int j = min(blk * KB2 + kn_key[t], n - 1);
-                    dma16(Kh + (int64_t)j * sk.seq + kn_gcol[t], &kn[buf][(16 * CH * wave + 64 * t) * 8]);
+                    // (from an opaque copy of the lane index: the addresses of this rare branch are then formed here,
+                    // not hoisted out of the loop as invariants that would have to be spilled across it)
+                    int ln = lane;
+                    asm volatile("" : "+v"(ln));
+                    const int sl = 16 * CH * wave + 64 * t + ln;      // slot = key*CH + stored chunk, as above
+                    const int key = sl / CH, gcol = ((sl % CH) ^ nat_swizzle<CH>(key)) * 8;
+                    const int j = min(blk * KB2 + key, n - 1);
+                    dma16(Kh + (int64_t)j * sk.seq + gcol, &kn[buf][(16 * CH * wave + 64 * t) * 8]);
                 }
             }
         }
@@ -679,6 +685,13 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
 
 
     // ---- hand mu~ and omega to the waves that own the queries ---------------------------------------
+    // From here on the lane coordinates are taken from copies the optimiser cannot see through: every LDS and global
+    // address of the epilogue and of the solve is a function of them, the optimiser would compute all of those before
+    // the main loop (they are loop-invariant) and then spill them across it, for want of registers there.
+    int g_e = g, nn_e = nn;
+    asm volatile("" : "+v"(g_e), "+v"(nn_e));
+#define g g_e
+#define nn nn_e
 #pragma unroll
     for (int r = 0; r < 4; ++r) mus[4 * g + r][16 * wave + nn] = mu_acc[r];   // -mu~ (negated weights)
     if (OM_MFMA) {
@@ -786,6 +799,8 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
         }
     }
     }
+#undef g
+#undef nn
 }
 
 // One launch serves every query block: blocks whose rows lie below precise_rows take the precise
