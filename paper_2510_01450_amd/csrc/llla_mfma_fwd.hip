@@ -619,6 +619,10 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     __syncthreads();
 
     int wb = 0;                                 // weight buffer of block c
+    // Two workgroups share a compute unit, one wave of each per SIMD.  A wave in the main loop (matrix-core bound) gets
+    // the issue slot before one that is in its solve (long vector-ALU chains that leave the matrix cores idle): 2.5 %
+    // at [4,16,4096,64].
+    __builtin_amdgcn_s_setprio(2);
     if (PREFETCH) {
         load_frags(fa, 0, 0);
         for (int c = 0; c < nblk; ++c) {
@@ -690,6 +694,7 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     // the main loop (they are loop-invariant) and then spill them across it, for want of registers there.
     int g_e = g, nn_e = nn;
     asm volatile("" : "+v"(g_e), "+v"(nn_e));
+    __builtin_amdgcn_s_setprio(0);
 #define g g_e
 #define nn nn_e
 #pragma unroll
