@@ -150,7 +150,7 @@ def measure(w, args, steps, warmup, headline):
     # clock settles below where a cold start finds it
     t_hot = time.perf_counter()
     hot_steps = 0
-    while time.perf_counter() - t_hot < 1.0:
+    while time.perf_counter() - t_hot < (0.0 if args.no_sustained else 1.0):
         for i in range(8):
             step(i)
         hot_steps += 8
@@ -380,6 +380,9 @@ def main():
     ap.add_argument("--path", default="auto", choices=["auto", "valu", "mfma"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--no-sustained", action="store_true",
+                    help="skip the second of continuous launches before ms_per_step_sustained (counter-collection runs, "
+                         "where every dispatch is slow and logged)")
     ap.add_argument("--no-secondary", action="store_true",
                     help="default run only: leave out the C3b forward and the C5 decode measurements")
     ap.add_argument("--cg", type=int, default=None, metavar="T",

@@ -28,7 +28,7 @@ struct Shape {
     static constexpr int NW = NB;                      // waves per workgroup (moments kernel): one mu~ block each
     static constexpr int QB = QW * NW;                 // queries per workgroup (moments kernel)
     static constexpr int NT = 64 * NW;                 // threads per workgroup (moments kernel)
-    static constexpr int YP = DD + 4;                  // pitch of a y row in the workspace: y1[0..D), y0 at [D]
+    static constexpr int YP = DD + 16;                 // pitch of a y row in the workspace: y1[0..D), y0 at [D]; rows start on 64-byte boundaries
     static constexpr int EARLY_ROWS = 2 * DD;          // rows served by the precise variant
     __host__ __device__ static constexpr int tix(int I, int J) { return I * NB - I * (I - 1) / 2 + (J - I); }
 };

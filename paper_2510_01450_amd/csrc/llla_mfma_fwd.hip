@@ -1156,7 +1156,7 @@ BackwardLayout mfma_backward_layout(int B, int H, int n, int d)
     BackwardLayout BL{};
     const Layout L = d == 64 ? make_layout<64>(B, H, n) : make_layout<128>(B, H, n);
     const size_t rows = (size_t)B * H * n;
-    BL.ypitch = d + 4;
+    BL.ypitch = d + 16;                                  // = Shape<d>::YP
     BL.npad = L.npad;
     BL.m = L.m;
     BL.y = L.y;
