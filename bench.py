@@ -31,6 +31,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_MFMA_16BIT = 2.5e15      # dense bf16/f16 MFMA, flop/s
+PEAK_MFMA_FP32 = 157.3e12     # dense fp32 MFMA, flop/s
 PEAK_FP32_VALU = 157.3e12     # fp32 vector, flop/s
 PEAK_HBM = 8.0e12             # B/s
 
@@ -200,7 +201,8 @@ def measure(w, args, steps, warmup, headline):
         elif dom == "moments":
             # logits, weights, omega, mu~, symmetric half of Sigma~, and the per-row solve
             flops = w.B * w.H * (pairs * (d * d + 5 * d) + w.n * (d ** 3 / 3.0 + 4 * d * d))
-            bound, peak = "mfma", PEAK_MFMA_16BIT
+            # fp32 inputs contract on v_mfma_f32_16x16x4_f32: the peak of that instruction, not the 16-bit one
+            bound, peak = "mfma", (PEAK_MFMA_FP32 if w.dtype == "f32" else PEAK_MFMA_16BIT)
         else:
             flops = forward_flops(w.B, w.H, w.n, d)
             bound, peak = ("mfma", PEAK_MFMA_16BIT) if (w.dtype != "f32" or dom != "valu_forward") else ("alu", PEAK_FP32_VALU)
@@ -212,7 +214,7 @@ def measure(w, args, steps, warmup, headline):
                                                   forward_flops(w.B, w.H, w.n, d)) / (float(np.mean(per)) * 1e-3) / 1e12}
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"], roof["traffic_source"] = measured_traffic(w.name, dom)
-    if roof["bound"] == "mfma" and headline:
+    if roof["bound"] == "mfma" and headline and w.dtype != "f32":
         # context for `peak`: the 16-bit MFMA rate this GPU sustains under a chip-wide matrix-core load (the
         # measurement library's probe: independent 16x16x32 f16 MFMAs and nothing else), measured here with HIP events
         sink = torch.zeros(64, dtype=torch.float32, device="cuda")
@@ -391,6 +393,9 @@ def main():
                     help="forward workloads: time llla_backward (gradients w.r.t. Q, K, V and the ridge of every row)")
     ap.add_argument("--ex", action="store_true",
                     help="forward workloads: time llla_forward_ex with a ridge per row and the statistics rho, delta")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="run nothing but three plain copies of 1 GiB (measurement library): under rocprofv3 --pmc this is the "
+                         "scale of the HBM counters, FETCH_SIZE or WRITE_SIZE units per byte")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures ONE GPU (one MI355X per box); --gpus %d is not run. "
@@ -406,6 +411,14 @@ def main():
         print("bench.py needs a GPU (no CPU fallback exists)", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
+    if args.copy_probe:
+        import paper_2510_01450_amd as llla
+        src = torch.ones(1 << 28, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        copied = [llla.probe_copy(src, dst) for _ in range(3)]
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_per_launch": copied[0], "launches": len(copied), "kernel": "copy_rate_kernel"}))
+        return
     default_run = args.workload is None and not (args.cg is not None or args.backward or args.ex)
     name = args.workload or "C3"
     w = workloads.ALL[name.upper() if name.upper() in workloads.ALL else name]

@@ -1,6 +1,6 @@
 /*
  * llla_measure.h -- measurement aids of the LLA library.  NOT part of the method and NOT exported by the
- * production library libllla.so: these three symbols exist only in libllla_measure.so, which is the same sources
+ * production library libllla.so: these four symbols exist only in libllla_measure.so, which is the same sources
  * compiled with -DLLLA_MEASURE (every kernel launcher then records HIP events) plus csrc/measure.  It exports the
  * whole of llla.h as well, so a benchmark loads it in place of the production library for its per-kernel pass.
  * The state below is process-wide and not thread-safe, which is why it lives in a library of its own.
@@ -31,6 +31,13 @@ int llla_profile_last(float *ms, const char **names, int max);
  * that is never written in practice (it only keeps the arithmetic alive).  1 <= iters <= 2^20.
  */
 llla_status llla_probe_mfma_f16(int iters, void *scratch, double *flops, void *stream);
+
+/*
+ * Enqueues one plain copy of `bytes` bytes from src to dst (device pointers, 16-byte aligned, bytes a multiple of
+ * 16, the two ranges disjoint): exactly `bytes` read and `bytes` written.  Run under a hardware counter it tells
+ * what that counter reads per byte of HBM traffic, the scale for the traffic figures of the other kernels.
+ */
+llla_status llla_probe_copy(const void *src, void *dst, size_t bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -82,6 +82,8 @@ def _declare(L, measure: bool):
         L.llla_profile_last.restype = i32
         L.llla_probe_mfma_f16.argtypes = [i32, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.llla_probe_mfma_f16.restype = i32
+        L.llla_probe_copy.argtypes = [vp, vp, sz, vp]
+        L.llla_probe_copy.restype = i32
 
 
 def _load(measure: bool):
@@ -140,6 +142,19 @@ def probe_mfma_f16(iters: int, scratch) -> float:
     if st != 0:
         raise LlaError(st, status_string(st))
     return float(flops.value)
+
+
+def probe_copy(src, dst) -> int:
+    """Measurement library only: enqueue one plain copy src -> dst (contiguous device tensors of equal byte size) on
+    the current stream; returns the bytes copied (that many read, that many written)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes or not (src.is_contiguous() and dst.is_contiguous()):
+        raise ValueError("probe_copy needs two contiguous tensors of the same size in bytes")
+    st = measure_lib().llla_probe_copy(ctypes.c_void_p(src.data_ptr()), ctypes.c_void_p(dst.data_ptr()), ctypes.c_size_t(nbytes),
+                                       ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    if st != 0:
+        raise LlaError(st, status_string(st))
+    return nbytes
 
 
 def forward_workspace_bytes(B, H, n, d, dtype) -> int:

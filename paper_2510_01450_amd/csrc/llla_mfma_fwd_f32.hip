@@ -86,15 +86,12 @@ __global__ __launch_bounds__(256, 2) void moments_f32_kernel(const float *__rest
     const int iq = i0 + nn, iqc = min(iq, n - 1);
     const int jlim = causal ? iq : n - 1;                              // last key the lane's query sees
     const bool q_live = iq < n;
-    float qreg[16];                                                    // Q[query nn][16 g + s], s = 0..15
+    // the 16 query rows wait in LDS (in the rows that hold mu~ after the sweep) instead of in 16 registers per lane:
+    // thread t brings floats 4 (t % 16) .. + 3 of query t / 16
     {
-        const float *qrow = Qh + (int64_t)iqc * sq.seq + 16 * g;
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const f32x4 t = *reinterpret_cast<const f32x4 *>(qrow + 4 * v);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) qreg[4 * v + e] = t[e];
-        }
+        const int qr = tid >> 4, qc = 4 * (tid & 15);
+        *reinterpret_cast<f32x4 *>(&sm.mus[qr][qc]) =
+            *reinterpret_cast<const f32x4 *>(Qh + (int64_t)min(i0 + qr, n - 1) * sq.seq + qc);
     }
 
     f32x4 acc[QW][10];
@@ -108,14 +105,29 @@ __global__ __launch_bounds__(256, 2) void moments_f32_kernel(const float *__rest
 
     // DMA of one K block: 16 KB = 16 wave transfers of 1 KB, four per wave; transfer t of wave w fills key rows
     // 16 w + 4 t .. + 3; lane l of it writes row 16 w + 4 t + l / 16, stored chunk l % 16
+    // Full blocks: a wave-uniform base address per block (scalar registers) plus one 32-bit byte offset per lane and
+    // transfer, formed when needed from an opaque copy of the lane index (nothing address-like stays live over the
+    // sweep); the last, ragged block clamps its rows to n - 1.
     auto issue_dma = [&](int blk) {
         float *dst = sm.kt[blk & 1];
+        int lane_e = lane;
+        asm volatile("" : "+v"(lane_e));
+        if (blk * FKB + FKB <= n && sk.seq < (int64_t(1) << 23)) {       // whole block, byte offsets fit 32 bits
+            const float *base = Kh + (int64_t)blk * FKB * sk.seq;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int row = 16 * wave + 4 * t + (lane >> 4);
-            const int j = min(blk * FKB + row, n - 1);
-            const int chunk = (lane & 15) ^ swz(row);
-            dma16(Kh + (int64_t)j * sk.seq + 4 * chunk, dst + (16 * wave + 4 * t) * FD);
+            for (int t = 0; t < 4; ++t) {
+                const int row = 16 * wave + 4 * t + (lane_e >> 4);
+                const int chunk = (lane_e & 15) ^ swz(row);
+                dma16_base(base, (unsigned)(row * (int)sk.seq + 4 * chunk) * 4u, dst + (16 * wave + 4 * t) * FD);
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int row = 16 * wave + 4 * t + (lane_e >> 4);
+                const int j = min(blk * FKB + row, n - 1);
+                const int chunk = (lane_e & 15) ^ swz(row);
+                dma16(Kh + (int64_t)j * sk.seq + 4 * chunk, dst + (16 * wave + 4 * t) * FD);
+            }
         }
     };
 
@@ -134,8 +146,9 @@ __global__ __launch_bounds__(256, 2) void moments_f32_kernel(const float *__rest
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const f32x4 kv = *reinterpret_cast<const f32x4 *>(krow + 4 * ((4 * g + v) ^ sw));
+                const f32x4 qv = *reinterpret_cast<const f32x4 *>(&sm.mus[nn][16 * g + 4 * v]);   // Q[query nn][16 g + 4 v ..]
 #pragma unroll
-                for (int e = 0; e < 4; ++e) z = __builtin_amdgcn_mfma_f32_16x16x4f32(kv[e], qreg[4 * v + e], z, 0, 0, 0);
+                for (int e = 0; e < 4; ++e) z = __builtin_amdgcn_mfma_f32_16x16x4f32(kv[e], qv[e], z, 0, 0, 0);
             }
         }
         float zs[4], pmx = -INFINITY;
@@ -195,11 +208,15 @@ __global__ __launch_bounds__(256, 2) void moments_f32_kernel(const float *__rest
 #pragma unroll
             for (int q = 0; q < QW; ++q) wq[q] = *reinterpret_cast<const f32x4 *>(&sm.wt[(QW * wave + q) * FWP + g * 16 + 4 * s4]);
             const f32x4 wa = *reinterpret_cast<const f32x4 *>(&sm.wt[nn * FWP + g * 16 + 4 * s4]);
+            // the operand addresses below are formed from copies of the lane indices that the compiler cannot see
+            // through: twenty of them are loop-invariant and would otherwise be kept in registers over the whole sweep
+            int g_e = g, nn_e = nn;
+            asm volatile("" : "+v"(g_e), "+v"(nn_e));
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const int row = 4 * (4 * s4 + e) + g;
-                const float *krow = kt + row * FD + (nn & 3);
-                const int sw = swz(row), c4 = nn >> 2;
+                const int row = 4 * (4 * s4 + e) + g_e;
+                const float *krow = kt + row * FD + (nn_e & 3);
+                const int sw = swz(row), c4 = nn_e >> 2;
                 float kf[NB];
 #pragma unroll
                 for (int I = 0; I < NB; ++I) kf[I] = krow[4 * ((4 * I + c4) ^ sw)];

@@ -33,8 +33,24 @@ __global__ __launch_bounds__(256, 2) void mfma_rate_kernel(int iters, float *__r
     if (s == 12345.678f) sink[0] = s;       // keeps the accumulators alive; never true for these operands
 }
 
+// Plain copy of known size: what the HBM counters (FETCH_SIZE, WRITE_SIZE) read per byte moved.
+__global__ __launch_bounds__(256) void copy_rate_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
 }  // namespace
 }  // namespace llla
+
+extern "C" llla_status llla_probe_copy(const void *src, void *dst, size_t bytes, void *stream)
+{
+    if (!src || !dst) return LLLA_ERR_NULL;
+    if (bytes == 0 || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return LLLA_ERR_PARAM;
+    using namespace llla;
+    copy_rate_kernel<<<4096, 256, 0, static_cast<hipStream_t>(stream)>>>(static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), bytes / 16);
+    return hipGetLastError() == hipSuccess ? LLLA_OK : LLLA_ERR_LAUNCH;
+}
 
 extern "C" llla_status llla_probe_mfma_f16(int iters, void *scratch, double *flops, void *stream)
 {

@@ -33,7 +33,7 @@ def test_measurement_aids_live_in_a_library_of_their_own():
     """The production library exports the method only; the profiling hooks and the MFMA probe exist in the
     measurement build, which also exports everything llla.h declares."""
     aids = _declared_symbols("llla_measure.h")
-    assert set(aids) == {"llla_profile_enable", "llla_profile_last", "llla_probe_mfma_f16"}
+    assert set(aids) == {"llla_profile_enable", "llla_profile_last", "llla_probe_mfma_f16", "llla_probe_copy"}
     assert not set(aids) & set(_declared_symbols())
     llla.lib()
     P = ctypes.CDLL(llla.lib_path())
