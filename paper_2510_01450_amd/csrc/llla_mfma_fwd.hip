@@ -406,9 +406,12 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
             for (int t = 0; t < 4; ++t) acc[q][S::tix(P, P)][t] = (nn == 4 * g + t) ? -lq : 0.f;
     }
     f32x4 mu_acc = {0.f, 0.f, 0.f, 0.f};
-    // omega: at d = 64 one wave sums it on the matrix cores (see mu_mfma); at d = 128, where the registers for that are
-    // not there (measured 5 % slower), every weight wave sums its own keys on the vector ALU
-    constexpr bool OM_MFMA = (DD == 64);
+    // omega: every weight wave sums the weights of its own keys on the vector ALU, exactly as the MFMAs see them (the
+    // rounded f16 values, two per v_dot2_f32_f16).  Summing it on the matrix cores with a tile of ones as the B operand
+    // of one more MFMA per half (OM_MFMA) was the d = 64 choice for a while; it costs eight registers that the
+    // alternating schedule below needs, and it made the one wave that did it the slowest of its workgroup.
+    constexpr bool OM_MFMA = false;
+    constexpr bool PIPE = (DD == 64) && !PRECISE;
     f32x4 om_acc = {0.f, 0.f, 0.f, 0.f};      // OM_MFMA, one wave: -omega of query 4g + r in every column
     float om_part = 0.f;                      // otherwise: this lane's share of omega for query i0 + nn
 
@@ -511,9 +514,13 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
         } else {
             half4 wv;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                wv[r] = (_Float16)wf[r];
-                if (!OM_MFMA) om_part -= (float)wv[r];      // omega sums the weights exactly as the MFMAs see them
+            for (int r = 0; r < 4; ++r) wv[r] = (_Float16)wf[r];
+            if (!OM_MFMA) {
+                // omega sums the weights exactly as the MFMAs see them: products with 1 are exact, the sum is fp32
+                typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+                const half2v minus_one = {(_Float16)-1.f, (_Float16)-1.f};
+                om_part = __builtin_amdgcn_fdot2(half2v{wv[0], wv[1]}, minus_one, om_part, false);
+                om_part = __builtin_amdgcn_fdot2(half2v{wv[2], wv[3]}, minus_one, om_part, false);
             }
             *reinterpret_cast<half4 *>(&wt[buf][nn * WT_PITCH + 16 * wave + 4 * g]) = wv;
         }
@@ -565,6 +572,34 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
                 }
             }
         }
+    };
+    // One query of one half with the vector and matrix-core instructions alternating: a wave's multiplies and MFMAs
+    // overlap only when they alternate (a run of four multiplies followed by a run of MFMAs costs the sum of the two),
+    // so the scaled operand of the NEXT item -- the next query's first item included, across halves and blocks -- is
+    // formed two multiplies at a time behind the MFMAs of this one.  pipe_af / pipe_wq carry that operand and the
+    // query's weights from one call to the next; frn and (wbn, hfn, qn) say where the next query's operands are.
+    half8 pipe_af, pipe_wq;
+    auto wq_read = [&](int wbuf, int hf, int q) {
+        return *reinterpret_cast<const half8 *>(&wt[wbuf][(QW * wave + q) * WT_PITCH + 32 * hf + 8 * g]);
+    };
+    auto pipe_query = [&](const Frags &fr, int q, const Frags &frn, int wbn, int hfn, int qn) {
+        const half8 wq_next = wq_read(wbn, hfn, qn);
+        half8 af = pipe_af;
+#pragma unroll
+        for (int I = 0; I < NB; ++I) {
+            const half8 afn = I + 1 < NB ? fr.f[I + 1] * pipe_wq : frn.f[0] * wq_next;
+#pragma unroll
+            for (int J = I; J < NB; ++J) acc[q][S::tix(I, J)] = mfma_f16(af, fr.f[J], acc[q][S::tix(I, J)]);
+            af = afn;
+        }
+        pipe_af = af;
+        pipe_wq = wq_next;
+#define SGB_MV() __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x002, 2, 0)
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        SGB_MV(); SGB_MV(); SGB_MV(); SGB_MV(); SGB_MV(); SGB_MV(); SGB_MV(); SGB_MV();
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+#undef SGB_MV
+        __builtin_amdgcn_sched_barrier(0);
     };
     // -mu~ of one half: the (negated) weights of all 16 query rows are the A operand (lane (g, nn): row nn, keys
     // 8g..8g+7), this wave's feature block of the tile the B operand (re-read from LDS: indexing f[] by the wave
@@ -623,7 +658,44 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     // the issue slot before one that is in its solve (long vector-ALU chains that leave the matrix cores idle): 2.5 %
     // at [4,16,4096,64].
     __builtin_amdgcn_s_setprio(2);
-    if (PREFETCH) {
+    if (PIPE) {
+        load_frags(fa, 0, 0);
+        pipe_wq = wq_read(0, 0, 0);
+        pipe_af = fa.f[0] * pipe_wq;
+        for (int c = 0; c < nblk; ++c) {
+            const int buf = c & 1, wbn = (wb == 2) ? 0 : wb + 1;
+            // ---- first half ---------------------------------------------------------------------------
+            load_frags(fb, buf, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            pipe_query(fa, 0, fa, wb, 0, 1);
+            pipe_query(fa, 1, fa, wb, 0, 2);
+            dma_wait();                         // this wave's part of block c+1 has landed
+            weights_load(buf ^ 1);
+            mu_load_b(buf, 0);
+            mu_load_a(wb, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            pipe_query(fa, 2, fa, wb, 0, 3);
+            f32x4 z = weights_logits();
+            mu_mfma();
+            __builtin_amdgcn_sched_barrier(0);
+            pipe_query(fa, 3, fb, wb, 1, 0);
+            weights_store(c + 1, wbn, z);
+            mu_load_b(buf, 1);                  // the last read of block c's tiles: they are overwritten after the barrier
+            __syncthreads();
+            if (c + 2 < nblk) issue_dma(c + 2);
+            // ---- second half --------------------------------------------------------------------------
+            load_frags(fa, buf ^ 1, 0);         // first half of block c+1 (unused after the last block)
+            mu_load_a(wb, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            pipe_query(fb, 0, fb, wb, 1, 1);
+            pipe_query(fb, 1, fb, wb, 1, 2);
+            pipe_query(fb, 2, fb, wb, 1, 3);
+            mu_mfma();
+            __builtin_amdgcn_sched_barrier(0);
+            pipe_query(fb, 3, fa, wbn, 0, 0);   // after the last block: the all-zero round of weights, operand unused
+            wb = wbn;
+        }
+    } else if (PREFETCH) {
         load_frags(fa, 0, 0);
         for (int c = 0; c < nblk; ++c) {
             const int buf = c & 1, wbn = (wb == 2) ? 0 : wb + 1;
