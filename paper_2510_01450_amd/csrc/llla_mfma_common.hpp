@@ -321,6 +321,15 @@ __device__ inline void dma16_base(const void *sbase, unsigned voff, void *lds_ba
     const unsigned lds = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void_ptr)lds_base);
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds) : "memory", "m0");
 }
+// The same with the LDS destination given as a byte offset into the workgroup's LDS (lds_offset of the array plus
+// plain integer arithmetic): a pointer that went through pointer arithmetic in the generic address space costs four
+// scalar instructions per transfer to turn back into an LDS address.
+__device__ inline unsigned lds_offset(const void *lds_object) { return (unsigned)(uintptr_t)(lds_void_ptr)lds_object; }
+__device__ inline void dma16_base_off(const void *sbase, unsigned voff, unsigned lds_byte_off)
+{
+    const unsigned lds = __builtin_amdgcn_readfirstlane(lds_byte_off);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds) : "memory", "m0");
+}
 // The same two transfers with the non-temporal hint, for data that is read exactly once (the decode kernel's cache
 // stream): without it the stream stays about 10 % below what plain streaming loads reach on this part.
 __device__ inline void dma16_nt(const void *gsrc, void *lds_base)

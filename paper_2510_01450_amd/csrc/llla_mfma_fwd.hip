@@ -447,21 +447,24 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
 #pragma unroll
     for (int t = 0; t < NAT_INSTR; ++t) kn_boff[t] = 2u * (unsigned)(kn_key[t] * (int)sk.seq + kn_gcol[t]);
     const bool small_pitch = sk.seq < (int64_t(1) << 23);       // the offsets above fit 32 bits
+    const unsigned kt_lds = lds_offset(&sm.kt[0][0][0]), kn_lds = lds_offset(&sm.kn[0][0]);
     auto issue_dma = [&](int blk) {     // block blk -> LDS buffer blk & 1
         const int buf = blk & 1;
         if (t_wave) {
             const _Float16 *src = KTh + (size_t)blk * (2 * KT_SUB);
+            const unsigned dst = kt_lds + 2u * (unsigned)(buf * 2 * DD * KB + tw * TR_SLOTS * 8);
 #pragma unroll
             for (int t = 0; t < TR_INSTR; ++t) {
-                dma16_base(src, tr_boff[t], &kt[buf][0][(tw * TR_SLOTS + 64 * t) * 8]);
-                dma16_base(src + KT_SUB, tr_boff[t], &kt[buf][1][(tw * TR_SLOTS + 64 * t) * 8]);
+                dma16_base_off(src, tr_boff[t], dst + 2u * (64 * t * 8));
+                dma16_base_off(src + KT_SUB, tr_boff[t], dst + 2u * (DD * KB + 64 * t * 8));
             }
         }
         if (w_wave) {
             if (small_pitch && blk * KB2 + KB2 <= n) {
                 const bf16_t *src = Kh + (int64_t)blk * KB2 * sk.seq;
+                const unsigned dst = kn_lds + 2u * (unsigned)(buf * KB2 * DD + 16 * CH * wave * 8);
 #pragma unroll
-                for (int t = 0; t < NAT_INSTR; ++t) dma16_base(src, kn_boff[t], &kn[buf][(16 * CH * wave + 64 * t) * 8]);
+                for (int t = 0; t < NAT_INSTR; ++t) dma16_base_off(src, kn_boff[t], dst + 2u * (64 * t * 8));
             } else {
 #pragma unroll
                 for (int t = 0; t < NAT_INSTR; ++t) {
@@ -493,24 +496,28 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
         for (int f = 0; f < NF; ++f) z = mfma_bf16(knf[f], qf[f], z);
         return z;
     };
+    // blocks 0 .. n_unmasked - 1 lie wholly before the workgroup's first query (causal) or wholly inside the sequence
+    // (not causal): no key of theirs is masked for any query of the workgroup
+    const int n_unmasked = QB == 16 ? (causal ? (i0 + 1) / KB2 : n / KB2) : 0;
     auto weights_store = [&](int blk, int buf, f32x4 z) {
         float wf[4];
-        // stored negated: the tiles accumulate -(w k) k^T.  A block that lies wholly before the workgroup's first
-        // query needs no causal mask (a scalar condition; most blocks of a long row)
-        if ((causal ? blk * KB2 + KB2 - 1 <= i0 : blk * KB2 + KB2 <= n) && QB == 16) {
+        // A block that lies wholly before the workgroup's first query needs no causal mask (a scalar condition; most
+        // blocks of a long row)
+        if (blk < n_unmasked) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) wf[r] = -__builtin_amdgcn_exp2f(z[r] * cscale - mrow);
+            for (int r = 0; r < 4; ++r) wf[r] = __builtin_amdgcn_exp2f(z[r] * cscale - mrow);
         } else {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int j = blk * KB2 + 16 * wave + 4 * g + r;
                 const float wgt = __builtin_amdgcn_exp2f(z[r] * cscale - mrow);
-                wf[r] = (q_live && j <= jlim) ? -wgt : 0.f;
+                wf[r] = (q_live && j <= jlim) ? wgt : 0.f;
             }
         }
+        // stored negated: the tiles accumulate -(w k) k^T
         if (PRECISE) {
-            *reinterpret_cast<f32x4 *>(&wt32[buf][nn * WT32_PITCH + 16 * wave + 4 * g]) = f32x4{wf[0], wf[1], wf[2], wf[3]};
-            if (!OM_MFMA) om_part -= (wf[0] + wf[1]) + (wf[2] + wf[3]);
+            *reinterpret_cast<f32x4 *>(&wt32[buf][nn * WT32_PITCH + 16 * wave + 4 * g]) = f32x4{-wf[0], -wf[1], -wf[2], -wf[3]};
+            if (!OM_MFMA) om_part += (wf[0] + wf[1]) + (wf[2] + wf[3]);
         } else {
             half4 wv;
 #pragma unroll
@@ -518,11 +525,11 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
             if (!OM_MFMA) {
                 // omega sums the weights exactly as the MFMAs see them: products with 1 are exact, the sum is fp32
                 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
-                const half2v minus_one = {(_Float16)-1.f, (_Float16)-1.f};
-                om_part = __builtin_amdgcn_fdot2(half2v{wv[0], wv[1]}, minus_one, om_part, false);
-                om_part = __builtin_amdgcn_fdot2(half2v{wv[2], wv[3]}, minus_one, om_part, false);
+                const half2v one = {(_Float16)1.f, (_Float16)1.f};
+                om_part = __builtin_amdgcn_fdot2(half2v{wv[0], wv[1]}, one, om_part, false);
+                om_part = __builtin_amdgcn_fdot2(half2v{wv[2], wv[3]}, one, om_part, false);
             }
-            *reinterpret_cast<half4 *>(&wt[buf][nn * WT_PITCH + 16 * wave + 4 * g]) = wv;
+            *reinterpret_cast<half4 *>(&wt[buf][nn * WT_PITCH + 16 * wave + 4 * g]) = -wv;     // the sign bits of two registers
         }
     };
 
