@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void prep_kernel(const bf16_t *__restrict__ Kg
 constexpr int VT_PITCH = KB + 8;     // halves
 
 template <bool MAXONLY, int DD>
-__global__ __launch_bounds__(256) void sweep_kernel(const bf16_t *__restrict__ Qg, const bf16_t *__restrict__ Kg,
+__global__ __launch_bounds__(256, 2) void sweep_kernel(const bf16_t *__restrict__ Qg, const bf16_t *__restrict__ Kg,
                                                     llla_strides sq, llla_strides sk, int H, int n, int nkb,
                                                     int first_row, float cscale, const bf16_t *__restrict__ VT,
                                                     float *__restrict__ Mg, const float *__restrict__ Yg,
@@ -239,12 +239,19 @@ __global__ __launch_bounds__(256) void sweep_kernel(const bf16_t *__restrict__ Q
                     cv[t] = (j <= jlim) ? cv[t] : 0.f;
                 }
             }
+            if (Csum != nullptr) {                                   // a scalar branch: the plain output call skips the sums
 #pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                csum += cv[t];
-                const __bf16 hi = (__bf16)cv[t];
-                ch[t] = hi;
-                cl[t] = (__bf16)(cv[t] - (float)hi);
+                for (int t = 0; t < 8; ++t) csum += cv[t];
+            }
+            // two values per conversion instruction (v_cvt_pk_bf16_f32)
+            typedef float float2v __attribute__((ext_vector_type(2)));
+            typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+#pragma unroll
+            for (int t = 0; t < 8; t += 2) {
+                const bf16x2v hi = __builtin_convertvector(float2v{cv[t], cv[t + 1]}, bf16x2v);
+                const bf16x2v lo = __builtin_convertvector(float2v{cv[t] - (float)hi[0], cv[t + 1] - (float)hi[1]}, bf16x2v);
+                ch[t] = hi[0]; ch[t + 1] = hi[1];
+                cl[t] = lo[0]; cl[t + 1] = lo[1];
             }
 #pragma unroll
             for (int J = 0; J < NB; ++J) {

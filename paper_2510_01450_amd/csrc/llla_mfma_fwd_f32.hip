@@ -295,7 +295,7 @@ struct OutShared {
     float v[FKB * FD];
 };
 
-__global__ __launch_bounds__(256) void output_f32_kernel(const float *__restrict__ Qg, const float *__restrict__ Kg,
+__global__ __launch_bounds__(256, 2) void output_f32_kernel(const float *__restrict__ Qg, const float *__restrict__ Kg,
                                                          const float *__restrict__ Vg, llla_strides sq, llla_strides sk,
                                                          llla_strides sv, int H, int n, int npad, float cscale,
                                                          const float *__restrict__ Mg, const float *__restrict__ Yg,
