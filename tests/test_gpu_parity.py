@@ -209,6 +209,27 @@ def test_lambda_and_scale_are_honoured():
         print(check(got, ref, np.arange(w.n), w.d, 1e-4, "lam=%g scale=%g" % (lam, scale)))
 
 
+@pytest.mark.parametrize("d,dtype", [(64, "bf16"), (128, "bf16"), (64, "f32")])
+@pytest.mark.parametrize("lam", [1e-3, 3e-4])
+def test_small_ridge_on_the_matrix_core_paths(d, dtype, lam):
+    """Ridges below the default 1e-2: the factorisation on the matrix-core paths raises a computed pivot that falls
+    below half the ridge to that value (in exact arithmetic every pivot is at least the ridge), so small ridges must
+    still give finite outputs, and outputs that pass the usual gate against the oracle."""
+    w = _small("smallridge", 1, 2, 600, d, dtype, index=150 + d).with_shape(lam=lam)
+    Q, K, V = workloads.make_inputs(w)
+    ref = oracle.forward(Q, K, V, lam, w.scale)
+    got = _run_forward(w, Q, K, V, path="mfma")
+    assert np.isfinite(got).all()
+    print(lam, check(got, ref, np.arange(w.n), d, w.tol, "small ridge %g d=%d %s" % (lam, d, dtype)))
+    if dtype == "bf16":
+        wd = _small("smallridgedec", 2, 2, 700, d, dtype, index=160 + d).with_shape(kind="decode", lam=lam)
+        q, Kc, Vc = workloads.make_inputs(wd)
+        refd = oracle.decode(q, Kc, Vc, lam, wd.scale)
+        gotd = llla.llla_decode(q.to(DEV), Kc.to(DEV), Vc.to(DEV), lam, wd.scale, path="mfma").cpu().numpy()
+        assert np.isfinite(gotd).all()
+        print(lam, check(gotd[:, :, None, :], refd[:, :, None, :], np.array([699]), d, wd.tol, "small ridge decode %g d=%d" % (lam, d)))
+
+
 def test_large_logits_do_not_overflow():
     """Row-max normalisation: logits up to +-60 (unit-norm rows, scale 60) must still give finite,
     correct outputs."""
