@@ -551,7 +551,28 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     };
     // The MFMAs of work items [lo, hi) of one half; item = (query q, feature block I), q-major.  wb = weight buffer.
     auto compute_items = [&](const Frags &fr, int wb, int hf, int lo, int hi) {
-        if (!PRECISE) {
+        if (!PRECISE && DD == 128) {
+            // one query per wave: the scaled operand of item I + 1 is formed behind the MFMAs of item I, two multiplies
+            // per MFMA (see pipe_query for why the two kinds alternate); 1.3 % at [1,16,8192,128]
+            const _Float16 *wrow = &wt[wb][QW * wave * WT_PITCH + 32 * hf + 8 * g];
+            const half8 wq = *reinterpret_cast<const half8 *>(wrow);
+            half8 af = fr.f[lo] * wq;
+#pragma unroll
+            for (int I = lo; I < hi; ++I) {
+                const half8 afn = fr.f[I + 1 < NB ? I + 1 : I] * wq;
+#pragma unroll
+                for (int J = I; J < NB; ++J) acc[0][S::tix(I, J)] = mfma_f16(af, fr.f[J], acc[0][S::tix(I, J)]);
+                af = afn;
+            }
+#define SGB_MV() __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x002, 2, 0)
+#define SGB_MV6() SGB_MV(); SGB_MV(); SGB_MV(); SGB_MV(); SGB_MV(); SGB_MV()
+            if (lo == 0 && hi == NB) {
+                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                SGB_MV6(); SGB_MV6(); SGB_MV6(); SGB_MV6(); SGB_MV6(); SGB_MV6();
+            }
+#undef SGB_MV6
+#undef SGB_MV
+        } else if (!PRECISE) {
             // the query's 8 weights of this lane's key chunk: one address per lane group (an LDS broadcast read)
             const _Float16 *wrow = &wt[wb][QW * wave * WT_PITCH + 32 * hf + 8 * g];
             half8 wq = *reinterpret_cast<const half8 *>(wrow + (lo / NB) * WT_PITCH);
