@@ -8,9 +8,10 @@
 // 16 broadcast tiles for mu~ and sum w v: 464 accumulator registers, more than one wave owns.  The four waves of
 // a workgroup therefore walk ONE key stream together and split the tiles: wave (a, b) owns the rows 64a..64a+63
 // of Sigma~ and G~ restricted to the columns 64b..64b+63 (the lower-left quarter of Sigma~ is not needed), and
-// the two broadcast moments are dealt out so that the waves carry 30 / 32 / 24 / 30 tiles.  Every wave computes
-// the 32 logits of a step itself (8 MFMAs) so that weights, running maximum and rescaling decisions are
-// bit-identical in the four waves without any exchange.  A step's K and V tiles (16 KB) are brought into LDS
+// the two broadcast moments are dealt out so that the waves carry 34 / 36 / 16 / 30 tiles.  The wave with
+// the 16 tiles also forms the 32 logits of the NEXT step (8 MFMAs), the running maximum and the weights, and hands them
+// to the other three through a 264-byte record in LDS that the step's barrier publishes: every wave forming them
+// for itself (bit-identical, no exchange) cost each of them as many vector instructions again as its moments do.  A step's K and V tiles (16 KB) are brought into LDS
 // by all four waves (a quarter each, which the same wave then converts from bf16 to f16 in place) and four
 // stages rotate with one workgroup barrier per step.
 #include "llla_mfma_common.hpp"
@@ -33,6 +34,10 @@ constexpr int PART_F = HDR + NTILES * 256;     // floats per partial record
 constexpr int MIN_L = 256;                     // shorter caches go to the vector path
 constexpr int MAX_SPLIT = 32;
 constexpr int PRECISE_L = 4 * D;               // sequences up to this length take the two-term weights
+// Exchange record of one step's weights (floats): [0, 32) the fp32 weights, [32, 48) the same rounded to f16, [48, 64)
+// their f16 tails, [64] the factor by which the moments so far are rescaled before the step is added, [65] the running
+// maximum the weights refer to.  Lane group g owns weights 8 g .. 8 g + 7 (keys 4 g .. 4 g + 3 and 16 + 4 g .. 16 + 4 g + 3).
+constexpr int XREC_F = 128;
 
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) short4v *lds_short4_ptr;
@@ -95,13 +100,15 @@ struct PartialArgs {
 
 // The share of wave (WA, WB): rows 4 WA .. 4 WA + 3 (feature blocks), columns 4 WB .. 4 WB + 3.
 template <int WA, int WB, bool PRECISE>
-__device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage, int wave, int lane)
+__device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage, float *xrec, int wave, int lane)
 {
     constexpr bool SIG_DIAG = (WA == WB);                 // 10 tiles of a diagonal quarter of Sigma~
     constexpr bool SIG_FULL = (WA == 0 && WB == 1);       // the 16 tiles of the upper-right quarter
     constexpr int NS = SIG_DIAG ? 10 : (SIG_FULL ? 16 : 1);
-    constexpr bool HAS_MU = (WB == 0);                    // mu~ blocks 4 WA .. 4 WA + 3
-    constexpr bool HAS_YV = (WA == 1);                    // (sum w v) blocks 4 WB .. 4 WB + 3
+    // the broadcast moments stay away from the wave (1, 0), which also forms the weights of the next step (of the
+    // assignments that allows, this one measured fastest)
+    constexpr bool HAS_MU = (WA == WB);                   // mu~ blocks 4 WA .. 4 WA + 3
+    constexpr bool HAS_YV = (WA == 0);                    // (sum w v) blocks 4 WB .. 4 WB + 3
 
     const int g = lane / 16, nn = lane % 16;
     const int bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
@@ -232,14 +239,52 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
         mx = fmaxf(mx, rows_2_3_from_row_1(mx));
         return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mx), 63));
     };
-    // running maximum over the workgroup's keys (the accumulators are rescaled only when it moves), then the weights
-    // of the step: wq (f16), and for short sequences the fp32 weights and their f16 tail as well
+    // The wave that forms the weights (PRODUCER) keeps the running maximum over the workgroup's keys; a step's record
+    // says by what factor the moments so far shrink before the step is added (1 unless the maximum moved) and carries
+    // the weights relative to the new maximum: wq (f16), and for short sequences the fp32 weights and their f16 tails.
+    constexpr bool PRODUCER = (WA == 1 && WB == 0);
     float wf[8];
     half8 wq, wl;
-    auto weights = [&](float mx, const float (&tl)[8]) {
+    auto produce = [&](float mx, const float (&tl)[8], int slot) {
+        float alpha = 1.f;
         if (mx > m) {      // both are wave-uniform
-            const float alpha = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - mx);
+            alpha = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - mx);
             m = mx;
+        }
+        const float mref = (m == -INFINITY) ? 0.f : m;                // an idle workgroup has no maximum yet
+        float pf[8];
+        half8 pq, pl;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            pf[t] = __builtin_amdgcn_exp2f(tl[t] - mref);             // exp2(-inf) = 0 masks the tail
+            pq[t] = (_Float16)pf[t];
+            pl[t] = (_Float16)(pf[t] - (float)pq[t]);
+        }
+        float *rec = xrec + slot * XREC_F;
+        if (nn == 0) {                                                // the 16 lanes of a group hold the same 8 weights
+            if constexpr (precise) {
+                *reinterpret_cast<f32x4 *>(rec + 8 * g) = f32x4{pf[0], pf[1], pf[2], pf[3]};
+                *reinterpret_cast<f32x4 *>(rec + 8 * g + 4) = f32x4{pf[4], pf[5], pf[6], pf[7]};
+                *reinterpret_cast<half8 *>(rec + 48 + 4 * g) = pl;
+            }
+            *reinterpret_cast<half8 *>(rec + 32 + 4 * g) = pq;
+            if (g == 0) { rec[64] = alpha; rec[65] = m; }
+        }
+    };
+    // every wave, after the barrier that follows the record's writing: shrink the moments if the maximum moved, take the
+    // weights; omega sums them exactly as the matrix cores see them (only the wave that writes it keeps it)
+    auto take = [&](int slot) {
+        const float *rec = xrec + slot * XREC_F;
+        const float alpha = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, rec[64])));
+        if constexpr (!PRODUCER) m = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, rec[65])));
+        wq = *reinterpret_cast<const half8 *>(rec + 32 + 4 * g);
+        if constexpr (precise) {
+            const f32x4 f0 = *reinterpret_cast<const f32x4 *>(rec + 8 * g), f1 = *reinterpret_cast<const f32x4 *>(rec + 8 * g + 4);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) { wf[t] = f0[t]; wf[4 + t] = f1[t]; }
+            wl = *reinterpret_cast<const half8 *>(rec + 48 + 4 * g);
+        }
+        if (alpha != 1.f) {      // wave-uniform
             om *= alpha;
 #pragma unroll
             for (int t = 0; t < NS; ++t) sig[t] *= alpha;
@@ -247,17 +292,6 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
             for (int t = 0; t < 16; ++t) gt[t] *= alpha;
 #pragma unroll
             for (int t = 0; t < 4; ++t) { muacc[t] *= alpha; yvacc[t] *= alpha; }
-        }
-        const float mref = (m == -INFINITY) ? 0.f : m;                // an idle workgroup has no maximum yet
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            wf[t] = __builtin_amdgcn_exp2f(tl[t] - mref);             // exp2(-inf) = 0 masks the tail
-            wq[t] = (_Float16)wf[t];
-        }
-        // omega sums the weights exactly as the matrix cores see them; only the wave that writes it keeps it
-        if constexpr (precise) {
-#pragma unroll
-            for (int t = 0; t < 8; ++t) wl[t] = (_Float16)(wf[t] - (float)wq[t]);
         }
         if constexpr (WA == 0 && WB == 0) {
 #pragma unroll
@@ -278,10 +312,10 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
     dma_wait_pending<DMA_PER_WAVE *(NSTAGE - 2)>();
     convert_own(lds0);
     __syncthreads();
-    {
+    if constexpr (PRODUCER) {
         float tl[8];
         const float mx = logits(lds0, 0, tl);
-        weights(mx, tl);
+        produce(mx, tl, 0);                    // published by the barrier of the first iteration
     }
     unsigned read_off = 0;
     for (int s = 0; s < nsteps; ++s) {
@@ -294,6 +328,7 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
         convert_own(kn);
         __syncthreads();
         issue_dma(s + NSTAGE - 1);
+        take(s & 1);
         const unsigned vt = kt + TILE_H * 2;
         read_off = next_off;
 
@@ -328,7 +363,8 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
             }
         };
         float tln[8];
-        const float mxn = logits(kn, s + 1, tln);
+        float mxn = -INFINITY;
+        if constexpr (PRODUCER) mxn = logits(kn, s + 1, tln);
         if constexpr (!precise) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) row_mfmas(i, kA[i] * wq);
@@ -350,7 +386,7 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
             bcast_mfmas(wq);
             bcast_mfmas(wl);
         }
-        weights(mxn, tln);
+        if constexpr (PRODUCER) produce(mxn, tln, (s + 1) & 1);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // drain the clamped tail transfers before the wave ends
 
@@ -382,23 +418,24 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void decode128_partial_kernel(PartialArgs a)
 {
     __shared__ __align__(16) bf16_t stage[NSTAGE * STAGE_H];       // 4 stages x 16 KB
+    __shared__ __align__(16) float xrec[2][XREC_F];                // the weights of a step, from the wave that forms them to all four
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64), lane = threadIdx.x % 64;
     // Scalar branches: each wave runs the loop of its own share; all of them meet at the same barriers.  The shares
-    // differ in work (24 to 32 tiles), and wave w of every workgroup runs on SIMD w of its compute unit; the shares
+    // differ in work (16 tiles plus the weights, 30 to 36 tiles), and wave w of every workgroup runs on SIMD w of its compute unit; the shares
     // therefore rotate with the workgroup index, so that no SIMD gets the heaviest share from both of its workgroups.
     const int b = (int)blockIdx.y / a.H;
     const int L = a.seqlens ? min(max(a.seqlens[b], 1), a.L_max) : a.L_max;
     const int role = (wave + (int)blockIdx.x + (int)blockIdx.y) & 3;
     if (__builtin_amdgcn_readfirstlane(L <= PRECISE_L ? 1 : 0)) {
-        if (role == 0) partial_body<0, 0, true>(a, stage, wave, lane);
-        else if (role == 1) partial_body<0, 1, true>(a, stage, wave, lane);
-        else if (role == 2) partial_body<1, 0, true>(a, stage, wave, lane);
-        else partial_body<1, 1, true>(a, stage, wave, lane);
+        if (role == 0) partial_body<0, 0, true>(a, stage, &xrec[0][0], wave, lane);
+        else if (role == 1) partial_body<0, 1, true>(a, stage, &xrec[0][0], wave, lane);
+        else if (role == 2) partial_body<1, 0, true>(a, stage, &xrec[0][0], wave, lane);
+        else partial_body<1, 1, true>(a, stage, &xrec[0][0], wave, lane);
     } else {
-        if (role == 0) partial_body<0, 0, false>(a, stage, wave, lane);
-        else if (role == 1) partial_body<0, 1, false>(a, stage, wave, lane);
-        else if (role == 2) partial_body<1, 0, false>(a, stage, wave, lane);
-        else partial_body<1, 1, false>(a, stage, wave, lane);
+        if (role == 0) partial_body<0, 0, false>(a, stage, &xrec[0][0], wave, lane);
+        else if (role == 1) partial_body<0, 1, false>(a, stage, &xrec[0][0], wave, lane);
+        else if (role == 2) partial_body<1, 0, false>(a, stage, &xrec[0][0], wave, lane);
+        else partial_body<1, 1, false>(a, stage, &xrec[0][0], wave, lane);
     }
 }
 
