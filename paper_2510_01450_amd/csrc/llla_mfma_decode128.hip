@@ -11,9 +11,10 @@
 // the two broadcast moments are dealt out so that the waves carry 34 / 36 / 16 / 30 tiles.  The wave with
 // the 16 tiles also forms the 32 logits of the NEXT step (8 MFMAs), the running maximum and the weights, and hands them
 // to the other three through a 264-byte record in LDS that the step's barrier publishes: every wave forming them
-// for itself (bit-identical, no exchange) cost each of them as many vector instructions again as its moments do.  A step's K and V tiles (16 KB) are brought into LDS
-// by all four waves (a quarter each, which the same wave then converts from bf16 to f16 in place) and four
-// stages rotate with one workgroup barrier per step.
+// for itself (bit-identical, no exchange) cost each of them as many vector instructions again as its moments do.
+// A step's K and V tiles (16 KB) come into LDS in 16 transfers, five by each of the three other waves and one by the
+// weight wave; a wave converts what it brought from bf16 to f16 in place; four stages rotate with one workgroup
+// barrier per step.
 #include "llla_mfma_common.hpp"
 
 namespace llla {
@@ -27,7 +28,6 @@ constexpr int STEP = 32;                       // keys per MFMA step
 constexpr int NSTAGE = 4;                      // LDS stages per workgroup: two being read, two being filled
 constexpr int TILE_H = STEP * D;               // halves of one natural [32 keys][128] tile (8 KB)
 constexpr int STAGE_H = 2 * TILE_H;            // K tile + V tile
-constexpr int DMA_PER_WAVE = 4;                // transfers one wave issues per stage (2 for K, 2 for V)
 constexpr int NSIG = 36, NTILES = 100;         // Sigma~ upper triangle, then G~ row-major [I][J]
 constexpr int HDR = 3 * D;                     // [m, omega, ..pad], mu~ at [D, 2D), sum w v at [2D, 3D)
 constexpr int PART_F = HDR + NTILES * 256;     // floats per partial record
@@ -136,16 +136,21 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
         qf[c] = __builtin_bit_cast(half8, make_uint4(bf16x2_to_f16x2(u.x), bf16x2_to_f16x2(u.y), bf16x2_to_f16x2(u.z), bf16x2_to_f16x2(u.w)));
     }
 
-    // this wave's part of a stage: LDS chunk slots [128 wave, 128 wave + 128) of the K tile and of the V tile
-    int dma_key[2], dma_col[2];
-    unsigned koff[2], voff[2];
+    // This wave's part of a stage.  A stage is 16 transfers of 1 KB (8 for the K tile, then 8 for the V tile; transfer T
+    // fills LDS chunk slots [64 (T % 8), 64 (T % 8) + 64) of its tile).  The wave that forms the weights brings one of
+    // them, each of the other three brings five: bringing a transfer also means converting it, and the weight wave has
+    // the most vector work already.
+    constexpr bool PRODUCER = (WA == 1 && WB == 0);
+    constexpr int NTR = PRODUCER ? 1 : 5;          // (0 / 5 / 5 / 6 and 0 / 6 / 4 / 6 measured the same)
+    constexpr int TR0 = PRODUCER ? 0 : (WA == 0 ? (WB == 0 ? 1 : 6) : 11);
+    int dma_key[NTR], dma_col[NTR];
+    unsigned dma_off[NTR];
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        const int sl = 128 * wave + 64 * t + lane;
+    for (int t = 0; t < NTR; ++t) {
+        const int T = TR0 + t, sl = 64 * (T % 8) + lane;
         dma_key[t] = sl >> 4;
         dma_col[t] = ((sl & 15) ^ swz(dma_key[t])) * 8;
-        koff[t] = 2u * (unsigned)(dma_key[t] * (int)a.sk.seq + dma_col[t]);
-        voff[t] = 2u * (unsigned)(dma_key[t] * (int)a.sv.seq + dma_col[t]);
+        dma_off[t] = 2u * (unsigned)(dma_key[t] * (int)(T < 8 ? a.sk.seq : a.sv.seq) + dma_col[t]);
     }
     // logits operand (natural rows): key 16 sub + nn, chunks 4 c + g
     // (LDS byte addresses relative to the start of a stage: a step adds the stage's scalar base once per address,
@@ -181,21 +186,21 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
     const int rot = nsteps > 0 ? (int)((part * 7u + bh * 13u) % (unsigned)nsteps) : 0;
     auto step_pos = [&](int step) { const int t = step + rot; return t >= nsteps ? t - nsteps : t; };
     auto issue_dma = [&](int step) {
-        bf16_t *dst = stage + (step % NSTAGE) * STAGE_H + 1024 * wave;
+        bf16_t *dst = stage + (step % NSTAGE) * STAGE_H;
         const int j0 = r0 + step_pos(step < nsteps ? step : 0) * STEP;
         if (j0 + STEP <= L) {
             const bf16_t *kb = Kh + (int64_t)j0 * a.sk.seq, *vb = Vh + (int64_t)j0 * a.sv.seq;
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                dma16_base_nt(kb, koff[t], dst + 512 * t);
-                dma16_base_nt(vb, voff[t], dst + TILE_H + 512 * t);
+            for (int t = 0; t < NTR; ++t) {
+                const int T = TR0 + t;
+                dma16_base_nt(T < 8 ? kb : vb, dma_off[t], dst + (T / 8) * TILE_H + 512 * (T % 8));
             }
         } else {      // a step that reaches past the sequence (or an idle workgroup): rows clamped to the last valid one
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
+            for (int t = 0; t < NTR; ++t) {
+                const int T = TR0 + t;
                 const int j = max(min(j0 + dma_key[t], L - 1), 0);
-                dma16_nt(Kh + (int64_t)j * a.sk.seq + dma_col[t], dst + 512 * t);
-                dma16_nt(Vh + (int64_t)j * a.sv.seq + dma_col[t], dst + TILE_H + 512 * t);
+                dma16_nt((T < 8 ? Kh + (int64_t)j * a.sk.seq : Vh + (int64_t)j * a.sv.seq) + dma_col[t], dst + (T / 8) * TILE_H + 512 * (T % 8));
             }
         }
     };
@@ -203,10 +208,11 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
     // bf16 -> f16 in place for the part of a stage that this wave's own transfers brought in (so only the wave's own
     // wait is needed before it): every element is converted once per workgroup, not once per wave that uses it
     auto convert_own = [&](unsigned st) {
-        const unsigned base = st + 2048u * (unsigned)wave + 16u * (unsigned)lane;
+        const unsigned base = st + 16u * (unsigned)lane;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const lds_uint4_ptr ptr = (lds_uint4_ptr)(uintptr_t)(base + 1024u * (t & 1) + (t >> 1) * (TILE_H * 2));
+        for (int t = 0; t < NTR; ++t) {
+            const int T = TR0 + t;
+            const lds_uint4_ptr ptr = (lds_uint4_ptr)(uintptr_t)(base + 1024u * (T % 8) + (T / 8) * (TILE_H * 2));
             const uint4v u = *ptr;
             *ptr = uint4v{bf16x2_to_f16x2(u.x), bf16x2_to_f16x2(u.y), bf16x2_to_f16x2(u.z), bf16x2_to_f16x2(u.w)};
         }
@@ -242,7 +248,6 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
     // The wave that forms the weights (PRODUCER) keeps the running maximum over the workgroup's keys; a step's record
     // says by what factor the moments so far shrink before the step is added (1 unless the maximum moved) and carries
     // the weights relative to the new maximum: wq (f16), and for short sequences the fp32 weights and their f16 tails.
-    constexpr bool PRODUCER = (WA == 1 && WB == 0);
     float wf[8];
     half8 wq, wl;
     auto produce = [&](float mx, const float (&tl)[8], int slot) {
@@ -305,11 +310,11 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
     // An iteration therefore reads stages s and s + 1: it first waits for this wave's transfers of step s + 1 and
     // converts what they brought, then meets the other waves (now the whole stage s + 1 is there as f16, and
     // everybody has finished reading stage s - 1), and only then refills that oldest stage with step s + NSTAGE - 1.  Every iteration issues exactly
-    // one stage (clamped past the end), so "at most DMA_PER_WAVE (NSTAGE - 3) transfers pending" always means
+    // one stage (clamped past the end), so "at most NTR (NSTAGE - 3) of its own transfers pending" always means
     // "step s + 1 has landed".
 #pragma unroll
     for (int st = 0; st < NSTAGE - 1; ++st) issue_dma(st);
-    dma_wait_pending<DMA_PER_WAVE *(NSTAGE - 2)>();
+    dma_wait_pending<NTR *(NSTAGE - 2)>();
     convert_own(lds0);
     __syncthreads();
     if constexpr (PRODUCER) {
@@ -324,7 +329,7 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
         const unsigned next_off = (read_off == (NSTAGE - 1) * STAGE_H * 2) ? 0u : read_off + STAGE_H * 2;
         unsigned kt = lds0 + read_off, kn = lds0 + next_off;
         asm volatile("" : "+s"(kt), "+s"(kn));
-        dma_wait_pending<DMA_PER_WAVE *(NSTAGE - 3)>();
+        dma_wait_pending<NTR *(NSTAGE - 3)>();
         convert_own(kn);
         __syncthreads();
         issue_dma(s + NSTAGE - 1);
