@@ -342,6 +342,17 @@ __device__ inline void dma16_base_nt(const void *sbase, unsigned voff, void *lds
     const unsigned lds = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void_ptr)lds_base);
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt" ::"v"(voff), "s"(sbase), "s"(lds) : "memory", "m0");
 }
+// (and with the LDS destination as a byte offset, see dma16_base_off)
+__device__ inline void dma16_nt_off(const void *gsrc, unsigned lds_byte_off)
+{
+    const unsigned lds = __builtin_amdgcn_readfirstlane(lds_byte_off);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt" ::"v"(gsrc), "s"(lds) : "memory", "m0");
+}
+__device__ inline void dma16_base_nt_off(const void *sbase, unsigned voff, unsigned lds_byte_off)
+{
+    const unsigned lds = __builtin_amdgcn_readfirstlane(lds_byte_off);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt" ::"v"(voff), "s"(sbase), "s"(lds) : "memory", "m0");
+}
 #pragma clang diagnostic pop
 __device__ inline void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 

@@ -157,21 +157,22 @@ __device__ __forceinline__ void decode_partial_body(bf16_t (&stage)[4][NSTAGE][S
         voff[t] = 2u * (unsigned)(dma_key[t] * (int)sv.seq + dma_col[t]);
     }
     auto issue_dma = [&](int step) {
-        bf16_t *dst = mystage + (step % NSTAGE) * STAGE_H;
+        // (LDS destinations as byte offsets: a generic pointer costs four scalar instructions per transfer to turn back)
+        const unsigned dst = lds_offset(mystage) + 2u * (unsigned)((step % NSTAGE) * STAGE_H);
         const int j0 = r0 + step_pos(step < nsteps ? step : 0) * STEP;
         if (j0 + STEP <= L) {
             const bf16_t *kb = Kh + (int64_t)j0 * sk.seq, *vb = Vh + (int64_t)j0 * sv.seq;
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                dma16_base_nt(kb, koff[t], dst + 512 * t);
-                dma16_base_nt(vb, voff[t], dst + TILE_H + 512 * t);
+                dma16_base_nt_off(kb, koff[t], dst + 2u * (512 * t));
+                dma16_base_nt_off(vb, voff[t], dst + 2u * (TILE_H + 512 * t));
             }
         } else {
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const int j = min(j0 + dma_key[t], L - 1);
-                dma16_nt(Kh + (int64_t)j * sk.seq + dma_col[t], dst + 512 * t);
-                dma16_nt(Vh + (int64_t)j * sv.seq + dma_col[t], dst + TILE_H + 512 * t);
+                dma16_nt_off(Kh + (int64_t)j * sk.seq + dma_col[t], dst + 2u * (512 * t));
+                dma16_nt_off(Vh + (int64_t)j * sv.seq + dma_col[t], dst + 2u * (TILE_H + 512 * t));
             }
         }
     };

@@ -186,21 +186,22 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
     const int rot = nsteps > 0 ? (int)((part * 7u + bh * 13u) % (unsigned)nsteps) : 0;
     auto step_pos = [&](int step) { const int t = step + rot; return t >= nsteps ? t - nsteps : t; };
     auto issue_dma = [&](int step) {
-        bf16_t *dst = stage + (step % NSTAGE) * STAGE_H;
+        const unsigned dst = lds0 + 2u * (unsigned)((step % NSTAGE) * STAGE_H);      // LDS byte address of the stage
         const int j0 = r0 + step_pos(step < nsteps ? step : 0) * STEP;
         if (j0 + STEP <= L) {
             const bf16_t *kb = Kh + (int64_t)j0 * a.sk.seq, *vb = Vh + (int64_t)j0 * a.sv.seq;
 #pragma unroll
             for (int t = 0; t < NTR; ++t) {
                 const int T = TR0 + t;
-                dma16_base_nt(T < 8 ? kb : vb, dma_off[t], dst + (T / 8) * TILE_H + 512 * (T % 8));
+                dma16_base_nt_off(T < 8 ? kb : vb, dma_off[t], dst + 2u * ((T / 8) * TILE_H + 512 * (T % 8)));
             }
         } else {      // a step that reaches past the sequence (or an idle workgroup): rows clamped to the last valid one
 #pragma unroll
             for (int t = 0; t < NTR; ++t) {
                 const int T = TR0 + t;
                 const int j = max(min(j0 + dma_key[t], L - 1), 0);
-                dma16_nt((T < 8 ? Kh + (int64_t)j * a.sk.seq : Vh + (int64_t)j * a.sv.seq) + dma_col[t], dst + (T / 8) * TILE_H + 512 * (T % 8));
+                dma16_nt_off((T < 8 ? Kh + (int64_t)j * a.sk.seq : Vh + (int64_t)j * a.sv.seq) + dma_col[t],
+                             dst + 2u * ((T / 8) * TILE_H + 512 * (T % 8)));
             }
         }
     };
