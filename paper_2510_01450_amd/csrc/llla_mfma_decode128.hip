@@ -210,12 +210,19 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
     // wait is needed before it): every element is converted once per workgroup, not once per wave that uses it
     auto convert_own = [&](unsigned st) {
         const unsigned base = st + 16u * (unsigned)lane;
+        // all reads first, then all writes: read and written addresses are the same ones, but the compiler cannot know
+        // that the transfers do not overlap each other and would wait for every read before the write in front of the next
+        uint4v u[NTR];
 #pragma unroll
         for (int t = 0; t < NTR; ++t) {
             const int T = TR0 + t;
-            const lds_uint4_ptr ptr = (lds_uint4_ptr)(uintptr_t)(base + 1024u * (T % 8) + (T / 8) * (TILE_H * 2));
-            const uint4v u = *ptr;
-            *ptr = uint4v{bf16x2_to_f16x2(u.x), bf16x2_to_f16x2(u.y), bf16x2_to_f16x2(u.z), bf16x2_to_f16x2(u.w)};
+            u[t] = *(lds_uint4_ptr)(uintptr_t)(base + 1024u * (T % 8) + (T / 8) * (TILE_H * 2));
+        }
+#pragma unroll
+        for (int t = 0; t < NTR; ++t) {
+            const int T = TR0 + t;
+            *(lds_uint4_ptr)(uintptr_t)(base + 1024u * (T % 8) + (T / 8) * (TILE_H * 2)) =
+                uint4v{bf16x2_to_f16x2(u[t].x), bf16x2_to_f16x2(u[t].y), bf16x2_to_f16x2(u[t].z), bf16x2_to_f16x2(u[t].w)};
         }
     };
     // logits of the 32 keys of a step whose K tile lies at LDS byte address kt: lane (g, *) gets keys 4g..4g+3
