@@ -16,6 +16,7 @@
 // weight wave; a wave converts what it brought from bf16 to f16 in place; four stages rotate with one workgroup
 // barrier per step.
 #include "llla_mfma_common.hpp"
+#include <type_traits>
 
 namespace llla {
 namespace {
@@ -330,20 +331,26 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
         const float mx = logits(lds0, 0, tl);
         produce(mx, tl, 0);                    // published by the barrier of the first iteration
     }
-    unsigned read_off = 0;
-    for (int s = 0; s < nsteps; ++s) {
-        // LDS byte addresses of the two stages, kept as scalars that the optimiser cannot take apart (it would
-        // otherwise carry one induction register per read and spend two vector-ALU operations on each)
-        const unsigned next_off = (read_off == (NSTAGE - 1) * STAGE_H * 2) ? 0u : read_off + STAGE_H * 2;
-        unsigned kt = lds0 + read_off, kn = lds0 + next_off;
-        asm volatile("" : "+s"(kt), "+s"(kn));
+    // The loop is unrolled over the NSTAGE stages (for the long sequences; the short ones keep the stage a run-time
+    // scalar): with the stage a compile-time constant, its LDS offset becomes part of the immediate offset of every
+    // read, and the per-lane addresses need no vector addition per read and step.
+    auto iteration = [&](int s, auto stage_tag) {
+        constexpr int STG = decltype(stage_tag)::value;                      // >= 0: the stage of step s, known here
+        unsigned kt, kn;
+        if constexpr (STG >= 0) {
+            kt = lds_offset(stage) + STG * (STAGE_H * 2);
+            kn = lds_offset(stage) + ((STG + 1) % NSTAGE) * (STAGE_H * 2);
+        } else {
+            kt = lds0 + (unsigned)(s % NSTAGE) * (STAGE_H * 2);
+            kn = lds0 + (unsigned)((s + 1) % NSTAGE) * (STAGE_H * 2);
+            asm volatile("" : "+s"(kt), "+s"(kn));      // scalars that the optimiser cannot take apart into per-read induction registers
+        }
         dma_wait_pending<NTR *(NSTAGE - 3)>();
         convert_own(kn);
         __syncthreads();
         issue_dma(s + NSTAGE - 1);
         take(s & 1);
         const unsigned vt = kt + TILE_H * 2;
-        read_off = next_off;
 
         half8 kA[4], vB[4], kB[SIG_FULL ? 4 : 1];
 #pragma unroll
@@ -400,6 +407,17 @@ __device__ __forceinline__ void partial_body(const PartialArgs &a, bf16_t *stage
             bcast_mfmas(wl);
         }
         if constexpr (PRODUCER) produce(mxn, tln, (s + 1) & 1);
+    };
+    if constexpr (!precise) {
+        static_assert(NSTAGE == 4, "the unrolled loop below names the stages");
+        for (int s = 0; s < nsteps; s += NSTAGE) {
+            iteration(s, std::integral_constant<int, 0>{});
+            if (s + 1 < nsteps) iteration(s + 1, std::integral_constant<int, 1>{});
+            if (s + 2 < nsteps) iteration(s + 2, std::integral_constant<int, 2>{});
+            if (s + 3 < nsteps) iteration(s + 3, std::integral_constant<int, 3>{});
+        }
+    } else {
+        for (int s = 0; s < nsteps; ++s) iteration(s, std::integral_constant<int, -1>{});
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // drain the clamped tail transfers before the wave ends
 
