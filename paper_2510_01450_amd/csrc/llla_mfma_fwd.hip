@@ -310,7 +310,8 @@ struct MomentsShared {
     _Float16 kt[2][2][DD * KB];                // transposed K, two buffers x two 32-key sub-tiles
     bf16_t kn[2][KB2 * DD];                    // natural K, two buffers
     union {
-        _Float16 h[3][16 * WT_PITCH];          // f16 weights (fast variant), 16 query rows (MFMA width), 3 blocks in flight
+        _Float16 h[4][16 * WT_PITCH];          // f16 weights (fast variant), 16 query rows (MFMA width); 3 blocks are in
+                                               // flight, the d = 64 loop rotates over 4 buffers (a power of two, see there)
         float f[3][16 * WT32_PITCH];           // fp32 weights (precise variant)
     } w;
     float omp[4][16];
@@ -697,8 +698,15 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
         load_frags(fa, 0, 0);
         pipe_wq = wq_read(0, 0, 0);
         pipe_af = fa.f[0] * pipe_wq;
-        for (int c = 0; c < nblk; ++c) {
-            const int buf = c & 1, wbn = (wb == 2) ? 0 : wb + 1;
+        // Unrolled four times with the tile buffer (c % 2) and the weight buffer (c % 4; four of them instead of the
+        // three that are needed, so that the two periods divide the unroll factor) as compile-time constants: every LDS
+        // address of the loop is then a per-lane register plus an immediate, and the dozen vector additions per block
+        // that added the buffers' offsets are gone.
+        // (The backward's variant of this kernel, which carries a second right-hand side through the solve and has fewer
+        // registers to spare, keeps the buffers as run-time values: unrolled it spills heavily inside the loop.)
+        auto pipe_block = [&](int c, auto ktag) {
+            constexpr int KK = decltype(ktag)::value;
+            const int buf = KK >= 0 ? (KK & 1) : (c & 1), wb = KK >= 0 ? (KK & 3) : (c & 3), wbn = (wb + 1) & 3;
             // ---- first half ---------------------------------------------------------------------------
             load_frags(fb, buf, 1);
             __builtin_amdgcn_sched_barrier(0);
@@ -728,7 +736,16 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
             mu_mfma();
             __builtin_amdgcn_sched_barrier(0);
             pipe_query(fb, 3, fa, wbn, 0, 0);   // after the last block: the all-zero round of weights, operand unused
-            wb = wbn;
+        };
+        if constexpr (!WITH_U) {
+            for (int c = 0; c < nblk; c += 4) {
+                pipe_block(c, std::integral_constant<int, 0>{});
+                if (c + 1 < nblk) pipe_block(c + 1, std::integral_constant<int, 1>{});
+                if (c + 2 < nblk) pipe_block(c + 2, std::integral_constant<int, 2>{});
+                if (c + 3 < nblk) pipe_block(c + 3, std::integral_constant<int, 3>{});
+            }
+        } else {
+            for (int c = 0; c < nblk; ++c) pipe_block(c, std::integral_constant<int, -1>{});
         }
     } else if (PREFETCH) {
         load_frags(fa, 0, 0);
