@@ -170,23 +170,39 @@ __global__ __launch_bounds__(256, 2) void sweep_kernel(const bf16_t *__restrict_
 
     const int ilast = min(i0 + 63, n - 1);
     const int nblk = causal ? ilast / KB + 1 : (n + KB - 1) / KB;
-    for (int c = 0; c < nblk; ++c) {
-        __syncthreads();
-        // stage K (natural) and V^T tiles
-        for (int idx = tid; idx < KB * (DD / 8); idx += 256) {
+    // The K (natural) and V^T tiles of block c + 1 are fetched into registers while block c is computed, and written
+    // to LDS at the top of the next iteration: the global-memory latency is off the path between the two barriers
+    // (the row-maximum sweep has four MFMAs of work per block and was waiting for memory most of the time).
+    constexpr int NLD = DD / 64;         // 16-byte pieces per thread and tile
+    uint4 kpre[NLD], vpre[MAXONLY ? 1 : NLD];
+    auto fetch = [&](int c) {
+#pragma unroll
+        for (int u = 0; u < NLD; ++u) {
+            const int idx = tid + 256 * u;
             const int key = idx / (DD / 8), ch = (idx % (DD / 8)) * 8;
             const int j = c * KB + key;
-            uint4 kv = make_uint4(0, 0, 0, 0);
-            if (j < n) kv = *reinterpret_cast<const uint4 *>(Kh + (int64_t)j * sk.seq + ch);
-            *reinterpret_cast<uint4 *>(&kn[key * KN_PITCH + ch]) = kv;
-        }
-        if (!MAXONLY) {
-            for (int idx = tid; idx < DD * 4; idx += 256) {
+            kpre[u] = make_uint4(0, 0, 0, 0);
+            if (j < n) kpre[u] = *reinterpret_cast<const uint4 *>(Kh + (int64_t)j * sk.seq + ch);
+            if (!MAXONLY) {
                 const int feat = idx / 4, k0 = (idx % 4) * 8;
-                const uint4 vv = *reinterpret_cast<const uint4 *>(VT + ((size_t)bh * nkb + c) * (DD * KB) + feat * KB + k0);
-                *reinterpret_cast<uint4 *>(&vt[feat * VT_PITCH + k0]) = vv;
+                vpre[u] = *reinterpret_cast<const uint4 *>(VT + ((size_t)bh * nkb + c) * (DD * KB) + feat * KB + k0);
             }
         }
+    };
+    fetch(0);
+    for (int c = 0; c < nblk; ++c) {
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < NLD; ++u) {
+            const int idx = tid + 256 * u;
+            const int key = idx / (DD / 8), ch = (idx % (DD / 8)) * 8;
+            *reinterpret_cast<uint4 *>(&kn[key * KN_PITCH + ch]) = kpre[u];
+            if (!MAXONLY) {
+                const int feat = idx / 4, k0 = (idx % 4) * 8;
+                *reinterpret_cast<uint4 *>(&vt[feat * VT_PITCH + k0]) = vpre[u];
+            }
+        }
+        if (c + 1 < nblk) fetch(c + 1);
         __syncthreads();
         f32x4 st[2], ut[2];
 #pragma unroll
@@ -374,7 +390,7 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     const bf16_t *Kh = Kg + b * sk.batch + h * sk.head;
     const bf16_t *Qh = Qg + b * sq.batch + h * sq.head;
     const _Float16 *KTh = KT + (size_t)bh * nkb * KT_SUB;
-    const bool w_wave = wave < 4;                       // computes weights: 16 keys x 16 query columns per block
+    const bool w_wave = (NW == 4) || wave < 4;          // computes weights: 16 keys x 16 query columns per block
     const bool t_wave = (NW == 4) || wave >= 4;         // fetches the transposed tiles
     const int tw = (NW == 4) ? wave : wave - 4;
 
@@ -455,6 +471,7 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
 #pragma unroll
     for (int t = 0; t < NAT_INSTR; ++t) kn_boff[t] = 2u * (unsigned)(kn_key[t] * (int)sk.seq + kn_gcol[t]);
     const bool small_pitch = sk.seq < (int64_t(1) << 23);       // the offsets above fit 32 bits
+    const int n_whole_small = small_pitch ? n / KB2 : 0;        // blocks below this are whole tiles that the scalar-base transfers can fetch
     const unsigned kt_lds = lds_offset(&sm.kt[0][0][0]), kn_lds = lds_offset(&sm.kn[0][0]);
     auto issue_dma = [&](int blk) {     // block blk -> LDS buffer blk & 1
         const int buf = blk & 1;
@@ -468,7 +485,7 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
             }
         }
         if (w_wave) {
-            if (small_pitch && blk * KB2 + KB2 <= n) {
+            if (blk < n_whole_small) {
                 const bf16_t *src = Kh + (int64_t)blk * KB2 * sk.seq;
                 const unsigned dst = kn_lds + 2u * (unsigned)(buf * KB2 * DD + 16 * CH * wave * 8);
 #pragma unroll
@@ -511,15 +528,13 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
         float wf[4];
         // A block that lies wholly before the workgroup's first query needs no causal mask (a scalar condition; most
         // blocks of a long row)
-        if (blk < n_unmasked) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) wf[r] = __builtin_amdgcn_exp2f(z[r] * cscale - mrow);
-        } else {
+        for (int r = 0; r < 4; ++r) wf[r] = __builtin_amdgcn_exp2f(z[r] * cscale - mrow);
+        if (blk >= n_unmasked) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int j = blk * KB2 + 16 * wave + 4 * g + r;
-                const float wgt = __builtin_amdgcn_exp2f(z[r] * cscale - mrow);
-                wf[r] = (q_live && j <= jlim) ? wgt : 0.f;
+                wf[r] = (q_live && j <= jlim) ? wf[r] : 0.f;
             }
         }
         // stored negated: the tiles accumulate -(w k) k^T
