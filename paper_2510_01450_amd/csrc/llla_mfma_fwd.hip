@@ -739,13 +739,19 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
             pipe_query(fa, 3, fb, wb, 1, 0);
             weights_store(c + 1, wbn, z);
             mu_load_b(buf, 1);                  // the last read of block c's tiles: they are overwritten after the barrier
-            __syncthreads();
-            if (c + 2 < nblk) issue_dma(c + 2);
-            // ---- second half --------------------------------------------------------------------------
-            load_frags(fa, buf ^ 1, 0);         // first half of block c+1 (unused after the last block)
+            // ---- second half (its fragments are in registers already) ----------------------------------
             mu_load_a(wb, 1);
             __builtin_amdgcn_sched_barrier(0);
             pipe_query(fb, 0, fb, wb, 1, 1);
+            // The block's barrier comes one query into the second half: the exponentials, the conversion and the LDS
+            // write of the weights, and the skew between the waves, then pass behind ten MFMAs instead of in front of
+            // an idle matrix pipe.  What the barrier orders is unchanged: the weights of block c + 1 are first read by
+            // the last query of this half, the tiles of block c + 1 right below, and the tiles of block c were last
+            // read above.
+            __syncthreads();
+            if (c + 2 < nblk) issue_dma(c + 2);
+            load_frags(fa, buf ^ 1, 0);         // first half of block c+1 (unused after the last block)
+            __builtin_amdgcn_sched_barrier(0);
             pipe_query(fb, 1, fb, wb, 1, 2);
             pipe_query(fb, 2, fb, wb, 1, 3);
             mu_mfma();
