@@ -215,7 +215,7 @@ __global__ __launch_bounds__(256, 2) void sweep_kernel(const bf16_t *__restrict_
             for (int f = 0; f < NF; ++f) z = mfma_bf16(kf[f], qf[f], z);
             st[s] = z;
             if (!MAXONLY) {
-                f32x4 u = {0.f, 0.f, 0.f, 0.f};
+                f32x4 u = {y0, y0, y0, y0};         // y0 + k . y1: the intercept rides in as the accumulator's initial value
 #pragma unroll
                 for (int f = 0; f < NF; ++f) u = mfma_bf16(kf[f], yl[f], u);
 #pragma unroll
@@ -247,7 +247,7 @@ __global__ __launch_bounds__(256, 2) void sweep_kernel(const bf16_t *__restrict_
             for (int s = 0; s < 2; ++s)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    cv[4 * s + r] = __builtin_amdgcn_exp2f(st[s][r] * cscale - mrow) * (y0 + ut[s][r]);
+                    cv[4 * s + r] = __builtin_amdgcn_exp2f(st[s][r] * cscale - mrow) * ut[s][r];
             if (masked) {
 #pragma unroll
                 for (int t = 0; t < 8; ++t) {
