@@ -356,38 +356,16 @@ __device__ inline void dma16_base_nt_off(const void *sbase, unsigned voff, unsig
 #pragma clang diagnostic pop
 __device__ inline void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-// Exact solve of the wave's QW augmented systems, all in registers / wave-private LDS scratch:
-//   in : acc[q][tix(I,J)]  upper-triangular 16x16 tiles of T_q = -(Sigma~_q + lambda I) (MFMA accumulator layout)
-//        build_rhs(rhs)    fills rhs[q][P], a tile column with -mu~_q in column 0 and -q_q in column 1 (other
-//                          columns 0); it is called after the factorisation so that the 16 right-hand-side
-//                          registers per query are not live while the diagonal tiles are factorised
-//        om4[q]            omega_q;  scw: >= QW*16*SC_PITCH floats of LDS owned by this wave
-//        pivot_floor       per lane: half the ridge of the query of the lane's group (see chol_inv16)
-//   out: rhs[q][P] column 0 (lanes nn == 0) = y1_q,  y0v[q] = y0_q (valid in lanes nn == 0)
-// with [omega mu~^T; mu~ Sigma~ + lambda I] [y0; y1] = [1; q].  16-blocked upper Cholesky
-// Sigma~ + lambda I = U^T U whose block products are C += A^T B on fp32 MFMA; diagonal tiles of the QW
-// queries are factorised together in (query, row) lanes with DPP row broadcasts; then forward
-// substitution of both right-hand sides, the Schur step on the intercept, and back substitution.
-// The matrix cores only add products, so everything that the textbook recursion subtracts is carried
-// negated instead: the trailing matrix (T), the inverse diagonal factors (N_P = -U_PP^{-1}), and the
-// partial right-hand sides; no tile is ever negated on the vector ALU.
-// WITH_U (the backward pass): build_rhs also puts -r1_q into column 2 and r0v[q] holds r0_q; a second system
-// [omega mu~^T; mu~ Sigma~ + lambda I] [u0; u1] = [r0; r1] is solved alongside at no extra matrix-core work (it
-// rides in a padding column of the right-hand-side tiles): on return column 1 (lanes nn == 1) = u1_q and
-// u0v[q] = u0_q (valid in lanes nn < 4).
-template <int DD, bool WITH_U = false, class BuildRhs>
-__device__ __forceinline__ void solve_wave(f32x4 (&acc)[Shape<DD>::QW][Shape<DD>::NTILE],
-                                           f32x4 (&rhs)[Shape<DD>::QW][Shape<DD>::NB], float (&y0v)[Shape<DD>::QW],
-                                           const float (&om4)[Shape<DD>::QW], float *scw, int g, int nn,
-                                           float pivot_floor, BuildRhs build_rhs, const float *r0v = nullptr,
-                                           float *u0v = nullptr)
+// The factorisation of solve_wave (see there): on return acc(P,J), P < J, holds U(P,J) and acc(P,P) holds N_P =
+// -U(P,P)^{-1}, with Sigma~ + lambda I = U^T U and the tiles given as T = -(Sigma~ + lambda I).
+template <int DD>
+__device__ __forceinline__ void factorise_wave(f32x4 (&acc)[Shape<DD>::QW][Shape<DD>::NTILE], float *scw, int g, int nn,
+                                               float pivot_floor)
 {
     using S = Shape<DD>;
     constexpr int QW = S::QW, NB = S::NB;
     const int gq = (g < QW) ? g : QW - 1;       // lane groups beyond the wave's queries shadow the last one
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-
-    // ---- factorisation: afterwards acc(P,J), P < J, holds U(P,J) and acc(P,P) holds N_P = -U(P,P)^{-1} -----
 #pragma unroll
     for (int P = 0; P < NB; ++P) {
         // diagonal tiles -> (query, row) lanes, symmetrised
@@ -435,6 +413,40 @@ __device__ __forceinline__ void solve_wave(f32x4 (&acc)[Shape<DD>::QW][Shape<DD>
         }
         wave_sync();
     }
+
+}
+
+// Exact solve of the wave's QW augmented systems, all in registers / wave-private LDS scratch:
+//   in : acc[q][tix(I,J)]  upper-triangular 16x16 tiles of T_q = -(Sigma~_q + lambda I) (MFMA accumulator layout)
+//        build_rhs(rhs)    fills rhs[q][P], a tile column with -mu~_q in column 0 and -q_q in column 1 (other
+//                          columns 0); it is called after the factorisation so that the 16 right-hand-side
+//                          registers per query are not live while the diagonal tiles are factorised
+//        om4[q]            omega_q;  scw: >= QW*16*SC_PITCH floats of LDS owned by this wave
+//        pivot_floor       per lane: half the ridge of the query of the lane's group (see chol_inv16)
+//   out: rhs[q][P] column 0 (lanes nn == 0) = y1_q,  y0v[q] = y0_q (valid in lanes nn == 0)
+// with [omega mu~^T; mu~ Sigma~ + lambda I] [y0; y1] = [1; q].  16-blocked upper Cholesky
+// Sigma~ + lambda I = U^T U whose block products are C += A^T B on fp32 MFMA; diagonal tiles of the QW
+// queries are factorised together in (query, row) lanes with DPP row broadcasts; then forward
+// substitution of both right-hand sides, the Schur step on the intercept, and back substitution.
+// The matrix cores only add products, so everything that the textbook recursion subtracts is carried
+// negated instead: the trailing matrix (T), the inverse diagonal factors (N_P = -U_PP^{-1}), and the
+// partial right-hand sides; no tile is ever negated on the vector ALU.
+// WITH_U (the backward pass): build_rhs also puts -r1_q into column 2 and r0v[q] holds r0_q; a second system
+// [omega mu~^T; mu~ Sigma~ + lambda I] [u0; u1] = [r0; r1] is solved alongside at no extra matrix-core work (it
+// rides in a padding column of the right-hand-side tiles): on return column 1 (lanes nn == 1) = u1_q and
+// u0v[q] = u0_q (valid in lanes nn < 4).
+template <int DD, bool WITH_U = false, class BuildRhs>
+__device__ __forceinline__ void solve_wave(f32x4 (&acc)[Shape<DD>::QW][Shape<DD>::NTILE],
+                                           f32x4 (&rhs)[Shape<DD>::QW][Shape<DD>::NB], float (&y0v)[Shape<DD>::QW],
+                                           const float (&om4)[Shape<DD>::QW], float *scw, int g, int nn,
+                                           float pivot_floor, BuildRhs build_rhs, const float *r0v = nullptr,
+                                           float *u0v = nullptr)
+{
+    using S = Shape<DD>;
+    constexpr int QW = S::QW, NB = S::NB;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+
+    factorise_wave<DD>(acc, scw, g, nn, pivot_floor);
 
     // ---- forward substitution of [mu~ q]:  t_P = -r_P + sum_{I<P} U(I,P)^T r_I,  r_P <- N_P^T t_P -------------
     build_rhs(rhs);

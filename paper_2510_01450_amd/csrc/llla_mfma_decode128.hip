@@ -16,6 +16,7 @@
 // weight wave; a wave converts what it brought from bf16 to f16 in place; four stages rotate with one workgroup
 // barrier per step.
 #include "llla_mfma_common.hpp"
+#include "llla_mfma_solve128.hpp"
 #include <type_traits>
 
 namespace llla {
@@ -520,17 +521,10 @@ __global__ __launch_bounds__(NT, 1) void decode128_merge_kernel(const bf16_t *__
         for (int P = 0; P < NB; ++P)        // solve_wave takes -(Sigma~ + lambda I)
 #pragma unroll
             for (int t = 0; t < 4; ++t) acc[0][S128::tix(P, P)][t] -= (nn == 4 * g + t) ? lambda : 0.f;
-        solve_wave<128>(acc, rhs, y0v, om4, scw, g, nn, 0.5f * lambda, [&](f32x4 (&r)[1][NB]) {
-#pragma unroll
-            for (int P = 0; P < NB; ++P) {
-                const int row0 = 16 * P + 4 * g;
-                const f32x4 mv = *reinterpret_cast<const f32x4 *>(&mus[row0]);
-                const uint2 qb = *reinterpret_cast<const uint2 *>(qg + (size_t)bh * D + row0);
-                const float qv[4] = {__uint_as_float(qb.x << 16), __uint_as_float(qb.x & 0xffff0000u),
-                                     __uint_as_float(qb.y << 16), __uint_as_float(qb.y & 0xffff0000u)};
-#pragma unroll
-                for (int t = 0; t < 4; ++t) r[0][P][t] = (nn == 0) ? -mv[t] : ((nn == 1) ? -qv[t] : 0.f);
-            }
+        solve_wave_v1<128>(acc, rhs, y0v, om4, scw, g, nn, 0.5f * lambda, [&](int P, float &m, float &q, float &e) {
+            m = -mus[16 * P + nn];
+            q = -bf16_to_f32(qg[(size_t)bh * D + 16 * P + nn]);
+            (void)e;
         });
         if (nn == 0) {
 #pragma unroll

@@ -18,6 +18,7 @@
 
 #include "llla_mfma_common.hpp"
 #include "llla_mfma_solve64.hpp"
+#include "llla_mfma_solve128.hpp"
 
 namespace llla {
 namespace {
@@ -902,33 +903,20 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
 #pragma unroll
         for (int q = 0; q < QW; ++q) r0v[q] = Rg[((size_t)bh * n + min(i0 + QW * wave + q, n - 1)) * YP + DD];
     }
-    solve_wave<DD, WITH_U>(acc, rhs, y0v, om4, &sc[wave][0][0], g, nn, pivot_floor, [&](f32x4 (&r)[QW][NB]) {
-#pragma unroll
-        for (int q = 0; q < QW; ++q) {
-            const int qi = QW * wave + q;
-            const bf16_t *qrow = Qh + (int64_t)min(i0 + qi, n - 1) * sq.seq;
-            const float *rrow = WITH_U ? Rg + ((size_t)bh * n + min(i0 + qi, n - 1)) * YP : nullptr;
-#pragma unroll
-            for (int P = 0; P < NB; ++P) {
-                // every lane loads all values and selects: a load under a lane-dependent condition would become a
-                // branch with its own wait per tile register; four consecutive rows per load, so that a tile costs
-                // one load per source instead of four that the compiler waits for one by one
-                const int row0 = 16 * P + 4 * g;
-                const f32x4 mv = *reinterpret_cast<const f32x4 *>(&mus[qi][row0]);
-                const uint2 qb = *reinterpret_cast<const uint2 *>(qrow + row0);
-                const float qv[4] = {__uint_as_float(qb.x << 16), __uint_as_float(qb.x & 0xffff0000u),
-                                     __uint_as_float(qb.y << 16), __uint_as_float(qb.y & 0xffff0000u)};
-                f32x4 rv = {0.f, 0.f, 0.f, 0.f};
-                if constexpr (WITH_U) rv = *reinterpret_cast<const f32x4 *>(rrow + row0);
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    float v = (nn == 0) ? mv[t] : ((nn == 1) ? -qv[t] : 0.f);   // mus holds -mu~
-                    if constexpr (WITH_U) v = (nn == 2) ? -rv[t] : v;
-                    r[q][P][t] = v;
-                }
-            }
-        }
-    }, r0v, u0v);
+    // one query per wave: factorisation on the matrix cores, substitutions on the vector ALU (solve_wave_v1)
+    static_assert(QW == 1, "the general path serves d = 128, one query per wave");
+    {
+        const int row = min(i0 + wave, n - 1);
+        const bf16_t *qrow = Qh + (int64_t)row * sq.seq;
+        const float *rrow = WITH_U ? Rg + ((size_t)bh * n + row) * YP : nullptr;
+        solve_wave_v1<DD, WITH_U>(acc, rhs, y0v, om4, &sc[wave][0][0], g, nn, pivot_floor,
+                                  [&](int P, float &m, float &q, float &e) {
+                                      m = mus[wave][16 * P + nn];                 // mus holds -mu~
+                                      q = -bf16_to_f32(qrow[16 * P + nn]);
+                                      if constexpr (WITH_U) e = -rrow[16 * P + nn];
+                                  },
+                                  r0v, u0v);
+    }
 
 #pragma unroll
     for (int q = 0; q < QW; ++q) {
