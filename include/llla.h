@@ -40,7 +40,7 @@
  *
  * Value range of the matrix-core kernels.  LLLA_PATH_AUTO serves bf16 inputs with d = 64 or 128 on
  * the matrix cores (llla_forward, llla_forward_ex, llla_forward_cg, llla_backward, and llla_decode
- * with a cache capacity of at least 256 rows).  Those kernels hand the keys (and, in decode, queries and
+ * with a cache capacity of at least 256 rows; llla_forward and llla_forward_ex also d = 32, and d = 16 from 1024 rows on).  Those kernels hand the keys (and, in decode, queries and
  * values) to the MFMA units as f16: every |x| must be at most 65504 (larger ones become
  * infinite and the affected rows NaN; no status is returned, the data being device memory), and
  * magnitudes below 6.1e-5 lose bits to the f16 subnormal range.  bf16 values of ordinary size
@@ -101,7 +101,13 @@ llla_status llla_forward(const void *Q, const void *K, const void *V, void *O,
                          int causal, float lambda, float scale,
                          void *workspace, size_t workspace_bytes, void *stream);
 
-/* Same as llla_forward with the kernel family chosen by the caller. */
+/* Same as llla_forward with the kernel family chosen by the caller.  LLLA_PATH_MFMA: bf16 inputs with d = 64 or 128,
+ * fp32 inputs with d = 64, and -- for either dtype -- d = 16 and 32, which run the d = 64 kernels on zero-padded
+ * copies held in the workspace (exact: with features d..63 zero the system of Eq. (query_specific) splits into the
+ * original one and lambda * y = 0); other calls return LLLA_ERR_UNSUPPORTED.  LLLA_PATH_AUTO takes the matrix-core
+ * kernels wherever they exist, except where the vector kernels measured faster: d = 16 / 32 with fp32 inputs, and
+ * bf16 inputs with d = 16 and fewer than 1024 rows.  bf16 inputs on the matrix cores are subject to the f16 value
+ * range stated at the top of this file. */
 llla_status llla_forward_path(const void *Q, const void *K, const void *V, void *O,
                               llla_strides sq, llla_strides sk, llla_strides sv, llla_strides so,
                               int B, int H, int n, int d, llla_dtype in, llla_dtype out,

@@ -9,6 +9,11 @@ namespace {
 using llla::Problem;
 
 constexpr int kMaxGridY = 65535;
+// LLLA_PATH_AUTO and the padded matrix-core forward (d = 16 / 32 run at d = 64).  Measured at 64 heads, vector vs padded:
+// bf16 d = 32: 0.19 vs 0.10 ms at n = 128, 22 vs 2.5 ms at n = 4096 -> always; bf16 d = 16: 0.18 vs 0.22 ms at n = 512,
+// 0.50 vs 0.39 at 1024, 6.1 vs 2.4 at 4096 -> from 1024 rows on; fp32 (fp32 MFMA, a sixteenth of the 16-bit rate, against
+// 16 or 4 times less vector work than at d = 64): the vector kernels are faster at every size -> only when forced.
+bool auto_takes_padded(int n, int d, llla_dtype in) { return in == LLLA_BF16 && (d == 32 || n >= 1024); }
 
 bool dim_supported(int d) { return d == 16 || d == 32 || d == 64 || d == 128; }
 bool dtype_ok(llla_dtype t) { return t == LLLA_F32 || t == LLLA_BF16; }
@@ -57,6 +62,7 @@ extern "C" {
 size_t llla_forward_workspace_bytes(int B, int H, int n, int d, llla_dtype in)
 {
     if (B <= 0 || H <= 0 || n <= 0 || !dim_supported(d) || !dtype_ok(in)) return 0;
+    if (llla::padded_forward_supported(d, in)) return llla::padded_forward_workspace_bytes(B, H, n, d, in);
     if (in == LLLA_F32) return llla::mfma_forward_f32_supported(d, true) ? llla::mfma_forward_f32_workspace_bytes(B, H, n) : 0;
     return llla::mfma_forward_workspace_bytes(B, H, n, d, in);
 }
@@ -84,12 +90,15 @@ llla_status llla_forward_ex(const void *Q, const void *K, const void *V, void *O
 
     // the matrix-core sweeps put their 64-row blocks on grid.y: at most 65535 of them
     const bool f32_mfma = in == LLLA_F32 && llla::mfma_forward_f32_supported(d, causal != 0);
-    const bool has_mfma = (f32_mfma || llla::mfma_forward_supported(d, in, causal != 0)) && (n + 63) / 64 <= kMaxGridY;
+    // d = 16 / 32: the d = 64 kernels on zero-padded copies
+    const bool padded = llla::padded_forward_supported(d, in);
+    const bool has_mfma = (padded || f32_mfma || llla::mfma_forward_supported(d, in, causal != 0)) && (n + 63) / 64 <= kMaxGridY;
     if (path == LLLA_PATH_MFMA && !has_mfma) return LLLA_ERR_UNSUPPORTED;
-    const bool use_mfma = has_mfma && path != LLLA_PATH_VALU;
+    const bool use_mfma = has_mfma && path != LLLA_PATH_VALU && !(padded && path == LLLA_PATH_AUTO && !auto_takes_padded(n, d, in));
     if (use_mfma) {
-        st = check_workspace(f32_mfma ? llla::mfma_forward_f32_workspace_bytes(B, H, n)
-                                      : llla::mfma_forward_workspace_bytes(B, H, n, d, in), workspace, workspace_bytes);
+        st = check_workspace(padded ? llla::padded_forward_workspace_bytes(B, H, n, d, in)
+                             : f32_mfma ? llla::mfma_forward_f32_workspace_bytes(B, H, n)
+                                        : llla::mfma_forward_workspace_bytes(B, H, n, d, in), workspace, workspace_bytes);
         if (st != LLLA_OK) return st;
     }
 
@@ -106,7 +115,9 @@ llla_status llla_forward_ex(const void *Q, const void *K, const void *V, void *O
     p.stream = static_cast<hipStream_t>(stream);
     llla::stage_begin(p.stream);
     if (!use_mfma) llla::stage_mark(p.stream, "valu_forward");
-    const hipError_t e = use_mfma ? (f32_mfma ? llla::mfma_forward_f32(p) : llla::mfma_forward(p)) : llla::valu_forward(p);
+    const hipError_t e = !use_mfma ? llla::valu_forward(p)
+                         : padded  ? llla::padded_forward(p)
+                         : f32_mfma ? llla::mfma_forward_f32(p) : llla::mfma_forward(p);
     llla::stage_end(p.stream);
     return e == hipSuccess ? LLLA_OK : LLLA_ERR_LAUNCH;
 }

@@ -85,6 +85,10 @@ hipError_t mfma_forward(const Problem &p);
 bool mfma_forward_f32_supported(int d, bool causal);
 size_t mfma_forward_f32_workspace_bytes(int B, int H, int n);
 hipError_t mfma_forward_f32(const Problem &p);
+// head dimensions 16 and 32 (bf16 or fp32): the d = 64 matrix-core forward on zero-padded copies (llla_pad.hip)
+bool padded_forward_supported(int d, llla_dtype in);
+size_t padded_forward_workspace_bytes(int B, int H, int n, int d, llla_dtype in);
+hipError_t padded_forward(const Problem &p);
 // approximate mode: T conjugate-gradient steps per row (bf16, d = 64 / 128, causal); iters: [B,H,n] steps done, or nullptr
 size_t mfma_forward_cg_workspace_bytes(int B, int H, int n, int d, llla_dtype in);
 hipError_t mfma_forward_cg(const Problem &p, int T, float eps, int32_t *iters);
