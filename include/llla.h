@@ -168,7 +168,9 @@ llla_status llla_forward_cg(const void *Q, const void *K, const void *V, void *O
  *   path        : LLLA_PATH_AUTO / VALU / MFMA as in llla_forward_path.  The vector path serves every supported d and
  *                 both dtypes in fp32 arithmetic.  The matrix-core path (bf16, d = 64 or 128) recomputes the row
  *                 moments and does both solves of a row with the forward's matrix-core kernel; the O(d)-per-pair
- *                 sweeps around it run in fp32 on the vector ALU.
+ *                 sweeps around it run in fp32 on the vector ALU.  bf16 inputs with d = 16 or 32 run it at d = 64 on
+ *                 zero-padded copies, as the forward does (the gradient of a padded feature is zero and is dropped);
+ *                 LLLA_PATH_AUTO takes that route for d = 32, and for d = 16 from 1024 rows on.
  * Causal only.  Workspace: llla_backward_workspace_bytes (Theta(B H n d); enough for either path).
  */
 size_t llla_backward_workspace_bytes(int B, int H, int n, int d, llla_dtype in);

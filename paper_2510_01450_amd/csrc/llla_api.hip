@@ -186,7 +186,9 @@ llla_status llla_forward_cg(const void *Q, const void *K, const void *V, void *O
 size_t llla_backward_workspace_bytes(int B, int H, int n, int d, llla_dtype in)
 {
     if (B <= 0 || H <= 0 || n <= 0 || !dim_supported(d) || !dtype_ok(in)) return 0;
-    return llla::backward_workspace_bytes(B, H, n, d, in, LLLA_PATH_AUTO);
+    const size_t a = llla::backward_workspace_bytes(B, H, n, d, in, LLLA_PATH_AUTO);
+    const size_t b = llla::padded_backward_workspace_bytes(B, H, n, d, in);
+    return a > b ? a : b;
 }
 
 llla_status llla_backward(const void *Q, const void *K, const void *V, const void *dO, llla_strides sq, llla_strides sk,
@@ -206,9 +208,14 @@ llla_status llla_backward(const void *Q, const void *K, const void *V, const voi
         (reinterpret_cast<uintptr_t>(lambda_rows) & 3u))
         return LLLA_ERR_ALIGN;
     if (path != LLLA_PATH_AUTO && path != LLLA_PATH_VALU && path != LLLA_PATH_MFMA) return LLLA_ERR_PARAM;
-    if (path == LLLA_PATH_MFMA && (!llla::mfma_forward_supported(d, in, true) || (n + 63) / 64 > kMaxGridY))
+    const bool padded = llla::padded_backward_supported(d, in);
+    if (path == LLLA_PATH_MFMA && ((!padded && !llla::mfma_forward_supported(d, in, true)) || (n + 63) / 64 > kMaxGridY))
         return LLLA_ERR_UNSUPPORTED;
-    st = check_workspace(llla::backward_workspace_bytes(B, H, n, d, in, path), workspace, workspace_bytes);
+    // d = 16 / 32 (bf16): the d = 64 matrix-core backward on zero-padded copies, where LLLA_PATH_AUTO takes the padded forward
+    const bool use_padded = padded && (n + 63) / 64 <= kMaxGridY &&
+                            (path == LLLA_PATH_MFMA || (path == LLLA_PATH_AUTO && auto_takes_padded(n, d, in)));
+    st = check_workspace(use_padded ? llla::padded_backward_workspace_bytes(B, H, n, d, in)
+                                    : llla::backward_workspace_bytes(B, H, n, d, in, path), workspace, workspace_bytes);
     if (st != LLLA_OK) return st;
 
     llla::BackwardProblem p{};
@@ -220,7 +227,7 @@ llla_status llla_backward(const void *Q, const void *K, const void *V, const voi
     p.lambda = lambda; p.lambda_rows = lambda_rows; p.scale = scale;
     p.ws = workspace; p.ws_bytes = workspace_bytes;
     p.stream = static_cast<hipStream_t>(stream);
-    return llla::backward(p, path) == hipSuccess ? LLLA_OK : LLLA_ERR_LAUNCH;
+    return (use_padded ? llla::padded_backward(p) : llla::backward(p, path)) == hipSuccess ? LLLA_OK : LLLA_ERR_LAUNCH;
 }
 
 size_t llla_decode_workspace_bytes(int B, int H, int L_max, int d, llla_dtype in)

@@ -89,6 +89,9 @@ hipError_t mfma_forward_f32(const Problem &p);
 bool padded_forward_supported(int d, llla_dtype in);
 size_t padded_forward_workspace_bytes(int B, int H, int n, int d, llla_dtype in);
 hipError_t padded_forward(const Problem &p);
+bool padded_backward_supported(int d, llla_dtype in);          // bf16 only, like the matrix-core backward itself
+size_t padded_backward_workspace_bytes(int B, int H, int n, int d, llla_dtype in);
+hipError_t padded_backward(const BackwardProblem &p);
 // approximate mode: T conjugate-gradient steps per row (bf16, d = 64 / 128, causal); iters: [B,H,n] steps done, or nullptr
 size_t mfma_forward_cg_workspace_bytes(int B, int H, int n, int d, llla_dtype in);
 hipError_t mfma_forward_cg(const Problem &p, int T, float eps, int32_t *iters);

@@ -82,28 +82,55 @@ __global__ __launch_bounds__(256) void unpad_rows_kernel(const T *__restrict__ s
     *reinterpret_cast<T *>(dst + e * ESZ + c * CB) = src[row * CPR + c];
 }
 
-hipError_t pad_rows(const void *src, llla_strides s, const Problem &p, void *dst)
+struct Rows {
+    int B, H, n, d;
+    hipStream_t stream;
+};
+
+hipError_t pad_rows(const void *src, llla_strides s, const Rows &r, bool f32, void *dst)
 {
-    const size_t rows = (size_t)p.B * p.H * p.n;
-    if (p.in == LLLA_F32) {
+    const size_t rows = (size_t)r.B * r.H * r.n;
+    if (f32) {
         const size_t nch = rows * (PD * 4 / 16);
-        pad_rows_kernel<4><<<dim3((unsigned)((nch + 255) / 256)), dim3(256), 0, p.stream>>>(
-            static_cast<const char *>(src), s, p.H, p.n, p.d, nch, static_cast<uint4 *>(dst));
+        pad_rows_kernel<4><<<dim3((unsigned)((nch + 255) / 256)), dim3(256), 0, r.stream>>>(
+            static_cast<const char *>(src), s, r.H, r.n, r.d, nch, static_cast<uint4 *>(dst));
     } else {
         const size_t nch = rows * (PD * 2 / 16);
-        pad_rows_kernel<2><<<dim3((unsigned)((nch + 255) / 256)), dim3(256), 0, p.stream>>>(
-            static_cast<const char *>(src), s, p.H, p.n, p.d, nch, static_cast<uint4 *>(dst));
+        pad_rows_kernel<2><<<dim3((unsigned)((nch + 255) / 256)), dim3(256), 0, r.stream>>>(
+            static_cast<const char *>(src), s, r.H, r.n, r.d, nch, static_cast<uint4 *>(dst));
     }
     return hipGetLastError();
 }
 
 template <int ESZ, class T>
-hipError_t unpad_rows(const void *src, void *dst, llla_strides s, const Problem &p)
+hipError_t unpad_rows(const void *src, void *dst, llla_strides s, const Rows &r)
 {
-    const size_t nch = (size_t)p.B * p.H * p.n * (p.d * ESZ / sizeof(T));
-    unpad_rows_kernel<ESZ, T><<<dim3((unsigned)((nch + 255) / 256)), dim3(256), 0, p.stream>>>(
-        static_cast<const T *>(src), static_cast<char *>(dst), s, p.H, p.n, p.d, nch);
+    const size_t nch = (size_t)r.B * r.H * r.n * (r.d * ESZ / sizeof(T));
+    unpad_rows_kernel<ESZ, T><<<dim3((unsigned)((nch + 255) / 256)), dim3(256), 0, r.stream>>>(
+        static_cast<const T *>(src), static_cast<char *>(dst), s, r.H, r.n, r.d, nch);
     return hipGetLastError();
+}
+
+struct PadBackwardLayout {
+    size_t q, k, v, g, dq, dk, dv, inner, total;
+};
+
+PadBackwardLayout make_pad_backward_layout(int B, int H, int n)
+{
+    const size_t rows = (size_t)B * H * n;
+    PadBackwardLayout L{};
+    size_t off = 0;
+    L.q = off; off += round_up(rows * PD * 2, 256);
+    L.k = off; off += round_up(rows * PD * 2, 256);
+    L.v = off; off += round_up(rows * PD * 2, 256);
+    L.g = off; off += round_up(rows * PD * 2, 256);
+    L.dq = off; off += round_up(rows * PD * 4, 256);
+    L.dk = off; off += round_up(rows * PD * 4, 256);
+    L.dv = off; off += round_up(rows * PD * 4, 256);
+    L.inner = off;
+    off += round_up(backward_workspace_bytes(B, H, n, PD, LLLA_BF16, LLLA_PATH_MFMA), 256);
+    L.total = off;
+    return L;
 }
 
 }  // namespace
@@ -127,12 +154,14 @@ hipError_t padded_forward(const Problem &p)
     char *ws = static_cast<char *>(p.ws);
     const llla_strides sp = {(int64_t)p.H * p.n * PD, (int64_t)p.n * PD, (int64_t)PD};
 
+    const Rows r{p.B, p.H, p.n, p.d, p.stream};
+    const bool f32 = p.in == LLLA_F32;
     stage_mark(p.stream, "pad");
-    hipError_t e = pad_rows(p.Q, p.sq, p, ws + L.q);
+    hipError_t e = pad_rows(p.Q, p.sq, r, f32, ws + L.q);
     if (e != hipSuccess) return e;
-    e = pad_rows(p.K, p.sk, p, ws + L.k);
+    e = pad_rows(p.K, p.sk, r, f32, ws + L.k);
     if (e != hipSuccess) return e;
-    e = pad_rows(p.V, p.sv, p, ws + L.v);
+    e = pad_rows(p.V, p.sv, r, f32, ws + L.v);
     if (e != hipSuccess) return e;
 
     Problem q = p;
@@ -146,13 +175,63 @@ hipError_t padded_forward(const Problem &p)
     if (e != hipSuccess) return e;
 
     stage_mark(p.stream, "unpad");
-    e = p.out == LLLA_F32 ? unpad_rows<4, uint4>(ws + L.o, p.O, p.so, p) : unpad_rows<2, uint4>(ws + L.o, p.O, p.so, p);
+    e = p.out == LLLA_F32 ? unpad_rows<4, uint4>(ws + L.o, p.O, p.so, r) : unpad_rows<2, uint4>(ws + L.o, p.O, p.so, r);
     if (e != hipSuccess) return e;
     if (p.rho) {
         const llla_strides sr = {(int64_t)p.H * p.n * p.d, (int64_t)p.n * p.d, (int64_t)p.d};
-        e = unpad_rows<4, uint32_t>(ws + L.rho, p.rho, sr, p);
+        e = unpad_rows<4, uint32_t>(ws + L.rho, p.rho, sr, r);
     }
     return e;
+}
+
+// The backward pass at d = 16 / 32 (bf16): the same padding.  The gradient with respect to a padded feature is zero to
+// first order -- a padded key feature enters the output only through its product with the padded part of y, and both
+// factors vanish -- so the padded columns of dQ, dK and dV are dropped; dlambda has no feature index.
+bool padded_backward_supported(int d, llla_dtype in)
+{
+    return (d == 16 || d == 32) && in == LLLA_BF16 && mfma_forward_supported(PD, in, true);
+}
+
+size_t padded_backward_workspace_bytes(int B, int H, int n, int d, llla_dtype in)
+{
+    if (!padded_backward_supported(d, in)) return 0;
+    return make_pad_backward_layout(B, H, n).total;
+}
+
+hipError_t padded_backward(const BackwardProblem &p)
+{
+    const PadBackwardLayout L = make_pad_backward_layout(p.B, p.H, p.n);
+    char *ws = static_cast<char *>(p.ws);
+    const llla_strides sp = {(int64_t)p.H * p.n * PD, (int64_t)p.n * PD, (int64_t)PD};
+    const Rows r{p.B, p.H, p.n, p.d, p.stream};
+
+    hipError_t e = pad_rows(p.Q, p.sq, r, false, ws + L.q);
+    if (e != hipSuccess) return e;
+    e = pad_rows(p.K, p.sk, r, false, ws + L.k);
+    if (e != hipSuccess) return e;
+    e = pad_rows(p.V, p.sv, r, false, ws + L.v);
+    if (e != hipSuccess) return e;
+    e = pad_rows(p.dO, p.sdo, r, false, ws + L.g);
+    if (e != hipSuccess) return e;
+
+    BackwardProblem q = p;
+    q.Q = ws + L.q; q.K = ws + L.k; q.V = ws + L.v; q.dO = ws + L.g;
+    q.sq = q.sk = q.sv = q.sdo = sp;
+    q.dQ = reinterpret_cast<float *>(ws + L.dq);
+    q.dK = reinterpret_cast<float *>(ws + L.dk);
+    q.dV = reinterpret_cast<float *>(ws + L.dv);
+    q.d = PD;
+    q.ws = ws + L.inner;
+    q.ws_bytes = L.total - L.inner;
+    e = backward(q, LLLA_PATH_MFMA);
+    if (e != hipSuccess) return e;
+
+    const llla_strides sg = {(int64_t)p.H * p.n * p.d, (int64_t)p.n * p.d, (int64_t)p.d};
+    e = unpad_rows<4, uint4>(q.dQ, p.dQ, sg, r);
+    if (e != hipSuccess) return e;
+    e = unpad_rows<4, uint4>(q.dK, p.dK, sg, r);
+    if (e != hipSuccess) return e;
+    return unpad_rows<4, uint4>(q.dV, p.dV, sg, r);
 }
 
 }  // namespace llla

@@ -162,7 +162,7 @@ def _bwd(Q=FAKE, K=FAKE, V=FAKE, dO=FAKE, dQ=FAKE, dK=FAKE, dV=FAKE, dlam=None, 
     (dict(n=0), 2), (dict(s=_Strides(64 * 64, 64 * 64, 32)), 2),
     (dict(din=5), 3),
     (dict(lam=0.0), 4), (dict(scale=float("nan")), 4), (dict(path=5), 4),
-    (dict(path=2), 7), (dict(path=2, din=1, d=32), 7),
+    (dict(path=2), 7), (dict(path=2, din=0, d=32), 7), (dict(path=2, din=1, d=32), 6),
     (dict(dQ=FAKE + 8), 5), (dict(dlam=FAKE + 2), 5), (dict(lam_rows=FAKE + 1), 5),
     (dict(), 6), (dict(ws=FAKE + 16, wsb=1 << 30), 6), (dict(ws=FAKE, wsb=16), 6),
     (dict(d=24), 7),

@@ -188,7 +188,7 @@ def test_f32_matrix_core_path_all_outputs(n, values, scale):
 def test_mfma_path_refuses_what_it_does_not_serve():
     x = torch.zeros(1, 1, 64, 32, dtype=torch.bfloat16, device=DEV)
     with pytest.raises(llla.LlaError) as e:
-        llla.llla_backward(x, x, x, x, 1e-2, 0.2, path="mfma")      # the backward has no matrix-core path at d = 32
+        llla.llla_forward_cg(x, x, x, 1e-2, 0.2, 4)                 # the approximate mode serves d = 64 and 128 only
     assert e.value.code == 7
     y = torch.zeros(1, 1, 64, 128, dtype=torch.float32, device=DEV)
     with pytest.raises(llla.LlaError) as e:

@@ -96,3 +96,48 @@ def test_padded_forward_non_causal(n, d, dtype):
     O = llla.llla_forward(Q.to(DEV), K.to(DEV), V.to(DEV), w.lam, w.scale, causal=False, path="mfma")
     torch.cuda.synchronize()
     print(check(O.cpu().numpy(), ref, np.full(n, n - 1), d, w.tol, "padded noncausal n=%d d=%d %s" % (n, d, dtype)))
+
+
+# ---- backward (bf16): the d = 64 matrix-core backward on the same padded copies ------------------------------------
+
+def _upstream(w, seed):
+    g = torch.Generator(device="cpu").manual_seed(workloads.SEED0 + 9000 + seed)
+    return torch.randn((w.B, w.H, w.n, w.d), generator=g, dtype=torch.float32).to(workloads.torch_dtype(w))
+
+
+@pytest.mark.parametrize("n,d,ridge_per_row", [(1, 16, False), (77, 16, False), (131, 32, False), (400, 32, True), (300, 16, True)])
+def test_padded_backward_all_gradients(n, d, ridge_per_row):
+    """dQ, dK, dV and dlambda against the backward oracle (the gate and its tolerance are those of
+    tests/test_gpu_backward.py), inputs in [B, n, H, d] memory."""
+    from oracle import backward as ob
+    from parity import check_grad
+    w = _case("padbwd", 2, 2, n, d, "bf16", index=470 + n + d)
+    Q, K, V = workloads.make_inputs(w)
+    G = _upstream(w, n + d)
+    if ridge_per_row:
+        g = torch.Generator(device="cpu").manual_seed(workloads.SEED0 + 9600 + n)
+        lam = (0.03 * torch.exp(0.7 * torch.randn((w.B, w.H, n), generator=g))).float()
+        lam_ref, lam_dev, lam_typ = lam.double().numpy(), lam.to(DEV), float(lam.double().mean())
+    else:
+        lam_ref = lam_dev = lam_typ = w.lam
+    ref = ob.backward(Q, K, V, G, lam_ref, w.scale)
+    dev = [t.to(DEV).permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (Q, K, V, G)]
+    got = llla.llla_backward(dev[0], dev[1], dev[2], dev[3], lam_dev, w.scale, path="mfma", return_dlambda=True)
+    torch.cuda.synchronize()
+    f = float(G.double().norm()) / math.sqrt(w.B * w.H) * float(V.double().pow(2).mean().sqrt())
+    floor = {"dQ": f, "dK": f, "dV": f, "dlambda": f / lam_typ}
+    for name, a, r in zip(("dQ", "dK", "dV", "dlambda"), got, ref):
+        print(name, check_grad(a.cpu().numpy(), r, d, w.tol, "padded backward n=%d d=%d %s" % (n, d, name), floor=floor[name]))
+
+
+def test_what_auto_takes_in_the_backward():
+    """As in the forward: bf16 d = 32 goes to the matrix cores, d = 16 below 1024 rows stays on the vector kernels."""
+    for n, d, padded in ((200, 32, True), (200, 16, False), (1100, 16, True)):
+        w = _case("padbwdauto", 1, 2, n, d, "bf16", index=480 + d)
+        Q, K, V = [t.to(DEV) for t in workloads.make_inputs(w)]
+        G = _upstream(w, d).to(DEV)
+        a = llla.llla_backward(Q, K, V, G, w.lam, w.scale)
+        m = llla.llla_backward(Q, K, V, G, w.lam, w.scale, path="mfma" if padded else "valu")
+        torch.cuda.synchronize()
+        for x, y in zip(a, m):
+            assert torch.equal(x, y), (n, d)
