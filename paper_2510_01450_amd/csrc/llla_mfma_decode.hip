@@ -460,6 +460,118 @@ __global__ __launch_bounds__(NT, 1) void decode_merge_kernel(const bf16_t *__res
     }
 }
 
+// The same for ONE head per workgroup, for calls with few heads (small-batch serving), where the kernel above would
+// leave most compute units idle and its phase 1 -- one wave adding a head's partial records one after the other, 26 KB
+// per round trip to memory -- is the longest part of the whole decode step.  Here the four waves share the head's 26
+// tiles (wave w: tiles w, w + 4, ...) and fetch them for up to eight partials at a time, so a head's records are in
+// after one or two round trips; wave 0 solves (the three other systems that solve_wave carries are lambda I with a
+// zero right-hand side); wave J forms column block J of the output.
+__global__ __launch_bounds__(NT, 1) void decode_merge1_kernel(const bf16_t *__restrict__ qg, const float *__restrict__ parts,
+                                                              int nparts, float lambda, void *__restrict__ og, int out_bf16)
+{
+    __shared__ __align__(16) float merged[NTILES][256];
+    __shared__ __align__(16) float scw[QW * 16 * SC_PITCH];
+    __shared__ __align__(16) float mus[D], yvs[D], ys[D + 4];
+    __shared__ float oms;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64, g = lane / 16,
+              nn = lane % 16;
+    const int hq = blockIdx.x;
+    constexpr int PG = 8, TW = (NTILES + 3) / 4;
+
+    {   // phase 1
+        const float *P0 = parts + (size_t)hq * nparts * PART_F;
+        const float mstar = wave_max_strided(P0, 0, nparts, PART_F, lane);
+        float s1 = 0.f;              // wave 0: mu~[lane], wave 1: (sum w v)[lane], wave 2: omega
+        f32x4 acc[TW];
+#pragma unroll
+        for (int i = 0; i < TW; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int pb = 0; pb < nparts; pb += PG) {
+            const float *P[PG];
+            float f[PG], v1[PG];
+            f32x4 v[PG][TW];
+#pragma unroll
+            for (int k = 0; k < PG; ++k) {
+                P[k] = P0 + (size_t)min(pb + k, nparts - 1) * PART_F;      // past the end: the last record again, factor 0
+                f[k] = P[k][0];
+                v1[k] = wave == 0 ? P[k][64 + lane] : (wave == 1 ? P[k][128 + lane] : (wave == 2 ? P[k][1] : 0.f));
+#pragma unroll
+                for (int i = 0; i < TW; ++i) {
+                    const int t = min(wave + 4 * i, NTILES - 1);            // (a repeated tile is not stored below)
+                    v[k][i] = *reinterpret_cast<const f32x4 *>(P[k] + 192 + t * 256 + lane * 4);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < PG; ++k) {
+                const float fk = (pb + k >= nparts || f[k] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(f[k] - mstar);
+                s1 = fmaf(fk, v1[k], s1);
+#pragma unroll
+                for (int i = 0; i < TW; ++i) acc[i] += fk * v[k][i];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < TW; ++i)
+            if (wave + 4 * i < NTILES) *reinterpret_cast<f32x4 *>(&merged[wave + 4 * i][lane * 4]) = acc[i];
+        if (wave == 0) mus[lane] = s1;
+        if (wave == 1) yvs[lane] = s1;
+        if (wave == 2 && lane == 0) oms = s1;
+    }
+    __syncthreads();
+
+    if (wave == 0) {   // phase 2 (scalar branch: the block contains MFMAs)
+        f32x4 acc[QW][10], rhs[QW][4];
+        float om4[QW], y0v[QW];
+#pragma unroll
+        for (int q = 0; q < QW; ++q) {
+            om4[q] = q == 0 ? oms : 1.f;
+#pragma unroll
+            for (int t = 0; t < 10; ++t)
+                acc[q][t] = q == 0 ? -*reinterpret_cast<const f32x4 *>(&merged[t][lane * 4]) : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int P = 0; P < 4; ++P)     // solve_wave takes -(Sigma~ + lambda I)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) acc[q][Shape<64>::tix(P, P)][t] -= (nn == 4 * g + t) ? lambda : 0.f;
+        }
+        solve_wave<64>(acc, rhs, y0v, om4, scw, g, nn, 0.5f * lambda, [&](f32x4 (&r)[QW][4]) {
+#pragma unroll
+            for (int q = 0; q < QW; ++q)
+#pragma unroll
+                for (int P = 0; P < 4; ++P)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const int row = 16 * P + 4 * g + t;
+                        const float mv = mus[row], qv = bf16_to_f32(qg[(size_t)hq * D + row]);
+                        r[q][P][t] = q != 0 ? 0.f : ((nn == 0) ? -mv : ((nn == 1) ? -qv : 0.f));
+                    }
+        });
+        if (nn == 0) {
+#pragma unroll
+            for (int P = 0; P < 4; ++P) *reinterpret_cast<f32x4 *>(&ys[16 * P + 4 * g]) = rhs[0][P];
+            if (g == 0) ys[D] = y0v[0];
+        }
+    }
+    __syncthreads();
+
+    {   // phase 3: wave J, column block J
+        const int J = wave;
+        const float y0 = ys[D];
+        float s = 0.f;
+#pragma unroll
+        for (int I = 0; I < 4; ++I) {
+            const f32x4 gv = *reinterpret_cast<const f32x4 *>(&merged[10 + 4 * I + J][lane * 4]);
+            const f32x4 y1 = *reinterpret_cast<const f32x4 *>(&ys[16 * I + 4 * g]);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) s = fmaf(gv[t], y1[t], s);          // G~[16I+4g+t][16J+nn] y1[16I+4g+t]
+        }
+        s += __shfl_xor(s, 16);
+        s += __shfl_xor(s, 32);
+        const float o = fmaf(y0, yvs[16 * J + nn], s);
+        if (g == 0) {
+            if (out_bf16) ((bf16_t *)og)[(size_t)hq * D + 16 * J + nn] = f32_to_bf16(o);
+            else ((float *)og)[(size_t)hq * D + 16 * J + nn] = o;
+        }
+    }
+}
+
 }  // namespace
 
 bool mfma_decode_supported(int d, llla_dtype in) { return (d == D || d == 128) && in == LLLA_BF16; }
@@ -500,8 +612,14 @@ hipError_t mfma_decode(const Problem &p)
         merge_in = parts2;
     }
     stage_mark(p.stream, "decode_merge");
-    hipLaunchKernelGGL(decode_merge_kernel, dim3((bh + QW - 1) / QW), dim3(NT), 0, p.stream, (const bf16_t *)p.Q,
-                       merge_in, bh, s.ngroups, p.lambda, p.O, p.out == LLLA_BF16 ? 1 : 0);
+    // up to one workgroup per compute unit: a head per workgroup, its waves sharing the merge; beyond that four heads
+    // per workgroup, solved together
+    if (bh <= 256)
+        hipLaunchKernelGGL(decode_merge1_kernel, dim3(bh), dim3(NT), 0, p.stream, (const bf16_t *)p.Q, merge_in, s.ngroups,
+                           p.lambda, p.O, p.out == LLLA_BF16 ? 1 : 0);
+    else
+        hipLaunchKernelGGL(decode_merge_kernel, dim3((bh + QW - 1) / QW), dim3(NT), 0, p.stream, (const bf16_t *)p.Q,
+                           merge_in, bh, s.ngroups, p.lambda, p.O, p.out == LLLA_BF16 ? 1 : 0);
     return hipGetLastError();
 }
 
