@@ -487,6 +487,24 @@ def test_c4_long_context_sampled_rows():
     _sampled(w, [(0, h) for h in range(w.H)])
 
 
+@pytest.mark.parametrize("n,d,H", [(65536, 64, 2), (49152 + 77, 128, 1)])
+def test_very_long_sequences_sampled_rows(n, d, H):
+    """Sequences eight times the longest benchmark shape (1024 key blocks per row, a ragged last block at d = 128):
+    offsets into the re-tiled keys, the row maxima and the y rows far beyond 2^16 rows, rows at both ends and at block
+    boundaries in between."""
+    w = _small("verylong", 1, H, n, d, "bf16", index=1700 + d)
+    Q, K, V = workloads.make_inputs(w)
+    rows = np.array(sorted({0, 1, 63, 64, 2 * d - 1, 2 * d, 4095, 4096, 32767, 32768, 32769, n // 2 + 31, n - 65, n - 64, n - 2,
+                            n - 1}))
+    O = llla.llla_forward(Q.to(DEV), K.to(DEV), V.to(DEV), w.lam, w.scale)
+    torch.cuda.synchronize()
+    O = O.cpu().numpy()
+    assert np.all(np.isfinite(O))
+    for h in range(H):
+        ref = oracle.forward_head(Q[0, h], K[0, h], V[0, h], w.lam, w.scale, rows=rows)
+        print(h, check(O[0, h][rows][None, None], ref[None, None], rows, d, w.tol, "n=%d d=%d head %d" % (n, d, h)))
+
+
 def test_c5_decode_all_heads():
     """Every one of the 512 outputs of the decode configuration against the oracle, one sequence (16 heads) at a time."""
     w = workloads.C5
