@@ -9,11 +9,12 @@ namespace {
 using llla::Problem;
 
 constexpr int kMaxGridY = 65535;
-// LLLA_PATH_AUTO and the padded matrix-core forward (d = 16 / 32 run at d = 64).  Measured at 64 heads, vector vs padded:
-// bf16 d = 32: 0.19 vs 0.10 ms at n = 128, 22 vs 2.5 ms at n = 4096 -> always; bf16 d = 16: 0.18 vs 0.22 ms at n = 512,
-// 0.50 vs 0.39 at 1024, 6.1 vs 2.4 at 4096 -> from 1024 rows on; fp32 (fp32 MFMA, a sixteenth of the 16-bit rate, against
-// 16 or 4 times less vector work than at d = 64): the vector kernels are faster at every size -> only when forced.
-bool auto_takes_padded(int n, int d, llla_dtype in) { return in == LLLA_BF16 && (d == 32 || n >= 1024); }
+// LLLA_PATH_AUTO and the padded matrix-core forward (d = 16 / 32 run at d = 64, padded tiles skipped).  Measured at 64
+// heads, vector vs padded: bf16 d = 32: 0.19 vs 0.07 ms at n = 128, 22 vs 1.8 ms at n = 4096 -> always; bf16 d = 16: 0.063
+// vs 0.068 ms at n = 128, 0.087 vs 0.10 at 256, 0.19 vs 0.16 at 512, 6.3 vs 1.6 at 4096 -> from 512 rows on; fp32 (fp32 MFMA, a
+// sixteenth of the 16-bit rate, against 16 or 4 times less vector work than at d = 64): the vector kernels are faster at
+// every size -> only when forced.
+bool auto_takes_padded(int n, int d, llla_dtype in) { return in == LLLA_BF16 && (d == 32 || n >= 512); }
 
 bool dim_supported(int d) { return d == 16 || d == 32 || d == 64 || d == 128; }
 bool dtype_ok(llla_dtype t) { return t == LLLA_F32 || t == LLLA_BF16; }

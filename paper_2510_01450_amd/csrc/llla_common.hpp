@@ -18,6 +18,7 @@ struct Problem {
     int B, H, n, d;            // n = sequence length (forward) or L_max (decode)
     llla_dtype in, out;
     int causal;
+    int live_d;                // forward on zero-padded copies: features [live_d, d) are zero in Q and K; 0 = none are
     float lambda, scale;
     const float *lambda_rows;  // forward only: [B,H,n] ridge per query row, or nullptr (then `lambda` for all rows)
     float *rho, *delta;        // forward only: optional outputs [B,H,n,d] and [B,H,n] (Eq. (lla)), or nullptr
@@ -33,6 +34,7 @@ struct BackwardProblem {
     float *dQ, *dK, *dV;         // [B,H,n,d]
     float *dlambda;              // [B,H,n] or nullptr
     int B, H, n, d;
+    int live_d;                  // on zero-padded copies: features [live_d, d) of Q and K are zero; 0 = none are
     llla_dtype in;
     float lambda, scale;
     const float *lambda_rows;    // [B,H,n] or nullptr

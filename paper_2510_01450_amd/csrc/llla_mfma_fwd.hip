@@ -355,7 +355,10 @@ __device__ inline BlockMap moments_block()
 // second moment; used for the first rows of a sequence, whose systems are the worst conditioned.
 // WITH_U (the backward pass): Rg holds, per row, r1 (DD floats) and r0 at [DD] (pitch YP); the solve then also
 // returns u = M^{-1} [r0; r1] in Ug, laid out like Yg.
-template <bool PRECISE, int DD, bool WITH_U = false>
+// LIVE: feature blocks of 16 that can be non-zero (all of them, except for calls at d = 16 / 32 that run here on
+// zero-padded copies: tiles of Sigma~ with a padded block stay at their starting value, 0 or -lambda on the diagonal, so
+// neither their MFMAs nor the scaled operands of padded blocks are issued).
+template <bool PRECISE, int DD, bool WITH_U = false, int LIVE = Shape<DD>::NB>
 __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t *__restrict__ Qg,
                                              const bf16_t *__restrict__ Kg, llla_strides sq, llla_strides sk, int H,
                                              int n, int nkb, float cscale, float lambda,
@@ -367,6 +370,7 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     using S = Shape<DD>;
     constexpr int NB = S::NB, NTILE = S::NTILE, NF = S::NF, QW = S::QW, NW = S::NW, QB = S::QB, YP = S::YP;
     constexpr int CH = DD / 8;                          // 16-byte chunks of a natural row
+    static_assert(LIVE == NB || DD == 64, "padded calls run at d = 64");
     constexpr int KT_SUB = DD * KB;                     // halves per transposed 32-key sub-tile
     constexpr int NAT_INSTR = 16 * CH / 64;             // DMA instructions of a weight wave: its 16 keys
     constexpr int TW = (NW == 4) ? 4 : NW - 4;          // waves that fetch the transposed tiles
@@ -564,7 +568,7 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     Frags fa, fb;
     auto load_frags = [&](Frags &fr, int buf, int hf) {
 #pragma unroll
-        for (int I = 0; I < NB; ++I) fr.f[I] = *reinterpret_cast<const half8 *>(&kt[buf][hf][kt_r + I * 512]);
+        for (int I = 0; I < LIVE; ++I) fr.f[I] = *reinterpret_cast<const half8 *>(&kt[buf][hf][kt_r + I * 512]);
     };
     // The MFMAs of work items [lo, hi) of one half; item = (query q, feature block I), q-major.  wb = weight buffer.
     auto compute_items = [&](const Frags &fr, int wb, int hf, int lo, int hi) {
@@ -597,15 +601,17 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
             for (int it = lo; it < hi; ++it) {
                 const int q = it / NB, I = it % NB;
                 if (I == 0 && it != lo) wq = *reinterpret_cast<const half8 *>(wrow + q * WT_PITCH);
+                if (I >= LIVE) continue;
                 const half8 af = fr.f[I] * wq;
 #pragma unroll
-                for (int J = I; J < NB; ++J) acc[q][S::tix(I, J)] = mfma_f16(af, fr.f[J], acc[q][S::tix(I, J)]);
+                for (int J = I; J < LIVE; ++J) acc[q][S::tix(I, J)] = mfma_f16(af, fr.f[J], acc[q][S::tix(I, J)]);
             }
         } else {
             float wq[8];
 #pragma unroll
             for (int it = lo; it < hi; ++it) {
                 const int q = it / NB, I = it % NB;
+                if (I >= LIVE) continue;
                 if (I == 0 || it == lo) {
                     const float *wp = &wt32[wb][(QW * wave + q) * WT32_PITCH + 32 * hf + 8 * g];
                     const f32x4 w0 = *reinterpret_cast<const f32x4 *>(wp), w1 = *reinterpret_cast<const f32x4 *>(wp + 4);
@@ -618,7 +624,7 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
                 for (int t = 0; t < 8; ++t) pr[t] = (float)fr.f[I][t] * wq[t];
                 split_f16(pr, ahi, alo);
 #pragma unroll
-                for (int J = I; J < NB; ++J) {
+                for (int J = I; J < LIVE; ++J) {
                     acc[q][S::tix(I, J)] = mfma_f16(alo, fr.f[J], acc[q][S::tix(I, J)]);
                     acc[q][S::tix(I, J)] = mfma_f16(ahi, fr.f[J], acc[q][S::tix(I, J)]);
                 }
@@ -638,18 +644,24 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
         const half8 wq_next = wq_read(wbn, hfn, qn);
         half8 af = pipe_af;
 #pragma unroll
-        for (int I = 0; I < NB; ++I) {
-            const half8 afn = I + 1 < NB ? fr.f[I + 1] * pipe_wq : frn.f[0] * wq_next;
+        for (int I = 0; I < LIVE; ++I) {
+            const half8 afn = I + 1 < LIVE ? fr.f[I + 1] * pipe_wq : frn.f[0] * wq_next;
 #pragma unroll
-            for (int J = I; J < NB; ++J) acc[q][S::tix(I, J)] = mfma_f16(af, fr.f[J], acc[q][S::tix(I, J)]);
+            for (int J = I; J < LIVE; ++J) acc[q][S::tix(I, J)] = mfma_f16(af, fr.f[J], acc[q][S::tix(I, J)]);
             af = afn;
         }
         pipe_af = af;
         pipe_wq = wq_next;
 #define SGB_MV() __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x002, 2, 0)
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        SGB_MV(); SGB_MV(); SGB_MV(); SGB_MV(); SGB_MV(); SGB_MV(); SGB_MV(); SGB_MV();
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        if constexpr (LIVE == NB) {
+            SGB_MV(); SGB_MV(); SGB_MV(); SGB_MV(); SGB_MV(); SGB_MV(); SGB_MV(); SGB_MV();
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        } else {
+            // LIVE (LIVE + 1) / 2 MFMAs and 4 LIVE multiplies: more vector than matrix work, two multiplies behind each MFMA
+#pragma unroll
+            for (int m = 0; m < LIVE * (LIVE + 1) / 2; ++m) { SGB_MV(); }
+        }
 #undef SGB_MV
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -943,7 +955,7 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
 
 // One launch serves every query block: blocks whose rows lie below precise_rows take the precise
 // variant.  The choice depends on blockIdx only, so it is a scalar branch (MFMA ignores EXEC).
-template <int DD>
+template <int DD, int LIVE = Shape<DD>::NB>
 __global__ __launch_bounds__(Shape<DD>::NT, DD == 64 ? 2 : 1) void moments_kernel(
     const bf16_t *__restrict__ Qg, const bf16_t *__restrict__ Kg, llla_strides sq, llla_strides sk, int H, int n, int nkb,
     int precise_rows, float cscale, float lambda, const float *__restrict__ lam_rows, const _Float16 *__restrict__ KT,
@@ -952,13 +964,13 @@ __global__ __launch_bounds__(Shape<DD>::NT, DD == 64 ? 2 : 1) void moments_kerne
     __shared__ __align__(16) MomentsShared<DD> sm;
     const int i0 = ((int)gridDim.x - 1 - moments_block<DD>().blk) * Shape<DD>::QB;
     if (i0 < precise_rows)
-        moments_body<true, DD>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg, nullptr, nullptr, causal);
+        moments_body<true, DD, false, LIVE>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg, nullptr, nullptr, causal);
     else
-        moments_body<false, DD>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg, nullptr, nullptr, causal);
+        moments_body<false, DD, false, LIVE>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg, nullptr, nullptr, causal);
 }
 
 // The same with the backward's second system (see moments_body).
-template <int DD>
+template <int DD, int LIVE = Shape<DD>::NB>
 __global__ __launch_bounds__(Shape<DD>::NT, DD == 64 ? 2 : 1) void moments_u_kernel(
     const bf16_t *__restrict__ Qg, const bf16_t *__restrict__ Kg, llla_strides sq, llla_strides sk, int H, int n, int nkb,
     int precise_rows, float cscale, float lambda, const float *__restrict__ lam_rows, const _Float16 *__restrict__ KT,
@@ -967,9 +979,9 @@ __global__ __launch_bounds__(Shape<DD>::NT, DD == 64 ? 2 : 1) void moments_u_ker
     __shared__ __align__(16) MomentsShared<DD> sm;
     const int i0 = ((int)gridDim.x - 1 - moments_block<DD>().blk) * Shape<DD>::QB;
     if (i0 < precise_rows)
-        moments_body<true, DD, true>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg, Rg, Ug);
+        moments_body<true, DD, true, LIVE>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg, Rg, Ug);
     else
-        moments_body<false, DD, true>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg, Rg, Ug);
+        moments_body<false, DD, true, LIVE>(sm, Qg, Kg, sq, sk, H, n, nkb, cscale, lambda, lam_rows, KT, Mg, Yg, Rg, Ug);
 }
 
 // Optional statistics of Eq. (lla) from the solved y of every row: with y1 = -rho/delta and
@@ -1027,8 +1039,19 @@ hipError_t forward_impl(const Problem &p)
                        0, cscale, VT, M, Y, p.O, p.so, 0, (float *)nullptr, p.causal);
     const int nqb = (p.n + S::QB - 1) / S::QB;
     stage_mark(p.stream, "moments");
-    hipLaunchKernelGGL((moments_kernel<DD>), dim3(nqb, bh), dim3(S::NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
-                       first, cscale, p.lambda, p.lambda_rows, KT, M, Y, p.causal);
+    // a call at d = 16 / 32 on zero-padded copies (live_d features can be non-zero): the variant that skips padded tiles
+    const int live = (DD == 64 && p.live_d > 0) ? (p.live_d + 15) / 16 : S::NB;
+    if constexpr (DD == 64) {
+        if (live == 1)
+            hipLaunchKernelGGL((moments_kernel<DD, 1>), dim3(nqb, bh), dim3(S::NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n,
+                               L.nkb, first, cscale, p.lambda, p.lambda_rows, KT, M, Y, p.causal);
+        else if (live == 2)
+            hipLaunchKernelGGL((moments_kernel<DD, 2>), dim3(nqb, bh), dim3(S::NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n,
+                               L.nkb, first, cscale, p.lambda, p.lambda_rows, KT, M, Y, p.causal);
+    }
+    if (live == S::NB)
+        hipLaunchKernelGGL((moments_kernel<DD>), dim3(nqb, bh), dim3(S::NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
+                           first, cscale, p.lambda, p.lambda_rows, KT, M, Y, p.causal);
     if (p.rho != nullptr || p.delta != nullptr) {
         stage_mark(p.stream, "statistics");
         hipLaunchKernelGGL((stats_kernel<DD>), dim3((p.n + 3) / 4, bh), dim3(256), 0, p.stream, Q, p.sq, p.H, p.n, Y, p.rho,
@@ -1276,9 +1299,21 @@ hipError_t backward_solve_impl(const BackwardProblem &p, const BackwardLayout &B
     float *U = reinterpret_cast<float *>(base + BL.u);
     const int first = S::EARLY_ROWS < p.n ? S::EARLY_ROWS : p.n;
     stage_mark(p.stream, "moments_and_two_solves");
-    hipLaunchKernelGGL((moments_u_kernel<DD>), dim3((p.n + S::QB - 1) / S::QB, p.B * p.H), dim3(S::NT), 0, p.stream,
-                       static_cast<const bf16_t *>(p.Q), static_cast<const bf16_t *>(p.K), p.sq, p.sk, p.H, p.n, L.nkb, first,
-                       p.scale * LOG2E, p.lambda, p.lambda_rows, KT, M, Y, R, U);
+    // (on zero-padded copies of a d = 16 / 32 call: the variant that skips the padded tiles, as in the forward)
+    const int live = (DD == 64 && p.live_d > 0) ? (p.live_d + 15) / 16 : S::NB;
+    const dim3 grid((p.n + S::QB - 1) / S::QB, p.B * p.H);
+    const bf16_t *Q = static_cast<const bf16_t *>(p.Q), *K = static_cast<const bf16_t *>(p.K);
+    if constexpr (DD == 64) {
+        if (live == 1)
+            hipLaunchKernelGGL((moments_u_kernel<DD, 1>), grid, dim3(S::NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb, first,
+                               p.scale * LOG2E, p.lambda, p.lambda_rows, KT, M, Y, R, U);
+        else if (live == 2)
+            hipLaunchKernelGGL((moments_u_kernel<DD, 2>), grid, dim3(S::NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb, first,
+                               p.scale * LOG2E, p.lambda, p.lambda_rows, KT, M, Y, R, U);
+    }
+    if (live == S::NB)
+        hipLaunchKernelGGL((moments_u_kernel<DD>), grid, dim3(S::NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb, first,
+                           p.scale * LOG2E, p.lambda, p.lambda_rows, KT, M, Y, R, U);
     return hipGetLastError();
 }
 

@@ -168,6 +168,7 @@ hipError_t padded_forward(const Problem &p)
     q.Q = ws + L.q; q.K = ws + L.k; q.V = ws + L.v; q.O = ws + L.o;
     q.sq = q.sk = q.sv = q.so = sp;
     q.d = PD;
+    q.live_d = p.d;
     q.rho = p.rho ? reinterpret_cast<float *>(ws + L.rho) : nullptr;
     q.ws = ws + L.inner;
     q.ws_bytes = L.total - L.inner;
@@ -221,6 +222,7 @@ hipError_t padded_backward(const BackwardProblem &p)
     q.dK = reinterpret_cast<float *>(ws + L.dk);
     q.dV = reinterpret_cast<float *>(ws + L.dv);
     q.d = PD;
+    q.live_d = p.d;
     q.ws = ws + L.inner;
     q.ws_bytes = L.total - L.inner;
     e = backward(q, LLLA_PATH_MFMA);
