@@ -40,7 +40,7 @@
  *
  * Value range of the matrix-core kernels.  LLLA_PATH_AUTO serves bf16 inputs with d = 64 or 128 on
  * the matrix cores (llla_forward, llla_forward_ex, llla_forward_cg, llla_backward, and llla_decode
- * with a cache capacity of at least 256 rows; llla_forward and llla_forward_ex also d = 32, and d = 16 from 512 rows on).  Those kernels hand the keys (and, in decode, queries and
+ * with a cache capacity of at least 256 rows; llla_forward and llla_forward_ex also d = 16 and 32 from 32 rows on).  Those kernels hand the keys (and, in decode, queries and
  * values) to the MFMA units as f16: every |x| must be at most 65504 (larger ones become
  * infinite and the affected rows NaN; no status is returned, the data being device memory), and
  * magnitudes below 6.1e-5 lose bits to the f16 subnormal range.  bf16 values of ordinary size
@@ -106,7 +106,7 @@ llla_status llla_forward(const void *Q, const void *K, const void *V, void *O,
  * copies held in the workspace (exact: with features d..63 zero the system of Eq. (query_specific) splits into the
  * original one and lambda * y = 0); other calls return LLLA_ERR_UNSUPPORTED.  LLLA_PATH_AUTO takes the matrix-core
  * kernels wherever they exist, except where the vector kernels measured faster: d = 16 / 32 with fp32 inputs, and
- * bf16 inputs with d = 16 and fewer than 512 rows.  bf16 inputs on the matrix cores are subject to the f16 value
+ * bf16 inputs with d = 16 / 32 and fewer than 32 rows.  bf16 inputs on the matrix cores are subject to the f16 value
  * range stated at the top of this file. */
 llla_status llla_forward_path(const void *Q, const void *K, const void *V, void *O,
                               llla_strides sq, llla_strides sk, llla_strides sv, llla_strides so,
@@ -170,7 +170,7 @@ llla_status llla_forward_cg(const void *Q, const void *K, const void *V, void *O
  *                 moments and does both solves of a row with the forward's matrix-core kernel; the O(d)-per-pair
  *                 sweeps around it run in fp32 on the vector ALU.  bf16 inputs with d = 16 or 32 run it at d = 64 on
  *                 zero-padded copies, as the forward does (the gradient of a padded feature is zero and is dropped);
- *                 LLLA_PATH_AUTO takes that route for d = 32, and for d = 16 from 512 rows on.
+ *                 LLLA_PATH_AUTO takes that route for d = 32 from 64 rows on, and for d = 16 from 512 rows on.
  * Causal only.  Workspace: llla_backward_workspace_bytes (Theta(B H n d); enough for either path).
  */
 size_t llla_backward_workspace_bytes(int B, int H, int n, int d, llla_dtype in);

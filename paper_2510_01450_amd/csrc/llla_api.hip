@@ -9,12 +9,15 @@ namespace {
 using llla::Problem;
 
 constexpr int kMaxGridY = 65535;
-// LLLA_PATH_AUTO and the padded matrix-core forward (d = 16 / 32 run at d = 64, padded tiles skipped).  Measured at 64
-// heads, vector vs padded: bf16 d = 32: 0.19 vs 0.07 ms at n = 128, 22 vs 1.8 ms at n = 4096 -> always; bf16 d = 16: 0.063
-// vs 0.068 ms at n = 128, 0.087 vs 0.10 at 256, 0.19 vs 0.16 at 512, 6.3 vs 1.6 at 4096 -> from 512 rows on; fp32 (fp32 MFMA, a
-// sixteenth of the 16-bit rate, against 16 or 4 times less vector work than at d = 64): the vector kernels are faster at
-// every size -> only when forced.
-bool auto_takes_padded(int n, int d, llla_dtype in) { return in == LLLA_BF16 && (d == 32 || n >= 512); }
+// LLLA_PATH_AUTO and the padded matrix-core calls (d = 16 / 32 run at d = 64; padded tiles and solve blocks skipped).
+// Measured at 64 heads, bf16, vector vs padded.  Forward, d = 32: 0.028 vs 0.036 ms at n = 16, 0.075 vs 0.037 at 32, 0.19 vs
+// 0.057 at 128, 22.5 vs 1.56 at 4096; d = 16: 0.028 vs 0.036 at n = 16, 0.045 vs 0.038 at 32, 0.064 vs 0.053 at 128, 6.2 vs 1.2 at
+// 4096 -> from 32 rows on.  Backward, d = 32: 0.055 vs 0.057 at n = 32, 0.080 vs 0.070 at 64, 42.5 vs 3.7 at 4096 -> from 64 rows
+// on; d = 16: 0.071 vs 0.106 at n = 128, 0.32 vs 0.21 at 512, 15.1 vs 3.2 at 4096 -> from 512 rows on.  fp32 inputs (fp32 MFMA, a
+// sixteenth of the 16-bit rate, against 16 or 4 times less vector work than at d = 64; forward only): the vector
+// kernels are faster at every size -> only when forced.
+bool auto_takes_padded(int n, int d, llla_dtype in) { (void)d; return in == LLLA_BF16 && n >= 32; }
+bool auto_takes_padded_backward(int n, int d, llla_dtype in) { return in == LLLA_BF16 && n >= (d == 32 ? 64 : 512); }
 
 bool dim_supported(int d) { return d == 16 || d == 32 || d == 64 || d == 128; }
 bool dtype_ok(llla_dtype t) { return t == LLLA_F32 || t == LLLA_BF16; }
@@ -214,7 +217,7 @@ llla_status llla_backward(const void *Q, const void *K, const void *V, const voi
         return LLLA_ERR_UNSUPPORTED;
     // d = 16 / 32 (bf16): the d = 64 matrix-core backward on zero-padded copies, where LLLA_PATH_AUTO takes the padded forward
     const bool use_padded = padded && (n + 63) / 64 <= kMaxGridY &&
-                            (path == LLLA_PATH_MFMA || (path == LLLA_PATH_AUTO && auto_takes_padded(n, d, in)));
+                            (path == LLLA_PATH_MFMA || (path == LLLA_PATH_AUTO && auto_takes_padded_backward(n, d, in)));
     st = check_workspace(use_padded ? llla::padded_backward_workspace_bytes(B, H, n, d, in)
                                     : llla::backward_workspace_bytes(B, H, n, d, in, path), workspace, workspace_bytes);
     if (st != LLLA_OK) return st;

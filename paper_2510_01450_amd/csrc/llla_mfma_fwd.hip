@@ -890,7 +890,7 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
             if constexpr (WITH_U) te[P] = -Rg[((size_t)bh * n + row) * YP + 16 * P + nn];
         }
         if constexpr (WITH_U) r0 = Rg[((size_t)bh * n + row) * YP + DD];
-        solve_wave_q4<WITH_U>(acc, tmu, tq, te, r0, oms[qi], &sc[wave][0][0], g, nn, pivot_floor, y1, y0, u1, u0);
+        solve_wave_q4<WITH_U, LIVE>(acc, tmu, tq, te, r0, oms[qi], &sc[wave][0][0], g, nn, pivot_floor, y1, y0, u1, u0);
         if (i0 + qi < n) {
             float *yr = Yg + ((size_t)bh * n + row) * YP;
 #pragma unroll

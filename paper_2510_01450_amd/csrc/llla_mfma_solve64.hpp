@@ -171,13 +171,17 @@ __device__ inline float row_transpose_sum(const float (&p)[16], int nn)
 //        scw               >= 4 * 16 * SC_PITCH floats of LDS owned by this wave; pivot_floor as in chol_inv16
 //   out: y1[P] = y1_q[16P + r] in lane (q, r), y0 of the lane's query in every lane;  WITH_U: u1[P], u0 likewise
 // with [omega mu~^T; mu~ Sigma~ + lambda I] [y0; y1] = [1; q] and, WITH_U, the same matrix times [u0; u1] = [r0; r1].
-template <bool WITH_U>
+// LIVE < 4 (a call at d = 16 / 32 on zero-padded copies): feature blocks LIVE..3 of every key and query are zero, the
+// matrix is block diagonal with lambda I in those blocks and their right-hand sides are zero, so the solution vanishes
+// there and only blocks 0..LIVE-1 are factorised and substituted.
+template <bool WITH_U, int LIVE = 4>
 __device__ __forceinline__ void solve_wave_q4(f32x4 (&acc)[4][10], float (&tmu)[4], float (&tq)[4], float (&te)[4], float r0,
                                               float omega, float *scw, int g, int nn, float pivot_floor, float (&y1)[4],
                                               float &y0, float (&u1)[4], float &u0)
 {
     using S = Shape<64>;
-    constexpr int QW = 4, NB = 4;
+    constexpr int QW = 4, NB = LIVE;       // blocks LIVE..3 are lambda I with zero right-hand sides (see above): y1 = u1 = 0 there
+    static_assert(LIVE >= 1 && LIVE <= 4, "four 16-wide blocks");
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 
     // ---- factorisation (as in solve_wave): acc(P,J), P < J, becomes U(P,J); acc(P,P) becomes N_P = -U(P,P)^{-1} -----
@@ -227,7 +231,12 @@ __device__ __forceinline__ void solve_wave_q4(f32x4 (&acc)[4][10], float (&tmu)[
     // ---- every tile from the accumulator layout to columns: lane (q, r) now holds column r of query q's tile,
     //      element c = 4 g' + t in register acc[g'][tile][t] ---------------------------------------------------------
 #pragma unroll
-    for (int tl = 0; tl < 10; ++tl) rows_transpose4(acc[0][tl], acc[1][tl], acc[2][tl], acc[3][tl]);
+    for (int I = 0; I < NB; ++I)
+#pragma unroll
+        for (int J = I; J < NB; ++J) {
+            const int tl = S::tix(I, J);
+            rows_transpose4(acc[0][tl], acc[1][tl], acc[2][tl], acc[3][tl]);
+        }
 
     // ---- forward substitution of the right-hand sides: a_P = N_P^T t_P, then t_I += U(P,I)^T a_P for I > P ----------
 #pragma unroll
@@ -260,6 +269,8 @@ __device__ __forceinline__ void solve_wave_q4(f32x4 (&acc)[4][10], float (&tmu)[
     const float dinv = 1.f / (omega - saa);
     y0 = (1.f - sac) * dinv;
     float z[4], zu[4];
+#pragma unroll
+    for (int P = NB; P < 4; ++P) { y1[P] = 0.f; u1[P] = 0.f; }
 #pragma unroll
     for (int P = 0; P < NB; ++P) z[P] = tmu[P] * y0 - tq[P];
     if constexpr (WITH_U) {

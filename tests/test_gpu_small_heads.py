@@ -38,11 +38,11 @@ def test_padded_forward_all_outputs(n, d, dtype):
     print(check(O.cpu().numpy(), ref, np.arange(n), d, w.tol, "padded n=%d d=%d %s" % (n, d, dtype)))
 
 
-@pytest.mark.parametrize("n,d,dtype,padded", [(1100, 16, "bf16", True), (300, 16, "bf16", False), (300, 32, "bf16", True),
-                                              (1100, 16, "f32", False), (1100, 32, "f32", False)])
+@pytest.mark.parametrize("n,d,dtype,padded", [(1100, 16, "bf16", True), (300, 16, "bf16", True), (20, 16, "bf16", False),
+                                              (40, 32, "bf16", True), (1100, 16, "f32", False), (1100, 32, "f32", False)])
 def test_what_auto_takes(n, d, dtype, padded):
-    """LLLA_PATH_AUTO: bf16 with d = 32, and with d = 16 from 512 rows on, gives the bits of the forced matrix-core
-    call; elsewhere those of the vector kernels.  Inside the gate either way."""
+    """LLLA_PATH_AUTO: bf16 with d = 16 / 32 from 32 rows on gives the bits of the forced matrix-core call; fewer rows
+    and fp32 inputs those of the vector kernels.  Inside the gate either way."""
     w = _case("padauto", 1, 2, n, d, dtype, index=430 + d)
     Q, K, V = [t.to(DEV) for t in workloads.make_inputs(w)]
     a = llla.llla_forward(Q, K, V, w.lam, w.scale)
@@ -131,8 +131,8 @@ def test_padded_backward_all_gradients(n, d, ridge_per_row):
 
 
 def test_what_auto_takes_in_the_backward():
-    """As in the forward: bf16 d = 32 goes to the matrix cores, d = 16 below 512 rows stays on the vector kernels."""
-    for n, d, padded in ((200, 32, True), (200, 16, False), (1100, 16, True)):
+    """bf16 d = 32 goes to the matrix cores from 64 rows on, d = 16 from 512 rows on; below, the vector kernels."""
+    for n, d, padded in ((200, 32, True), (40, 32, False), (200, 16, False), (1100, 16, True)):
         w = _case("padbwdauto", 1, 2, n, d, "bf16", index=480 + d)
         Q, K, V = [t.to(DEV) for t in workloads.make_inputs(w)]
         G = _upstream(w, d).to(DEV)
