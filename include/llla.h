@@ -105,8 +105,8 @@ llla_status llla_forward(const void *Q, const void *K, const void *V, void *O,
  * fp32 inputs with d = 64, and -- for either dtype -- d = 16 and 32, which run the d = 64 kernels on zero-padded
  * copies held in the workspace (exact: with features d..63 zero the system of Eq. (query_specific) splits into the
  * original one and lambda * y = 0); other calls return LLLA_ERR_UNSUPPORTED.  LLLA_PATH_AUTO takes the matrix-core
- * kernels wherever they exist, except where the vector kernels measured faster: d = 16 / 32 with fp32 inputs, and
- * bf16 inputs with d = 16 / 32 and fewer than 32 rows.  bf16 inputs on the matrix cores are subject to the f16 value
+ * kernels wherever they exist, except where the vector kernels measured faster: d = 16 with fp32 inputs, d = 32 with
+ * fp32 inputs and fewer than 1024 rows, and bf16 inputs with d = 16 / 32 and fewer than 32 rows.  bf16 inputs on the matrix cores are subject to the f16 value
  * range stated at the top of this file. */
 llla_status llla_forward_path(const void *Q, const void *K, const void *V, void *O,
                               llla_strides sq, llla_strides sk, llla_strides sv, llla_strides so,

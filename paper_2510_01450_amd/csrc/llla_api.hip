@@ -14,9 +14,10 @@ constexpr int kMaxGridY = 65535;
 // 0.057 at 128, 22.5 vs 1.56 at 4096; d = 16: 0.028 vs 0.036 at n = 16, 0.045 vs 0.038 at 32, 0.064 vs 0.053 at 128, 6.2 vs 1.2 at
 // 4096 -> from 32 rows on.  Backward, d = 32: 0.055 vs 0.057 at n = 32, 0.080 vs 0.070 at 64, 42.5 vs 3.7 at 4096 -> from 64 rows
 // on; d = 16: 0.071 vs 0.106 at n = 128, 0.32 vs 0.21 at 512, 15.1 vs 3.2 at 4096 -> from 512 rows on.  fp32 inputs (fp32 MFMA, a
-// sixteenth of the 16-bit rate, against 16 or 4 times less vector work than at d = 64; forward only): the vector
-// kernels are faster at every size -> only when forced.
-bool auto_takes_padded(int n, int d, llla_dtype in) { (void)d; return in == LLLA_BF16 && n >= 32; }
+// sixteenth of the 16-bit rate; forward only), d = 32: 0.34 vs 0.36 ms at n = 256, 0.73 vs 0.53 at 512, 2.0 vs 1.1 at 1024, 24.3
+// vs 11.1 at 4096, but 0.196 vs 0.217 at 2 heads x 1024 -> from 1024 rows on; d = 16: 0.062 vs 0.30 at n = 128, 0.53 vs 0.77 at 1024,
+// 6.5 vs 6.9 at 4096 -> only when forced.
+bool auto_takes_padded(int n, int d, llla_dtype in) { return in == LLLA_BF16 ? n >= 32 : (d == 32 && n >= 1024); }
 bool auto_takes_padded_backward(int n, int d, llla_dtype in) { return in == LLLA_BF16 && n >= (d == 32 ? 64 : 512); }
 
 bool dim_supported(int d) { return d == 16 || d == 32 || d == 64 || d == 128; }

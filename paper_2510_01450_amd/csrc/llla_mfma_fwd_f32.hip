@@ -63,6 +63,9 @@ struct F32Shared {
     float sc[4][4][16 * SC_PITCH];
 };
 
+// LIVE: feature blocks of 16 that can be non-zero (4, except for calls at d = 16 / 32 that run here on zero-padded
+// copies: the tiles, scaled operands and solve blocks of padded feature blocks are skipped, see moments_body).
+template <int LIVE>
 __global__ __launch_bounds__(256, 2) void moments_f32_kernel(const float *__restrict__ Qg, const float *__restrict__ Kg,
                                                             llla_strides sq, llla_strides sk, int H, int n, int npad,
                                                             float cscale, float lambda, const float *__restrict__ lam_rows,
@@ -219,15 +222,15 @@ __global__ __launch_bounds__(256, 2) void moments_f32_kernel(const float *__rest
                 const int sw = swz(row), c4 = nn_e >> 2;
                 float kf[NB];
 #pragma unroll
-                for (int I = 0; I < NB; ++I) kf[I] = krow[4 * ((4 * I + c4) ^ sw)];
+                for (int I = 0; I < LIVE; ++I) kf[I] = krow[4 * ((4 * I + c4) ^ sw)];
                 const float kmu = krow[4 * ((4 * wave + c4) ^ sw)];                   // this wave's feature block of mu~
 #pragma unroll
                 for (int q = 0; q < QW; ++q)
 #pragma unroll
-                    for (int I = 0; I < NB; ++I) {
+                    for (int I = 0; I < LIVE; ++I) {
                         const float af = kf[I] * wq[q][e];
 #pragma unroll
-                        for (int J = I; J < NB; ++J)
+                        for (int J = I; J < LIVE; ++J)
                             acc[q][S::tix(I, J)] = __builtin_amdgcn_mfma_f32_16x16x4f32(af, kf[J], acc[q][S::tix(I, J)], 0, 0, 0);
                     }
                 mu_acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[e], kmu, mu_acc, 0, 0, 0);   // -mu~'[query 4g+r][16 wave + nn]
@@ -275,7 +278,7 @@ __global__ __launch_bounds__(256, 2) void moments_f32_kernel(const float *__rest
         tq[P] = -qrow[16 * P + nn];
         te[P] = 0.f; y1[P] = 0.f; u1[P] = 0.f;
     }
-    solve_wave_q4<false>(acc, tmu, tq, te, 0.f, sm.oms[qi], &sm.sc[wave][0][0], g, nn, pivot_floor, y1, y0, u1, u0);
+    solve_wave_q4<false, LIVE>(acc, tmu, tq, te, 0.f, sm.oms[qi], &sm.sc[wave][0][0], g, nn, pivot_floor, y1, y0, u1, u0);
     if (i0 + qi < n) {
         float *yr = Yg + ((size_t)bh * n + row) * YP;
 #pragma unroll
@@ -430,8 +433,17 @@ hipError_t mfma_forward_f32(const Problem &p)
     const int bh = p.B * p.H;
     const float *Q = static_cast<const float *>(p.Q), *K = static_cast<const float *>(p.K);
     stage_mark(p.stream, "moments");
-    hipLaunchKernelGGL(moments_f32_kernel, dim3((p.n + S::QB - 1) / S::QB, bh), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H,
-                       p.n, L.npad, p.scale * LOG2E, p.lambda, p.lambda_rows, M, LF, Y, p.causal);
+    const int live = p.live_d > 0 ? (p.live_d + 15) / 16 : 4;      // a d = 16 / 32 call on zero-padded copies: 1 or 2
+    const dim3 grid((p.n + S::QB - 1) / S::QB, bh);
+    if (live == 1)
+        hipLaunchKernelGGL(moments_f32_kernel<1>, grid, dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.npad,
+                           p.scale * LOG2E, p.lambda, p.lambda_rows, M, LF, Y, p.causal);
+    else if (live == 2)
+        hipLaunchKernelGGL(moments_f32_kernel<2>, grid, dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.npad,
+                           p.scale * LOG2E, p.lambda, p.lambda_rows, M, LF, Y, p.causal);
+    else
+        hipLaunchKernelGGL(moments_f32_kernel<4>, grid, dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.npad,
+                           p.scale * LOG2E, p.lambda, p.lambda_rows, M, LF, Y, p.causal);
     if (p.rho != nullptr || p.delta != nullptr) {
         stage_mark(p.stream, "statistics");
         hipLaunchKernelGGL(stats_f32_kernel, dim3((p.n + 3) / 4, bh), dim3(256), 0, p.stream, Q, p.sq, p.H, p.n, L.npad,

@@ -39,10 +39,11 @@ def test_padded_forward_all_outputs(n, d, dtype):
 
 
 @pytest.mark.parametrize("n,d,dtype,padded", [(1100, 16, "bf16", True), (300, 16, "bf16", True), (20, 16, "bf16", False),
-                                              (40, 32, "bf16", True), (1100, 16, "f32", False), (1100, 32, "f32", False)])
+                                              (40, 32, "bf16", True), (1100, 16, "f32", False), (1100, 32, "f32", True),
+                                              (600, 32, "f32", False)])
 def test_what_auto_takes(n, d, dtype, padded):
-    """LLLA_PATH_AUTO: bf16 with d = 16 / 32 from 32 rows on gives the bits of the forced matrix-core call; fewer rows
-    and fp32 inputs those of the vector kernels.  Inside the gate either way."""
+    """LLLA_PATH_AUTO: bf16 with d = 16 / 32 from 32 rows on, and fp32 with d = 32 from 1024 rows on, gives the bits of the
+    forced matrix-core call; the other calls those of the vector kernels.  Inside the gate either way."""
     w = _case("padauto", 1, 2, n, d, dtype, index=430 + d)
     Q, K, V = [t.to(DEV) for t in workloads.make_inputs(w)]
     a = llla.llla_forward(Q, K, V, w.lam, w.scale)
