@@ -42,10 +42,10 @@
  * the matrix cores (llla_forward, llla_forward_ex, llla_forward_cg, llla_backward, and llla_decode
  * with a cache capacity of at least 256 rows; llla_forward and llla_forward_ex also d = 16 and 32 from 32 rows on).  Those kernels hand the keys (and, in decode, queries and
  * values) to the MFMA units as f16: every |x| must be at most 65504 (larger ones become
- * infinite and the affected rows NaN; no status is returned, the data being device memory), and
+ * infinite and the rows whose 64-key blocks hold them NaN; no status is returned, the data being device memory), and
  * magnitudes below 6.1e-5 lose bits to the f16 subnormal range.  bf16 values of ordinary size
  * (8 significant bits, |x| in [6.1e-5, 65504]) convert exactly.  LLLA_PATH_VALU computes in fp32
- * throughout and has no such limit.
+ * throughout and has no such limit (what it can carry is bounded by the conditioning of the rows' systems in fp32).
  */
 #ifndef LLLA_H
 #define LLLA_H

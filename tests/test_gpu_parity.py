@@ -689,3 +689,20 @@ def test_forward_cg_many_steps_approaches_the_exact_forward():
         errs.append(float((np.linalg.norm(O - exact, axis=-1) / np.linalg.norm(exact, axis=-1)).max()))
     print("max rel. distance to the oracle's exact forward on rows >= 256 for T = 2, 8, 32, 128:", errs)
     assert errs[-1] < 2e-2 and errs[-1] <= errs[0]
+
+
+def test_f16_value_range_of_the_matrix_core_forward():
+    """What include/llla.h states about values beyond the f16 range: the matrix-core kernels hand the keys to the MFMA
+    units as f16, so a bf16 key entry of 1e5 becomes infinite and every row that sees that key is NaN, with no status
+    (as are the rows just before it whose last 64-key block holds the key under a zero weight: 0 times infinity); rows
+    whose blocks end before it are untouched and inside the gate."""
+    n, d, j0 = 300, 64, 180
+    w = _small("range", 1, 1, n, d, "bf16", index=1800)
+    Q, K, V = workloads.make_inputs(w)
+    K[0, 0, j0, 5] = 1e5
+    ref = oracle.forward(Q, K, V, w.lam, w.scale)
+    got = _run_forward(w, Q, K, V, path="mfma")
+    clean = 64 * (j0 // 64)
+    assert np.isfinite(got[0, 0, :clean]).all() and not np.isfinite(got[0, 0, j0:]).any()
+    rows = np.arange(clean)
+    print(check(got[:, :, :clean], ref[:, :, :clean], rows, d, w.tol, "rows before the out-of-range key's block"))
