@@ -97,7 +97,9 @@ __global__ __launch_bounds__(256) void prep_kernel(const bf16_t *__restrict__ Kg
 //   else   : third loop of Algorithm 1: S = W (y0 + K y1), O = S V.
 constexpr int VT_PITCH = KB + 8;     // halves
 
-template <bool MAXONLY, int DD>
+// LIVE < NB (a d = 16 / 32 call on zero-padded copies): features and value columns from 16 LIVE on are zero, so the
+// contractions over features stop after the chunks that hold live ones and only LIVE output tiles are formed and stored.
+template <bool MAXONLY, int DD, int LIVE = Shape<DD>::NB>
 __global__ __launch_bounds__(256, 2) void sweep_kernel(const bf16_t *__restrict__ Qg, const bf16_t *__restrict__ Kg,
                                                     llla_strides sq, llla_strides sk, int H, int n, int nkb,
                                                     int first_row, float cscale, const bf16_t *__restrict__ VT,
@@ -110,7 +112,7 @@ __global__ __launch_bounds__(256, 2) void sweep_kernel(const bf16_t *__restrict_
     // approximate mode).  Yg == nullptr means y0 = 1, y1 = 0 (plain weights); Csum, if given, receives sum_j of the
     // coefficients of every row.
     using S = Shape<DD>;
-    constexpr int NF = S::NF, NB = S::NB, YP = S::YP;
+    constexpr int NF = (16 * LIVE + 31) / 32, NB = LIVE, YP = S::YP;     // feature chunks of 32 and output tiles that are live
     constexpr int KN_PITCH = DD + 16;    // halves; rows of the natural K tile stay 16-byte aligned (measured 2-3 % faster than DD + 8)
     __shared__ __align__(16) bf16_t kn[KB * KN_PITCH];
     __shared__ __align__(16) bf16_t vt[MAXONLY ? 8 : DD * VT_PITCH];
@@ -1035,12 +1037,21 @@ hipError_t forward_impl(const Problem &p)
     hipLaunchKernelGGL((prep_kernel<DD>), dim3(L.nkb, bh), dim3(256), 0, p.stream, K, V, p.sk, p.sv, p.H, p.n, L.nkb, KT, VT);
     const int nq64 = (p.n + 63) / 64;
     stage_mark(p.stream, "rowmax");
-    hipLaunchKernelGGL((sweep_kernel<true, DD>), dim3(bh, nq64), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
-                       0, cscale, VT, M, Y, p.O, p.so, 0, (float *)nullptr, p.causal);
+    // a call at d = 16 / 32 on zero-padded copies (live_d features can be non-zero): the variants that skip padded tiles
+    const int live = (DD == 64 && p.live_d > 0) ? (p.live_d + 15) / 16 : S::NB;
+    if constexpr (DD == 64) {
+        if (live == 1)
+            hipLaunchKernelGGL((sweep_kernel<true, DD, 1>), dim3(bh, nq64), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n,
+                               L.nkb, 0, cscale, VT, M, Y, p.O, p.so, 0, (float *)nullptr, p.causal);
+        else if (live == 2)
+            hipLaunchKernelGGL((sweep_kernel<true, DD, 2>), dim3(bh, nq64), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n,
+                               L.nkb, 0, cscale, VT, M, Y, p.O, p.so, 0, (float *)nullptr, p.causal);
+    }
+    if (live == S::NB)
+        hipLaunchKernelGGL((sweep_kernel<true, DD>), dim3(bh, nq64), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n, L.nkb,
+                           0, cscale, VT, M, Y, p.O, p.so, 0, (float *)nullptr, p.causal);
     const int nqb = (p.n + S::QB - 1) / S::QB;
     stage_mark(p.stream, "moments");
-    // a call at d = 16 / 32 on zero-padded copies (live_d features can be non-zero): the variant that skips padded tiles
-    const int live = (DD == 64 && p.live_d > 0) ? (p.live_d + 15) / 16 : S::NB;
     if constexpr (DD == 64) {
         if (live == 1)
             hipLaunchKernelGGL((moments_kernel<DD, 1>), dim3(nqb, bh), dim3(S::NT), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n,
@@ -1067,8 +1078,18 @@ hipError_t forward_impl(const Problem &p)
     if (first < p.n) {
         const int nq64b = (p.n - first + 63) / 64;
         stage_mark(p.stream, "output");
-        hipLaunchKernelGGL((sweep_kernel<false, DD>), dim3(bh, nq64b), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n,
-                           L.nkb, first, cscale, VT, M, Y, p.O, p.so, p.out == LLLA_BF16 ? 1 : 0, (float *)nullptr, p.causal);
+        const int obf = p.out == LLLA_BF16 ? 1 : 0;
+        if constexpr (DD == 64) {
+            if (live == 1)
+                hipLaunchKernelGGL((sweep_kernel<false, DD, 1>), dim3(bh, nq64b), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H,
+                                   p.n, L.nkb, first, cscale, VT, M, Y, p.O, p.so, obf, (float *)nullptr, p.causal);
+            else if (live == 2)
+                hipLaunchKernelGGL((sweep_kernel<false, DD, 2>), dim3(bh, nq64b), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H,
+                                   p.n, L.nkb, first, cscale, VT, M, Y, p.O, p.so, obf, (float *)nullptr, p.causal);
+        }
+        if (live == S::NB)
+            hipLaunchKernelGGL((sweep_kernel<false, DD>), dim3(bh, nq64b), dim3(256), 0, p.stream, Q, K, p.sq, p.sk, p.H, p.n,
+                               L.nkb, first, cscale, VT, M, Y, p.O, p.so, obf, (float *)nullptr, p.causal);
     }
     return hipGetLastError();
 }
