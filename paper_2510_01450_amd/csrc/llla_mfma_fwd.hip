@@ -711,7 +711,7 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     // is behind still reads those of block c-1.  Past the last block every key is masked (j > iq): that extra
     // round stores zeros.  `wave` is a scalar, so every branch around an MFMA is a real branch (MFMA ignores EXEC).
     constexpr int ITEMS = QW * NB, Q2 = ITEMS / 2, Q3 = 3 * ITEMS / 4;
-    constexpr bool PREFETCH = (DD == 64);       // d = 128 has no registers for a second fragment set (see below)
+    constexpr bool PREFETCH = (DD == 64) && !PRECISE;   // a second fragment set: d = 128 has no registers for one, nor has the fp32-accurate variant (it spilled 55 registers per block with it)
     issue_dma(0);
     if (PREFETCH && nblk > 1) issue_dma(1);
     dma_wait();
