@@ -711,7 +711,10 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     // is behind still reads those of block c-1.  Past the last block every key is masked (j > iq): that extra
     // round stores zeros.  `wave` is a scalar, so every branch around an MFMA is a real branch (MFMA ignores EXEC).
     constexpr int ITEMS = QW * NB, Q2 = ITEMS / 2, Q3 = 3 * ITEMS / 4;
-    constexpr bool PREFETCH = (DD == 64) && !PRECISE;   // a second fragment set: d = 128 has no registers for one, nor has the fp32-accurate variant (it spilled 55 registers per block with it)
+    // A second fragment set: d = 128 has no registers for one, nor has the forward's fp32-accurate variant (it spilled 55
+    // registers per block with it).  The backward's kernel keeps it in both variants: without it the allocator, which
+    // works on the whole kernel, spills the transfer offsets of the fast variant instead (5 % of that kernel).
+    constexpr bool PREFETCH = (DD == 64) && (!PRECISE || WITH_U);
     issue_dma(0);
     if (PREFETCH && nblk > 1) issue_dma(1);
     dma_wait();
