@@ -86,7 +86,7 @@ __global__ __launch_bounds__(256, 2) void moments_f32_kernel(const float *__rest
     const float *Qh = Qg + b * sq.batch + h * sq.head;
 
     // weight role: lane (g, nn) of wave w serves query i0 + nn and keys 16 w + 4 g + r of a block
-    const int iq = i0 + nn, iqc = min(iq, n - 1);
+    const int iq = i0 + nn;
     const int jlim = causal ? iq : n - 1;                              // last key the lane's query sees
     const bool q_live = iq < n;
     // the 16 query rows wait in LDS (in the rows that hold mu~ after the sweep) instead of in 16 registers per lane:
