@@ -178,3 +178,22 @@ def test_backward_workspace_size():
     assert llla.lib().llla_backward_workspace_bytes(1, 1, 0, 64, 0) == 0
     # a bad scalar ridge is ignored when a ridge per row is given: the call gets as far as the workspace check
     assert _bwd(lam=0.0, lam_rows=FAKE) == 6
+
+
+def test_small_head_dimensions_dispatch_on_the_host():
+    """d = 16 / 32: the workspace holds the zero-padded copies and the d = 64 workspace behind them; a forced
+    matrix-core call is served (it fails for lack of a workspace, not as unsupported), for both dtypes."""
+    L = llla.lib()
+    for din in (0, 1):
+        inner = L.llla_forward_workspace_bytes(2, 3, 500, 64, din)
+        esz = 4 if din == 0 else 2
+        for d in (16, 32):
+            need = L.llla_forward_workspace_bytes(2, 3, 500, d, din)
+            rows = 2 * 3 * 500
+            assert need >= inner + rows * 64 * (3 * esz + 8)          # Q, K, V copies, O and rho rows
+            assert _fwd(d=d, din=din, dout=din, path=2) == 6             # served: the workspace is what is missing
+    # LLLA_PATH_AUTO, bf16, 64 rows, d = 32: the padded call (its workspace is checked, and missing)
+    assert _fwd(d=32, din=1, n=64, path=0) == 6
+    assert _bwd(d=32, din=1, n=64, path=0) == 6                          # backward: padded from 64 rows on at d = 32
+    assert _bwd(d=16, din=1, n=64, path=2) == 6
+    assert _bwd(d=16, din=0, n=64, path=2) == 7                          # no fp32 matrix-core backward
