@@ -139,8 +139,8 @@ llla_status llla_forward_ex(const void *Q, const void *K, const void *V, void *O
  * Sigma_i rho = mu_i, started at 0, with Sigma_i applied matrix-free; delta_i and the output follow from Eq. (lla)
  * with that rho_i.  A row whose residual norm ||mu_i - Sigma_i rho|| is at or below `eps` when a step starts takes
  * no further steps (the paper's active mask); eps = 0 runs max_steps steps unless the residual becomes exactly 0.
- * max_steps = 0 gives softmax attention (rho = 0).  Causal; bf16 inputs with d = 64 or 128 only
- * (LLLA_ERR_UNSUPPORTED otherwise).  0 <= max_steps <= 4096, eps >= 0.
+ * max_steps = 0 gives softmax attention (rho = 0).  Causal; bf16 inputs only (LLLA_ERR_UNSUPPORTED otherwise); d = 16
+ * and 32 run at d = 64 on zero-padded copies, whose padded entries stay zero in every iterate.  0 <= max_steps <= 4096, eps >= 0.
  *   rho, delta : optional outputs as in llla_forward_ex;  steps: optional device int32 [B, H, n], steps taken per row.
  * Workspace: llla_forward_cg_workspace_bytes (larger than the exact forward's: the CG vectors of every row).
  */

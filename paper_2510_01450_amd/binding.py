@@ -242,7 +242,7 @@ def forward_cg_workspace_bytes(B, H, n, d, dtype) -> int:
 @_on_callers_stream
 def llla_forward_cg(Q, K, V, lam: float, scale: float, max_steps: int, eps: float = 0.0, out_dtype=None,
                     workspace=None, out=None, stream=None, return_stats: bool = False):
-    """The paper's approximate forward: rho from at most ``max_steps`` conjugate-gradient steps (bf16, d = 64 / 128,
+    """The paper's approximate forward: rho from at most ``max_steps`` conjugate-gradient steps (bf16,
     causal).  Returns O, or (O, rho, delta, steps) with ``return_stats``."""
     if not (Q.is_cuda and K.is_cuda and V.is_cuda):
         raise ValueError("llla_forward_cg needs device tensors; this library has no CPU path")

@@ -148,7 +148,8 @@ llla_status llla_forward(const void *Q, const void *K, const void *V, void *O, l
 size_t llla_forward_cg_workspace_bytes(int B, int H, int n, int d, llla_dtype in)
 {
     if (B <= 0 || H <= 0 || n <= 0 || !dim_supported(d) || !dtype_ok(in)) return 0;
-    return llla::mfma_forward_cg_workspace_bytes(B, H, n, d, in);
+    const size_t padded = llla::padded_forward_cg_workspace_bytes(B, H, n, d, in);
+    return padded ? padded : llla::mfma_forward_cg_workspace_bytes(B, H, n, d, in);
 }
 
 llla_status llla_forward_cg(const void *Q, const void *K, const void *V, void *O, llla_strides sq, llla_strides sk,
@@ -168,8 +169,9 @@ llla_status llla_forward_cg(const void *Q, const void *K, const void *V, void *O
         (reinterpret_cast<uintptr_t>(rho) & 3u) || (reinterpret_cast<uintptr_t>(delta) & 3u) ||
         (reinterpret_cast<uintptr_t>(steps) & 3u))
         return LLLA_ERR_ALIGN;
-    if (!llla::mfma_forward_supported(d, in, true) || (n + 63) / 64 > kMaxGridY) return LLLA_ERR_UNSUPPORTED;
-    st = check_workspace(llla::mfma_forward_cg_workspace_bytes(B, H, n, d, in), workspace, workspace_bytes);
+    const size_t padded_ws = llla::padded_forward_cg_workspace_bytes(B, H, n, d, in);     // d = 16 / 32: run at d = 64 on zero-padded copies
+    if ((padded_ws == 0 && !llla::mfma_forward_supported(d, in, true)) || (n + 63) / 64 > kMaxGridY) return LLLA_ERR_UNSUPPORTED;
+    st = check_workspace(padded_ws ? padded_ws : llla::mfma_forward_cg_workspace_bytes(B, H, n, d, in), workspace, workspace_bytes);
     if (st != LLLA_OK) return st;
 
     Problem p{};
@@ -183,7 +185,7 @@ llla_status llla_forward_cg(const void *Q, const void *K, const void *V, void *O
     p.ws = workspace; p.ws_bytes = workspace_bytes;
     p.stream = static_cast<hipStream_t>(stream);
     llla::stage_begin(p.stream);
-    const hipError_t e = llla::mfma_forward_cg(p, max_steps, eps, steps);
+    const hipError_t e = padded_ws ? llla::padded_forward_cg(p, max_steps, eps, steps) : llla::mfma_forward_cg(p, max_steps, eps, steps);
     llla::stage_end(p.stream);
     return e == hipSuccess ? LLLA_OK : LLLA_ERR_LAUNCH;
 }

@@ -91,6 +91,8 @@ hipError_t mfma_forward_f32(const Problem &p);
 bool padded_forward_supported(int d, llla_dtype in);
 size_t padded_forward_workspace_bytes(int B, int H, int n, int d, llla_dtype in);
 hipError_t padded_forward(const Problem &p);
+size_t padded_forward_cg_workspace_bytes(int B, int H, int n, int d, llla_dtype in);   // bf16 only, like the mode itself
+hipError_t padded_forward_cg(const Problem &p, int T, float eps, int32_t *iters);
 bool padded_backward_supported(int d, llla_dtype in);          // bf16 only, like the matrix-core backward itself
 size_t padded_backward_workspace_bytes(int B, int H, int n, int d, llla_dtype in);
 hipError_t padded_backward(const BackwardProblem &p);

@@ -21,7 +21,7 @@ struct PadLayout {
     size_t q, k, v, o, rho, inner, total;
 };
 
-PadLayout make_pad_layout(int B, int H, int n, llla_dtype in)
+PadLayout make_pad_layout(int B, int H, int n, llla_dtype in, bool cg = false)
 {
     const size_t rows = (size_t)B * H * n;
     const size_t esz = in == LLLA_F32 ? 4 : 2;
@@ -33,7 +33,8 @@ PadLayout make_pad_layout(int B, int H, int n, llla_dtype in)
     L.o = off; off += round_up(rows * PD * 4, 256);         // fp32 or bf16 output rows
     L.rho = off; off += round_up(rows * PD * 4, 256);
     L.inner = off;
-    off += round_up(in == LLLA_F32 ? mfma_forward_f32_workspace_bytes(B, H, n) : mfma_forward_workspace_bytes(B, H, n, PD, in), 256);
+    off += round_up(cg ? mfma_forward_cg_workspace_bytes(B, H, n, PD, in)
+                       : in == LLLA_F32 ? mfma_forward_f32_workspace_bytes(B, H, n) : mfma_forward_workspace_bytes(B, H, n, PD, in), 256);
     L.total = off;
     return L;
 }
@@ -176,6 +177,45 @@ hipError_t padded_forward(const Problem &p)
     if (e != hipSuccess) return e;
 
     stage_mark(p.stream, "unpad");
+    e = p.out == LLLA_F32 ? unpad_rows<4, uint4>(ws + L.o, p.O, p.so, r) : unpad_rows<2, uint4>(ws + L.o, p.O, p.so, r);
+    if (e != hipSuccess) return e;
+    if (p.rho) {
+        const llla_strides sr = {(int64_t)p.H * p.n * p.d, (int64_t)p.n * p.d, (int64_t)p.d};
+        e = unpad_rows<4, uint32_t>(ws + L.rho, p.rho, sr, r);
+    }
+    return e;
+}
+
+// The approximate mode (conjugate gradients) at d = 16 / 32 (bf16): the same padding.  The padded entries of every
+// iterate stay zero -- the residual there is mu_pad - (Sigma p)_pad = 0 - lambda * 0 -- so steps, residuals and the
+// active mask are those of the original system.
+size_t padded_forward_cg_workspace_bytes(int B, int H, int n, int d, llla_dtype in)
+{
+    if (in != LLLA_BF16 || !padded_forward_supported(d, in)) return 0;
+    return make_pad_layout(B, H, n, in, true).total;
+}
+
+hipError_t padded_forward_cg(const Problem &p, int T, float eps, int32_t *iters)
+{
+    const PadLayout L = make_pad_layout(p.B, p.H, p.n, p.in, true);
+    char *ws = static_cast<char *>(p.ws);
+    const llla_strides sp = {(int64_t)p.H * p.n * PD, (int64_t)p.n * PD, (int64_t)PD};
+    const Rows r{p.B, p.H, p.n, p.d, p.stream};
+    hipError_t e = pad_rows(p.Q, p.sq, r, false, ws + L.q);
+    if (e != hipSuccess) return e;
+    e = pad_rows(p.K, p.sk, r, false, ws + L.k);
+    if (e != hipSuccess) return e;
+    e = pad_rows(p.V, p.sv, r, false, ws + L.v);
+    if (e != hipSuccess) return e;
+    Problem q = p;
+    q.Q = ws + L.q; q.K = ws + L.k; q.V = ws + L.v; q.O = ws + L.o;
+    q.sq = q.sk = q.sv = q.so = sp;
+    q.d = PD;
+    q.rho = p.rho ? reinterpret_cast<float *>(ws + L.rho) : nullptr;
+    q.ws = ws + L.inner;
+    q.ws_bytes = L.total - L.inner;
+    e = mfma_forward_cg(q, T, eps, iters);
+    if (e != hipSuccess) return e;
     e = p.out == LLLA_F32 ? unpad_rows<4, uint4>(ws + L.o, p.O, p.so, r) : unpad_rows<2, uint4>(ws + L.o, p.O, p.so, r);
     if (e != hipSuccess) return e;
     if (p.rho) {

@@ -114,7 +114,8 @@ def test_forward_cg_validation():
     assert call(lam=0.0) == 4
     assert call(rho=FAKE + 2) == 5
     assert call(din=0) == 7            # fp32 inputs have no approximate mode
-    assert call(d=32) == 7
+    assert call(d=32) == 6             # served on zero-padded copies: the workspace is what is missing
+    assert call(d=32, din=0) == 7
     assert call() == 6                 # everything valid but no workspace
     assert llla.lib().llla_forward_cg_workspace_bytes(1, 1, 64, 64, 1) > llla.lib().llla_forward_workspace_bytes(1, 1, 64, 64, 1)
     assert llla.lib().llla_forward_cg_workspace_bytes(1, 1, 64, 64, 0) == 0
