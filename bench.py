@@ -4,7 +4,7 @@
 One "step" = one pass of the whole hot path (llla_forward, or llla_decode for the decode workload)
 over one batch of seeded synthetic input that is already resident in HBM.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3|C3b|C3d32|C4|C2|C1|C5|C5d128|E2] [--path auto|valu|mfma]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3|C3b|C3d32|C4|C2|C1|C5|C5s|C5d128|E2] [--path auto|valu|mfma]
                   [--ex | --cg T | --backward] [--no-secondary]
 
 metric  : tokens/s of the causal forward (B*n / t)  -- or generated tokens/s for decode (B / t)

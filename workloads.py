@@ -60,11 +60,13 @@ C5 = _w("C5_decode_bf16_L32768_d64", 4, "decode", 32, 16, 32768, 64, "bf16", "no
 C5D128 = _w("C5d128_decode_bf16_L32768_d128", 8, "decode", 16, 16, 32768, 128, "bf16", "normal")
 # the prefill shape at head dimension 32 (served by the d = 64 matrix-core kernels on zero-padded copies)
 C3D32 = _w("C3d32_prefill_bf16_n4096_d32", 9, "forward", 4, 16, 4096, 32, "bf16", "normal")
+# a small-batch decode step: one sequence, 16 heads, 4096 cached keys (bound by the kernels' latency, not by the stream)
+C5S = _w("C5s_decode_bf16_L4096_d64", 10, "decode", 1, 16, 4096, 64, "bf16", "normal")
 # E2: the paper's test-time regression task (Section 4 and Appendix "Experiments": L = 1024, d = 64, S = 256), one
 # sequence per batch entry; E2S is the same task at a size the oracle finishes in seconds.
 E2 = replace(_w("E2_piecewise_bf16_L1024_d64", 6, "forward", 1024, 1, 1024, 64, "bf16", "piecewise"), segment=256)
 E2S = replace(_w("E2s_piecewise_f32_L256_d16", 7, "forward", 8, 1, 256, 16, "f32", "piecewise"), segment=32)
-ALL = {w.name.split("_")[0].upper(): w for w in (C1, C2, C3, C3B, C3D32, C4, C5, C5D128, E2, E2S)}
+ALL = {w.name.split("_")[0].upper(): w for w in (C1, C2, C3, C3B, C3D32, C4, C5, C5S, C5D128, E2, E2S)}
 
 
 def torch_dtype(w: Workload):
