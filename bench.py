@@ -40,21 +40,21 @@ CSRC = os.path.join(ROOT, "paper_2510_01450_amd", "csrc")
 # scaled with a copy kernel of known size.  Each entry names the summary it was taken from and the hash of the kernel's
 # source file at the time: when the source has changed since, the figure is not reported (traffic = null).
 MEASURED_TRAFFIC = {
-    ("C3_prefill_bf16_n4096_d64", "moments"): {"fetch_bytes": 1.041e+08, "write_bytes": 8.209e+07, "source": "profiles/forward_C3_C3b_moments_kernel_mfma_counters.md",
+    ("C3_prefill_bf16_n4096_d64", "moments"): {"fetch_bytes": 1.043e+08, "write_bytes": 8.153e+07, "source": "profiles/forward_C3_C3b_moments_kernel_mfma_counters.md",
         "kernel_files": ["llla_mfma_fwd.hip", "llla_mfma_common.hpp", "llla_mfma_solve64.hpp"],
-        "kernel_sha16": "e846a6644424d620,6432e08743053cb5,1f4531be53eb35cf"},
-    ("C3b_prefill_bf16_n8192_d64", "moments"): {"fetch_bytes": 1.071e+08, "write_bytes": 8.608e+07, "source": "profiles/forward_C3_C3b_moments_kernel_mfma_counters.md",
+        "kernel_sha16": "cc9e278b1d26fd88,13fbb5de8c328a9c,1ab82f954063627c"},
+    ("C3b_prefill_bf16_n8192_d64", "moments"): {"fetch_bytes": 1.064e+08, "write_bytes": 8.605e+07, "source": "profiles/forward_C3_C3b_moments_kernel_mfma_counters.md",
         "kernel_files": ["llla_mfma_fwd.hip", "llla_mfma_common.hpp", "llla_mfma_solve64.hpp"],
-        "kernel_sha16": "e846a6644424d620,6432e08743053cb5,1f4531be53eb35cf"},
+        "kernel_sha16": "cc9e278b1d26fd88,13fbb5de8c328a9c,1ab82f954063627c"},
     ("C5_decode_bf16_L32768_d64", "decode_partial"): {"fetch_bytes": 4.31e+09, "write_bytes": 5.564e+07, "source": "profiles/decode_C5_bf16_L32768_d64_hbm_traffic.md",
         "kernel_files": ["llla_mfma_decode.hip", "llla_mfma_common.hpp"],
-        "kernel_sha16": "2c09a74142e06a71,6432e08743053cb5"},
-    ("C5d128_decode_bf16_L32768_d128", "decode_partial"): {"fetch_bytes": 4.309e+09, "write_bytes": 5.297e+07, "source": "profiles/decode_C5d128_bf16_L32768_d128_hbm_traffic.md",
+        "kernel_sha16": "0e4506854346e98d,13fbb5de8c328a9c"},
+    ("C5d128_decode_bf16_L32768_d128", "decode_partial"): {"fetch_bytes": 4.31e+09, "write_bytes": 5.297e+07, "source": "profiles/decode_C5d128_bf16_L32768_d128_hbm_traffic.md",
         "kernel_files": ["llla_mfma_decode128.hip", "llla_mfma_common.hpp"],
-        "kernel_sha16": "c2d759d493efaf1e,6432e08743053cb5"},
-    ("C2_f32_n1024_d64", "moments"): {"fetch_bytes": 9.091e+06, "write_bytes": 4.85e+06, "source": "profiles/forward_C2_f32_n1024_d64_counters.md",
+        "kernel_sha16": "43376581dc93a91c,13fbb5de8c328a9c"},
+    ("C2_f32_n1024_d64", "moments"): {"fetch_bytes": 9.069e+06, "write_bytes": 4.85e+06, "source": "profiles/forward_C2_f32_n1024_d64_counters.md",
         "kernel_files": ["llla_mfma_fwd_f32.hip", "llla_mfma_common.hpp", "llla_mfma_solve64.hpp"],
-        "kernel_sha16": "931352b9d2528c92,6432e08743053cb5,1f4531be53eb35cf"},
+        "kernel_sha16": "931352b9d2528c92,13fbb5de8c328a9c,1ab82f954063627c"},
 }
 
 

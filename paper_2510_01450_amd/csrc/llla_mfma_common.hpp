@@ -265,7 +265,7 @@ __device__ inline void trinv_row(float (&li)[16], float mul)
 
 // Upper Cholesky factor and its inverse for the diagonal tiles of the wave's four queries at once:
 // lane 16q + r owns row r of query q's symmetric 16x16 tile (a[c] = T[r][c]).  On return
-// li[c] = -(L^{-1})[r][c] with T = L L^T (zero above the diagonal); the sign is the one solve_wave wants.
+// li[c] = -(L^{-1})[r][c] with T = L L^T (zero above the diagonal); the sign is the one factorise_wave wants.
 // pivot_floor: every pivot of the Cholesky factorisation of (a positive semi-definite matrix + lambda I) is
 // at least lambda in exact arithmetic; a computed pivot below the floor (half of lambda) is a rounding
 // artefact of an ill-conditioned early row and is raised to it, which keeps the factorisation finite.
@@ -356,8 +356,17 @@ __device__ inline void dma16_base_nt_off(const void *sbase, unsigned voff, unsig
 #pragma clang diagnostic pop
 __device__ inline void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-// The factorisation of solve_wave (see there): on return acc(P,J), P < J, holds U(P,J) and acc(P,P) holds N_P =
-// -U(P,P)^{-1}, with Sigma~ + lambda I = U^T U and the tiles given as T = -(Sigma~ + lambda I).
+// Blocked factorisation of the wave's QW systems, all in registers / wave-private LDS scratch (the first half of the
+// per-query solve; the substitutions are solve_wave_q4 at d = 64 and solve_wave_v1 at d = 128):
+//   in : acc[q][tix(I,J)]  upper-triangular 16x16 tiles of T_q = -(Sigma~_q + lambda I) (MFMA accumulator layout)
+//        scw               >= QW*16*SC_PITCH floats of LDS owned by this wave
+//        pivot_floor       per lane: half the ridge of the query of the lane's group (see chol_inv16)
+//   out: acc(P,J), P < J, holds U(P,J) and acc(P,P) holds N_P = -U(P,P)^{-1}, with Sigma~ + lambda I = U^T U.
+// 16-blocked upper Cholesky whose block products are C += A^T B on fp32 MFMA; the diagonal tiles of the QW queries
+// are factorised together in (query, row) lanes with DPP row broadcasts.  The matrix cores only add products, so
+// everything that the textbook recursion subtracts is carried negated instead: the trailing matrix (T), the inverse
+// diagonal factors (N_P), and, in the substitutions, the partial right-hand sides; no tile is ever negated on the
+// vector ALU.
 template <int DD>
 __device__ __forceinline__ void factorise_wave(f32x4 (&acc)[Shape<DD>::QW][Shape<DD>::NTILE], float *scw, int g, int nn,
                                                float pivot_floor)
@@ -416,132 +425,6 @@ __device__ __forceinline__ void factorise_wave(f32x4 (&acc)[Shape<DD>::QW][Shape
 
 }
 
-// Exact solve of the wave's QW augmented systems, all in registers / wave-private LDS scratch:
-//   in : acc[q][tix(I,J)]  upper-triangular 16x16 tiles of T_q = -(Sigma~_q + lambda I) (MFMA accumulator layout)
-//        build_rhs(rhs)    fills rhs[q][P], a tile column with -mu~_q in column 0 and -q_q in column 1 (other
-//                          columns 0); it is called after the factorisation so that the 16 right-hand-side
-//                          registers per query are not live while the diagonal tiles are factorised
-//        om4[q]            omega_q;  scw: >= QW*16*SC_PITCH floats of LDS owned by this wave
-//        pivot_floor       per lane: half the ridge of the query of the lane's group (see chol_inv16)
-//   out: rhs[q][P] column 0 (lanes nn == 0) = y1_q,  y0v[q] = y0_q (valid in lanes nn == 0)
-// with [omega mu~^T; mu~ Sigma~ + lambda I] [y0; y1] = [1; q].  16-blocked upper Cholesky
-// Sigma~ + lambda I = U^T U whose block products are C += A^T B on fp32 MFMA; diagonal tiles of the QW
-// queries are factorised together in (query, row) lanes with DPP row broadcasts; then forward
-// substitution of both right-hand sides, the Schur step on the intercept, and back substitution.
-// The matrix cores only add products, so everything that the textbook recursion subtracts is carried
-// negated instead: the trailing matrix (T), the inverse diagonal factors (N_P = -U_PP^{-1}), and the
-// partial right-hand sides; no tile is ever negated on the vector ALU.
-// WITH_U (the backward pass): build_rhs also puts -r1_q into column 2 and r0v[q] holds r0_q; a second system
-// [omega mu~^T; mu~ Sigma~ + lambda I] [u0; u1] = [r0; r1] is solved alongside at no extra matrix-core work (it
-// rides in a padding column of the right-hand-side tiles): on return column 1 (lanes nn == 1) = u1_q and
-// u0v[q] = u0_q (valid in lanes nn < 4).
-template <int DD, bool WITH_U = false, class BuildRhs>
-__device__ __forceinline__ void solve_wave(f32x4 (&acc)[Shape<DD>::QW][Shape<DD>::NTILE],
-                                           f32x4 (&rhs)[Shape<DD>::QW][Shape<DD>::NB], float (&y0v)[Shape<DD>::QW],
-                                           const float (&om4)[Shape<DD>::QW], float *scw, int g, int nn,
-                                           float pivot_floor, BuildRhs build_rhs, const float *r0v = nullptr,
-                                           float *u0v = nullptr)
-{
-    using S = Shape<DD>;
-    constexpr int QW = S::QW, NB = S::NB;
-    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-
-    factorise_wave<DD>(acc, scw, g, nn, pivot_floor);
-
-    // ---- forward substitution of [mu~ q]:  t_P = -r_P + sum_{I<P} U(I,P)^T r_I,  r_P <- N_P^T t_P -------------
-    build_rhs(rhs);
-#pragma unroll
-    for (int P = 0; P < NB; ++P) {
-#pragma unroll
-        for (int q = 0; q < QW; ++q) {
-            rhs[q][P] = tile_atb(zero, acc[q][S::tix(P, P)], rhs[q][P]);
-#pragma unroll
-            for (int I = P + 1; I < NB; ++I) rhs[q][I] = tile_atb(rhs[q][I], acc[q][S::tix(P, I)], rhs[q][P]);
-        }
-    }
-
-    // rhs[q][P]: column 0 = a = U^{-T} mu~, column 1 = c = U^{-T} q.  Schur step on the intercept:
-    // y0 = (1 - a.c) / (omega - a.a);  y1 = U^{-1} (c - a y0), started below as z = a y0 - c
-#pragma unroll
-    for (int q = 0; q < QW; ++q) {
-        if constexpr (WITH_U) {
-            // column 2 = e = U^{-T} r1:  u0 = (r0 - a.e) / (omega - a.a),  u1 = U^{-1} (e - a u0); every lane of the
-            // first quad of a row (nn < 4) sees a, c and e of that row
-            float saa = 0.f, sac = 0.f, sae = 0.f;
-#pragma unroll
-            for (int P = 0; P < NB; ++P)
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const float v = rhs[q][P][t];
-                    const float av = quad_bcast<0>(v), cv = quad_bcast<1>(v), ev = quad_bcast<2>(v);
-                    saa = fmaf(av, av, saa);
-                    sac = fmaf(av, cv, sac);
-                    sae = fmaf(av, ev, sae);
-                }
-            saa += __shfl_xor(saa, 16); saa += __shfl_xor(saa, 32);
-            sac += __shfl_xor(sac, 16); sac += __shfl_xor(sac, 32);
-            sae += __shfl_xor(sae, 16); sae += __shfl_xor(sae, 32);
-            const float dinv = 1.f / (om4[q] - saa);
-            const float y0 = (1.f - sac) * dinv, u0 = (r0v[q] - sae) * dinv;       // valid in lanes nn < 4
-            y0v[q] = y0;
-            u0v[q] = u0;
-#pragma unroll
-            for (int P = 0; P < NB; ++P)
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const float v = rhs[q][P][t];
-                    const float av = quad_bcast<0>(v), cv = quad_bcast<1>(v), ev = quad_bcast<2>(v);
-                    rhs[q][P][t] = (nn == 0) ? (av * y0 - cv) : ((nn == 1) ? (av * u0 - ev) : 0.f);
-                }
-        } else {
-        float saa = 0.f, sac = 0.f;
-#pragma unroll
-        for (int P = 0; P < NB; ++P)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const float v = rhs[q][P][t];
-                const float o = lane_xor1(v);
-                saa = fmaf(v, v, saa);
-                sac = fmaf(v, o, sac);
-            }
-        saa += __shfl_xor(saa, 16); saa += __shfl_xor(saa, 32);
-        sac += __shfl_xor(sac, 16); sac += __shfl_xor(sac, 32);
-        const float y0 = (1.f - sac) / (om4[q] - saa);       // valid in lanes nn == 0
-        y0v[q] = y0;
-#pragma unroll
-        for (int P = 0; P < NB; ++P)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const float av = rhs[q][P][t];
-                const float cv = lane_xor1(av);
-                rhs[q][P][t] = (nn == 0) ? (av * y0 - cv) : 0.f;
-            }
-        }
-    }
-
-    // ---- back substitution, block rows 3..0:  z_P += sum_{J>P} U(P,J) x_J,  x_P = N_P z_P.  C += A^T B needs
-    //      the transposes of U(P,J) and of N_P as A: one trip through the scratch tile each ---------------
-#pragma unroll
-    for (int P = NB - 1; P >= 0; --P) {
-#pragma unroll
-        for (int J = P + 1; J <= NB; ++J) {
-            const bool diag = (J == NB);
-#pragma unroll
-            for (int q = 0; q < QW; ++q)
-                *reinterpret_cast<f32x4 *>(scw + q * 16 * SC_PITCH + nn * SC_PITCH + 4 * g) = acc[q][diag ? S::tix(P, P) : S::tix(P, J)];
-            wave_sync();
-#pragma unroll
-            for (int q = 0; q < QW; ++q) {
-                f32x4 tr;
-#pragma unroll
-                for (int t = 0; t < 4; ++t) tr[t] = scw[q * 16 * SC_PITCH + (4 * g + t) * SC_PITCH + nn];
-                if (diag) rhs[q][P] = tile_atb(zero, tr, rhs[q][P]);             // N_P z
-                else rhs[q][P] = tile_atb(rhs[q][P], tr, rhs[q][J]);             // z += U(P,J) x_J
-            }
-            wave_sync();
-        }
-    }
-}
 
 }  // namespace mfma
 }  // namespace llla

@@ -12,6 +12,7 @@
 // where [y0; y1] solves [omega mu~^T; mu~ Sigma~ + lambda I] y = [1; q].  A small second kernel merges
 // the partial moments of a head with a max-rescale, solves on chip, and writes o.
 #include "llla_mfma_common.hpp"
+#include "llla_mfma_solve64.hpp"
 
 namespace llla {
 namespace {
@@ -360,7 +361,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 2))) void
 // Merge, solve, output for 4 heads per workgroup (4 waves):
 //   phase 1  wave w sums the partial moments of head 4*block + w with the max-rescale factors
 //            2^(m_p - m*) into LDS (the merge step of Algorithm 1's running maximum);
-//   phase 2  wave 0 solves the four systems together (solve_wave works on four queries per wave);
+//   phase 2  wave 0 solves the four systems together (solve_wave_q4: four queries per wave, lane group = head);
 //   phase 3  wave w forms o = y0 * (sum w v) + G~^T y1 for its head.
 __global__ __launch_bounds__(NT, 1) void decode_merge_kernel(const bf16_t *__restrict__ qg, const float *__restrict__ parts,
                                                              int BH, int nparts, float lambda, void *__restrict__ og,
@@ -398,41 +399,29 @@ __global__ __launch_bounds__(NT, 1) void decode_merge_kernel(const bf16_t *__res
     }
     __syncthreads();
 
-    if (wave == 0) {   // phase 2 (scalar branch: the block contains MFMAs)
-        f32x4 acc[QW][10], rhs[QW][4];
-        float om4[QW], y0v[QW];
+    if (wave == 0) {   // phase 2 (scalar branch: the block contains MFMAs); lane (g, nn) = (head, element) in the solve
+        f32x4 acc[QW][10];
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
-            om4[q] = oms[q];
 #pragma unroll
             for (int t = 0; t < 10; ++t) acc[q][t] = -*reinterpret_cast<const f32x4 *>(&merged[q][t][lane * 4]);
 #pragma unroll
-            for (int P = 0; P < 4; ++P)     // solve_wave takes -(Sigma~ + lambda I)
+            for (int P = 0; P < 4; ++P)     // the solve takes -(Sigma~ + lambda I)
 #pragma unroll
                 for (int t = 0; t < 4; ++t) acc[q][Shape<64>::tix(P, P)][t] -= (nn == 4 * g + t) ? lambda : 0.f;
         }
-        solve_wave<64>(acc, rhs, y0v, om4, scw, g, nn, 0.5f * lambda, [&](f32x4 (&r)[QW][4]) {
+        const int hs = min((int)blockIdx.x * QW + g, BH - 1);
+        float tmu[4], tq[4], te[4], y1[4], u1[4], y0 = 0.f, u0 = 0.f;
 #pragma unroll
-            for (int q = 0; q < QW; ++q) {
-                const int hq = min((int)blockIdx.x * QW + q, BH - 1);
-#pragma unroll
-                for (int P = 0; P < 4; ++P)
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        const int row = 16 * P + 4 * g + t;
-                        const float mv = mus[q][row], qv = bf16_to_f32(qg[(size_t)hq * D + row]);
-                        r[q][P][t] = (nn == 0) ? -mv : ((nn == 1) ? -qv : 0.f);
-                    }
-            }
-        });
-        if (nn == 0) {
-#pragma unroll
-            for (int q = 0; q < QW; ++q) {
-#pragma unroll
-                for (int P = 0; P < 4; ++P) *reinterpret_cast<f32x4 *>(&ys[q][16 * P + 4 * g]) = rhs[q][P];
-                if (g == 0) ys[q][D] = y0v[q];
-            }
+        for (int P = 0; P < 4; ++P) {
+            tmu[P] = -mus[g][16 * P + nn];
+            tq[P] = -bf16_to_f32(qg[(size_t)hs * D + 16 * P + nn]);
+            te[P] = 0.f; y1[P] = 0.f; u1[P] = 0.f;
         }
+        solve_wave_q4<false>(acc, tmu, tq, te, 0.f, oms[g], scw, g, nn, 0.5f * lambda, y1, y0, u1, u0);
+#pragma unroll
+        for (int P = 0; P < 4; ++P) ys[g][16 * P + nn] = y1[P];
+        if (nn == 0) ys[g][D] = y0;
     }
     __syncthreads();
 
@@ -464,7 +453,7 @@ __global__ __launch_bounds__(NT, 1) void decode_merge_kernel(const bf16_t *__res
 // leave most compute units idle and its phase 1 -- one wave adding a head's partial records one after the other, 26 KB
 // per round trip to memory -- is the longest part of the whole decode step.  Here the four waves share the head's 26
 // tiles (wave w: tiles w, w + 4, ...) and fetch them for up to eight partials at a time, so a head's records are in
-// after one or two round trips; wave 0 solves (the three other systems that solve_wave carries are lambda I with a
+// after one or two round trips; wave 0 solves (the three other systems that solve_wave_q4 carries are lambda I with a
 // zero right-hand side); wave J forms column block J of the output.
 __global__ __launch_bounds__(NT, 1) void decode_merge1_kernel(const bf16_t *__restrict__ qg, const float *__restrict__ parts,
                                                               int nparts, float lambda, void *__restrict__ og, int out_bf16)
@@ -517,36 +506,30 @@ __global__ __launch_bounds__(NT, 1) void decode_merge1_kernel(const bf16_t *__re
     }
     __syncthreads();
 
-    if (wave == 0) {   // phase 2 (scalar branch: the block contains MFMAs)
-        f32x4 acc[QW][10], rhs[QW][4];
-        float om4[QW], y0v[QW];
+    if (wave == 0) {   // phase 2 (scalar branch: the block contains MFMAs); lane group 0 = the head, groups 1..3 idle systems
+        f32x4 acc[QW][10];
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
-            om4[q] = q == 0 ? oms : 1.f;
 #pragma unroll
             for (int t = 0; t < 10; ++t)
                 acc[q][t] = q == 0 ? -*reinterpret_cast<const f32x4 *>(&merged[t][lane * 4]) : f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int P = 0; P < 4; ++P)     // solve_wave takes -(Sigma~ + lambda I)
+            for (int P = 0; P < 4; ++P)     // the solve takes -(Sigma~ + lambda I)
 #pragma unroll
                 for (int t = 0; t < 4; ++t) acc[q][Shape<64>::tix(P, P)][t] -= (nn == 4 * g + t) ? lambda : 0.f;
         }
-        solve_wave<64>(acc, rhs, y0v, om4, scw, g, nn, 0.5f * lambda, [&](f32x4 (&r)[QW][4]) {
+        float tmu[4], tq[4], te[4], y1[4], u1[4], y0 = 0.f, u0 = 0.f;
 #pragma unroll
-            for (int q = 0; q < QW; ++q)
+        for (int P = 0; P < 4; ++P) {
+            tmu[P] = g == 0 ? -mus[16 * P + nn] : 0.f;
+            tq[P] = g == 0 ? -bf16_to_f32(qg[(size_t)hq * D + 16 * P + nn]) : 0.f;
+            te[P] = 0.f; y1[P] = 0.f; u1[P] = 0.f;
+        }
+        solve_wave_q4<false>(acc, tmu, tq, te, 0.f, g == 0 ? oms : 1.f, scw, g, nn, 0.5f * lambda, y1, y0, u1, u0);
+        if (g == 0) {
 #pragma unroll
-                for (int P = 0; P < 4; ++P)
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        const int row = 16 * P + 4 * g + t;
-                        const float mv = mus[row], qv = bf16_to_f32(qg[(size_t)hq * D + row]);
-                        r[q][P][t] = q != 0 ? 0.f : ((nn == 0) ? -mv : ((nn == 1) ? -qv : 0.f));
-                    }
-        });
-        if (nn == 0) {
-#pragma unroll
-            for (int P = 0; P < 4; ++P) *reinterpret_cast<f32x4 *>(&ys[16 * P + 4 * g]) = rhs[0][P];
-            if (g == 0) ys[D] = y0v[0];
+            for (int P = 0; P < 4; ++P) ys[16 * P + nn] = y1[P];
+            if (nn == 0) ys[D] = y0;
         }
     }
     __syncthreads();

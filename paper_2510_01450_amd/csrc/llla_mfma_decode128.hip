@@ -518,7 +518,7 @@ __global__ __launch_bounds__(NT, 1) void decode128_merge_kernel(const bf16_t *__
 #pragma unroll
         for (int t = 0; t < NSIG; ++t) acc[0][t] = -*reinterpret_cast<const f32x4 *>(&merged[t][lane * 4]);
 #pragma unroll
-        for (int P = 0; P < NB; ++P)        // solve_wave takes -(Sigma~ + lambda I)
+        for (int P = 0; P < NB; ++P)        // the solve takes -(Sigma~ + lambda I)
 #pragma unroll
             for (int t = 0; t < 4; ++t) acc[0][S128::tix(P, P)][t] -= (nn == 4 * g + t) ? lambda : 0.f;
         solve_wave_v1<128>(acc, rhs, y0v, om4, scw, g, nn, 0.5f * lambda, [&](int P, float &m, float &q, float &e) {

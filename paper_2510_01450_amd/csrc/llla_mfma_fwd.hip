@@ -425,7 +425,7 @@ __device__ __forceinline__ void moments_body(MomentsShared<DD> &sm, const bf16_t
     for (int q = 0; q < QW; ++q)
 #pragma unroll
         for (int t = 0; t < NTILE; ++t) acc[q][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    // The tiles accumulate T = -(Sigma~ + lambda I), the sign the solve works in (see solve_wave): the ridge is
+    // The tiles accumulate T = -(Sigma~ + lambda I), the sign the solve works in (see factorise_wave): the ridge is
     // the starting value of the diagonal, and the scaled MFMA operand carries a minus sign that costs nothing.
 #pragma unroll
     for (int q = 0; q < QW; ++q) {

@@ -1,5 +1,5 @@
 // Exact solve of ONE augmented system per wave (head dimension 128, one query per wave): the 16-blocked Cholesky
-// factorisation of solve_wave on the matrix cores, forward and back substitutions on the vector ALU.
+// factorisation (factorise_wave) on the matrix cores, forward and back substitutions on the vector ALU.
 //
 // Why.  With one query per wave a substitution step is a 16x16 tile times two or three right-hand-side columns; as a
 // 16x16x16 fp32 tile product it occupies the matrix cores for 128 cycles and uses two or three of sixteen output
@@ -13,7 +13,7 @@
 //     the wave), which gives C;  X v (back substitution: U x = z) takes v in C, multiplies per lane and sums over n (the
 //     16 lanes of a row), which gives R;
 //   * C <-> R goes through the wave's scratch tile in LDS (16 floats per vector).
-// The sign conventions are solve_wave's: tiles hold T = -(Sigma~ + lambda I) factorised as U^T U with acc(P,P) = N_P =
+// The sign conventions are factorise_wave's: tiles hold T = -(Sigma~ + lambda I) factorised as U^T U with acc(P,P) = N_P =
 // -U(P,P)^{-1}, right-hand sides come in negated.
 #pragma once
 

@@ -1,5 +1,5 @@
 // Exact solve of four augmented systems per wave at head dimension 64 (the moments kernels' case): the 16-blocked
-// Cholesky factorisation of solve_wave, followed by forward and back substitutions on the vector ALU instead of the
+// Cholesky factorisation of factorise_wave, followed by forward and back substitutions on the vector ALU instead of the
 // matrix cores.
 //
 // Why.  A substitution multiplies a 16x16 tile by two or three right-hand-side columns; as a 16x16x16 fp32 tile
@@ -184,7 +184,7 @@ __device__ __forceinline__ void solve_wave_q4(f32x4 (&acc)[4][10], float (&tmu)[
     static_assert(LIVE >= 1 && LIVE <= 4, "four 16-wide blocks");
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 
-    // ---- factorisation (as in solve_wave): acc(P,J), P < J, becomes U(P,J); acc(P,P) becomes N_P = -U(P,P)^{-1} -----
+    // ---- factorisation (as in factorise_wave): acc(P,J), P < J, becomes U(P,J); acc(P,P) becomes N_P = -U(P,P)^{-1} -----
 #pragma unroll
     for (int P = 0; P < NB; ++P) {
 #pragma unroll
