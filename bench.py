@@ -53,6 +53,9 @@ MEASURED_TRAFFIC = {
     ("C5d128_decode_bf16_L32768_d128", "decode_partial"): {"fetch_bytes": 4.31e+09, "write_bytes": 5.297e+07, "source": "profiles/decode_C5d128_bf16_L32768_d128_hbm_traffic.md",
         "kernel_files": ["llla_mfma_decode128.hip", "llla_mfma_common.hpp"],
         "kernel_sha16": "43376581dc93a91c,13fbb5de8c328a9c"},
+    ("C4_longctx_bf16_n8192_d128", "moments"): {"fetch_bytes": 9.259e+08, "write_bytes": 8.703e+07, "source": "profiles/forward_C4_bf16_n8192_d128_hbm_traffic.md",
+        "kernel_files": ["llla_mfma_fwd.hip", "llla_mfma_common.hpp", "llla_mfma_solve128.hpp"],
+        "kernel_sha16": "cc9e278b1d26fd88,13fbb5de8c328a9c,4d7e6e915f78b32e"},
     ("C2_f32_n1024_d64", "moments"): {"fetch_bytes": 9.069e+06, "write_bytes": 4.85e+06, "source": "profiles/forward_C2_f32_n1024_d64_counters.md",
         "kernel_files": ["llla_mfma_fwd_f32.hip", "llla_mfma_common.hpp", "llla_mfma_solve64.hpp"],
         "kernel_sha16": "931352b9d2528c92,13fbb5de8c328a9c,1ab82f954063627c"},
