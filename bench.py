@@ -12,8 +12,8 @@ roofline: the dominant kernel's algorithmic flops (forward; d^2+11d per causal p
           d^3/3+4d^2 per row) or bytes (decode; K and V read once) over its measured duration
 cpu_baseline: the fp64 oracle as it stands, timed on the host cores on a bounded sample.
 secondary: with no --workload, the line also carries the forward at the shape the matrix-core target is quoted
-          for (d = 64, n = 8192), the long-context forward at d = 128 and the decode configuration, each with its own
-          timing, roofline and parity summary.
+          for (d = 64, n = 8192), the long-context forward at d = 128 and the decode configuration at d = 64 and at
+          d = 128, each with its own timing, roofline and parity summary.
 
 `value` is timed on the production library.  The per-kernel durations behind `roofline` come from a second loop over
 the same launches through the measurement build of the same sources (HIP events around every kernel, on the stream
@@ -446,9 +446,9 @@ def main():
     result = measure(w, args, steps, warmup, headline=True)
     if default_run and not args.no_secondary:
         # the same driver run witnesses the shape the 40 % matrix-core target is quoted for, the d = 128 forward and the
-        # decode configuration
+        # decode configuration at both head dimensions
         result["secondary"] = []
-        for sw in (workloads.C3B, workloads.C4, workloads.C5):
+        for sw in (workloads.C3B, workloads.C4, workloads.C5, workloads.C5D128):
             torch.cuda.empty_cache()
             r = measure(sw, args, steps, warmup, headline=False)
             result["secondary"].append({k: r[k] for k in ("metric", "value", "unit", "ms_per_step", "ms_per_step_sustained",
